@@ -1,0 +1,242 @@
+"""Seeded synthetic inputs for the bounded-cache rollout decode path.
+
+This module holds *no* arithmetic of the method (no attention, no eviction, no
+encoding): it only produces reproducible tensors and workload descriptions.  It
+serves the HIP path, the CPU oracle's tests and the benchmark alike, so both
+sides see bit-identical inputs.
+
+Every value is a pure function of (seed, stream, t, b, head, i):
+
+    value = scale * head_scale[head] * QTAB[ mix64(counter ^ mix64(stream_key)) & 0xFFFF ]
+
+* ``counter`` is the row-major index of the element in a ``[T, B, H, d]`` tensor.
+* ``mix64`` is the splitmix64 output mix (Steele, Lea & Flood 2014), a bijection
+  on 64-bit integers built from xor-shifts and two odd multiplications.
+* ``QTAB`` is a 65 536-entry fp32 table of standard-normal quantiles
+  ``Phi^-1((n + 0.5) / 65536)`` built once on the host in fp64.
+* The product is evaluated in fp32 and, for bf16 workloads, rounded to nearest
+  even.
+
+Only integer operations and one table lookup run on the device, so the CPU and
+the GPU generator agree bit for bit, and any single rollout's history can be
+rebuilt on the host without storing the whole run.
+
+The workloads stand in for the paper's RL rollouts (Experimental Setup section:
+real models on a public math training set, which are not available here): the
+attention shapes are those of the paper's three model families, the values are
+Gaussian with the scale of normalised activations.
+"""
+from __future__ import annotations
+
+import dataclasses
+import math
+from typing import Optional, Tuple
+
+import numpy as np
+import torch
+
+MASK64 = (1 << 64) - 1
+_C1 = 0xBF58476D1CE4E5B9
+_C2 = 0x94D049BB133111EB
+_GOLDEN = 0x9E3779B97F4A7C15
+
+STREAM_Q, STREAM_K, STREAM_V = 0, 1, 2
+STREAM_QG, STREAM_KG, STREAM_VG = 3, 4, 5
+STREAM_WAQ, STREAM_WAK, STREAM_WAV = 6, 7, 8
+STREAM_HEAD_SCALE_Q, STREAM_HEAD_SCALE_K, STREAM_HEAD_SCALE_V = 9, 10, 11
+
+
+def _signed(x: int) -> int:
+    x &= MASK64
+    return x - (1 << 64) if x >= (1 << 63) else x
+
+
+def mix64_int(x: int) -> int:
+    """splitmix64 output mix on a Python integer (the definition the tensor version is tested against)."""
+    x &= MASK64
+    x ^= x >> 30
+    x = (x * _C1) & MASK64
+    x ^= x >> 27
+    x = (x * _C2) & MASK64
+    x ^= x >> 31
+    return x
+
+
+def _lsr(x: torch.Tensor, s: int) -> torch.Tensor:
+    # logical shift right of a two's-complement int64 tensor
+    return (x >> s) & ((1 << (64 - s)) - 1)
+
+
+def mix64(x: torch.Tensor) -> torch.Tensor:
+    """splitmix64 output mix on an int64 tensor (bit pattern = unsigned 64-bit value)."""
+    x = x ^ _lsr(x, 30)
+    x = x * _signed(_C1)
+    x = x ^ _lsr(x, 27)
+    x = x * _signed(_C2)
+    x = x ^ _lsr(x, 31)
+    return x
+
+
+def stream_key(seed: int, stream: int) -> int:
+    return mix64_int((seed * 16 + stream + 1) * _GOLDEN)
+
+
+_QTAB_CACHE = {}
+
+
+def normal_table(device="cpu") -> torch.Tensor:
+    """fp32 table of 65 536 standard-normal quantiles, built in fp64 on the host."""
+    key = str(device)
+    if key not in _QTAB_CACHE:
+        from scipy.special import ndtri
+
+        n = np.arange(65536, dtype=np.float64)
+        tab = ndtri((n + 0.5) / 65536.0).astype(np.float32)
+        _QTAB_CACHE[key] = torch.from_numpy(tab).to(device)
+    return _QTAB_CACHE[key]
+
+
+def uniform01_int(seed: int, stream: int, index: int) -> float:
+    """A uniform in [0,1) with 24 bits, from the same hash (host only)."""
+    h = mix64_int(index ^ stream_key(seed, stream))
+    return ((h >> 16) & 0xFFFFFF) / float(1 << 24)
+
+
+def gaussian(seed: int, stream: int, t0: int, t1: int, B: int, H: int, d: int, scale: float,
+             head_scale: Optional[torch.Tensor] = None, dtype=torch.float32, device="cpu",
+             b0: int = 0, b1: Optional[int] = None, B_total: Optional[int] = None) -> torch.Tensor:
+    """Elements [t0:t1, b0:b1, :, :] of the virtual ``[T, B_total, H, d]`` tensor of a stream.
+
+    ``head_scale`` (fp32, ``[H]``) multiplies each head; ``scale`` multiplies everything.
+    The result has shape ``[t1-t0, b1-b0, H, d]`` and dtype ``dtype``.
+    """
+    B_total = B if B_total is None else B_total
+    b1 = B if b1 is None else b1
+    dev = torch.device(device)
+    t = torch.arange(t0, t1, dtype=torch.int64, device=dev).view(-1, 1, 1, 1)
+    b = torch.arange(b0, b1, dtype=torch.int64, device=dev).view(1, -1, 1, 1)
+    h = torch.arange(H, dtype=torch.int64, device=dev).view(1, 1, -1, 1)
+    i = torch.arange(d, dtype=torch.int64, device=dev).view(1, 1, 1, -1)
+    counter = ((t * B_total + b) * H + h) * d + i
+    bits = mix64(counter ^ _signed(stream_key(seed, stream))) & 0xFFFF
+    z = normal_table(dev)[bits]
+    s = torch.full((1, 1, H, 1), float(np.float32(scale)), dtype=torch.float32, device=dev)
+    if head_scale is not None:
+        s = s * head_scale.to(device=dev, dtype=torch.float32).view(1, 1, H, 1)
+    return (z * s).to(dtype)
+
+
+def head_scales(seed: int, stream: int, H: int, lo: float, hi: float) -> torch.Tensor:
+    """One fp32 scale per head, uniform in [lo, hi), drawn once per (seed, stream)."""
+    u = [uniform01_int(seed, stream, h) for h in range(H)]
+    return torch.tensor([lo + (hi - lo) * x for x in u], dtype=torch.float32)
+
+
+@dataclasses.dataclass(frozen=True)
+class Workload:
+    """One decode workload: a single attention layer's shapes plus the run recipe."""
+
+    name: str
+    dtype: str            # "f32" | "bf16"
+    batch: int            # B rollouts
+    n_q_heads: int        # H_q
+    n_kv_heads: int       # H_kv
+    head_dim: int         # d
+    window: int           # W ring slots
+    chunk: int            # C tokens evicted at once
+    steps: int            # T decode steps (for ragged runs: the cap on the per-rollout length)
+    scale: float          # std of q/k/v before the per-head factor
+    seed: int
+    per_head_scale: bool = False   # per-head factor U(0.5, 1.5), independent for q, k and v heads
+    ragged: bool = False           # per-rollout length lognormal(median 3000, sigma 0.8), capped at `steps`
+    n_global: int = 32             # G global tokens (paper, Experimental Setup: 32 global tokens)
+    rank: int = 32                 # r latent width (paper, Experimental Setup: LoRA rank 32)
+
+    @property
+    def torch_dtype(self):
+        return torch.float32 if self.dtype == "f32" else torch.bfloat16
+
+    @property
+    def elem_bytes(self) -> int:
+        return 4 if self.dtype == "f32" else 2
+
+    @property
+    def d_q(self) -> int:
+        return self.n_q_heads * self.head_dim
+
+    @property
+    def d_kv(self) -> int:
+        return self.n_kv_heads * self.head_dim
+
+    def replace(self, **kw) -> "Workload":
+        return dataclasses.replace(self, **kw)
+
+
+WORKLOADS = {
+    # the five benchmark configurations, in the order the baseline lists them
+    "tiny_f32": Workload("tiny_f32", "f32", 4, 4, 1, 64, 256, 32, 512, 1.0 / 8.0, 1001),
+    "qwen3b": Workload("qwen3b", "bf16", 64, 16, 2, 128, 2048, 64, 4096, 0.088, 1002),
+    "qwen7b": Workload("qwen7b", "bf16", 128, 28, 4, 128, 4096, 128, 8192, 0.088, 1003, per_head_scale=True),
+    "llama8b": Workload("llama8b", "bf16", 256, 32, 8, 128, 8192, 256, 16384, 0.088, 1004),
+    "ragged": Workload("ragged", "bf16", 512, 16, 2, 128, 1024, 64, 16384, 0.088, 1005, ragged=True),
+}
+
+
+def qkv_head_scales(wl: Workload) -> Tuple[Optional[torch.Tensor], Optional[torch.Tensor], Optional[torch.Tensor]]:
+    if not wl.per_head_scale:
+        return None, None, None
+    return (head_scales(wl.seed, STREAM_HEAD_SCALE_Q, wl.n_q_heads, 0.5, 1.5),
+            head_scales(wl.seed, STREAM_HEAD_SCALE_K, wl.n_kv_heads, 0.5, 1.5),
+            head_scales(wl.seed, STREAM_HEAD_SCALE_V, wl.n_kv_heads, 0.5, 1.5))
+
+
+def qkv_steps(wl: Workload, t0: int, t1: int, device="cpu", b0: int = 0, b1: Optional[int] = None):
+    """q ``[t1-t0, b, H_q, d]``, k and v ``[t1-t0, b, H_kv, d]`` for decode steps t0..t1-1 (0-based)."""
+    sq, sk, sv = qkv_head_scales(wl)
+    kw = dict(dtype=wl.torch_dtype, device=device, b0=b0, b1=b1, B_total=wl.batch)
+    q = gaussian(wl.seed, STREAM_Q, t0, t1, wl.batch, wl.n_q_heads, wl.head_dim, wl.scale, sq, **kw)
+    k = gaussian(wl.seed, STREAM_K, t0, t1, wl.batch, wl.n_kv_heads, wl.head_dim, wl.scale, sk, **kw)
+    v = gaussian(wl.seed, STREAM_V, t0, t1, wl.batch, wl.n_kv_heads, wl.head_dim, wl.scale, sv, **kw)
+    return q, k, v
+
+
+def encoder_params(wl: Workload, device="cpu", with_global_kv: bool = True):
+    """Synthetic encoder parameters of the workload's dtype.
+
+    Returns dict with q_g ``[G, d_q]``, WaQ ``[d_q, r]``, WaK ``[d_kv, r]``, WaV ``[d_kv, r]`` and,
+    unless ``with_global_kv`` is false, k_g and v_g ``[G, d_kv]``.  Projections have std
+    1/sqrt(fan_in); global tokens have the workload's activation scale.
+    """
+    G, r, dt = wl.n_global, wl.rank, wl.torch_dtype
+
+    def g2(stream, rows, cols, scale):
+        return gaussian(wl.seed, stream, 0, 1, 1, rows, cols, scale, dtype=dt, device=device).view(rows, cols)
+
+    p = {
+        "q_g": g2(STREAM_QG, G, wl.d_q, wl.scale),
+        "WaQ": g2(STREAM_WAQ, wl.d_q, r, 1.0 / math.sqrt(wl.d_q)),
+        "WaK": g2(STREAM_WAK, wl.d_kv, r, 1.0 / math.sqrt(wl.d_kv)),
+        "WaV": g2(STREAM_WAV, wl.d_kv, r, 1.0 / math.sqrt(wl.d_kv)),
+    }
+    if with_global_kv:
+        p["k_g"] = g2(STREAM_KG, G, wl.d_kv, wl.scale)
+        p["v_g"] = g2(STREAM_VG, G, wl.d_kv, wl.scale)
+    return p
+
+
+def rollout_lengths(wl: Workload) -> np.ndarray:
+    """Per-rollout generation length (int64 ``[B]``).
+
+    Fixed-length workloads return ``steps`` for every rollout.  Ragged ones draw
+    ``min(round(exp(N(ln 3000, 0.8^2))), steps)`` (at least 1) from a seeded host generator.
+    """
+    if not wl.ragged:
+        return np.full(wl.batch, wl.steps, dtype=np.int64)
+    rng = np.random.default_rng(wl.seed)
+    L = np.rint(np.exp(rng.normal(math.log(3000.0), 0.8, size=wl.batch))).astype(np.int64)
+    return np.clip(L, 1, wl.steps)
+
+
+def active_mask(lengths: np.ndarray, t: int) -> np.ndarray:
+    """uint8 ``[B]``: rollout b takes decode step t (0-based) iff t < lengths[b]."""
+    return (t < lengths).astype(np.uint8)
