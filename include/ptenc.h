@@ -1,0 +1,182 @@
+/*
+ * ptenc -- bounded-cache rollout decode for Progressive Thought Encoding on one MI355X (gfx950).
+ *
+ * One context = one attention layer decoding B independent rollouts.  Per rollout the library
+ * keeps a ring-buffer KV cache of W token slots, two counters (len = tokens appended, base =
+ * tokens evicted; live positions are [base, len), position p lives in slot p mod W) and the
+ * fixed-size context state S (G x r, fp32).
+ *
+ * The calls follow the paper's problem statement:
+ *   - a cache policy that prunes the KV cache online during decoding, so that every token is
+ *     generated from a pruned context (Challenges for Efficient RL Training, the rollout
+ *     distribution under cache policy D);
+ *   - the decode step extends the cache by the new k, v first and then lets the query attend
+ *     over it, its own key included (Notation and Preliminaries, decode-stage equation);
+ *   - when the cache is full the earliest thinking tokens are evicted as a chunk and folded
+ *     into the context state: S' = ((q_g W^a_Q)(K_e W^a_K)^T)(V_e W^a_V), then
+ *     S <- Normalize(S + S') (Our Approach, the Delta-W equation and the update rule); S starts
+ *     from the same contraction applied to the global tokens' own k_g, v_g (same section).
+ *
+ * Conventions for every entry point
+ *   - All "d_" pointers are DEVICE pointers, all "h_" pointers are HOST pointers.
+ *   - Ownership: every device buffer is allocated and freed by the caller.  The library
+ *     allocates only the small host-side context.  d_cache, d_state and d_scratch must be
+ *     256-byte aligned, at least as large as ptenc_query_sizes reports, and must outlive the
+ *     context.  Encoder parameters are read during ptenc_set_encoder and ptenc_evict_encode /
+ *     ptenc_decode_step; W^a_K and W^a_V are borrowed until the next ptenc_set_encoder.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
+ *     asynchronous on that stream and never synchronise, except ptenc_get_counters,
+ *     ptenc_get_state and ptenc_poll_error, which synchronise the stream they are given.
+ *   - Errors: every function returns a ptenc_status and never throws or aborts.  Problems the
+ *     host can see (NULL pointer, bad configuration, unsupported value, HIP failure) return a
+ *     code at once and leave all state untouched.  Misuse only the device can see (append to a
+ *     full window, attention of an active rollout with an empty window) sets a bit in a sticky
+ *     device error word, skips the offending rollout, and is reported by ptenc_poll_error.
+ *   - Masks: d_active is uint8[B] or NULL (= all active).  A rollout with d_active[b] == 0 is
+ *     untouched by append / evict and its rows of `out` are written as zeros.
+ *   - Element type: q, k, v, out, the cache and the encoder parameters all have cfg.dtype.
+ *     Scores, softmax statistics, accumulators and S are fp32.
+ *   - Overlapping calls on one context from different streams race; serialise them.
+ */
+#ifndef PTENC_H
+#define PTENC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  PTENC_OK = 0,
+  PTENC_ERR_INVALID_ARG = 1,
+  PTENC_ERR_STATE = 2,        /* call order: e.g. evict_encode before set_encoder */
+  PTENC_ERR_UNSUPPORTED = 3,
+  PTENC_ERR_HIP = 4,
+  PTENC_ERR_NOMEM = 5
+} ptenc_status;
+
+typedef enum { PTENC_F32 = 0, PTENC_BF16 = 1 } ptenc_dtype;
+
+/* Normalize in S <- Normalize(S + S') is not defined by the paper; the default treats the
+ * state as one object: X / max(||X||_F, eps).  ROW_L2 divides each of the G rows by its own
+ * 2-norm; NONE is the identity (the plain linear-attention state). */
+typedef enum { PTENC_NORM_FROBENIUS = 0, PTENC_NORM_ROW_L2 = 1, PTENC_NORM_NONE = 2 } ptenc_norm;
+
+/* Bits of the sticky device error word. */
+enum { PTENC_DEVERR_APPEND_FULL = 1, PTENC_DEVERR_ATTEND_EMPTY = 2 };
+
+/* Tunables for ptenc_set_option. */
+typedef enum {
+  PTENC_OPT_SPLITS = 0,       /* window splits per (rollout, KV head); 1..PTENC_MAX_SPLITS; 0 = heuristic */
+  PTENC_OPT_FORCE_GENERIC = 1 /* 1 = use the plain ALU attention kernel even where the MFMA one applies */
+} ptenc_option;
+
+#define PTENC_MAX_SPLITS 32
+
+typedef struct {
+  int32_t batch;          /* B rollouts */
+  int32_t n_q_heads;      /* H_q */
+  int32_t n_kv_heads;     /* H_kv, divides H_q */
+  int32_t head_dim;       /* d, 1..256 */
+  int32_t window;         /* W ring slots */
+  int32_t chunk;          /* C tokens evicted at once, 1 <= C <= W */
+  int32_t n_sink;         /* permanently retained prompt tokens: reserved, must be 0 */
+  int32_t n_global;       /* G global tokens, 1..64 */
+  int32_t rank;           /* r latent width, 1..64 */
+  int32_t dtype;          /* ptenc_dtype */
+  int32_t norm_mode;      /* ptenc_norm */
+  float norm_eps;         /* 0 => 1e-12 */
+  float softmax_scale;    /* 0 => 1/sqrt(head_dim) (Notation and Preliminaries, attention equation) */
+} ptenc_config;
+
+typedef struct ptenc_ctx ptenc_ctx; /* opaque, host side */
+
+/* Bytes the caller must provide for the cache, the state block and the scratch block. */
+ptenc_status ptenc_query_sizes(const ptenc_config* cfg, size_t* cache_bytes, size_t* state_bytes,
+                               size_t* scratch_bytes);
+
+/* Validates cfg and binds the caller's device buffers.  Touches no device memory: call
+ * ptenc_set_encoder and ptenc_reset before decoding. */
+ptenc_status ptenc_create(const ptenc_config* cfg, void* d_cache, void* d_state, void* d_scratch,
+                          ptenc_ctx** out);
+ptenc_status ptenc_destroy(ptenc_ctx* ctx);
+
+ptenc_status ptenc_set_option(ptenc_ctx* ctx, int32_t option, int32_t value);
+
+/* Encoder parameters (row-major, cfg.dtype): q_g [G, H_q*d], W^a_Q [H_q*d, r], W^a_K and W^a_V
+ * [H_kv*d, r], k_g and v_g [G, H_kv*d] (both NULL => S_0 = 0, the zero-initialised ablation).
+ * Computes Q_a = q_g W^a_Q and S_0 = (Q_a (k_g W^a_K)^T)(v_g W^a_V) on the device (Our Approach,
+ * initialisation with learnable global tokens).  S_0 is not normalised. */
+ptenc_status ptenc_set_encoder(ptenc_ctx* ctx, const void* d_qg, const void* d_WaQ, const void* d_WaK,
+                               const void* d_WaV, const void* d_kg, const void* d_vg, void* stream);
+
+/* len = base = 0 and S = S_0 for the rollouts selected by d_mask (uint8[B], NULL = all);
+ * clears the error word when d_mask is NULL.  Cache contents are left as they are (dead slots
+ * are never read). */
+ptenc_status ptenc_reset(ptenc_ctx* ctx, const uint8_t* d_mask, void* stream);
+
+/* Writes k, v [B, H_kv, d] of every active rollout to slot len mod W, then len += 1
+ * (Notation and Preliminaries: the cache is extended by k_{t+1}, v_{t+1} before attending). */
+ptenc_status ptenc_cache_append(ptenc_ctx* ctx, const void* d_k, const void* d_v,
+                                const uint8_t* d_active, void* stream);
+
+/* out[b, h] = softmax(q[b, h] . K_live / sqrt(d)) V_live over rollout b's live positions,
+ * query head h reading KV head h / (H_q / H_kv); q and out are [B, H_q, d]
+ * (Notation and Preliminaries, attention equation, restricted to the pruned context). */
+ptenc_status ptenc_decode_attn(ptenc_ctx* ctx, const void* d_q, void* d_out, const uint8_t* d_active,
+                               void* stream);
+
+/* For every active rollout whose window is full (len - base == W): takes its C oldest
+ * positions [base, base + C), oldest first, folds them into S as defined above, and
+ * base += C.  Other rollouts are untouched.  d_dbg_chunk is NULL, or [B, 2, C, H_kv*d] of
+ * cfg.dtype receiving K_e (index 0) and V_e (index 1) of each evicting rollout in logical
+ * order (rows of rollouts that did not evict are left untouched). */
+ptenc_status ptenc_evict_encode(ptenc_ctx* ctx, const uint8_t* d_active, void* d_dbg_chunk, void* stream);
+
+/* One decode step: evict_encode, cache_append, decode_attn, in this order. */
+ptenc_status ptenc_decode_step(ptenc_ctx* ctx, const void* d_q, const void* d_k, const void* d_v,
+                               void* d_out, const uint8_t* d_active, void* stream);
+
+/* n_steps decode steps from step-major buffers: q and out [n_steps, B, H_q, d], k and v
+ * [n_steps, B, H_kv, d], d_active NULL or uint8 [n_steps, B].  Same result as n_steps calls of
+ * ptenc_decode_step; the loop runs on the host without synchronising. */
+ptenc_status ptenc_decode_run(ptenc_ctx* ctx, const void* d_q, const void* d_k, const void* d_v,
+                              void* d_out, const uint8_t* d_active, int64_t n_steps, void* stream);
+
+/* Counters to / from host arrays of B int64 each.  set_counters requires
+ * 0 <= base <= len <= base + W for every rollout (used for resume and rotation tests). */
+ptenc_status ptenc_get_counters(ptenc_ctx* ctx, int64_t* h_len, int64_t* h_base, void* stream);
+ptenc_status ptenc_set_counters(ptenc_ctx* ctx, const int64_t* h_len, const int64_t* h_base, void* stream);
+
+/* S to / from a host array [B, G, r] fp32. */
+ptenc_status ptenc_get_state(ptenc_ctx* ctx, float* h_S, void* stream);
+ptenc_status ptenc_set_state(ptenc_ctx* ctx, const float* h_S, void* stream);
+
+/* Q_a [G, r] and S_0 [G, r] (fp32) as computed by ptenc_set_encoder; either may be NULL. */
+ptenc_status ptenc_get_encoder_state(ptenc_ctx* ctx, float* h_Qa, float* h_S0, void* stream);
+
+/* Live window in logical order (oldest first) into d_K, d_V [B, H_kv, W, d] of cfg.dtype; rows
+ * at and beyond len - base are zero-filled.  Debug / checkpoint helper. */
+ptenc_status ptenc_gather_window(ptenc_ctx* ctx, void* d_K, void* d_V, void* stream);
+
+/* Element offset, within d_cache, of element i of the key (which = 0) or value (which = 1) of
+ * KV head h of rollout b stored in ring slot `slot`.  Documents the physical layout for tests
+ * that poison or inspect raw slots. */
+ptenc_status ptenc_cache_offset(ptenc_ctx* ctx, int32_t b, int32_t h, int32_t slot, int32_t i,
+                                int32_t which, size_t* elem_offset);
+
+/* Reads and returns the sticky device error word (does not clear it; ptenc_reset(NULL) does). */
+ptenc_status ptenc_poll_error(ptenc_ctx* ctx, int32_t* h_flags, void* stream);
+
+/* Which kernels this context runs: *attn_kernel = 0 plain ALU, 1 MFMA tiled; *n_splits = window
+ * splits in use; *encode_kernel likewise. Any pointer may be NULL. */
+ptenc_status ptenc_get_plan(ptenc_ctx* ctx, int32_t* attn_kernel, int32_t* n_splits, int32_t* encode_kernel);
+
+const char* ptenc_status_string(ptenc_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PTENC_H */

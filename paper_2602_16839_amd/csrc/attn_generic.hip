@@ -1,0 +1,131 @@
+// Plain-ALU windowed decode attention (any dtype / head_dim <= 256 / layout) and the split combine.
+//
+// out[b,h] = softmax(q[b,h] . K_live * scale) V_live over the live positions of rollout b
+// (Notation and Preliminaries, attention equation, over the pruned context).  One workgroup per
+// (rollout, query head, window split): a thread scores one token, the block reduces max and sum,
+// then one thread per output column accumulates the values.  Partial results are
+// (m, l, unnormalised out) in the base-2 domain and are merged by combine_kernel.
+#include "ptenc_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ inline float block_reduce(float v, float* red, bool is_max) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float u = __shfl_xor(v, o, 64);
+    v = is_max ? fmaxf(v, u) : v + u;
+  }
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float r = red[0];
+  for (int i = 1; i < kThreads / 64; ++i) r = is_max ? fmaxf(r, red[i]) : r + red[i];
+  return r;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void attn_generic_kernel(PtDev c, const T* __restrict__ q,
+                                                               const uint8_t* __restrict__ active) {
+  __shared__ float qs[256];
+  __shared__ float ps[kThreads];
+  __shared__ int slots[kThreads];
+  __shared__ float red[kThreads / 64];
+  const int bh = blockIdx.x, b = bh / c.Hq, h = bh - b * c.Hq, split = blockIdx.y, t = threadIdx.x;
+  float* po = c.partial + ((size_t)bh * c.n_splits + split) * (c.d + 2);
+  const bool act = !active || active[b];
+  const long long len = c.len[b], base = c.base[b];
+  const int n_live = act ? (int)(len - base) : 0;
+  const int per = (n_live + c.n_splits - 1) / c.n_splits;
+  const int j0 = split * per, j1 = min(n_live, j0 + per);
+  const int s0 = (int)(base % c.W);
+  const T* slab = (const T*)c.cache + (size_t)(b * c.Hkv + h / c.group) * pt_slab_elems(c.W, c.d);
+
+  for (int i = t; i < c.d; i += kThreads) qs[i] = pt_ld<T>(q + (size_t)bh * c.d + i);
+  __syncthreads();
+
+  float m_run = -INFINITY, l_run = 0.f, acc = 0.f;
+  for (int jb = j0; jb < j1; jb += kThreads) {
+    const int j = jb + t;
+    float s = -INFINITY;
+    int slot = 0;
+    if (j < j1) {
+      slot = s0 + j; if (slot >= c.W) slot -= c.W;
+      float dot = 0.f;
+      for (int i = 0; i < c.d; ++i) dot = fmaf(qs[i], pt_ld<T>(slab + pt_k_off(c.tiled, c.W, c.d, slot, i)), dot);
+      s = dot * c.scale_log2;
+    }
+    slots[t] = slot;
+    const float mx = block_reduce(s, red, true);
+    const float m_new = fmaxf(m_run, mx);
+    const float p = j < j1 ? exp2f(s - m_new) : 0.f;
+    ps[t] = p;
+    const float sm = block_reduce(p, red, false);   // has barriers: ps/slots visible afterwards
+    const float alpha = exp2f(m_run - m_new);
+    l_run = l_run * alpha + sm;
+    if (t < c.d) {
+      acc *= alpha;
+      const int n = min(kThreads, j1 - jb);
+      for (int x = 0; x < n; ++x)
+        acc = fmaf(ps[x], pt_ld<T>(slab + pt_v_off(c.tiled, c.W, c.d, slots[x], t)), acc);
+    }
+    m_run = m_new;
+    __syncthreads();
+  }
+  if (t == 0) { po[0] = m_run; po[1] = l_run; }
+  if (t < c.d) po[2 + t] = acc;
+}
+
+// Merge the window splits of one (rollout, query head) and write the output row.
+template <typename T>
+__global__ void combine_kernel(PtDev c, T* __restrict__ out, const uint8_t* __restrict__ active) {
+  const int bh = blockIdx.x, b = bh / c.Hq;
+  const float* pp = c.partial + (size_t)bh * c.n_splits * (c.d + 2);
+  const bool act = !active || active[b];
+  float M = -INFINITY;
+  if (act)
+    for (int s = 0; s < c.n_splits; ++s) M = fmaxf(M, pp[(size_t)s * (c.d + 2)]);
+  if (M == -INFINITY) {
+    for (int i = threadIdx.x; i < c.d; i += blockDim.x) pt_st<T>(out + (size_t)bh * c.d + i, 0.f);
+    if (act && threadIdx.x == 0) atomicOr(c.err, PTENC_DEVERR_ATTEND_EMPTY);
+    return;
+  }
+  float L = 0.f;
+  for (int s = 0; s < c.n_splits; ++s) {
+    const float* p = pp + (size_t)s * (c.d + 2);
+    L += exp2f(p[0] - M) * p[1];
+  }
+  for (int i = threadIdx.x; i < c.d; i += blockDim.x) {
+    float o = 0.f;
+    for (int s = 0; s < c.n_splits; ++s) {
+      const float* p = pp + (size_t)s * (c.d + 2);
+      const float f = exp2f(p[0] - M);
+      if (f != 0.f) o = fmaf(f, p[2 + i], o);
+    }
+    pt_st<T>(out + (size_t)bh * c.d + i, o / L);
+  }
+}
+
+}  // namespace
+
+hipError_t pt_launch_combine(const PtDev& c, void* out, const uint8_t* active, hipStream_t s) {
+  const int threads = c.d <= 64 ? 64 : 128;
+  if (c.dtype == PTENC_F32)
+    hipLaunchKernelGGL(combine_kernel<float>, dim3(c.B * c.Hq), dim3(threads), 0, s, c, (float*)out, active);
+  else
+    hipLaunchKernelGGL(combine_kernel<uint16_t>, dim3(c.B * c.Hq), dim3(threads), 0, s, c, (uint16_t*)out, active);
+  return hipGetLastError();
+}
+
+hipError_t pt_launch_attn_generic(const PtDev& c, const void* q, void* out, const uint8_t* active,
+                                  hipStream_t s) {
+  dim3 grid(c.B * c.Hq, c.n_splits);
+  if (c.dtype == PTENC_F32)
+    hipLaunchKernelGGL(attn_generic_kernel<float>, grid, dim3(kThreads), 0, s, c, (const float*)q, active);
+  else
+    hipLaunchKernelGGL(attn_generic_kernel<uint16_t>, grid, dim3(kThreads), 0, s, c, (const uint16_t*)q, active);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return pt_launch_combine(c, out, active, s);
+}

@@ -1,0 +1,317 @@
+// Ring-buffer cache maintenance and the plain-ALU thought encoder.
+//
+//  * reset / gather / counters helpers
+//  * step prologue: [evict the oldest chunk of a full window and fold it into S] then
+//    [append the new k, v], one workgroup per rollout so the two never race on a slot
+//  * encoder set-up: Q_a = q_g W^a_Q and S_0
+//
+// The encoder here is the general one (any dtype, layout, G and r up to 64).  It evaluates
+// S' = (Q_a (K_e W^a_K)^T)(V_e W^a_V) (Our Approach, the Delta-W equation) in the paper's
+// association, 32 tokens at a time, with fp32 accumulation.
+#include "ptenc_internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kSub = 32;   // tokens per sub-chunk
+constexpr int kKB = 64;    // contraction block over d_kv
+constexpr int kMaxGR = 64; // max G and r
+
+// ---- token sources ---------------------------------------------------------------------------
+template <typename T>
+struct CacheChunk {   // the C oldest live tokens of rollout b, logical order
+  const T* cache; int b, Hkv, d, W, tiled, s0;
+  __device__ float get(int which, int tok, int kk) const {
+    int slot = s0 + tok; if (slot >= W) slot -= W;
+    const int h = kk / d, i = kk - h * d;
+    const T* slab = cache + (size_t)(b * Hkv + h) * pt_slab_elems(W, d);
+    const size_t off = which == 0 ? pt_k_off(tiled, W, d, slot, i) : pt_v_off(tiled, W, d, slot, i);
+    return pt_ld<T>(slab + off);
+  }
+};
+
+template <typename T>
+struct GlobalTokens { // k_g, v_g: row-major [G, d_kv]
+  const T* kg; const T* vg; int dkv;
+  __device__ float get(int which, int tok, int kk) const {
+    return pt_ld<T>((which == 0 ? kg : vg) + (size_t)tok * dkv + kk);
+  }
+};
+
+struct EncSmem {
+  float Ks[kSub][kKB + 1];
+  float Ws[kKB][kMaxGR];       // reused as the G x r staging area of the state update
+  float Ka[kSub][kMaxGR + 1];
+  float Va[kSub][kMaxGR + 1];
+  float P[kMaxGR][kSub + 1];
+  float red[kThreads / 64 + 1];
+};
+
+// S' of a chunk of n_tok tokens; thread t ends up with entries t, t+256, ... of the row-major
+// G x r result in sacc[].  dbg (may be null) receives the raw chunk [2][n_tok][d_kv].
+template <typename T, typename Src>
+__device__ void encode_chunk(EncSmem& sm, const Src& src, int n_tok, int dkv, int G, int r,
+                             const float* __restrict__ Qa, const T* __restrict__ WaK,
+                             const T* __restrict__ WaV, T* dbg, float sacc[16]) {
+  const int t = threadIdx.x;
+  const int tok = t & (kSub - 1), cg = t >> 5;   // 8 column groups
+#pragma unroll
+  for (int x = 0; x < 16; ++x) sacc[x] = 0.f;
+
+  for (int sub0 = 0; sub0 < n_tok; sub0 += kSub) {
+    const int ntok = min(kSub, n_tok - sub0);
+    for (int which = 0; which < 2; ++which) {
+      const T* Wsrc = which == 0 ? WaK : WaV;
+      float acc[8];
+#pragma unroll
+      for (int x = 0; x < 8; ++x) acc[x] = 0.f;
+      for (int kb = 0; kb < dkv; kb += kKB) {
+        const int nk = min(kKB, dkv - kb);
+        for (int idx = t; idx < kSub * kKB; idx += kThreads) {
+          const int tk = idx / kKB, kk = idx - tk * kKB;
+          float val = 0.f;
+          if (tk < ntok && kk < nk) {
+            val = src.get(which, sub0 + tk, kb + kk);
+            if (dbg) pt_st<T>(dbg + ((size_t)which * n_tok + sub0 + tk) * dkv + kb + kk, val);
+          }
+          sm.Ks[tk][kk] = val;
+        }
+        for (int idx = t; idx < kKB * r; idx += kThreads) {
+          const int kk = idx / r, col = idx - kk * r;
+          sm.Ws[kk][col] = kk < nk ? pt_ld<T>(Wsrc + (size_t)(kb + kk) * r + col) : 0.f;
+        }
+        __syncthreads();
+        for (int kk = 0; kk < kKB; ++kk) {
+          const float kv = sm.Ks[tok][kk];
+#pragma unroll
+          for (int x = 0; x < 8; ++x) {
+            const int col = cg + 8 * x;
+            if (col < r) acc[x] = fmaf(kv, sm.Ws[kk][col], acc[x]);
+          }
+        }
+        __syncthreads();
+      }
+#pragma unroll
+      for (int x = 0; x < 8; ++x) {
+        const int col = cg + 8 * x;
+        if (col < r) (which == 0 ? sm.Ka : sm.Va)[tok][col] = acc[x];
+      }
+    }
+    __syncthreads();
+    // P = Q_a K_a^T  (G x 32)
+    for (int idx = t; idx < G * kSub; idx += kThreads) {
+      const int g = idx / kSub, tk = idx - g * kSub;
+      float p = 0.f;
+      if (tk < ntok)
+        for (int a = 0; a < r; ++a) p = fmaf(Qa[g * r + a], sm.Ka[tk][a], p);
+      sm.P[g][tk] = p;
+    }
+    __syncthreads();
+    // S' += P V_a  (G x r)
+#pragma unroll
+    for (int x = 0; x < 16; ++x) {
+      const int idx = t + kThreads * x;
+      if (idx < G * r) {
+        const int g = idx / r, col = idx - g * r;
+        float s = sacc[x];
+        for (int tk = 0; tk < ntok; ++tk) s = fmaf(sm.P[g][tk], sm.Va[tk][col], s);
+        sacc[x] = s;
+      }
+    }
+    __syncthreads();
+  }
+}
+
+__device__ float block_sum(float v, float* red) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  const int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  float tot = 0.f;
+  for (int i = 0; i < kThreads / 64; ++i) tot += red[i];
+  return tot;
+}
+
+// ---- step prologue ----------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(kThreads) void step_prologue_kernel(PtDev c, int do_evict, int do_append,
+                                                                const T* __restrict__ knew,
+                                                                const T* __restrict__ vnew,
+                                                                const uint8_t* __restrict__ active,
+                                                                T* dbg_chunk) {
+  __shared__ EncSmem sm;
+  const int b = blockIdx.x, t = threadIdx.x;
+  if (active && !active[b]) return;
+  const long long len = c.len[b];
+  long long base = c.base[b];
+  const int dkv = c.Hkv * c.d;
+  T* cache = (T*)c.cache;
+
+  if (do_evict && len - base == c.W) {
+    CacheChunk<T> src{cache, b, c.Hkv, c.d, c.W, c.tiled, (int)(base % c.W)};
+    float sacc[16];
+    T* dbg = dbg_chunk ? dbg_chunk + (size_t)b * 2 * c.C * dkv : nullptr;
+    encode_chunk<T>(sm, src, c.C, dkv, c.G, c.r, c.Qa, (const T*)c.WaK, (const T*)c.WaV, dbg, sacc);
+    // S <- Normalize(S + S')   (Our Approach, the update rule)
+    float* S = c.S + (size_t)b * c.G * c.r;
+    float* stage = &sm.Ws[0][0];
+    float ss = 0.f;
+#pragma unroll
+    for (int x = 0; x < 16; ++x) {
+      const int idx = t + kThreads * x;
+      if (idx < c.G * c.r) {
+        sacc[x] += S[idx];
+        ss = fmaf(sacc[x], sacc[x], ss);
+        stage[idx] = sacc[x];
+      }
+    }
+    if (c.norm_mode == PTENC_NORM_FROBENIUS) {
+      const float nrm = fmaxf(sqrtf(block_sum(ss, sm.red)), c.norm_eps);
+#pragma unroll
+      for (int x = 0; x < 16; ++x) {
+        const int idx = t + kThreads * x;
+        if (idx < c.G * c.r) S[idx] = sacc[x] / nrm;
+      }
+    } else if (c.norm_mode == PTENC_NORM_ROW_L2) {
+      __syncthreads();
+#pragma unroll
+      for (int x = 0; x < 16; ++x) {
+        const int idx = t + kThreads * x;
+        if (idx < c.G * c.r) {
+          const int g = idx / c.r;
+          float rs = 0.f;
+          for (int a = 0; a < c.r; ++a) rs = fmaf(stage[g * c.r + a], stage[g * c.r + a], rs);
+          S[idx] = sacc[x] / fmaxf(sqrtf(rs), c.norm_eps);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int x = 0; x < 16; ++x) {
+        const int idx = t + kThreads * x;
+        if (idx < c.G * c.r) S[idx] = sacc[x];
+      }
+    }
+    base += c.C;
+    __syncthreads();   // every read of the evicted slots is done before the append below
+    if (t == 0) c.base[b] = base;
+  }
+
+  if (do_append) {
+    if (len - base >= c.W) {
+      if (t == 0) atomicOr(c.err, PTENC_DEVERR_APPEND_FULL);
+      return;
+    }
+    const int slot = (int)(len % c.W);
+    for (int idx = t; idx < dkv; idx += kThreads) {
+      const int h = idx / c.d, i = idx - h * c.d;
+      T* slab = cache + (size_t)(b * c.Hkv + h) * pt_slab_elems(c.W, c.d);
+      const size_t src = (size_t)b * dkv + idx;
+      slab[pt_k_off(c.tiled, c.W, c.d, slot, i)] = knew[src];
+      slab[pt_v_off(c.tiled, c.W, c.d, slot, i)] = vnew[src];
+    }
+    if (t == 0) c.len[b] = len + 1;
+  }
+}
+
+// ---- reset / gather -----------------------------------------------------------------------------
+__global__ void reset_kernel(PtDev c, const uint8_t* __restrict__ mask, int clear_err) {
+  const int b = blockIdx.x;
+  if (clear_err && b == 0 && threadIdx.x == 0) *c.err = 0;
+  if (mask && !mask[b]) return;
+  const int n = c.G * c.r;
+  for (int i = threadIdx.x; i < n; i += blockDim.x) c.S[(size_t)b * n + i] = c.S0[i];
+  if (threadIdx.x == 0) { c.len[b] = 0; c.base[b] = 0; }
+}
+
+template <typename T>
+__global__ void gather_kernel(PtDev c, T* __restrict__ Kout, T* __restrict__ Vout) {
+  const int slab = blockIdx.x, b = slab / c.Hkv;
+  const long long len = c.len[b], base = c.base[b];
+  const int n_live = (int)(len - base), s0 = (int)(base % c.W);
+  const T* src = (const T*)c.cache + (size_t)slab * pt_slab_elems(c.W, c.d);
+  for (int j = blockIdx.y; j < c.W; j += gridDim.y) {
+    int slot = s0 + j; if (slot >= c.W) slot -= c.W;
+    for (int i = threadIdx.x; i < c.d; i += blockDim.x) {
+      const size_t o = ((size_t)slab * c.W + j) * c.d + i;
+      if (j < n_live) {
+        Kout[o] = src[pt_k_off(c.tiled, c.W, c.d, slot, i)];
+        Vout[o] = src[pt_v_off(c.tiled, c.W, c.d, slot, i)];
+      } else {
+        Kout[o] = (T)0; Vout[o] = (T)0;
+      }
+    }
+  }
+}
+
+// ---- encoder set-up -----------------------------------------------------------------------------
+template <typename T>
+__global__ void qa_kernel(PtDev c, const T* __restrict__ qg, const T* __restrict__ WaQ) {
+  const int g = blockIdx.x, a = threadIdx.x;
+  if (a >= c.r) return;
+  const int dq = c.Hq * c.d;
+  float acc = 0.f;
+  for (int x = 0; x < dq; ++x) acc = fmaf(pt_ld<T>(qg + (size_t)g * dq + x), pt_ld<T>(WaQ + (size_t)x * c.r + a), acc);
+  c.Qa[g * c.r + a] = acc;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void s0_kernel(PtDev c, const T* __restrict__ kg, const T* __restrict__ vg) {
+  __shared__ EncSmem sm;
+  const int t = threadIdx.x;
+  float sacc[16];
+#pragma unroll
+  for (int x = 0; x < 16; ++x) sacc[x] = 0.f;
+  if (kg && vg) {
+    GlobalTokens<T> src{kg, vg, c.Hkv * c.d};
+    encode_chunk<T>(sm, src, c.G, c.Hkv * c.d, c.G, c.r, c.Qa, (const T*)c.WaK, (const T*)c.WaV, (T*)nullptr, sacc);
+  }
+#pragma unroll
+  for (int x = 0; x < 16; ++x) {
+    const int idx = t + kThreads * x;
+    if (idx < c.G * c.r) c.S0[idx] = sacc[x];
+  }
+}
+
+}  // namespace
+
+hipError_t pt_launch_reset(const PtDev& c, const uint8_t* mask, bool clear_err, hipStream_t s) {
+  hipLaunchKernelGGL(reset_kernel, dim3(c.B), dim3(256), 0, s, c, mask, clear_err ? 1 : 0);
+  return hipGetLastError();
+}
+
+hipError_t pt_launch_step_prologue(const PtDev& c, bool do_evict, bool do_append, int encode_kernel,
+                                   const void* k, const void* v, const uint8_t* active, void* dbg_chunk,
+                                   hipStream_t s) {
+  (void)encode_kernel;
+  if (c.dtype == PTENC_F32)
+    hipLaunchKernelGGL(step_prologue_kernel<float>, dim3(c.B), dim3(kThreads), 0, s, c, do_evict ? 1 : 0,
+                       do_append ? 1 : 0, (const float*)k, (const float*)v, active, (float*)dbg_chunk);
+  else
+    hipLaunchKernelGGL(step_prologue_kernel<uint16_t>, dim3(c.B), dim3(kThreads), 0, s, c, do_evict ? 1 : 0,
+                       do_append ? 1 : 0, (const uint16_t*)k, (const uint16_t*)v, active, (uint16_t*)dbg_chunk);
+  return hipGetLastError();
+}
+
+hipError_t pt_launch_gather(const PtDev& c, void* K, void* V, hipStream_t s) {
+  dim3 grid(c.B * c.Hkv, c.W < 64 ? c.W : 64);
+  const int threads = c.d <= 64 ? 64 : (c.d <= 128 ? 128 : 256);
+  if (c.dtype == PTENC_F32)
+    hipLaunchKernelGGL(gather_kernel<float>, grid, dim3(threads), 0, s, c, (float*)K, (float*)V);
+  else
+    hipLaunchKernelGGL(gather_kernel<uint16_t>, grid, dim3(threads), 0, s, c, (uint16_t*)K, (uint16_t*)V);
+  return hipGetLastError();
+}
+
+hipError_t pt_launch_encoder_init(const PtDev& c, const void* qg, const void* WaQ, const void* kg,
+                                  const void* vg, hipStream_t s) {
+  if (c.dtype == PTENC_F32) {
+    hipLaunchKernelGGL(qa_kernel<float>, dim3(c.G), dim3(64), 0, s, c, (const float*)qg, (const float*)WaQ);
+    hipLaunchKernelGGL(s0_kernel<float>, dim3(1), dim3(kThreads), 0, s, c, (const float*)kg, (const float*)vg);
+  } else {
+    hipLaunchKernelGGL(qa_kernel<uint16_t>, dim3(c.G), dim3(64), 0, s, c, (const uint16_t*)qg, (const uint16_t*)WaQ);
+    hipLaunchKernelGGL(s0_kernel<uint16_t>, dim3(1), dim3(kThreads), 0, s, c, (const uint16_t*)kg, (const uint16_t*)vg);
+  }
+  return hipGetLastError();
+}

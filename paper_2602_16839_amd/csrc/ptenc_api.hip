@@ -1,0 +1,310 @@
+// Host side of libptenc: argument checks, context bookkeeping, kernel launches.
+#include <math.h>
+#include <new>
+#include <stdlib.h>
+#include <string.h>
+
+#include "ptenc_internal.h"
+
+namespace {
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct StateLayout {
+  size_t S, Qa, S0, len, base, err, total;
+};
+
+StateLayout state_layout(const ptenc_config& c) {
+  StateLayout L;
+  size_t off = 0;
+  const size_t gr = (size_t)c.n_global * c.rank * sizeof(float);
+  L.S = off;    off = align256(off + gr * c.batch);
+  L.Qa = off;   off = align256(off + gr);
+  L.S0 = off;   off = align256(off + gr);
+  L.len = off;  off = align256(off + sizeof(long long) * c.batch);
+  L.base = off; off = align256(off + sizeof(long long) * c.batch);
+  L.err = off;  off = align256(off + sizeof(int));
+  L.total = off;
+  return L;
+}
+
+ptenc_status check_config(const ptenc_config* c) {
+  if (!c) return PTENC_ERR_INVALID_ARG;
+  if (c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 1) return PTENC_ERR_INVALID_ARG;
+  if (c->n_q_heads % c->n_kv_heads != 0) return PTENC_ERR_INVALID_ARG;
+  if (c->window < 1 || c->chunk < 1 || c->chunk > c->window) return PTENC_ERR_INVALID_ARG;
+  if (c->n_global < 1 || c->rank < 1) return PTENC_ERR_INVALID_ARG;
+  if (c->dtype != PTENC_F32 && c->dtype != PTENC_BF16) return PTENC_ERR_INVALID_ARG;
+  if (c->norm_mode < PTENC_NORM_FROBENIUS || c->norm_mode > PTENC_NORM_NONE) return PTENC_ERR_INVALID_ARG;
+  if (!(c->norm_eps >= 0.f) || !(c->softmax_scale >= 0.f) || isinf(c->softmax_scale)) return PTENC_ERR_INVALID_ARG;
+  if (c->n_sink != 0) return PTENC_ERR_UNSUPPORTED;
+  if (c->head_dim > 256 || c->n_global > 64 || c->rank > 64) return PTENC_ERR_UNSUPPORTED;
+  if ((size_t)c->batch * c->n_q_heads > 0x7fffffffu / PTENC_MAX_SPLITS) return PTENC_ERR_UNSUPPORTED;
+  return PTENC_OK;
+}
+
+size_t elem_bytes(int dtype) { return dtype == PTENC_F32 ? 4 : 2; }
+
+bool mfma_attn_applies(const ptenc_config& c) {
+  return c.dtype == PTENC_BF16 && c.head_dim == 128 && c.window % 32 == 0 &&
+         c.n_q_heads / c.n_kv_heads <= 16;
+}
+
+// window splits: enough workgroups to fill 256 CUs twice over, no split shorter than 256 tokens
+int heuristic_splits(const ptenc_ctx* x) {
+  const ptenc_config& c = x->cfg;
+  const long rows = (long)c.batch * (x->attn_kernel ? c.n_kv_heads : c.n_q_heads);
+  long want = (1024 + rows - 1) / rows;
+  long cap = c.window / 256;
+  if (cap < 1) cap = 1;
+  if (want > cap) want = cap;
+  if (want > PTENC_MAX_SPLITS) want = PTENC_MAX_SPLITS;
+  if (want < 1) want = 1;
+  return (int)want;
+}
+
+void replan(ptenc_ctx* x) {
+  x->attn_kernel = (x->dev.tiled && !x->opt_force_generic) ? 1 : 0;
+  x->encode_kernel = 0;
+  x->dev.n_splits = x->opt_splits > 0 ? x->opt_splits : heuristic_splits(x);
+}
+
+inline hipStream_t S(void* s) { return (hipStream_t)s; }
+inline ptenc_status hip_status(hipError_t e) { return e == hipSuccess ? PTENC_OK : PTENC_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+ptenc_status ptenc_query_sizes(const ptenc_config* cfg, size_t* cache_bytes, size_t* state_bytes,
+                               size_t* scratch_bytes) {
+  ptenc_status st = check_config(cfg);
+  if (st != PTENC_OK) return st;
+  if (cache_bytes)
+    *cache_bytes = align256((size_t)cfg->batch * cfg->n_kv_heads * pt_slab_elems(cfg->window, cfg->head_dim) *
+                            elem_bytes(cfg->dtype));
+  if (state_bytes) *state_bytes = state_layout(*cfg).total;
+  if (scratch_bytes)
+    *scratch_bytes = align256((size_t)cfg->batch * cfg->n_q_heads * PTENC_MAX_SPLITS * (cfg->head_dim + 2) * sizeof(float));
+  return PTENC_OK;
+}
+
+ptenc_status ptenc_create(const ptenc_config* cfg, void* d_cache, void* d_state, void* d_scratch,
+                          ptenc_ctx** out) {
+  if (!out) return PTENC_ERR_INVALID_ARG;
+  *out = nullptr;
+  ptenc_status st = check_config(cfg);
+  if (st != PTENC_OK) return st;
+  if (!d_cache || !d_state || !d_scratch) return PTENC_ERR_INVALID_ARG;
+  if (((uintptr_t)d_cache | (uintptr_t)d_state | (uintptr_t)d_scratch) & 255) return PTENC_ERR_INVALID_ARG;
+  ptenc_ctx* x = new (std::nothrow) ptenc_ctx;
+  if (!x) return PTENC_ERR_NOMEM;
+  memset(x, 0, sizeof(*x));
+  x->cfg = *cfg;
+  if (x->cfg.norm_eps == 0.f) x->cfg.norm_eps = 1e-12f;
+  ptenc_query_sizes(cfg, &x->cache_bytes, &x->state_bytes, &x->scratch_bytes);
+  const StateLayout L = state_layout(*cfg);
+  char* sp = (char*)d_state;
+  PtDev& d = x->dev;
+  d.B = cfg->batch; d.Hq = cfg->n_q_heads; d.Hkv = cfg->n_kv_heads; d.d = cfg->head_dim;
+  d.W = cfg->window; d.C = cfg->chunk; d.G = cfg->n_global; d.r = cfg->rank;
+  d.group = cfg->n_q_heads / cfg->n_kv_heads;
+  d.dtype = cfg->dtype;
+  d.tiled = mfma_attn_applies(*cfg) ? 1 : 0;
+  d.norm_mode = cfg->norm_mode;
+  d.norm_eps = x->cfg.norm_eps;
+  const double scale = cfg->softmax_scale > 0.f ? (double)cfg->softmax_scale : 1.0 / sqrt((double)cfg->head_dim);
+  d.scale_log2 = (float)(scale * 1.4426950408889634074);
+  d.cache = d_cache;
+  d.S = (float*)(sp + L.S); d.Qa = (float*)(sp + L.Qa); d.S0 = (float*)(sp + L.S0);
+  d.len = (long long*)(sp + L.len); d.base = (long long*)(sp + L.base); d.err = (int*)(sp + L.err);
+  d.partial = (float*)d_scratch;
+  d.WaK = nullptr; d.WaV = nullptr;
+  replan(x);
+  *out = x;
+  return PTENC_OK;
+}
+
+ptenc_status ptenc_destroy(ptenc_ctx* ctx) {
+  if (!ctx) return PTENC_ERR_INVALID_ARG;
+  delete ctx;
+  return PTENC_OK;
+}
+
+ptenc_status ptenc_set_option(ptenc_ctx* ctx, int32_t option, int32_t value) {
+  if (!ctx) return PTENC_ERR_INVALID_ARG;
+  switch (option) {
+    case PTENC_OPT_SPLITS:
+      if (value < 0 || value > PTENC_MAX_SPLITS) return PTENC_ERR_INVALID_ARG;
+      ctx->opt_splits = value;
+      break;
+    case PTENC_OPT_FORCE_GENERIC:
+      if (value != 0 && value != 1) return PTENC_ERR_INVALID_ARG;
+      ctx->opt_force_generic = value;
+      break;
+    default:
+      return PTENC_ERR_INVALID_ARG;
+  }
+  replan(ctx);
+  return PTENC_OK;
+}
+
+ptenc_status ptenc_get_plan(ptenc_ctx* ctx, int32_t* attn_kernel, int32_t* n_splits, int32_t* encode_kernel) {
+  if (!ctx) return PTENC_ERR_INVALID_ARG;
+  if (attn_kernel) *attn_kernel = ctx->attn_kernel;
+  if (n_splits) *n_splits = ctx->dev.n_splits;
+  if (encode_kernel) *encode_kernel = ctx->encode_kernel;
+  return PTENC_OK;
+}
+
+ptenc_status ptenc_set_encoder(ptenc_ctx* ctx, const void* d_qg, const void* d_WaQ, const void* d_WaK,
+                               const void* d_WaV, const void* d_kg, const void* d_vg, void* stream) {
+  if (!ctx || !d_qg || !d_WaQ || !d_WaK || !d_WaV) return PTENC_ERR_INVALID_ARG;
+  if ((d_kg == nullptr) != (d_vg == nullptr)) return PTENC_ERR_INVALID_ARG;
+  PtDev d = ctx->dev;
+  d.WaK = d_WaK; d.WaV = d_WaV;
+  hipError_t e = pt_launch_encoder_init(d, d_qg, d_WaQ, d_kg, d_vg, S(stream));
+  if (e != hipSuccess) return PTENC_ERR_HIP;
+  ctx->dev = d;
+  ctx->encoder_set = 1;
+  return PTENC_OK;
+}
+
+ptenc_status ptenc_reset(ptenc_ctx* ctx, const uint8_t* d_mask, void* stream) {
+  if (!ctx) return PTENC_ERR_INVALID_ARG;
+  if (!ctx->encoder_set) return PTENC_ERR_STATE;
+  return hip_status(pt_launch_reset(ctx->dev, d_mask, d_mask == nullptr, S(stream)));
+}
+
+ptenc_status ptenc_cache_append(ptenc_ctx* ctx, const void* d_k, const void* d_v, const uint8_t* d_active,
+                                void* stream) {
+  if (!ctx || !d_k || !d_v) return PTENC_ERR_INVALID_ARG;
+  if (!ctx->encoder_set) return PTENC_ERR_STATE;
+  return hip_status(pt_launch_step_prologue(ctx->dev, false, true, ctx->encode_kernel, d_k, d_v, d_active,
+                                            nullptr, S(stream)));
+}
+
+ptenc_status ptenc_evict_encode(ptenc_ctx* ctx, const uint8_t* d_active, void* d_dbg_chunk, void* stream) {
+  if (!ctx) return PTENC_ERR_INVALID_ARG;
+  if (!ctx->encoder_set) return PTENC_ERR_STATE;
+  return hip_status(pt_launch_step_prologue(ctx->dev, true, false, ctx->encode_kernel, nullptr, nullptr,
+                                            d_active, d_dbg_chunk, S(stream)));
+}
+
+ptenc_status ptenc_decode_attn(ptenc_ctx* ctx, const void* d_q, void* d_out, const uint8_t* d_active,
+                               void* stream) {
+  if (!ctx || !d_q || !d_out) return PTENC_ERR_INVALID_ARG;
+  if (!ctx->encoder_set) return PTENC_ERR_STATE;
+  if (ctx->attn_kernel == 1) {
+    if (((uintptr_t)d_q | (uintptr_t)d_out) & 15) return PTENC_ERR_INVALID_ARG;
+    return hip_status(pt_launch_attn_mfma(ctx->dev, d_q, d_out, d_active, S(stream)));
+  }
+  return hip_status(pt_launch_attn_generic(ctx->dev, d_q, d_out, d_active, S(stream)));
+}
+
+ptenc_status ptenc_decode_step(ptenc_ctx* ctx, const void* d_q, const void* d_k, const void* d_v, void* d_out,
+                               const uint8_t* d_active, void* stream) {
+  if (!ctx || !d_q || !d_k || !d_v || !d_out) return PTENC_ERR_INVALID_ARG;
+  if (!ctx->encoder_set) return PTENC_ERR_STATE;
+  hipError_t e = pt_launch_step_prologue(ctx->dev, true, true, ctx->encode_kernel, d_k, d_v, d_active, nullptr,
+                                         S(stream));
+  if (e != hipSuccess) return PTENC_ERR_HIP;
+  return ptenc_decode_attn(ctx, d_q, d_out, d_active, stream);
+}
+
+ptenc_status ptenc_decode_run(ptenc_ctx* ctx, const void* d_q, const void* d_k, const void* d_v, void* d_out,
+                              const uint8_t* d_active, int64_t n_steps, void* stream) {
+  if (!ctx || !d_q || !d_k || !d_v || !d_out || n_steps < 0) return PTENC_ERR_INVALID_ARG;
+  const ptenc_config& c = ctx->cfg;
+  const size_t es = elem_bytes(c.dtype);
+  const size_t qb = (size_t)c.batch * c.n_q_heads * c.head_dim * es;
+  const size_t kb = (size_t)c.batch * c.n_kv_heads * c.head_dim * es;
+  for (int64_t t = 0; t < n_steps; ++t) {
+    ptenc_status st = ptenc_decode_step(ctx, (const char*)d_q + t * qb, (const char*)d_k + t * kb,
+                                        (const char*)d_v + t * kb, (char*)d_out + t * qb,
+                                        d_active ? d_active + t * c.batch : nullptr, stream);
+    if (st != PTENC_OK) return st;
+  }
+  return PTENC_OK;
+}
+
+ptenc_status ptenc_get_counters(ptenc_ctx* ctx, int64_t* h_len, int64_t* h_base, void* stream) {
+  if (!ctx || !h_len || !h_base) return PTENC_ERR_INVALID_ARG;
+  const size_t n = sizeof(long long) * ctx->cfg.batch;
+  if (hipMemcpyAsync(h_len, ctx->dev.len, n, hipMemcpyDeviceToHost, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
+  if (hipMemcpyAsync(h_base, ctx->dev.base, n, hipMemcpyDeviceToHost, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
+  return hip_status(hipStreamSynchronize(S(stream)));
+}
+
+ptenc_status ptenc_set_counters(ptenc_ctx* ctx, const int64_t* h_len, const int64_t* h_base, void* stream) {
+  if (!ctx || !h_len || !h_base) return PTENC_ERR_INVALID_ARG;
+  for (int b = 0; b < ctx->cfg.batch; ++b)
+    if (h_base[b] < 0 || h_len[b] < h_base[b] || h_len[b] - h_base[b] > ctx->cfg.window) return PTENC_ERR_INVALID_ARG;
+  const size_t n = sizeof(long long) * ctx->cfg.batch;
+  if (hipMemcpyAsync(ctx->dev.len, h_len, n, hipMemcpyHostToDevice, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
+  if (hipMemcpyAsync(ctx->dev.base, h_base, n, hipMemcpyHostToDevice, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
+  // the host arrays may be pageable and reused by the caller right after return
+  return hip_status(hipStreamSynchronize(S(stream)));
+}
+
+ptenc_status ptenc_get_state(ptenc_ctx* ctx, float* h_S, void* stream) {
+  if (!ctx || !h_S) return PTENC_ERR_INVALID_ARG;
+  const size_t n = sizeof(float) * ctx->cfg.batch * ctx->cfg.n_global * ctx->cfg.rank;
+  if (hipMemcpyAsync(h_S, ctx->dev.S, n, hipMemcpyDeviceToHost, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
+  return hip_status(hipStreamSynchronize(S(stream)));
+}
+
+ptenc_status ptenc_set_state(ptenc_ctx* ctx, const float* h_S, void* stream) {
+  if (!ctx || !h_S) return PTENC_ERR_INVALID_ARG;
+  const size_t n = sizeof(float) * ctx->cfg.batch * ctx->cfg.n_global * ctx->cfg.rank;
+  if (hipMemcpyAsync(ctx->dev.S, h_S, n, hipMemcpyHostToDevice, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
+  return hip_status(hipStreamSynchronize(S(stream)));
+}
+
+ptenc_status ptenc_get_encoder_state(ptenc_ctx* ctx, float* h_Qa, float* h_S0, void* stream) {
+  if (!ctx) return PTENC_ERR_INVALID_ARG;
+  if (!ctx->encoder_set) return PTENC_ERR_STATE;
+  const size_t n = sizeof(float) * ctx->cfg.n_global * ctx->cfg.rank;
+  if (h_Qa && hipMemcpyAsync(h_Qa, ctx->dev.Qa, n, hipMemcpyDeviceToHost, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
+  if (h_S0 && hipMemcpyAsync(h_S0, ctx->dev.S0, n, hipMemcpyDeviceToHost, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
+  return hip_status(hipStreamSynchronize(S(stream)));
+}
+
+ptenc_status ptenc_gather_window(ptenc_ctx* ctx, void* d_K, void* d_V, void* stream) {
+  if (!ctx || !d_K || !d_V) return PTENC_ERR_INVALID_ARG;
+  return hip_status(pt_launch_gather(ctx->dev, d_K, d_V, S(stream)));
+}
+
+ptenc_status ptenc_cache_offset(ptenc_ctx* ctx, int32_t b, int32_t h, int32_t slot, int32_t i, int32_t which,
+                                size_t* elem_offset) {
+  if (!ctx || !elem_offset) return PTENC_ERR_INVALID_ARG;
+  const ptenc_config& c = ctx->cfg;
+  if (b < 0 || b >= c.batch || h < 0 || h >= c.n_kv_heads || slot < 0 || slot >= c.window || i < 0 ||
+      i >= c.head_dim || (which != 0 && which != 1))
+    return PTENC_ERR_INVALID_ARG;
+  const size_t slab = (size_t)(b * c.n_kv_heads + h) * pt_slab_elems(c.window, c.head_dim);
+  *elem_offset = slab + (which == 0 ? pt_k_off(ctx->dev.tiled, c.window, c.head_dim, slot, i)
+                                    : pt_v_off(ctx->dev.tiled, c.window, c.head_dim, slot, i));
+  return PTENC_OK;
+}
+
+ptenc_status ptenc_poll_error(ptenc_ctx* ctx, int32_t* h_flags, void* stream) {
+  if (!ctx || !h_flags) return PTENC_ERR_INVALID_ARG;
+  if (hipMemcpyAsync(h_flags, ctx->dev.err, sizeof(int), hipMemcpyDeviceToHost, S(stream)) != hipSuccess)
+    return PTENC_ERR_HIP;
+  return hip_status(hipStreamSynchronize(S(stream)));
+}
+
+const char* ptenc_status_string(ptenc_status s) {
+  switch (s) {
+    case PTENC_OK: return "ok";
+    case PTENC_ERR_INVALID_ARG: return "invalid argument";
+    case PTENC_ERR_STATE: return "call out of order (encoder not set)";
+    case PTENC_ERR_UNSUPPORTED: return "unsupported configuration";
+    case PTENC_ERR_HIP: return "HIP runtime error";
+    case PTENC_ERR_NOMEM: return "out of host memory";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

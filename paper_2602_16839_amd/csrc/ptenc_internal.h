@@ -1,0 +1,126 @@
+// Internal definitions shared by the host API and the gfx950 kernels of libptenc.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ptenc.h"
+
+// ------------------------------------------------------------------------------------------
+// Device-visible view of a context (passed to kernels by value).
+// ------------------------------------------------------------------------------------------
+struct PtDev {
+  int B, Hq, Hkv, d, W, C, G, r;
+  int group;          // H_q / H_kv
+  int dtype;          // ptenc_dtype
+  int tiled;          // 1: bf16 d=128 MFMA-tiled cache layout, 0: row-major
+  int norm_mode;
+  int n_splits;
+  float norm_eps;
+  float scale_log2;   // softmax scale * log2(e): scores live in the base-2 domain
+  void* cache;
+  float* S;           // [B, G, r]
+  float* Qa;          // [G, r]
+  float* S0;          // [G, r]
+  long long* len;     // [B]
+  long long* base;    // [B]
+  int* err;           // sticky error word
+  float* partial;     // [rows][n_splits][2 + d]: (m, l, unnormalised out) per window split
+  const void* WaK;    // [H_kv*d, r] borrowed
+  const void* WaV;    // [H_kv*d, r] borrowed
+};
+
+struct ptenc_ctx {
+  ptenc_config cfg;
+  PtDev dev;
+  size_t cache_bytes, state_bytes, scratch_bytes;
+  int encoder_set;
+  int opt_splits;        // 0 = heuristic
+  int opt_force_generic;
+  int attn_kernel;       // 0 generic, 1 mfma
+  int encode_kernel;     // 0 generic, 1 mfma
+};
+
+// ------------------------------------------------------------------------------------------
+// Physical cache layout.
+//
+// The cache is an array of slabs, one per (rollout b, KV head h): slab = b * H_kv + h, each of
+// 2 * W * d elements.
+//
+// Row-major layout (fp32, or bf16 shapes the MFMA kernel does not take):
+//   K[slot][i] at slot * d + i,  V[slot][i] at W * d + slot * d + i.
+//
+// Tiled layout (bf16, d = 128, W % 32 == 0): the slab is W/32 groups of 32 consecutive slots;
+// a group is 16 KiB = [K tile 0 | K tile 1 | V], each part ordered so that one 16-byte load
+// per lane of a 64-wide wavefront is both a contiguous 1 KiB read and an MFMA 16x16x32 bf16
+// operand (lane = 16 * kgrp + row holds 8 consecutive contraction elements):
+//   K tile t (slots 16t .. 16t+15 of the group), 2048 elements:
+//       element ((c * 4 + kgrp) * 16 + m) * 8 + e  =  K[slot 16t + m][i = 32c + 8 kgrp + e]
+//   V part, 4096 elements, transposed so that the contraction runs over tokens:
+//       element ((it * 4 + kgrp) * 16 + m) * 8 + e  =  V[slot tl][i = 16 it + m],
+//       tl = (e / 4) * 16 + 4 * kgrp + (e % 4)
+//   (tl's order matches the register order in which the score MFMA leaves the 32 tokens of a
+//    group in each lane, so the probabilities feed the second MFMA without any lane exchange).
+// ------------------------------------------------------------------------------------------
+#define PT_GROUP_TOKENS 32
+#define PT_GROUP_ELEMS 8192      // 32 tokens * 128 * 2 (K and V)
+
+__host__ __device__ inline size_t pt_slab_elems(int W, int d) { return (size_t)2 * W * d; }
+
+__host__ __device__ inline size_t pt_k_off(int tiled, int W, int d, int slot, int i) {
+  if (!tiled) return (size_t)slot * d + i;
+  const int grp = slot >> 5, tl = slot & 31;
+  const int t = tl >> 4, m = tl & 15;
+  const int c = i >> 5, kgrp = (i & 31) >> 3, e = i & 7;
+  return (size_t)grp * PT_GROUP_ELEMS + t * 2048 + (((c * 4 + kgrp) * 16 + m) * 8 + e);
+}
+
+__host__ __device__ inline size_t pt_v_off(int tiled, int W, int d, int slot, int i) {
+  if (!tiled) return (size_t)W * d + (size_t)slot * d + i;
+  const int grp = slot >> 5, tl = slot & 31;
+  const int it = i >> 4, m = i & 15;
+  const int kgrp = (tl & 15) >> 2, e = ((tl >> 4) << 2) | (tl & 3);
+  return (size_t)grp * PT_GROUP_ELEMS + 4096 + (((it * 4 + kgrp) * 16 + m) * 8 + e);
+}
+
+// ------------------------------------------------------------------------------------------
+// bf16 <-> fp32 (round to nearest even; NaN stays NaN)
+// ------------------------------------------------------------------------------------------
+__host__ __device__ inline float pt_bf16_to_f32(uint16_t h) {
+  union { uint32_t u; float f; } x;
+  x.u = (uint32_t)h << 16;
+  return x.f;
+}
+
+__host__ __device__ inline uint16_t pt_f32_to_bf16(float f) {
+  union { uint32_t u; float f; } x;
+  x.f = f;
+  if ((x.u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((x.u >> 16) | 0x40u);
+  const uint32_t lsb = (x.u >> 16) & 1u;
+  x.u += 0x7fffu + lsb;
+  return (uint16_t)(x.u >> 16);
+}
+
+template <typename T> __device__ inline float pt_ld(const T* p);
+template <> __device__ inline float pt_ld<float>(const float* p) { return *p; }
+template <> __device__ inline float pt_ld<uint16_t>(const uint16_t* p) { return pt_bf16_to_f32(*p); }
+
+template <typename T> __device__ inline void pt_st(T* p, float v);
+template <> __device__ inline void pt_st<float>(float* p, float v) { *p = v; }
+template <> __device__ inline void pt_st<uint16_t>(uint16_t* p, float v) { *p = pt_f32_to_bf16(v); }
+
+// ------------------------------------------------------------------------------------------
+// Launchers implemented in the kernel files (host side, return hipError_t).
+// ------------------------------------------------------------------------------------------
+hipError_t pt_launch_reset(const PtDev& c, const uint8_t* mask, bool clear_err, hipStream_t s);
+hipError_t pt_launch_step_prologue(const PtDev& c, bool do_evict, bool do_append, int encode_kernel,
+                                   const void* k, const void* v, const uint8_t* active, void* dbg_chunk,
+                                   hipStream_t s);
+hipError_t pt_launch_gather(const PtDev& c, void* K, void* V, hipStream_t s);
+hipError_t pt_launch_encoder_init(const PtDev& c, const void* qg, const void* WaQ, const void* kg,
+                                  const void* vg, hipStream_t s);
+hipError_t pt_launch_attn_generic(const PtDev& c, const void* q, void* out, const uint8_t* active,
+                                  hipStream_t s);
+hipError_t pt_launch_combine(const PtDev& c, void* out, const uint8_t* active, hipStream_t s);
+hipError_t pt_launch_attn_mfma(const PtDev& c, const void* q, void* out, const uint8_t* active,
+                               hipStream_t s);

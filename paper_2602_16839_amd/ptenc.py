@@ -1,0 +1,326 @@
+"""Thin ctypes binding of libptenc (same names as the C ABI in include/ptenc.h).
+
+Argument marshalling only: torch tensors give device pointers and the current HIP stream;
+every step of the decode path runs in the library's kernels.  There is no CPU fallback: if the
+shared library is missing the import of this module's ``lib()`` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import numpy as np
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libptenc.so")
+
+OK, ERR_INVALID_ARG, ERR_STATE, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM = range(6)
+F32, BF16 = 0, 1
+NORM_FROBENIUS, NORM_ROW_L2, NORM_NONE = 0, 1, 2
+DEVERR_APPEND_FULL, DEVERR_ATTEND_EMPTY = 1, 2
+OPT_SPLITS, OPT_FORCE_GENERIC = 0, 1
+MAX_SPLITS = 32
+
+EXPORTS = [
+    "ptenc_query_sizes", "ptenc_create", "ptenc_destroy", "ptenc_set_option", "ptenc_set_encoder",
+    "ptenc_reset", "ptenc_cache_append", "ptenc_decode_attn", "ptenc_evict_encode", "ptenc_decode_step",
+    "ptenc_decode_run", "ptenc_get_counters", "ptenc_set_counters", "ptenc_get_state", "ptenc_set_state",
+    "ptenc_get_encoder_state", "ptenc_gather_window", "ptenc_cache_offset", "ptenc_poll_error",
+    "ptenc_get_plan", "ptenc_status_string",
+]
+
+
+class Config(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("window", C.c_int32), ("chunk", C.c_int32),
+                ("n_sink", C.c_int32), ("n_global", C.c_int32), ("rank", C.c_int32),
+                ("dtype", C.c_int32), ("norm_mode", C.c_int32), ("norm_eps", C.c_float),
+                ("softmax_scale", C.c_float)]
+
+
+class PtencError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (what, status_string(status), status))
+
+
+_LIB = None
+
+
+def lib() -> C.CDLL:
+    """Loads libptenc.so (built by ``paper_2602_16839_amd.build``); raises if it is not there."""
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                "%s is missing: build it with `python -m paper_2602_16839_amd.build`; there is no fallback path"
+                % LIB_PATH)
+        L = C.CDLL(LIB_PATH)
+        vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+        P = C.POINTER
+        sig = {
+            "ptenc_query_sizes": [P(Config), P(sz), P(sz), P(sz)],
+            "ptenc_create": [P(Config), vp, vp, vp, P(vp)],
+            "ptenc_destroy": [vp],
+            "ptenc_set_option": [vp, i32, i32],
+            "ptenc_set_encoder": [vp, vp, vp, vp, vp, vp, vp, vp],
+            "ptenc_reset": [vp, vp, vp],
+            "ptenc_cache_append": [vp, vp, vp, vp, vp],
+            "ptenc_decode_attn": [vp, vp, vp, vp, vp],
+            "ptenc_evict_encode": [vp, vp, vp, vp],
+            "ptenc_decode_step": [vp, vp, vp, vp, vp, vp, vp],
+            "ptenc_decode_run": [vp, vp, vp, vp, vp, vp, i64, vp],
+            "ptenc_get_counters": [vp, vp, vp, vp],
+            "ptenc_set_counters": [vp, vp, vp, vp],
+            "ptenc_get_state": [vp, vp, vp],
+            "ptenc_set_state": [vp, vp, vp],
+            "ptenc_get_encoder_state": [vp, vp, vp, vp],
+            "ptenc_gather_window": [vp, vp, vp, vp],
+            "ptenc_cache_offset": [vp, i32, i32, i32, i32, i32, P(sz)],
+            "ptenc_poll_error": [vp, P(i32), vp],
+            "ptenc_get_plan": [vp, P(i32), P(i32), P(i32)],
+        }
+        for name, args in sig.items():
+            fn = getattr(L, name)
+            fn.argtypes = args
+            fn.restype = C.c_int
+        L.ptenc_status_string.argtypes = [C.c_int]
+        L.ptenc_status_string.restype = C.c_char_p
+        _LIB = L
+    return _LIB
+
+
+def status_string(status: int) -> str:
+    return lib().ptenc_status_string(status).decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != OK:
+        raise PtencError(status, what)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensor expected"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+# ---- functions with the C ABI's names -------------------------------------------------------
+
+def ptenc_query_sizes(cfg: Config):
+    a, b, c = C.c_size_t(), C.c_size_t(), C.c_size_t()
+    _check(lib().ptenc_query_sizes(C.byref(cfg), C.byref(a), C.byref(b), C.byref(c)), "ptenc_query_sizes")
+    return a.value, b.value, c.value
+
+
+def ptenc_create(cfg: Config, d_cache, d_state, d_scratch):
+    h = C.c_void_p()
+    _check(lib().ptenc_create(C.byref(cfg), _ptr(d_cache), _ptr(d_state), _ptr(d_scratch), C.byref(h)), "ptenc_create")
+    return h
+
+
+def ptenc_destroy(ctx):
+    _check(lib().ptenc_destroy(ctx), "ptenc_destroy")
+
+
+def ptenc_set_option(ctx, option: int, value: int):
+    _check(lib().ptenc_set_option(ctx, option, value), "ptenc_set_option")
+
+
+def ptenc_set_encoder(ctx, q_g, WaQ, WaK, WaV, k_g=None, v_g=None):
+    _check(lib().ptenc_set_encoder(ctx, _ptr(q_g), _ptr(WaQ), _ptr(WaK), _ptr(WaV), _ptr(k_g), _ptr(v_g), _stream()),
+           "ptenc_set_encoder")
+
+
+def ptenc_reset(ctx, mask=None):
+    _check(lib().ptenc_reset(ctx, _ptr(mask), _stream()), "ptenc_reset")
+
+
+def ptenc_cache_append(ctx, k, v, active=None):
+    _check(lib().ptenc_cache_append(ctx, _ptr(k), _ptr(v), _ptr(active), _stream()), "ptenc_cache_append")
+
+
+def ptenc_decode_attn(ctx, q, out, active=None):
+    _check(lib().ptenc_decode_attn(ctx, _ptr(q), _ptr(out), _ptr(active), _stream()), "ptenc_decode_attn")
+
+
+def ptenc_evict_encode(ctx, active=None, dbg_chunk=None):
+    _check(lib().ptenc_evict_encode(ctx, _ptr(active), _ptr(dbg_chunk), _stream()), "ptenc_evict_encode")
+
+
+def ptenc_decode_step(ctx, q, k, v, out, active=None):
+    _check(lib().ptenc_decode_step(ctx, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(active), _stream()),
+           "ptenc_decode_step")
+
+
+def ptenc_decode_run(ctx, q, k, v, out, active, n_steps: int):
+    _check(lib().ptenc_decode_run(ctx, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(active), n_steps, _stream()),
+           "ptenc_decode_run")
+
+
+def ptenc_get_counters(ctx, batch: int):
+    ln = np.zeros(batch, dtype=np.int64)
+    base = np.zeros(batch, dtype=np.int64)
+    _check(lib().ptenc_get_counters(ctx, ln.ctypes.data_as(C.c_void_p), base.ctypes.data_as(C.c_void_p), _stream()),
+           "ptenc_get_counters")
+    return ln, base
+
+
+def ptenc_set_counters(ctx, ln, base):
+    ln = np.ascontiguousarray(ln, dtype=np.int64)
+    base = np.ascontiguousarray(base, dtype=np.int64)
+    _check(lib().ptenc_set_counters(ctx, ln.ctypes.data_as(C.c_void_p), base.ctypes.data_as(C.c_void_p), _stream()),
+           "ptenc_set_counters")
+
+
+def ptenc_get_state(ctx, batch: int, G: int, r: int):
+    S = np.zeros((batch, G, r), dtype=np.float32)
+    _check(lib().ptenc_get_state(ctx, S.ctypes.data_as(C.c_void_p), _stream()), "ptenc_get_state")
+    return S
+
+
+def ptenc_set_state(ctx, S):
+    S = np.ascontiguousarray(S, dtype=np.float32)
+    _check(lib().ptenc_set_state(ctx, S.ctypes.data_as(C.c_void_p), _stream()), "ptenc_set_state")
+
+
+def ptenc_get_encoder_state(ctx, G: int, r: int):
+    Qa = np.zeros((G, r), dtype=np.float32)
+    S0 = np.zeros((G, r), dtype=np.float32)
+    _check(lib().ptenc_get_encoder_state(ctx, Qa.ctypes.data_as(C.c_void_p), S0.ctypes.data_as(C.c_void_p), _stream()),
+           "ptenc_get_encoder_state")
+    return Qa, S0
+
+
+def ptenc_gather_window(ctx, K, V):
+    _check(lib().ptenc_gather_window(ctx, _ptr(K), _ptr(V), _stream()), "ptenc_gather_window")
+
+
+def ptenc_cache_offset(ctx, b: int, h: int, slot: int, i: int, which: int) -> int:
+    off = C.c_size_t()
+    _check(lib().ptenc_cache_offset(ctx, b, h, slot, i, which, C.byref(off)), "ptenc_cache_offset")
+    return off.value
+
+
+def ptenc_poll_error(ctx) -> int:
+    f = C.c_int32()
+    _check(lib().ptenc_poll_error(ctx, C.byref(f), _stream()), "ptenc_poll_error")
+    return f.value
+
+
+def ptenc_get_plan(ctx):
+    a, s, e = C.c_int32(), C.c_int32(), C.c_int32()
+    _check(lib().ptenc_get_plan(ctx, C.byref(a), C.byref(s), C.byref(e)), "ptenc_get_plan")
+    return a.value, s.value, e.value
+
+
+# ---- convenience owner of the device buffers (plumbing only) ---------------------------------
+
+class Layer:
+    """Allocates the cache / state / scratch tensors for one context and forwards to the C ABI."""
+
+    def __init__(self, batch, n_q_heads, n_kv_heads, head_dim, window, chunk, dtype=torch.bfloat16,
+                 n_global=32, rank=32, norm_mode=NORM_FROBENIUS, norm_eps=0.0, softmax_scale=0.0,
+                 device="cuda:0", poison_cache=False):
+        self.cfg = Config(batch, n_q_heads, n_kv_heads, head_dim, window, chunk, 0, n_global, rank,
+                          F32 if dtype == torch.float32 else BF16, norm_mode, norm_eps, softmax_scale)
+        self.dtype, self.device = dtype, torch.device(device)
+        cb, sb, xb = ptenc_query_sizes(self.cfg)
+        self.cache = torch.empty(cb, dtype=torch.uint8, device=self.device)
+        if poison_cache:
+            self.cache.fill_(0xFF)      # every bf16 / fp32 element reads as NaN
+        self.state = torch.zeros(sb, dtype=torch.uint8, device=self.device)
+        self.scratch = torch.empty(xb, dtype=torch.uint8, device=self.device)
+        self.ctx = ptenc_create(self.cfg, self.cache, self.state, self.scratch)
+        self._enc = None
+
+    def close(self):
+        if self.ctx is not None:
+            ptenc_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def B(self):
+        return self.cfg.batch
+
+    def set_encoder(self, q_g, WaQ, WaK, WaV, k_g=None, v_g=None):
+        self._enc = (q_g, WaQ, WaK, WaV, k_g, v_g)       # keep the borrowed tensors alive
+        ptenc_set_encoder(self.ctx, q_g, WaQ, WaK, WaV, k_g, v_g)
+
+    def reset(self, mask=None):
+        ptenc_reset(self.ctx, mask)
+
+    def append(self, k, v, active=None):
+        ptenc_cache_append(self.ctx, k, v, active)
+
+    def attend(self, q, out=None, active=None):
+        if out is None:
+            out = torch.empty_like(q)
+        ptenc_decode_attn(self.ctx, q, out, active)
+        return out
+
+    def evict_encode(self, active=None, dbg_chunk=None):
+        ptenc_evict_encode(self.ctx, active, dbg_chunk)
+
+    def step(self, q, k, v, out=None, active=None):
+        if out is None:
+            out = torch.empty_like(q)
+        ptenc_decode_step(self.ctx, q, k, v, out, active)
+        return out
+
+    def run(self, q, k, v, out=None, active=None):
+        if out is None:
+            out = torch.empty_like(q)
+        ptenc_decode_run(self.ctx, q, k, v, out, active, q.shape[0])
+        return out
+
+    def counters(self):
+        return ptenc_get_counters(self.ctx, self.B)
+
+    def set_counters(self, ln, base):
+        ptenc_set_counters(self.ctx, ln, base)
+
+    def get_state(self):
+        return ptenc_get_state(self.ctx, self.B, self.cfg.n_global, self.cfg.rank)
+
+    def set_state(self, S):
+        ptenc_set_state(self.ctx, S)
+
+    def encoder_state(self):
+        return ptenc_get_encoder_state(self.ctx, self.cfg.n_global, self.cfg.rank)
+
+    def gather_window(self):
+        shape = (self.B, self.cfg.n_kv_heads, self.cfg.window, self.cfg.head_dim)
+        K = torch.empty(shape, dtype=self.dtype, device=self.device)
+        V = torch.empty(shape, dtype=self.dtype, device=self.device)
+        ptenc_gather_window(self.ctx, K, V)
+        return K, V
+
+    def cache_view(self):
+        """The raw cache as a flat tensor of the element dtype (for poisoning tests)."""
+        return self.cache.view(self.dtype)
+
+    def cache_offset(self, b, h, slot, i, which):
+        return ptenc_cache_offset(self.ctx, b, h, slot, i, which)
+
+    def poll_error(self):
+        return ptenc_poll_error(self.ctx)
+
+    def plan(self):
+        return ptenc_get_plan(self.ctx)
+
+    def set_option(self, option, value):
+        ptenc_set_option(self.ctx, option, value)

@@ -1,0 +1,94 @@
+"""Shared plumbing for the GPU parity tests: build the oracle and the HIP layer from one workload
+description, feed both the same seeded inputs, and compare with the stated tolerances."""
+import numpy as np
+import torch
+
+from oracle import pte_oracle as po
+from paper_2602_16839_amd import inputs as I
+
+# bf16 inputs, fp32 accumulation, bf16 outputs: the bar the task states
+BF16_ABS, BF16_REL = 1e-2, 2e-2
+# fp32 end to end (different summation order and exp2 vs exp only)
+F32_ABS, F32_REL = 2e-6, 2e-5
+# the state S is fp32 on the device for either input type
+S_ABS, S_REL = 1e-4, 1e-4
+
+
+def f64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def row_errors(got: np.ndarray, ref: np.ndarray):
+    """(max abs error, max over rows of ||g - r||_inf / max(||r||_inf, 1e-30)); rows = last axis."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    diff = np.abs(got - ref)
+    if diff.size == 0:
+        return 0.0, 0.0
+    row_err = diff.reshape(-1, ref.shape[-1]).max(axis=1)
+    row_ref = np.abs(ref).reshape(-1, ref.shape[-1]).max(axis=1)
+    return float(diff.max()), float((row_err / np.maximum(row_ref, 1e-30)).max())
+
+
+def assert_close(got, ref, abs_tol, rel_tol, what=""):
+    assert np.isfinite(np.asarray(got, dtype=np.float64)).all(), "%s: non-finite output" % what
+    a, r = row_errors(got, ref)
+    assert a <= abs_tol and r <= rel_tol, "%s: max abs %.3e (tol %.1e), max row-rel %.3e (tol %.1e)" % (
+        what, a, abs_tol, r, rel_tol)
+
+
+def tolerances(wl):
+    return (F32_ABS, F32_REL) if wl.dtype == "f32" else (BF16_ABS, BF16_REL)
+
+
+def make_oracle(wl, enc, norm_mode=po.NORM_FROBENIUS, keep_chunks=False, softmax_scale=None):
+    e = {k: f64(v) for k, v in enc.items()}
+    return po.OracleLayer(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
+                          e["q_g"], e["WaQ"], e["WaK"], e["WaV"], e.get("k_g"), e.get("v_g"),
+                          norm_mode=norm_mode, keep_chunks=keep_chunks, softmax_scale=softmax_scale)
+
+
+def make_layer(wl, enc, norm_mode=0, splits=0, force_generic=False, poison=True, softmax_scale=0.0):
+    from paper_2602_16839_amd import ptenc
+    layer = ptenc.Layer(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
+                        dtype=wl.torch_dtype, n_global=wl.n_global, rank=wl.rank, norm_mode=norm_mode,
+                        softmax_scale=softmax_scale, poison_cache=poison)
+    if force_generic:
+        layer.set_option(ptenc.OPT_FORCE_GENERIC, 1)
+    if splits:
+        layer.set_option(ptenc.OPT_SPLITS, splits)
+    dev = {k: v.to("cuda:0") for k, v in enc.items()}
+    layer.set_encoder(dev["q_g"], dev["WaQ"], dev["WaK"], dev["WaV"], dev.get("k_g"), dev.get("v_g"))
+    layer.reset()
+    return layer
+
+
+def run_both(wl, T, norm_mode=0, splits=0, force_generic=False, lengths=None, with_global_kv=True,
+             q_gain=1.0, check_every=1):
+    """Decode T steps on the oracle and on the HIP layer; compare outputs every `check_every` steps,
+    counters every step, and the state at the end.  Returns (layer, oracle)."""
+    enc = I.encoder_params(wl, with_global_kv=with_global_kv)
+    orc = make_oracle(wl, enc, norm_mode=norm_mode)
+    layer = make_layer(wl, enc, norm_mode=norm_mode, splits=splits, force_generic=force_generic)
+    q, k, v = I.qkv_steps(wl, 0, T)
+    if q_gain != 1.0:
+        q = (q.float() * q_gain).to(q.dtype)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    act_all = None
+    if lengths is not None:
+        act_all = np.stack([I.active_mask(lengths, t) for t in range(T)])
+        act_dev = torch.from_numpy(act_all).cuda()
+    abs_tol, rel_tol = tolerances(wl)
+    qn, kn, vn = f64(q), f64(k), f64(v)
+    for t in range(T):
+        act = None if act_all is None else act_all[t]
+        ref = orc.step(qn[t], kn[t], vn[t], act)
+        out = layer.step(qd[t], kd[t], vd[t], active=None if act_all is None else act_dev[t])
+        ln, base = layer.counters()
+        oln, obase = orc.counters()
+        assert np.array_equal(ln, oln) and np.array_equal(base, obase), "counters differ at step %d" % t
+        if t % check_every == 0 or t == T - 1:
+            assert_close(f64(out), ref, abs_tol, rel_tol, "out at step %d" % t)
+    assert_close(layer.get_state(), orc.state(), S_ABS, S_REL, "state S")
+    assert layer.poll_error() == 0
+    return layer, orc

@@ -1,0 +1,119 @@
+"""Host-only checks of the C-ABI library: it loads, exports every symbol the header declares,
+rejects bad configurations, and its documented cache layout is a bijection.  No kernel runs."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2602_16839_amd import ptenc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "ptenc.h")).read()
+    declared = set(re.findall(r"\b(ptenc_[a-z_]+)\s*\(", header))
+    assert declared == set(ptenc.EXPORTS)
+    L = ptenc.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def cfg(**kw):
+    base = dict(batch=2, n_q_heads=4, n_kv_heads=2, head_dim=128, window=64, chunk=16, n_sink=0,
+                n_global=32, rank=32, dtype=ptenc.BF16, norm_mode=0, norm_eps=0.0, softmax_scale=0.0)
+    base.update(kw)
+    return ptenc.Config(**base)
+
+
+def test_query_sizes():
+    cb, sb, xb = ptenc.ptenc_query_sizes(cfg())
+    assert cb == 2 * 2 * 2 * 64 * 128 * 2
+    assert sb % 256 == 0 and sb >= 2 * 32 * 32 * 4 + 2 * 32 * 32 * 4 + 2 * 2 * 8 + 4
+    assert xb >= 2 * 4 * ptenc.MAX_SPLITS * 130 * 4
+    cb32, _, _ = ptenc.ptenc_query_sizes(cfg(dtype=ptenc.F32, head_dim=64))
+    assert cb32 == 2 * 2 * 2 * 64 * 64 * 4
+
+
+@pytest.mark.parametrize("bad,status", [
+    (dict(batch=0), ptenc.ERR_INVALID_ARG),
+    (dict(n_q_heads=5), ptenc.ERR_INVALID_ARG),
+    (dict(chunk=0), ptenc.ERR_INVALID_ARG),
+    (dict(chunk=65), ptenc.ERR_INVALID_ARG),
+    (dict(dtype=7), ptenc.ERR_INVALID_ARG),
+    (dict(norm_mode=3), ptenc.ERR_INVALID_ARG),
+    (dict(softmax_scale=-1.0), ptenc.ERR_INVALID_ARG),
+    (dict(n_sink=4), ptenc.ERR_UNSUPPORTED),
+    (dict(head_dim=512), ptenc.ERR_UNSUPPORTED),
+    (dict(rank=65), ptenc.ERR_UNSUPPORTED),
+    (dict(n_global=128), ptenc.ERR_UNSUPPORTED),
+])
+def test_bad_configs_are_rejected(bad, status):
+    with pytest.raises(ptenc.PtencError) as e:
+        ptenc.ptenc_query_sizes(cfg(**bad))
+    assert e.value.status == status
+
+
+def _host_ctx(c):
+    """A context over fake (never dereferenced) aligned addresses: create touches no device memory."""
+    h = C.c_void_p()
+    st = ptenc.lib().ptenc_create(C.byref(c), C.c_void_p(0x10000), C.c_void_p(0x20000), C.c_void_p(0x30000), C.byref(h))
+    return st, h
+
+
+def test_create_checks_pointers_and_order_of_calls():
+    L = ptenc.lib()
+    h = C.c_void_p()
+    assert L.ptenc_create(C.byref(cfg()), None, C.c_void_p(256), C.c_void_p(256), C.byref(h)) == ptenc.ERR_INVALID_ARG
+    assert L.ptenc_create(C.byref(cfg()), C.c_void_p(0x10010), C.c_void_p(256), C.c_void_p(256), C.byref(h)) == ptenc.ERR_INVALID_ARG
+    st, h = _host_ctx(cfg())
+    assert st == ptenc.OK
+    # nothing may be decoded before the encoder is set
+    assert L.ptenc_reset(h, None, None) == ptenc.ERR_STATE
+    assert L.ptenc_cache_append(h, C.c_void_p(256), C.c_void_p(256), None, None) == ptenc.ERR_STATE
+    assert L.ptenc_decode_attn(h, None, C.c_void_p(256), None, None) == ptenc.ERR_INVALID_ARG
+    assert L.ptenc_set_option(h, ptenc.OPT_SPLITS, ptenc.MAX_SPLITS + 1) == ptenc.ERR_INVALID_ARG
+    assert L.ptenc_set_option(h, 99, 0) == ptenc.ERR_INVALID_ARG
+    assert L.ptenc_set_option(h, ptenc.OPT_SPLITS, 3) == ptenc.OK
+    assert ptenc.ptenc_get_plan(h) == (1, 3, 0)
+    assert L.ptenc_destroy(h) == ptenc.OK
+    assert L.ptenc_destroy(None) == ptenc.ERR_INVALID_ARG
+    assert ptenc.status_string(ptenc.ERR_UNSUPPORTED) == "unsupported configuration"
+
+
+@pytest.mark.parametrize("c", [cfg(), cfg(dtype=ptenc.F32, head_dim=64, window=48, chunk=5),
+                               cfg(window=40)])   # window 40 is not a multiple of 32: row-major bf16
+def test_cache_layout_is_a_bijection(c):
+    st, h = _host_ctx(c)
+    assert st == ptenc.OK
+    seen = set()
+    per_slab = 2 * c.window * c.head_dim
+    for b in (0, c.batch - 1):
+        for hh in range(c.n_kv_heads):
+            for slot in range(c.window):
+                for i in range(c.head_dim):
+                    for which in (0, 1):
+                        off = ptenc.ptenc_cache_offset(h, b, hh, slot, i, which)
+                        slab = b * c.n_kv_heads + hh
+                        assert slab * per_slab <= off < (slab + 1) * per_slab
+                        seen.add(off)
+    assert len(seen) == 2 * c.n_kv_heads * per_slab
+    with pytest.raises(ptenc.PtencError):
+        ptenc.ptenc_cache_offset(h, 0, 0, c.window, 0, 0)
+    ptenc.ptenc_destroy(h)
+
+
+def test_tiled_layout_matches_its_documented_formula():
+    # bf16, d = 128, W % 32 == 0: 16 KiB groups of 32 slots = [K tile 0 | K tile 1 | V^T]
+    c = cfg(window=96)
+    st, h = _host_ctx(c)
+    for slot, i in [(0, 0), (5, 77), (17, 127), (31, 8), (32, 0), (70, 33), (95, 127)]:
+        grp, tl = divmod(slot, 32)
+        t, m = divmod(tl, 16)
+        cc, kg, e = i // 32, (i % 32) // 8, i % 8
+        assert ptenc.ptenc_cache_offset(h, 0, 0, slot, i, 0) == grp * 8192 + t * 2048 + ((cc * 4 + kg) * 16 + m) * 8 + e
+        it, mm = divmod(i, 16)
+        kgv, ev = (tl % 16) // 4, (tl // 16) * 4 + tl % 4
+        assert ptenc.ptenc_cache_offset(h, 0, 0, slot, i, 1) == grp * 8192 + 4096 + ((it * 4 + kgv) * 16 + mm) * 8 + ev
+    ptenc.ptenc_destroy(h)

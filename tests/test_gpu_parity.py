@@ -1,0 +1,250 @@
+"""Parity of the HIP path (through the C ABI) with the CPU fp64 oracle, element by element, on
+seeded inputs small enough for the oracle yet spanning several 32-slot groups, window splits,
+ring wrap-around and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pte_oracle as po
+from oracle.ring_model import RingModel
+from paper_2602_16839_amd import inputs as I
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def small(name, **kw):
+    return I.WORKLOADS[name].replace(**kw)
+
+
+def test_tiny_f32_config_in_full():
+    # the small fp32 configuration, every rollout, every one of the 512 steps
+    wl = I.WORKLOADS["tiny_f32"]
+    layer, orc = H.run_both(wl, wl.steps)
+    ln, base = layer.counters()
+    assert (ln == 512).all() and (base == 256).all()
+    assert layer.plan()[0] == 0
+
+
+@pytest.mark.parametrize("splits", [1, 3])
+def test_bf16_mfma_path_small_window(splits):
+    # 5 groups of 32 slots, chunk 48 wraps and is not group aligned, 7 query heads per KV head
+    wl = small("qwen7b", batch=3, n_q_heads=14, n_kv_heads=2, window=160, chunk=48, steps=420)
+    layer, _ = H.run_both(wl, wl.steps, splits=splits)
+    assert layer.plan()[:2] == (1, splits)
+
+
+def test_bf16_generic_path_small_window():
+    wl = small("qwen3b", batch=2, n_q_heads=8, n_kv_heads=2, window=96, chunk=40, steps=250)
+    layer, _ = H.run_both(wl, wl.steps, force_generic=True, splits=2)
+    assert layer.plan()[0] == 0
+
+
+def test_bf16_row_major_when_window_is_not_a_multiple_of_32():
+    wl = small("qwen3b", batch=2, n_q_heads=4, n_kv_heads=2, window=50, chunk=7, steps=130)
+    layer, _ = H.run_both(wl, wl.steps)
+    assert layer.plan()[0] == 0
+
+
+@pytest.mark.parametrize("W,C", [(32, 32), (64, 1), (128, 128), (96, 32)])
+def test_degenerate_window_and_chunk_sizes(W, C):
+    wl = small("qwen3b", batch=2, n_q_heads=8, n_kv_heads=1, window=W, chunk=C, steps=2 * W + 9)
+    H.run_both(wl, wl.steps, splits=2 if W >= 64 else 1)
+
+
+@pytest.mark.parametrize("hq,hkv", [(16, 1), (4, 4), (32, 8)])
+def test_group_sizes_1_4_16(hq, hkv):
+    wl = small("llama8b", batch=2, n_q_heads=hq, n_kv_heads=hkv, window=64, chunk=16, steps=100)
+    H.run_both(wl, wl.steps)
+
+
+@pytest.mark.parametrize("norm", [po.NORM_FROBENIUS, po.NORM_ROW_L2, po.NORM_NONE])
+def test_norm_modes_and_zero_initialised_state(norm):
+    wl = small("qwen3b", batch=2, n_q_heads=4, n_kv_heads=2, window=64, chunk=32, steps=200,
+               n_global=16, rank=24)
+    H.run_both(wl, wl.steps, norm_mode=norm, with_global_kv=(norm != po.NORM_NONE), check_every=7)
+
+
+def test_peaky_softmax_exercises_the_online_rescale():
+    # queries scaled x64: scores ~ 4 N(0,1), i.e. a range of ~30 base-2 units across the window, so
+    # the running max keeps moving; values stay O(0.25) so that the absolute bar is not spent on
+    # the bf16 rounding of the output itself
+    wl = small("qwen3b", batch=2, n_q_heads=8, n_kv_heads=2, window=128, chunk=32, steps=300, scale=0.25)
+    H.run_both(wl, wl.steps, q_gain=64.0, splits=2)
+
+
+def test_ragged_rollouts_are_masked():
+    wl = small("ragged", batch=6, window=64, chunk=16, steps=200)
+    lengths = np.array([200, 1, 63, 64, 65, 130])
+    layer, orc = H.run_both(wl, wl.steps, lengths=lengths)
+    ln, base = layer.counters()
+    assert ln.tolist() == lengths.tolist()
+
+
+def test_init_state_matches_oracle():
+    for name in ("tiny_f32", "qwen7b"):
+        wl = I.WORKLOADS[name].replace(batch=2)
+        enc = I.encoder_params(wl)
+        layer = H.make_layer(wl, enc)
+        e = {k: H.f64(v) for k, v in enc.items()}
+        Qa_ref, S0_ref = po.init_state(e["q_g"], e["WaQ"], e["WaK"], e["WaV"], e["k_g"], e["v_g"])
+        Qa, S0 = layer.encoder_state()
+        H.assert_close(Qa, Qa_ref, 1e-5, 1e-5, "Q_a")
+        H.assert_close(S0, S0_ref, H.S_ABS, H.S_REL, "S_0")
+        H.assert_close(layer.get_state(), np.stack([S0_ref] * 2), H.S_ABS, H.S_REL, "S after reset")
+
+
+# ------------------------------------------------------------------------------------------------
+# integer / byte work: bit exact
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name,W,C", [("tiny_f32", 24, 5), ("qwen3b", 64, 24), ("qwen3b", 40, 40)])
+def test_ring_contents_and_eviction_order_are_bit_exact(name, W, C):
+    wl = small(name, batch=3, window=W, chunk=C, steps=3 * W + 5)
+    if name != "tiny_f32":
+        wl = wl.replace(n_q_heads=4, n_kv_heads=2)
+    enc = I.encoder_params(wl)
+    layer = H.make_layer(wl, enc)
+    ring = RingModel(wl.batch, W, C)
+    q, k, v = I.qkv_steps(wl, 0, wl.steps)
+    kd, vd = k.cuda(), v.cuda()
+    dkv = wl.d_kv
+    for t in range(wl.steps):
+        dbg = torch.zeros((wl.batch, 2, C, dkv), dtype=wl.torch_dtype, device="cuda")
+        layer.evict_encode(dbg_chunk=dbg)
+        evicted = ring.evict()
+        for b in range(wl.batch):
+            if evicted[b]:
+                p0 = int(ring.base[b]) - C          # positions [p0, p0 + C) just left
+                assert torch.equal(dbg[b, 0].cpu(), k[p0:p0 + C, b].reshape(C, dkv))
+                assert torch.equal(dbg[b, 1].cpu(), v[p0:p0 + C, b].reshape(C, dkv))
+            else:
+                assert not dbg[b].any()
+        layer.append(kd[t], vd[t])
+        ring.append()
+        ln, base = layer.counters()
+        assert np.array_equal(ln, ring.len) and np.array_equal(base, ring.base)
+        if t % 9 == 0 or t == wl.steps - 1:
+            Kw, Vw = layer.gather_window()
+            raw = layer.cache_view().cpu()
+            for b in range(wl.batch):
+                n = int(ring.n_live()[b])
+                p0 = int(ring.base[b])
+                assert torch.equal(Kw[b, :, :n].cpu(), k[p0:p0 + n, b].transpose(0, 1))
+                assert torch.equal(Vw[b, :, :n].cpu(), v[p0:p0 + n, b].transpose(0, 1))
+                assert not Kw[b, :, n:].any() and not Vw[b, :, n:].any()
+                # physical slots: slot s holds position slot_pos[b, s] (documented offset function)
+                for s in (0, W // 2, W - 1):
+                    p = int(ring.slot_pos[b, s])
+                    if p >= 0:
+                        off = layer.cache_offset(b, 1 if wl.n_kv_heads > 1 else 0, s, 3, 0)
+                        assert raw[off] == k[p, b, 1 if wl.n_kv_heads > 1 else 0, 3]
+    assert layer.poll_error() == 0
+
+
+def test_rotation_invariance_of_the_ring():
+    # starting the counters at x shifts every slot by x mod W; outputs, windows and S are bit-identical
+    wl = small("qwen3b", batch=2, n_q_heads=8, n_kv_heads=2, window=96, chunk=32, steps=230)
+    enc = I.encoder_params(wl)
+    q, k, v = (t.cuda() for t in I.qkv_steps(wl, 0, wl.steps))
+    results = []
+    for x in (0, 37, 96 * 1000003 + 95):
+        layer = H.make_layer(wl, enc)
+        layer.set_counters(np.full(2, x), np.full(2, x))
+        out = layer.run(q, k, v)
+        Kw, Vw = layer.gather_window()
+        ln, base = layer.counters()
+        results.append((out.cpu(), Kw.cpu(), Vw.cpu(), layer.get_state(), ln - x, base - x))
+    for r in results[1:]:
+        assert torch.equal(r[1], results[0][1]) and torch.equal(r[2], results[0][2])
+        assert np.array_equal(r[4], results[0][4]) and np.array_equal(r[5], results[0][5])
+        assert np.array_equal(r[3], results[0][3])
+        # attention walks physical groups, so the summation order (not the set of keys) rotates too
+        # (fp32 rounding order, hence now and then another bf16 rounding of the output's last bit)
+        H.assert_close(H.f64(r[0]), H.f64(results[0][0]), 2e-3, 2e-2, "rotated outputs")
+
+
+def test_decode_run_equals_repeated_decode_step():
+    wl = small("qwen7b", batch=2, n_q_heads=14, n_kv_heads=2, window=64, chunk=16, steps=150)
+    enc = I.encoder_params(wl)
+    q, k, v = (t.cuda() for t in I.qkv_steps(wl, 0, wl.steps))
+    a = H.make_layer(wl, enc)
+    out_a = a.run(q, k, v)
+    b = H.make_layer(wl, enc)
+    out_b = torch.stack([b.step(q[t], k[t], v[t]) for t in range(wl.steps)])
+    assert torch.equal(out_a, out_b)
+    assert np.array_equal(a.get_state(), b.get_state())
+    # and equals the three separate entry points
+    c = H.make_layer(wl, enc)
+    outs = []
+    for t in range(wl.steps):
+        c.evict_encode()
+        c.append(k[t], v[t])
+        outs.append(c.attend(q[t]))
+    assert torch.equal(torch.stack(outs), out_a)
+
+
+def test_snapshot_and_resume_is_bit_identical():
+    wl = small("qwen3b", batch=2, n_q_heads=8, n_kv_heads=2, window=64, chunk=16, steps=160)
+    enc = I.encoder_params(wl)
+    q, k, v = (t.cuda() for t in I.qkv_steps(wl, 0, wl.steps))
+    a = H.make_layer(wl, enc)
+    a.run(q[:100], k[:100], v[:100])
+    snap_cache, snap_S, (ln, base) = a.cache.clone(), a.get_state(), a.counters()
+    ref = a.run(q[100:], k[100:], v[100:])
+    b = H.make_layer(wl, enc)
+    b.cache.copy_(snap_cache)
+    b.set_state(snap_S)
+    b.set_counters(ln, base)
+    got = b.run(q[100:], k[100:], v[100:])
+    assert torch.equal(got, ref) and np.array_equal(a.get_state(), b.get_state())
+
+
+def test_device_side_misuse_sets_sticky_error_bits():
+    from paper_2602_16839_amd import ptenc
+    wl = small("qwen3b", batch=2, n_q_heads=4, n_kv_heads=2, window=32, chunk=8, steps=40)
+    enc = I.encoder_params(wl)
+    layer = H.make_layer(wl, enc)
+    q, k, v = (t.cuda() for t in I.qkv_steps(wl, 0, 40))
+    out = layer.attend(q[0])                       # empty window, active rollout
+    assert not out.any()
+    assert layer.poll_error() == ptenc.DEVERR_ATTEND_EMPTY
+    layer.reset()
+    assert layer.poll_error() == 0
+    for t in range(32):
+        layer.append(k[t], v[t])
+    assert layer.poll_error() == 0
+    before = layer.cache.clone()
+    layer.append(k[32], v[32])                     # window full, no eviction requested
+    assert layer.poll_error() == ptenc.DEVERR_APPEND_FULL
+    assert torch.equal(before, layer.cache)
+    ln, base = layer.counters()
+    assert (ln == 32).all() and (base == 0).all()
+    mask = torch.tensor([1, 0], dtype=torch.uint8, device="cuda")
+    layer.reset(mask)                              # partial reset keeps the sticky word
+    assert layer.poll_error() == ptenc.DEVERR_APPEND_FULL
+    ln, base = layer.counters()
+    assert ln.tolist() == [0, 32]
+
+
+def test_nan_poisoned_dead_slots_never_reach_outputs():
+    wl = small("qwen3b", batch=2, n_q_heads=8, n_kv_heads=2, window=96, chunk=40, steps=150)
+    enc = I.encoder_params(wl)
+    orc = H.make_oracle(wl, enc)
+    layer = H.make_layer(wl, enc, splits=2)
+    ring = RingModel(wl.batch, wl.window, wl.chunk)
+    q, k, v = I.qkv_steps(wl, 0, wl.steps)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    raw = layer.cache_view()
+    for t in range(wl.steps):
+        ref = orc.step(H.f64(q[t]), H.f64(k[t]), H.f64(v[t]))
+        layer.evict_encode()
+        layer.append(kd[t], vd[t])
+        ring.step()
+        # poison every dead slot of rollout 0 / head 1 before attending
+        dead = sorted(set(range(wl.window)) - set(ring.live_slots(0).tolist()))
+        for s in dead[:: max(1, len(dead) // 6)]:
+            for which in (0, 1):
+                raw[layer.cache_offset(0, 1, s, 5, which)] = float("nan")
+        out = layer.attend(qd[t])
+        H.assert_close(H.f64(out), ref, H.BF16_ABS, H.BF16_REL, "step %d" % t)
