@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the bounded-cache rollout decode path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload qwen7b] [--splits S]
+
+A step is one pass of the whole hot path (evict-and-encode where a window is full, ring append,
+windowed GQA decode attention) over one batch of B rollouts.  The default workload is the
+Qwen2.5-7B-shaped layer (bf16, 28 query / 4 KV heads, head_dim 128, window 4096, chunk 128,
+128 rollouts) decoded for 8192 steps from an empty cache; inputs are synthetic, seeded, and
+resident in HBM before the timed region starts.
+
+Prints ONE JSON line: whole-job decode tokens/s, the HBM roofline of the attention kernel
+(algorithmic bytes per launch / mean launch time measured with HIP events on the launch
+stream), and the CPU oracle timed on the host cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
+
+
+def n_live_at(t: int, W: int, C: int) -> int:
+    """Live tokens the attention of decode step t (1-based) reads, lazy chunk eviction."""
+    return t if t <= W else W - C + ((t - W - 1) % C) + 1
+
+
+def attention_bytes_per_step(wl, lengths, steps: int):
+    """Algorithmic bytes of the attention launch of every step: K and V stream over the live
+    window plus q in and out out, for every active rollout."""
+    import numpy as np
+    s = wl.elem_bytes
+    per_tok = 2 * wl.d_kv * s
+    qo = 2 * wl.d_q * s
+    out = np.zeros(steps, dtype=np.float64)
+    act = np.zeros(steps, dtype=np.int64)
+    uniq = {}
+    for L in lengths.tolist():
+        uniq[L] = uniq.get(L, 0) + 1
+    nl = np.array([n_live_at(t, wl.window, wl.chunk) for t in range(1, steps + 1)], dtype=np.float64)
+    for L, cnt in uniq.items():
+        n = min(L, steps)
+        out[:n] += cnt * (per_tok * nl[:n] + qo)
+        act[:n] += cnt
+    return out, act
+
+
+def prologue_bytes_total(wl, lengths, steps: int) -> float:
+    """Algorithmic bytes of append (every active step) and of evict-and-encode (chunk re-read plus
+    the read-modify-write of S) over the run."""
+    s = wl.elem_bytes
+    tot = 0.0
+    for L in lengths.tolist():
+        n = min(L, steps)
+        tot += n * 2 * wl.d_kv * s
+        ev = 0 if n <= wl.window else math.ceil((n - wl.window) / wl.chunk)
+        tot += ev * (2 * wl.chunk * wl.d_kv * s + 2 * wl.n_global * wl.rank * 4)
+    return tot
+
+
+def cpu_baseline(wl, budget_s: float = 15.0):
+    """The fp64 oracle, as it stands, on the host: one rollout of the workload's true per-token shape
+    with the window pre-filled to capacity, so the first timed step evicts and encodes a chunk."""
+    import numpy as np
+    import psutil
+    import torch
+
+    from oracle import pte_oracle as po
+    from paper_2602_16839_amd import inputs as I
+
+    one = wl.replace(batch=1)
+    enc = {k: v.to(torch.float64).numpy() for k, v in I.encoder_params(one).items()}
+    orc = po.OracleLayer(1, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
+                         enc["q_g"], enc["WaQ"], enc["WaK"], enc["WaV"], enc["k_g"], enc["v_g"])
+    W = wl.window
+    _, k, v = I.qkv_steps(one, 0, W)
+    k, v = k.to(torch.float64).numpy(), v.to(torch.float64).numpy()
+    for t in range(W):
+        orc.append(0, k[t, 0], v[t, 0])
+    max_steps = 16 * wl.chunk
+    q, k, v = (x.to(torch.float64).numpy() for x in I.qkv_steps(one, W, W + max_steps))
+    proc = psutil.Process()
+    c0 = proc.cpu_times()
+    t0 = time.perf_counter()
+    n = 0
+    while n < max_steps:
+        orc.step(q[n], k[n], v[n])
+        n += 1
+        if time.perf_counter() - t0 > budget_s:
+            break
+    wall = time.perf_counter() - t0
+    c1 = proc.cpu_times()
+    cpu = (c1.user - c0.user) + (c1.system - c0.system)
+    return {
+        "value": n / wall, "unit": "tokens/s", "cores": max(1, int(round(cpu / wall))), "kind": "oracle",
+        "sample": "1 rollout x %d decode steps of the %s shape (H_q %d, H_kv %d, d %d), window pre-filled to "
+                  "W=%d so that step 1 evicts and encodes a %d-token chunk; numpy fp64, %.1f s wall, "
+                  "%d host cores visible" % (n, wl.name, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, W, wl.chunk,
+                                             wall, len(os.sched_getaffinity(0))),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="decode steps to time (0 = the workload's full run)")
+    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--workload", default="qwen7b")
+    ap.add_argument("--splits", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true", help="skip the per-launch HIP-event pass")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this path runs on ONE GPU (rollouts are independent; several GPUs would each take a "
+              "slice of the batch with no exchange). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2602_16839_amd import inputs as I
+    from paper_2602_16839_amd import ptenc
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    wl = I.WORKLOADS[args.workload]
+    K = args.steps if args.steps > 0 else wl.steps
+    Wu = max(0, args.warmup)
+    lengths = I.rollout_lengths(wl)
+    if wl.ragged:
+        K = min(K, int(lengths.max()))
+
+    # ---- synthetic inputs, resident in HBM ----
+    T_gen = max(K, Wu)
+    q = torch.empty((T_gen, wl.batch, wl.n_q_heads, wl.head_dim), dtype=wl.torch_dtype, device=dev)
+    k = torch.empty((T_gen, wl.batch, wl.n_kv_heads, wl.head_dim), dtype=wl.torch_dtype, device=dev)
+    v = torch.empty_like(k)
+    blk = max(1, (1 << 26) // (wl.batch * wl.d_q))
+    for t0 in range(0, T_gen, blk):
+        t1 = min(T_gen, t0 + blk)
+        q[t0:t1], k[t0:t1], v[t0:t1] = I.qkv_steps(wl, t0, t1, device=dev)
+    out = torch.empty_like(q)
+    active = None
+    if wl.ragged:
+        tt = torch.arange(T_gen, device=dev).view(-1, 1)
+        active = (tt < torch.from_numpy(lengths).to(dev).view(1, -1)).to(torch.uint8).contiguous()
+    enc = I.encoder_params(wl, device=dev)
+
+    layer = ptenc.Layer(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
+                        dtype=wl.torch_dtype, n_global=wl.n_global, rank=wl.rank)
+    if args.splits:
+        layer.set_option(ptenc.OPT_SPLITS, args.splits)
+    layer.set_encoder(enc["q_g"], enc["WaQ"], enc["WaK"], enc["WaV"], enc["k_g"], enc["v_g"])
+    attn_kernel, n_splits, _ = layer.plan()
+
+    # ---- warmup, then the timed run from an empty cache ----
+    layer.reset()
+    if Wu:
+        layer.run(q[:Wu], k[:Wu], v[:Wu], out[:Wu], None if active is None else active[:Wu])
+    layer.reset()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    w0 = time.perf_counter()
+    e0.record()
+    layer.run(q[:K], k[:K], v[:K], out[:K], None if active is None else active[:K])
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - w0) * 1e3
+    gpu_ms = e0.elapsed_time(e1)
+    total_ms = max(gpu_ms, wall_ms)
+    assert layer.poll_error() == 0
+    ln, base = layer.counters()
+    assert np.array_equal(ln, np.minimum(lengths, K)), "counters after the run are not the step count"
+
+    abytes, act = attention_bytes_per_step(wl, lengths, K)
+    tokens = int(act.sum())
+    value = tokens / (total_ms * 1e-3)
+    all_bytes = float(abytes.sum()) + prologue_bytes_total(wl, lengths, K)
+
+    # ---- per-launch timing of the attention kernel (second pass over the same steps) ----
+    roofline = None
+    if not args.no_kernel_timing:
+        layer.reset()
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+        for t in range(K):
+            a = None if active is None else active[t]
+            layer.evict_encode(a)
+            layer.append(k[t], v[t], a)
+            evs[t][0].record()
+            layer.attend(q[t], out[t], a)
+            evs[t][1].record()
+        torch.cuda.synchronize()
+        attn_ms = float(sum(a.elapsed_time(b) for a, b in evs))
+        mean_s = attn_ms * 1e-3 / K
+        achieved = float(abytes.mean()) / mean_s / 1e9
+        roofline = {
+            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+            "kernel": "attn_mfma_kernel" if attn_kernel == 1 else "attn_generic_kernel",
+            "launches": K, "mean_launch_us": mean_s * 1e6, "algorithmic_bytes_per_launch": float(abytes.mean()),
+            "includes_combine_kernel": bool(n_splits > 1),
+        }
+
+    res = {
+        "metric": "rollout decode tokens/s per layer (bounded window)",
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wu,
+        "ms_per_step": total_ms / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {
+            "workload": "%s-shaped layer: B %d rollouts, %d Q / %d KV heads, head_dim %d, window %d, chunk %d, "
+                        "%d decode steps from an empty cache%s" % (
+                            wl.name, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk, K,
+                            ", ragged lengths" if wl.ragged else ""),
+            "name": wl.name, "batch": wl.batch, "window": wl.window, "chunk": wl.chunk, "tokens": tokens,
+            "attn_kernel": "mfma" if attn_kernel == 1 else "generic", "window_splits": n_splits,
+            "parallelism": "single GPU",
+        },
+        "gpu_ms": gpu_ms, "wall_ms": wall_ms,
+        "hbm_frac_whole_path": all_bytes / (total_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "algorithmic_gbytes": all_bytes / 1e9,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(res), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
