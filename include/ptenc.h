@@ -70,7 +70,9 @@ enum { PTENC_DEVERR_APPEND_FULL = 1, PTENC_DEVERR_ATTEND_EMPTY = 2 };
 /* Tunables for ptenc_set_option. */
 typedef enum {
   PTENC_OPT_SPLITS = 0,       /* window splits per (rollout, KV head); 1..PTENC_MAX_SPLITS; 0 = heuristic */
-  PTENC_OPT_FORCE_GENERIC = 1 /* 1 = use the plain ALU attention kernel even where the MFMA one applies */
+  PTENC_OPT_FORCE_GENERIC = 1,/* 1 = use the plain ALU attention kernel even where the MFMA one applies */
+  PTENC_OPT_NONTEMPORAL = 2   /* K/V stream with non-temporal loads: 1 / 0; -1 = heuristic (on when the cache
+                                 exceeds the memory-side cache) */
 } ptenc_option;
 
 #define PTENC_MAX_SPLITS 32
@@ -173,6 +175,14 @@ ptenc_status ptenc_poll_error(ptenc_ctx* ctx, int32_t* h_flags, void* stream);
 /* Which kernels this context runs: *attn_kernel = 0 plain ALU, 1 MFMA tiled; *n_splits = window
  * splits in use; *encode_kernel likewise. Any pointer may be NULL. */
 ptenc_status ptenc_get_plan(ptenc_ctx* ctx, int32_t* attn_kernel, int32_t* n_splits, int32_t* encode_kernel);
+
+/* Calibration helpers (no context needed): a plain streaming read of `bytes` (whole 16 KiB units,
+ * a multiple of 16384 is read; d_sink is 4 bytes that are practically never written) and a
+ * plain copy of `bytes` (multiple of 16), each on n_blocks workgroups of 256 threads.  They
+ * measure the HBM rate a kernel with no arithmetic reaches, and scale the profiler's byte
+ * counters.  Pointers are device pointers, 16-byte aligned. */
+ptenc_status ptenc_util_stream_read(const void* d_src, size_t bytes, void* d_sink, int32_t n_blocks, void* stream);
+ptenc_status ptenc_util_copy(void* d_dst, const void* d_src, size_t bytes, int32_t n_blocks, void* stream);
 
 const char* ptenc_status_string(ptenc_status s);
 

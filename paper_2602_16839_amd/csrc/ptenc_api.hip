@@ -50,11 +50,12 @@ bool mfma_attn_applies(const ptenc_config& c) {
          c.n_q_heads / c.n_kv_heads <= 16;
 }
 
-// window splits: enough workgroups to fill 256 CUs twice over, no split shorter than 256 tokens
+// window splits: two workgroups per CU (256 CUs) if the rows alone do not give that; no split
+// shorter than 256 tokens
 int heuristic_splits(const ptenc_ctx* x) {
   const ptenc_config& c = x->cfg;
   const long rows = (long)c.batch * (x->attn_kernel ? c.n_kv_heads : c.n_q_heads);
-  long want = (1024 + rows - 1) / rows;
+  long want = (512 + rows - 1) / rows;
   long cap = c.window / 256;
   if (cap < 1) cap = 1;
   if (want > cap) want = cap;
@@ -67,6 +68,8 @@ void replan(ptenc_ctx* x) {
   x->attn_kernel = (x->dev.tiled && !x->opt_force_generic) ? 1 : 0;
   x->encode_kernel = 0;
   x->dev.n_splits = x->opt_splits > 0 ? x->opt_splits : heuristic_splits(x);
+  // a cache that fits the 256 MiB memory-side cache is better served by ordinary loads
+  x->nontemporal = x->opt_nontemporal >= 0 ? x->opt_nontemporal : (x->cache_bytes > ((size_t)192 << 20) ? 1 : 0);
 }
 
 inline hipStream_t S(void* s) { return (hipStream_t)s; }
@@ -103,6 +106,7 @@ ptenc_status ptenc_create(const ptenc_config* cfg, void* d_cache, void* d_state,
   x->cfg = *cfg;
   if (x->cfg.norm_eps == 0.f) x->cfg.norm_eps = 1e-12f;
   ptenc_query_sizes(cfg, &x->cache_bytes, &x->state_bytes, &x->scratch_bytes);
+  x->opt_nontemporal = -1;
   const StateLayout L = state_layout(*cfg);
   char* sp = (char*)d_state;
   PtDev& d = x->dev;
@@ -137,6 +141,10 @@ ptenc_status ptenc_set_option(ptenc_ctx* ctx, int32_t option, int32_t value) {
     case PTENC_OPT_SPLITS:
       if (value < 0 || value > PTENC_MAX_SPLITS) return PTENC_ERR_INVALID_ARG;
       ctx->opt_splits = value;
+      break;
+    case PTENC_OPT_NONTEMPORAL:
+      if (value < -1 || value > 1) return PTENC_ERR_INVALID_ARG;
+      ctx->opt_nontemporal = value;
       break;
     case PTENC_OPT_FORCE_GENERIC:
       if (value != 0 && value != 1) return PTENC_ERR_INVALID_ARG;
@@ -197,7 +205,7 @@ ptenc_status ptenc_decode_attn(ptenc_ctx* ctx, const void* d_q, void* d_out, con
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_q | (uintptr_t)d_out) & 15) return PTENC_ERR_INVALID_ARG;
-    return hip_status(pt_launch_attn_mfma(ctx->dev, d_q, d_out, d_active, S(stream)));
+    return hip_status(pt_launch_attn_mfma(ctx->dev, ctx->nontemporal != 0, d_q, d_out, d_active, S(stream)));
   }
   return hip_status(pt_launch_attn_generic(ctx->dev, d_q, d_out, d_active, S(stream)));
 }

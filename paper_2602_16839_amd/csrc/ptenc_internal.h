@@ -37,6 +37,8 @@ struct ptenc_ctx {
   int encoder_set;
   int opt_splits;        // 0 = heuristic
   int opt_force_generic;
+  int opt_nontemporal;   // -1 = heuristic, 0, 1
+  int nontemporal;       // resolved
   int attn_kernel;       // 0 generic, 1 mfma
   int encode_kernel;     // 0 generic, 1 mfma
 };
@@ -122,5 +124,5 @@ hipError_t pt_launch_encoder_init(const PtDev& c, const void* qg, const void* Wa
 hipError_t pt_launch_attn_generic(const PtDev& c, const void* q, void* out, const uint8_t* active,
                                   hipStream_t s);
 hipError_t pt_launch_combine(const PtDev& c, void* out, const uint8_t* active, hipStream_t s);
-hipError_t pt_launch_attn_mfma(const PtDev& c, const void* q, void* out, const uint8_t* active,
+hipError_t pt_launch_attn_mfma(const PtDev& c, bool nontemporal, const void* q, void* out, const uint8_t* active,
                                hipStream_t s);

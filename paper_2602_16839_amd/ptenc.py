@@ -20,7 +20,7 @@ OK, ERR_INVALID_ARG, ERR_STATE, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM = range(6)
 F32, BF16 = 0, 1
 NORM_FROBENIUS, NORM_ROW_L2, NORM_NONE = 0, 1, 2
 DEVERR_APPEND_FULL, DEVERR_ATTEND_EMPTY = 1, 2
-OPT_SPLITS, OPT_FORCE_GENERIC = 0, 1
+OPT_SPLITS, OPT_FORCE_GENERIC, OPT_NONTEMPORAL = 0, 1, 2
 MAX_SPLITS = 32
 
 EXPORTS = [
@@ -28,7 +28,7 @@ EXPORTS = [
     "ptenc_reset", "ptenc_cache_append", "ptenc_decode_attn", "ptenc_evict_encode", "ptenc_decode_step",
     "ptenc_decode_run", "ptenc_get_counters", "ptenc_set_counters", "ptenc_get_state", "ptenc_set_state",
     "ptenc_get_encoder_state", "ptenc_gather_window", "ptenc_cache_offset", "ptenc_poll_error",
-    "ptenc_get_plan", "ptenc_status_string",
+    "ptenc_get_plan", "ptenc_status_string", "ptenc_util_stream_read", "ptenc_util_copy",
 ]
 
 
@@ -81,6 +81,8 @@ def lib() -> C.CDLL:
             "ptenc_cache_offset": [vp, i32, i32, i32, i32, i32, P(sz)],
             "ptenc_poll_error": [vp, P(i32), vp],
             "ptenc_get_plan": [vp, P(i32), P(i32), P(i32)],
+            "ptenc_util_stream_read": [vp, sz, vp, i32, vp],
+            "ptenc_util_copy": [vp, vp, sz, i32, vp],
         }
         for name, args in sig.items():
             fn = getattr(L, name)
@@ -219,6 +221,14 @@ def ptenc_get_plan(ctx):
     a, s, e = C.c_int32(), C.c_int32(), C.c_int32()
     _check(lib().ptenc_get_plan(ctx, C.byref(a), C.byref(s), C.byref(e)), "ptenc_get_plan")
     return a.value, s.value, e.value
+
+
+def ptenc_util_stream_read(src, nbytes: int, sink, n_blocks: int):
+    _check(lib().ptenc_util_stream_read(_ptr(src), nbytes, _ptr(sink), n_blocks, _stream()), "ptenc_util_stream_read")
+
+
+def ptenc_util_copy(dst, src, nbytes: int, n_blocks: int):
+    _check(lib().ptenc_util_copy(_ptr(dst), _ptr(src), nbytes, n_blocks, _stream()), "ptenc_util_copy")
 
 
 # ---- convenience owner of the device buffers (plumbing only) ---------------------------------
