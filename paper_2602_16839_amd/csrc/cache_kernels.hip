@@ -8,14 +8,14 @@
 // The encoder here is the general one (any dtype, layout, G and r up to 64).  It evaluates
 // S' = (Q_a (K_e W^a_K)^T)(V_e W^a_V) (Our Approach, the Delta-W equation) in the paper's
 // association, 32 tokens at a time, with fp32 accumulation.
-#include "ptenc_internal.h"
+#include "pt_encode_tail.h"
 
 namespace {
 
-constexpr int kThreads = 256;
-constexpr int kSub = 32;   // tokens per sub-chunk
-constexpr int kKB = 64;    // contraction block over d_kv
-constexpr int kMaxGR = 64; // max G and r
+constexpr int kThreads = kEncThreads;
+constexpr int kSub = kEncSub;     // tokens per sub-chunk
+constexpr int kKB = 64;           // contraction block over d_kv
+constexpr int kMaxGR = kEncMaxGR; // max G and r
 
 // ---- token sources ---------------------------------------------------------------------------
 template <typename T>
@@ -41,10 +41,7 @@ struct GlobalTokens { // k_g, v_g: row-major [G, d_kv]
 struct EncSmem {
   float Ks[kSub][kKB + 1];
   float Ws[kKB][kMaxGR];       // reused as the G x r staging area of the state update
-  float Ka[kSub][kMaxGR + 1];
-  float Va[kSub][kMaxGR + 1];
-  float P[kMaxGR][kSub + 1];
-  float red[kThreads / 64 + 1];
+  EncTailSmem tail;
 };
 
 // S' of a chunk of n_tok tokens; thread t ends up with entries t, t+256, ... of the row-major
@@ -94,44 +91,12 @@ __device__ void encode_chunk(EncSmem& sm, const Src& src, int n_tok, int dkv, in
 #pragma unroll
       for (int x = 0; x < 8; ++x) {
         const int col = cg + 8 * x;
-        if (col < r) (which == 0 ? sm.Ka : sm.Va)[tok][col] = acc[x];
+        if (col < r) (which == 0 ? sm.tail.Ka : sm.tail.Va)[tok][col] = acc[x];
       }
     }
     __syncthreads();
-    // P = Q_a K_a^T  (G x 32)
-    for (int idx = t; idx < G * kSub; idx += kThreads) {
-      const int g = idx / kSub, tk = idx - g * kSub;
-      float p = 0.f;
-      if (tk < ntok)
-        for (int a = 0; a < r; ++a) p = fmaf(Qa[g * r + a], sm.Ka[tk][a], p);
-      sm.P[g][tk] = p;
-    }
-    __syncthreads();
-    // S' += P V_a  (G x r)
-#pragma unroll
-    for (int x = 0; x < 16; ++x) {
-      const int idx = t + kThreads * x;
-      if (idx < G * r) {
-        const int g = idx / r, col = idx - g * r;
-        float s = sacc[x];
-        for (int tk = 0; tk < ntok; ++tk) s = fmaf(sm.P[g][tk], sm.Va[tk][col], s);
-        sacc[x] = s;
-      }
-    }
-    __syncthreads();
+    pt_encode_accumulate(sm.tail, Qa, G, r, ntok, sacc);
   }
-}
-
-__device__ float block_sum(float v, float* red) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  const int w = threadIdx.x >> 6;
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) red[w] = v;
-  __syncthreads();
-  float tot = 0.f;
-  for (int i = 0; i < kThreads / 64; ++i) tot += red[i];
-  return tot;
 }
 
 // ---- step prologue ----------------------------------------------------------------------------
@@ -143,82 +108,50 @@ __global__ __launch_bounds__(kThreads) void step_prologue_kernel(PtDev c, int do
                                                                 T* dbg_chunk) {
   __shared__ EncSmem sm;
   const int b = blockIdx.x, t = threadIdx.x;
-  if (active && !active[b]) return;
   const long long len = c.len[b];
   long long base = c.base[b];
+  long long len1 = len;
   const int dkv = c.Hkv * c.d;
   T* cache = (T*)c.cache;
+  const bool act = !active || active[b];
 
-  if (do_evict && len - base == c.W) {
+  if (act && do_evict && len - base == c.W) {
     CacheChunk<T> src{cache, b, c.Hkv, c.d, c.W, c.tiled, (int)(base % c.W)};
     float sacc[16];
     T* dbg = dbg_chunk ? dbg_chunk + (size_t)b * 2 * c.C * dkv : nullptr;
     encode_chunk<T>(sm, src, c.C, dkv, c.G, c.r, c.Qa, (const T*)c.WaK, (const T*)c.WaV, dbg, sacc);
     // S <- Normalize(S + S')   (Our Approach, the update rule)
-    float* S = c.S + (size_t)b * c.G * c.r;
-    float* stage = &sm.Ws[0][0];
-    float ss = 0.f;
-#pragma unroll
-    for (int x = 0; x < 16; ++x) {
-      const int idx = t + kThreads * x;
-      if (idx < c.G * c.r) {
-        sacc[x] += S[idx];
-        ss = fmaf(sacc[x], sacc[x], ss);
-        stage[idx] = sacc[x];
-      }
-    }
-    if (c.norm_mode == PTENC_NORM_FROBENIUS) {
-      const float nrm = fmaxf(sqrtf(block_sum(ss, sm.red)), c.norm_eps);
-#pragma unroll
-      for (int x = 0; x < 16; ++x) {
-        const int idx = t + kThreads * x;
-        if (idx < c.G * c.r) S[idx] = sacc[x] / nrm;
-      }
-    } else if (c.norm_mode == PTENC_NORM_ROW_L2) {
-      __syncthreads();
-#pragma unroll
-      for (int x = 0; x < 16; ++x) {
-        const int idx = t + kThreads * x;
-        if (idx < c.G * c.r) {
-          const int g = idx / c.r;
-          float rs = 0.f;
-          for (int a = 0; a < c.r; ++a) rs = fmaf(stage[g * c.r + a], stage[g * c.r + a], rs);
-          S[idx] = sacc[x] / fmaxf(sqrtf(rs), c.norm_eps);
-        }
-      }
-    } else {
-#pragma unroll
-      for (int x = 0; x < 16; ++x) {
-        const int idx = t + kThreads * x;
-        if (idx < c.G * c.r) S[idx] = sacc[x];
-      }
-    }
+    pt_state_update(c, b, sacc, &sm.Ws[0][0], sm.tail.red);
     base += c.C;
     __syncthreads();   // every read of the evicted slots is done before the append below
-    if (t == 0) c.base[b] = base;
   }
 
-  if (do_append) {
+  if (act && do_append) {
     if (len - base >= c.W) {
       if (t == 0) atomicOr(c.err, PTENC_DEVERR_APPEND_FULL);
-      return;
+    } else {
+      const int slot = (int)(len % c.W);
+      for (int idx = t; idx < dkv; idx += kThreads) {
+        const int h = idx / c.d, i = idx - h * c.d;
+        T* slab = cache + (size_t)(b * c.Hkv + h) * pt_slab_elems(c.W, c.d);
+        const size_t src = (size_t)b * dkv + idx;
+        slab[pt_k_off(c.tiled, c.W, c.d, slot, i)] = knew[src];
+        slab[pt_v_off(c.tiled, c.W, c.d, slot, i)] = vnew[src];
+      }
+      len1 = len + 1;
     }
-    const int slot = (int)(len % c.W);
-    for (int idx = t; idx < dkv; idx += kThreads) {
-      const int h = idx / c.d, i = idx - h * c.d;
-      T* slab = cache + (size_t)(b * c.Hkv + h) * pt_slab_elems(c.W, c.d);
-      const size_t src = (size_t)b * dkv + idx;
-      slab[pt_k_off(c.tiled, c.W, c.d, slot, i)] = knew[src];
-      slab[pt_v_off(c.tiled, c.W, c.d, slot, i)] = vnew[src];
-    }
-    if (t == 0) c.len[b] = len + 1;
   }
+  // counters go to the other buffer, for every rollout, changed or not
+  if (t == 0) { c.len_nx[b] = len1; c.base_nx[b] = base; }
 }
 
 // ---- reset / gather -----------------------------------------------------------------------------
 __global__ void reset_kernel(PtDev c, const uint8_t* __restrict__ mask, int clear_err) {
   const int b = blockIdx.x;
   if (clear_err && b == 0 && threadIdx.x == 0) *c.err = 0;
+  // arrival counters are zero between kernels anyway; a fresh context gets them zeroed here
+  if (threadIdx.x == 0) c.tick_rollout[b] = 0;
+  for (int h = threadIdx.x; h < c.Hkv; h += blockDim.x) c.tick_slab[b * c.Hkv + h] = 0;
   if (mask && !mask[b]) return;
   const int n = c.G * c.r;
   for (int i = threadIdx.x; i < n; i += blockDim.x) c.S[(size_t)b * n + i] = c.S0[i];

@@ -1,0 +1,549 @@
+// The bf16 / head_dim 128 decode step on the MFMA-tiled cache layout, as ONE kernel:
+//   [evict the oldest chunk of a full window and fold it into S]  (Our Approach, Delta-W equation,
+//                                                                  update rule)
+//   [append the new k, v]                                         (Notation and Preliminaries,
+//   [attend over the live window]                                  decode-stage / attention equations)
+// Each part can be switched off, so the same kernel also serves the three separate entry points.
+//
+// Work decomposition: one workgroup of 4 wavefronts per (rollout, KV head, window split).
+//
+// Attention.  A wavefront walks 32-slot groups of the ring (16 KiB each, contiguous in HBM).
+// Softmax does not care about the order of the keys, so the walk is in physical slot order
+// starting at the group that holds the oldest live token; only the first and last group of the
+// live range need a mask.  All H_q/H_kv query heads of the KV head ride in the N dimension of
+// the MFMA (padded to 16), so every K/V byte is fetched from HBM once per step and shared by
+// the whole query group in registers.  Per group and wavefront:
+//   S^T[token, query]  = K_tile (16 x 32k) * Q^T (32k x 16), 4 k-chunks, two 16-token tiles
+//   online softmax in the base-2 domain; lane (query = lane % 16) owns its query's statistics,
+//       the max is exchanged between the 4 lane groups with two xor-shuffles per group
+//   O^T[dcol, query]  += V^T_tile (16 dcols x 32 tokens) * P^T (32 tokens x 16 queries), 8 tiles
+// The V part of a group is stored token-minor in exactly the order the first MFMA leaves the
+// probabilities in each lane, so P goes from accumulator to operand with a bf16 pack only.
+// Window splits are merged by whichever workgroup of the (rollout, KV head) finishes last
+// (a counter, no waiting), in split order, so the result does not depend on the arrival order.
+//
+// Eviction.  The encoder sums over the concatenated KV heads, so the workgroup of KV head h
+// (last split) computes only its head's share of K_a = K_e W^a_K and V_a = V_e W^a_V with MFMA
+// and parks it in scratch; whichever workgroup of the rollout finishes last adds the shares in
+// head order, forms S' = (Q_a K_a^T) V_a and updates S.  The head's share is read before the same
+// workgroup overwrites the oldest slot with the new token, and the attention of this step
+// already runs on the window without the evicted chunk.
+//
+// Counters are double-buffered: a step reads (len, base) from one pair of arrays and writes the
+// other, so no workgroup has to wait for the rest of its rollout before the step can end.
+#include "pt_encode_tail.h"
+
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+union Op {   // one MFMA operand = 16 bytes per lane
+  u32x4 u;
+  bf16x8 h;
+  uint16_t s[8];
+};
+
+struct Frag {   // one 32-token group in registers: 64 VGPRs
+  Op k0[4], k1[4], v[8];
+};
+
+constexpr int kWaves = 4;
+constexpr int kORow = 132;   // padded fp32 row of the cross-wave merge buffer
+
+// NT = non-temporal loads: the stream is read once per step, so it should not displace anything
+// in L2 / the memory-side cache; on MI355X a plain read-only stream gains ~15 % from it.
+template <bool NT>
+__device__ inline u32x4 ld16(const u32x4* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+
+template <bool NT>
+__device__ inline void load_group(Frag& f, const u32x4* __restrict__ grp, int lane) {
+#pragma unroll
+  for (int c = 0; c < 4; ++c) f.k0[c].u = ld16<NT>(grp + c * 64 + lane);
+#pragma unroll
+  for (int c = 0; c < 4; ++c) f.k1[c].u = ld16<NT>(grp + 256 + c * 64 + lane);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) f.v[i].u = ld16<NT>(grp + 512 + i * 64 + lane);
+}
+
+struct Acc {
+  f32x4 o[8];      // O^T: tile it, reg e -> dcol 16 it + 4 kgrp + e, query = lane % 16
+  float m, l;      // running max (base-2 domain) and this lane's share of the running sum
+};
+
+__device__ inline void process_group(Frag& f, const Op q[4], Acc& a, int visit, int off0, int n_live,
+                                     float scale_log2, int kgrp) {
+  f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.k0[c].h, q[c].h, s0, 0, 0, 0);
+    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.k1[c].h, q[c].h, s1, 0, 0, 0);
+  }
+  // logical index of the group's first slot relative to the oldest live token
+  const int jg = visit * PT_GROUP_TOKENS - off0;
+  const bool interior = jg >= 0 && jg + PT_GROUP_TOKENS <= n_live;   // wave-uniform
+  float s[8];
+  if (interior) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { s[e] = s0[e] * scale_log2; s[4 + e] = s1[e] * scale_log2; }
+  } else {
+    // edge group: dead slots may hold anything (stale tokens, never-written memory):
+    // their scores become -inf and their value columns are zeroed before the second MFMA
+    const int jl = jg + 4 * kgrp;
+    uint32_t live = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const bool l0 = (unsigned)(jl + e) < (unsigned)n_live;
+      const bool l1 = (unsigned)(jl + 16 + e) < (unsigned)n_live;
+      s[e] = l0 ? s0[e] * scale_log2 : -INFINITY;
+      s[4 + e] = l1 ? s1[e] * scale_log2 : -INFINITY;
+      live |= (l0 ? 1u : 0u) << e | (l1 ? 1u : 0u) << (4 + e);
+    }
+    // V operand element e of this lane belongs to token (e/4)*16 + 4*kgrp + e%4: same bit order
+    const uint32_t m01 = ((live & 1u) ? 0x0000ffffu : 0u) | ((live & 2u) ? 0xffff0000u : 0u);
+    const uint32_t m23 = ((live & 4u) ? 0x0000ffffu : 0u) | ((live & 8u) ? 0xffff0000u : 0u);
+    const uint32_t m45 = ((live & 16u) ? 0x0000ffffu : 0u) | ((live & 32u) ? 0xffff0000u : 0u);
+    const uint32_t m67 = ((live & 64u) ? 0x0000ffffu : 0u) | ((live & 128u) ? 0xffff0000u : 0u);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      f.v[i].u[0] &= m01; f.v[i].u[1] &= m23; f.v[i].u[2] &= m45; f.v[i].u[3] &= m67;
+    }
+  }
+  float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+  mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  const float m_new = fmaxf(a.m, mx);
+  const float m_use = m_new == -INFINITY ? 0.f : m_new;   // nothing live yet: keep exp2 away from inf - inf
+  const float alpha = __builtin_amdgcn_exp2f(a.m - m_use);
+  float p[8], psum = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { p[e] = __builtin_amdgcn_exp2f(s[e] - m_use); psum += p[e]; }
+  a.l = a.l * alpha + psum;
+  a.m = m_new;
+  if (__any(alpha != 1.f)) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) a.o[i] *= alpha;
+  }
+  Op pf;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) pf.h[e] = (__bf16)p[e];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a.o[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.v[i].h, pf.h, a.o[i], 0, 0, 0);
+}
+
+// kp[c] = this lane's 16 bytes of the new key (k-chunk c), vp[i] = new value column 16 i + (lane % 16).
+__device__ inline void load_newest(Op kp[4], uint16_t vp[8], const uint16_t* __restrict__ knew,
+                                   const uint16_t* __restrict__ vnew, size_t src, int n, int kgrp) {
+#pragma unroll
+  for (int cc = 0; cc < 4; ++cc) kp[cc].u = *(const u32x4*)(knew + src + (cc * 4 + kgrp) * 8);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) vp[i] = vnew[src + 16 * i + n];
+}
+
+// One wavefront writes the new token into its ring slot: 16 key pieces of 16 bytes, 128 value elements.
+__device__ inline void store_newest(uint16_t* __restrict__ dst, int W, int slot, const Op kp[4], const uint16_t vp[8],
+                                    int n, int kgrp) {
+  if (n == 0) {
+#pragma unroll
+    for (int cc = 0; cc < 4; ++cc) *(u32x4*)(dst + pt_k_off(1, W, 128, slot, (cc * 4 + kgrp) * 8)) = kp[cc].u;
+  }
+  if (kgrp == 0) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) dst[pt_v_off(1, W, 128, slot, 16 * i + n)] = vp[i];
+  }
+}
+
+// The newest token is stored to the cache and, for this step's attention, written straight into
+// the registers of the wavefront that walks the last group: no wait for the store to land.
+__device__ inline void patch_newest(Frag& f, const Op kp[4], const uint16_t vp[8], int tl, int n, int kgrp) {
+  const int t = tl >> 4, m = tl & 15;
+  if (n == m) {
+    if (t == 0) {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) f.k0[c].u = kp[c].u;
+    } else {
+#pragma unroll
+      for (int c = 0; c < 4; ++c) f.k1[c].u = kp[c].u;
+    }
+  }
+  const int vkg = (tl & 15) >> 2, ve = ((tl >> 4) << 2) | (tl & 3);
+  if (kgrp == vkg) {
+    const int w = ve >> 1;
+    const uint32_t sh = (uint32_t)(ve & 1) * 16u, keep = ~(0xffffu << sh);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t val = (uint32_t)vp[i] << sh;
+#pragma unroll
+      for (int ww = 0; ww < 4; ++ww)
+        if (ww == w) f.v[i].u[ww] = (f.v[i].u[ww] & keep) | val;
+    }
+  }
+}
+
+// Data handed from one workgroup to another inside this kernel (split partials, the heads' encoder
+// shares) is written and read with device-scope relaxed atomics: such stores write through and
+// such loads bypass the per-CU and per-XCD caches, so the hand-over needs no cache write-back or
+// invalidation.  Order is given by: stores, wait for them (workgroup fence), barrier, ticket.
+__device__ inline float ld_agent(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void st_agent(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+struct StepArgs {
+  const uint16_t* q;       // [B, H_q, 128]
+  uint16_t* out;           // [B, H_q, 128]
+  const uint16_t* knew;    // [B, H_kv, 128]
+  const uint16_t* vnew;
+  const uint8_t* active;   // [B] or null
+  uint16_t* dbg_chunk;     // [B, 2, C, H_kv*128] or null
+  int do_evict, do_append, do_attend;
+};
+
+union StepSmem {
+  struct {
+    float o[kWaves][16][kORow];
+    float m[kWaves][16], l[kWaves][16];
+  } merge;
+  uint16_t vstage[kWaves][4096];   // one group's V part per wavefront (encoder operand transposition)
+  EncTailSmem enc;   // Ka and Va (contiguous, >= G*r floats) double as the row-norm staging area
+};
+
+// This head's share of K_a and V_a for the chunk [base, base + C): rows j = logical token, RP columns.
+__device__ inline void encode_head_share(const PtDev& c, StepSmem& sm, const u32x4* __restrict__ slab_p, int slab,
+                                         int hkv, int s0, int lane, int wave) {
+  const int n = lane & 15, kgrp = lane >> 4;
+  const int g0 = s0 >> 5, off0 = s0 & 31, NG = c.W >> 5;
+  const int n_vis = (off0 + c.C + PT_GROUP_TOKENS - 1) >> 5;
+  const int RP = c.n_rt * 16;
+  float* partK = c.enc_part + (size_t)slab * 2 * c.C * RP;
+  float* partV = partK + (size_t)c.C * RP;
+  const u32x4* WKp = (const u32x4*)c.WKp + (size_t)hkv * 4 * 4 * 64;
+  const u32x4* WVp = (const u32x4*)c.WVp + (size_t)hkv * 4 * 4 * 64;
+  uint16_t* vs = sm.vstage[wave];
+  for (int vis = wave; vis < n_vis; vis += kWaves) {
+    int pg = g0 + vis;
+    if (pg >= NG) pg -= NG;
+    if (pg >= NG) pg -= NG;
+    const u32x4* grp = slab_p + (size_t)pg * (PT_GROUP_ELEMS / 8);
+    // V part -> LDS as stored (the operand needs 8 consecutive columns of one token, which the
+    // token-minor layout scatters)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ((u32x4*)vs)[i * 64 + lane] = grp[512 + i * 64 + lane];
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      Op ka[4], va[4];
+      const int tl = t * 16 + n;                       // this lane's token within the group (A-operand row)
+      const int vkg = (tl & 15) >> 2, ve = ((tl >> 4) << 2) | (tl & 3);
+#pragma unroll
+      for (int cc = 0; cc < 4; ++cc) {
+        ka[cc].u = grp[t * 256 + cc * 64 + lane];
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+          const int i = cc * 32 + 8 * kgrp + x;        // value column
+          va[cc].s[x] = vs[(((i >> 4) * 4 + vkg) * 16 + (i & 15)) * 8 + ve];
+        }
+      }
+      for (int rt = 0; rt < c.n_rt; ++rt) {
+        f32x4 dk = {0.f, 0.f, 0.f, 0.f}, dv = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) {
+          Op wk, wv;
+          wk.u = WKp[(cc * 4 + rt) * 64 + lane];
+          wv.u = WVp[(cc * 4 + rt) * 64 + lane];
+          dk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[cc].h, wk.h, dk, 0, 0, 0);
+          dv = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[cc].h, wv.h, dv, 0, 0, 0);
+        }
+        // D[token 4 kgrp + e][column n] -> rows by logical token index
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int j = vis * PT_GROUP_TOKENS + t * 16 + 4 * kgrp + e - off0;
+          if ((unsigned)j < (unsigned)c.C) {
+            st_agent(partK + (size_t)j * RP + rt * 16 + n, dk[e]);
+            st_agent(partV + (size_t)j * RP + rt * 16 + n, dv[e]);
+          }
+        }
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
+// Last workgroup of a rollout: K_a, V_a = sum of the heads' shares (head order), S' = (Q_a K_a^T) V_a,
+// S <- Normalize(S + S').
+__device__ inline void encode_finish(const PtDev& c, StepSmem& sm, int b) {
+  const int t = threadIdx.x;
+  const int RP = c.n_rt * 16;
+  float sacc[16];
+#pragma unroll
+  for (int x = 0; x < 16; ++x) sacc[x] = 0.f;
+  const float* part0 = c.enc_part + (size_t)b * c.Hkv * 2 * c.C * RP;
+  for (int sub0 = 0; sub0 < c.C; sub0 += kEncSub) {
+    const int ntok = min(kEncSub, c.C - sub0);
+    for (int idx = t; idx < 2 * kEncSub * RP; idx += kEncThreads) {
+      const int which = idx / (kEncSub * RP), rem = idx - which * (kEncSub * RP);
+      const int tk = rem / RP, col = rem - tk * RP;
+      float v = 0.f;
+      if (tk < ntok)
+        for (int h = 0; h < c.Hkv; ++h)
+          v += ld_agent(part0 + ((size_t)(h * 2 + which) * c.C + sub0 + tk) * RP + col);
+      (which == 0 ? sm.enc.Ka : sm.enc.Va)[tk][col] = v;
+    }
+    __syncthreads();
+    pt_encode_accumulate(sm.enc, c.Qa, c.G, c.r, ntok, sacc);
+  }
+  pt_state_update(c, b, sacc, &sm.enc.Ka[0][0], sm.enc.red);
+}
+
+template <bool NT>
+__global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(PtDev c, StepArgs a) {
+  __shared__ StepSmem sm;
+  __shared__ int sm_ticket;
+
+  const int slab = blockIdx.x, split = blockIdx.y;
+  const int b = slab / c.Hkv, hkv = slab - b * c.Hkv;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n = lane & 15, kgrp = lane >> 4;
+  const int g = c.group;
+  const bool act = !a.active || a.active[b];
+
+  // counters as the step finds them, and as it leaves them
+  const long long len0 = c.len[b], base0 = c.base[b];
+  const bool evicting = act && a.do_evict && (len0 - base0 == c.W);
+  const long long base1 = base0 + (evicting ? c.C : 0);
+  const bool append_full = act && a.do_append && (len0 - base1 >= c.W);
+  const bool appending = act && a.do_append && !append_full;
+  const long long len1 = len0 + (appending ? 1 : 0);
+
+  // the live window this step attends over, as a walk over 32-slot groups
+  const int n_live = act ? (int)(len1 - base1) : 0;
+  const int s0 = (int)(base1 % c.W);
+  const int g0 = s0 >> 5, off0 = s0 & 31;
+  const int NG = c.W >> 5;
+  const int n_visits = n_live > 0 ? (off0 + n_live + PT_GROUP_TOKENS - 1) >> 5 : 0;
+  const int per = (n_visits + c.n_splits - 1) / c.n_splits;
+  const int v0 = split * per, v1 = min(n_visits, v0 + per);
+  // the split whose range ends with the newest position evicts / appends for this KV head
+  const bool owner = split == (n_visits > 0 ? (n_visits - 1) / per : 0);
+
+  u32x4* slab_p = (u32x4*)((uint16_t*)c.cache + (size_t)slab * pt_slab_elems(c.W, 128));
+
+  if (owner && (evicting || appending)) {
+    if (evicting) {
+      const int s0e = (int)(base0 % c.W);   // slot of the oldest token of the chunk
+      encode_head_share(c, sm, slab_p, slab, hkv, s0e, lane, wave);
+      if (a.dbg_chunk) {
+        const int dkv = c.Hkv * 128;
+        const uint16_t* src = (const uint16_t*)slab_p;
+        uint16_t* dK = a.dbg_chunk + (size_t)b * 2 * c.C * dkv + hkv * 128;
+        uint16_t* dV = dK + (size_t)c.C * dkv;
+        for (int idx = tid; idx < c.C * 128; idx += kWaves * 64) {
+          const int j = idx >> 7, i = idx & 127;
+          int slot = s0e + j; if (slot >= c.W) slot -= c.W;
+          dK[(size_t)j * dkv + i] = src[pt_k_off(1, c.W, 128, slot, i)];
+          dV[(size_t)j * dkv + i] = src[pt_v_off(1, c.W, 128, slot, i)];
+        }
+      }
+      __syncthreads();   // the chunk's oldest slot is about to be overwritten
+    }
+    if (appending && !a.do_attend && wave == 0) {
+      // append without attention: straight from the inputs (with attention the store happens after
+      // the walk, from the registers that also patch the last group)
+      Op kp[4];
+      uint16_t vp[8];
+      load_newest(kp, vp, a.knew, a.vnew, ((size_t)b * c.Hkv + hkv) * 128, n, kgrp);
+      store_newest((uint16_t*)slab_p, c.W, (int)(len0 % c.W), kp, vp, n, kgrp);
+    }
+  }
+  if (append_full && owner && hkv == 0 && tid == 0) atomicOr(c.err, PTENC_DEVERR_APPEND_FULL);
+
+  if (a.do_attend) {
+    Acc acc;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc.o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    acc.m = -INFINITY;
+    acc.l = 0.f;
+
+    if (v0 < v1) {
+      const bool patch = appending && owner;       // this workgroup's range ends with the new token
+      const int p_visit = n_visits - 1, p_tl = (int)(len0 % c.W) & 31;
+      Op kp[4];
+      uint16_t vp[8];
+      if (patch) load_newest(kp, vp, a.knew, a.vnew, ((size_t)b * c.Hkv + hkv) * 128, n, kgrp);
+      Op qf[4];
+      if (n < g) {
+        const u32x4* qp = (const u32x4*)(a.q + ((size_t)b * c.Hq + hkv * g + n) * 128);
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) qf[cc].u = qp[cc * 4 + kgrp];
+      } else {
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) qf[cc].u = u32x4{0u, 0u, 0u, 0u};
+      }
+      auto grp_ptr = [&](int visit) {
+        int pg = g0 + visit;
+        if (pg >= NG) pg -= NG;
+        if (pg >= NG) pg -= NG;   // a full ring that starts mid-group visits its first group twice
+        return (const u32x4*)slab_p + (size_t)pg * (PT_GROUP_ELEMS / 8);
+      };
+      int i = v0 + wave;
+      Frag fa, fb;
+      if (i < v1) load_group<NT>(fa, grp_ptr(i), lane);
+      while (i < v1) {
+        int nx = i + kWaves;
+        if (nx < v1) load_group<NT>(fb, grp_ptr(nx), lane);
+        if (patch && i == p_visit) patch_newest(fa, kp, vp, p_tl, n, kgrp);
+        process_group(fa, qf, acc, i, off0, n_live, c.scale_log2, kgrp);
+        i = nx;
+        if (i >= v1) break;
+        nx = i + kWaves;
+        if (nx < v1) load_group<NT>(fa, grp_ptr(nx), lane);
+        if (patch && i == p_visit) patch_newest(fb, kp, vp, p_tl, n, kgrp);
+        process_group(fb, qf, acc, i, off0, n_live, c.scale_log2, kgrp);
+        i = nx;
+      }
+      // the store of the new token rides behind the walk: its inputs arrived long ago, and the
+      // chunk of an evicting step was read before anything could overwrite its oldest slot
+      if (patch && wave == 0) store_newest((uint16_t*)slab_p, c.W, (int)(len0 % c.W), kp, vp, n, kgrp);
+    }
+
+    // ---- merge the 4 wavefronts through LDS ----
+    acc.l += __shfl_xor(acc.l, 16, 64);
+    acc.l += __shfl_xor(acc.l, 32, 64);
+    if (n < g) {
+      if (kgrp == 0) { sm.merge.m[wave][n] = acc.m; sm.merge.l[wave][n] = acc.l; }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) *(f32x4*)&sm.merge.o[wave][n][16 * i + 4 * kgrp] = acc.o[i];
+    }
+    __syncthreads();
+
+    const int qn = tid >> 4, part = tid & 15;   // 16 threads per query, 8 columns each
+    const bool has_row = qn < g;
+    const size_t row = (size_t)b * c.Hq + hkv * g + (has_row ? qn : 0);
+    float M = -INFINITY, L = 0.f, o[8];
+#pragma unroll
+    for (int x = 0; x < 8; ++x) o[x] = 0.f;
+    if (has_row) {
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) M = fmaxf(M, sm.merge.m[w][qn]);
+      if (M != -INFINITY) {
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+          const float fw = exp2f(sm.merge.m[w][qn] - M);
+          L = fmaf(fw, sm.merge.l[w][qn], L);
+#pragma unroll
+          for (int x = 0; x < 8; ++x) o[x] = fmaf(fw, sm.merge.o[w][qn][part * 8 + x], o[x]);
+        }
+      }
+    }
+    bool write_out = has_row;
+    if (c.n_splits > 1) {
+      // park this split's (M, L, o); the last split to arrive merges all of them in split order
+      if (has_row) {
+        float* po = c.partial + (row * c.n_splits + split) * (128 + 2);
+        if (part == 0) { st_agent(po, M); st_agent(po + 1, L); }
+#pragma unroll
+        for (int x = 0; x < 8; ++x) st_agent(po + 2 + part * 8 + x, o[x]);
+      }
+      __threadfence_block();
+      __syncthreads();
+      if (tid == 0) sm_ticket = atomicAdd(c.tick_slab + slab, 1);
+      __syncthreads();
+      const bool last = sm_ticket == c.n_splits - 1;
+      write_out = has_row && last;
+      if (last) {
+        if (has_row) {
+          const float* pp = c.partial + row * c.n_splits * (128 + 2);
+          M = -INFINITY;
+          for (int s = 0; s < c.n_splits; ++s) M = fmaxf(M, ld_agent(pp + (size_t)s * 130));
+          L = 0.f;
+#pragma unroll
+          for (int x = 0; x < 8; ++x) o[x] = 0.f;
+          if (M != -INFINITY) {
+            for (int s = 0; s < c.n_splits; ++s) {
+              const float* p = pp + (size_t)s * 130;
+              const float fw = exp2f(ld_agent(p) - M);
+              L = fmaf(fw, ld_agent(p + 1), L);
+#pragma unroll
+              for (int x = 0; x < 8; ++x) o[x] = fmaf(fw, ld_agent(p + 2 + part * 8 + x), o[x]);
+            }
+          }
+        }
+        if (tid == 0) c.tick_slab[slab] = 0;
+      }
+    }
+    if (write_out) {
+      const float inv = L > 0.f ? 1.f / L : 0.f;
+      Op r;
+#pragma unroll
+      for (int x = 0; x < 8; ++x) r.h[x] = (__bf16)(o[x] * inv);
+      *(u32x4*)(a.out + row * 128 + part * 8) = r.u;
+      if (act && n_live == 0 && part == 0 && qn == 0 && hkv == 0) atomicOr(c.err, PTENC_DEVERR_ATTEND_EMPTY);
+    }
+  }
+
+  // ---- counters go to the other buffer (nobody reads that one in this kernel) ----
+  if ((a.do_evict || a.do_append) && hkv == 0 && split == 0 && tid == 0) {
+    c.len_nx[b] = len1;
+    c.base_nx[b] = base1;
+  }
+
+  // ---- whoever finishes last for this rollout completes the encoding ----
+  if (evicting) {
+    __threadfence_block();
+    __syncthreads();
+    if (tid == 0) sm_ticket = atomicAdd(c.tick_rollout + b, 1);
+    __syncthreads();
+    if (sm_ticket == c.Hkv * c.n_splits - 1) {
+      encode_finish(c, sm, b);
+      if (tid == 0) c.tick_rollout[b] = 0;
+    }
+  }
+}
+
+// W^a (row-major [H_kv*128, r]) -> MFMA B operands: [head][k-chunk c][column tile rt][lane][8],
+// lane = 16 * kgrp + n holding rows 128 h + 32 c + 8 kgrp + e of column 16 rt + n (zero beyond r).
+__global__ void pack_weights_kernel(PtDev c, const uint16_t* __restrict__ WaK, const uint16_t* __restrict__ WaV) {
+  const int h = blockIdx.x, cc = blockIdx.y >> 2, rt = blockIdx.y & 3;
+  const int lane = threadIdx.x, n = lane & 15, kgrp = lane >> 4;
+  const int col = rt * 16 + n;
+  uint16_t* dk = (uint16_t*)c.WKp + ((((size_t)h * 4 + cc) * 4 + rt) * 64 + lane) * 8;
+  uint16_t* dv = (uint16_t*)c.WVp + ((((size_t)h * 4 + cc) * 4 + rt) * 64 + lane) * 8;
+  for (int e = 0; e < 8; ++e) {
+    const size_t rowi = (size_t)h * 128 + cc * 32 + 8 * kgrp + e;
+    dk[e] = col < c.r ? WaK[rowi * c.r + col] : (uint16_t)0;
+    dv[e] = col < c.r ? WaV[rowi * c.r + col] : (uint16_t)0;
+  }
+}
+
+}  // namespace
+
+hipError_t pt_launch_pack_weights(const PtDev& c, hipStream_t s) {
+  hipLaunchKernelGGL(pack_weights_kernel, dim3(c.Hkv, 16), dim3(64), 0, s, c, (const uint16_t*)c.WaK,
+                     (const uint16_t*)c.WaV);
+  return hipGetLastError();
+}
+
+hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, bool do_evict, bool do_append, bool do_attend,
+                                 const void* q, const void* k, const void* v, void* out, const uint8_t* active,
+                                 void* dbg_chunk, hipStream_t s) {
+  StepArgs a;
+  a.q = (const uint16_t*)q; a.out = (uint16_t*)out;
+  a.knew = (const uint16_t*)k; a.vnew = (const uint16_t*)v;
+  a.active = active; a.dbg_chunk = (uint16_t*)dbg_chunk;
+  a.do_evict = do_evict; a.do_append = do_append; a.do_attend = do_attend;
+  // without attention there is nothing to split
+  PtDev cc = c;
+  if (!do_attend) cc.n_splits = 1;
+  dim3 grid(cc.B * cc.Hkv, cc.n_splits);
+  if (nontemporal)
+    hipLaunchKernelGGL(decode_mfma_kernel<true>, grid, dim3(kWaves * 64), 0, s, cc, a);
+  else
+    hipLaunchKernelGGL(decode_mfma_kernel<false>, grid, dim3(kWaves * 64), 0, s, cc, a);
+  return hipGetLastError();
+}

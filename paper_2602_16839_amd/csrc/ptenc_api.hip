@@ -11,7 +11,7 @@ namespace {
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct StateLayout {
-  size_t S, Qa, S0, len, base, err, total;
+  size_t S, Qa, S0, len, base, len2, base2, err, tick_rollout, tick_slab, WKp, WVp, total;
 };
 
 StateLayout state_layout(const ptenc_config& c) {
@@ -23,7 +23,14 @@ StateLayout state_layout(const ptenc_config& c) {
   L.S0 = off;   off = align256(off + gr);
   L.len = off;  off = align256(off + sizeof(long long) * c.batch);
   L.base = off; off = align256(off + sizeof(long long) * c.batch);
+  L.len2 = off;  off = align256(off + sizeof(long long) * c.batch);
+  L.base2 = off; off = align256(off + sizeof(long long) * c.batch);
   L.err = off;  off = align256(off + sizeof(int));
+  L.tick_rollout = off; off = align256(off + sizeof(int) * c.batch);
+  L.tick_slab = off;    off = align256(off + sizeof(int) * c.batch * c.n_kv_heads);
+  const size_t packed = (size_t)c.n_kv_heads * 4 * 4 * 64 * 8 * 2;   // MFMA operand form of W^a_K / W^a_V
+  L.WKp = off;  off = align256(off + packed);
+  L.WVp = off;  off = align256(off + packed);
   L.total = off;
   return L;
 }
@@ -44,6 +51,15 @@ ptenc_status check_config(const ptenc_config* c) {
 }
 
 size_t elem_bytes(int dtype) { return dtype == PTENC_F32 ? 4 : 2; }
+
+size_t partial_bytes(const ptenc_config& c) {
+  return align256((size_t)c.batch * c.n_q_heads * PTENC_MAX_SPLITS * (c.head_dim + 2) * sizeof(float));
+}
+
+size_t enc_part_bytes(const ptenc_config& c) {
+  const size_t n_rt = (c.rank + 15) / 16;
+  return align256((size_t)c.batch * c.n_kv_heads * 2 * c.chunk * 16 * n_rt * sizeof(float));
+}
 
 bool mfma_attn_applies(const ptenc_config& c) {
   return c.dtype == PTENC_BF16 && c.head_dim == 128 && c.window % 32 == 0 &&
@@ -66,13 +82,21 @@ int heuristic_splits(const ptenc_ctx* x) {
 
 void replan(ptenc_ctx* x) {
   x->attn_kernel = (x->dev.tiled && !x->opt_force_generic) ? 1 : 0;
-  x->encode_kernel = 0;
+  x->encode_kernel = x->attn_kernel;
   x->dev.n_splits = x->opt_splits > 0 ? x->opt_splits : heuristic_splits(x);
   // a cache that fits the 256 MiB memory-side cache is better served by ordinary loads
   x->nontemporal = x->opt_nontemporal >= 0 ? x->opt_nontemporal : (x->cache_bytes > ((size_t)192 << 20) ? 1 : 0);
 }
 
 inline hipStream_t S(void* s) { return (hipStream_t)s; }
+
+// after a launch that advanced the counters: the buffer it wrote becomes the current one
+ptenc_status advanced(ptenc_ctx* x, hipError_t e) {
+  if (e != hipSuccess) return PTENC_ERR_HIP;
+  long long* t = x->dev.len; x->dev.len = x->dev.len_nx; x->dev.len_nx = t;
+  t = x->dev.base; x->dev.base = x->dev.base_nx; x->dev.base_nx = t;
+  return PTENC_OK;
+}
 inline ptenc_status hip_status(hipError_t e) { return e == hipSuccess ? PTENC_OK : PTENC_ERR_HIP; }
 
 }  // namespace
@@ -88,7 +112,7 @@ ptenc_status ptenc_query_sizes(const ptenc_config* cfg, size_t* cache_bytes, siz
                             elem_bytes(cfg->dtype));
   if (state_bytes) *state_bytes = state_layout(*cfg).total;
   if (scratch_bytes)
-    *scratch_bytes = align256((size_t)cfg->batch * cfg->n_q_heads * PTENC_MAX_SPLITS * (cfg->head_dim + 2) * sizeof(float));
+    *scratch_bytes = partial_bytes(*cfg) + enc_part_bytes(*cfg);
   return PTENC_OK;
 }
 
@@ -122,8 +146,13 @@ ptenc_status ptenc_create(const ptenc_config* cfg, void* d_cache, void* d_state,
   d.cache = d_cache;
   d.S = (float*)(sp + L.S); d.Qa = (float*)(sp + L.Qa); d.S0 = (float*)(sp + L.S0);
   d.len = (long long*)(sp + L.len); d.base = (long long*)(sp + L.base); d.err = (int*)(sp + L.err);
+  d.len_nx = (long long*)(sp + L.len2); d.base_nx = (long long*)(sp + L.base2);
   d.partial = (float*)d_scratch;
+  d.enc_part = (float*)((char*)d_scratch + partial_bytes(*cfg));
   d.WaK = nullptr; d.WaV = nullptr;
+  d.n_rt = (cfg->rank + 15) / 16;
+  d.tick_rollout = (int*)(sp + L.tick_rollout); d.tick_slab = (int*)(sp + L.tick_slab);
+  d.WKp = sp + L.WKp; d.WVp = sp + L.WVp;
   replan(x);
   *out = x;
   return PTENC_OK;
@@ -173,6 +202,10 @@ ptenc_status ptenc_set_encoder(ptenc_ctx* ctx, const void* d_qg, const void* d_W
   d.WaK = d_WaK; d.WaV = d_WaV;
   hipError_t e = pt_launch_encoder_init(d, d_qg, d_WaQ, d_kg, d_vg, S(stream));
   if (e != hipSuccess) return PTENC_ERR_HIP;
+  if (d.tiled) {
+    e = pt_launch_pack_weights(d, S(stream));
+    if (e != hipSuccess) return PTENC_ERR_HIP;
+  }
   ctx->dev = d;
   ctx->encoder_set = 1;
   return PTENC_OK;
@@ -188,15 +221,23 @@ ptenc_status ptenc_cache_append(ptenc_ctx* ctx, const void* d_k, const void* d_v
                                 void* stream) {
   if (!ctx || !d_k || !d_v) return PTENC_ERR_INVALID_ARG;
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
-  return hip_status(pt_launch_step_prologue(ctx->dev, false, true, ctx->encode_kernel, d_k, d_v, d_active,
-                                            nullptr, S(stream)));
+  if (ctx->attn_kernel == 1) {
+    if (((uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
+    return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, false, true, false, nullptr, d_k, d_v,
+                                               nullptr, d_active, nullptr, S(stream)));
+  }
+  return advanced(ctx, pt_launch_step_prologue(ctx->dev, false, true, ctx->encode_kernel, d_k, d_v, d_active,
+                                               nullptr, S(stream)));
 }
 
 ptenc_status ptenc_evict_encode(ptenc_ctx* ctx, const uint8_t* d_active, void* d_dbg_chunk, void* stream) {
   if (!ctx) return PTENC_ERR_INVALID_ARG;
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
-  return hip_status(pt_launch_step_prologue(ctx->dev, true, false, ctx->encode_kernel, nullptr, nullptr,
-                                            d_active, d_dbg_chunk, S(stream)));
+  if (ctx->attn_kernel == 1)
+    return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, true, false, false, nullptr, nullptr,
+                                               nullptr, nullptr, d_active, d_dbg_chunk, S(stream)));
+  return advanced(ctx, pt_launch_step_prologue(ctx->dev, true, false, ctx->encode_kernel, nullptr, nullptr,
+                                               d_active, d_dbg_chunk, S(stream)));
 }
 
 ptenc_status ptenc_decode_attn(ptenc_ctx* ctx, const void* d_q, void* d_out, const uint8_t* d_active,
@@ -205,7 +246,8 @@ ptenc_status ptenc_decode_attn(ptenc_ctx* ctx, const void* d_q, void* d_out, con
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_q | (uintptr_t)d_out) & 15) return PTENC_ERR_INVALID_ARG;
-    return hip_status(pt_launch_attn_mfma(ctx->dev, ctx->nontemporal != 0, d_q, d_out, d_active, S(stream)));
+    return hip_status(pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, false, false, true, d_q, nullptr,
+                                            nullptr, d_out, d_active, nullptr, S(stream)));
   }
   return hip_status(pt_launch_attn_generic(ctx->dev, d_q, d_out, d_active, S(stream)));
 }
@@ -214,9 +256,14 @@ ptenc_status ptenc_decode_step(ptenc_ctx* ctx, const void* d_q, const void* d_k,
                                const uint8_t* d_active, void* stream) {
   if (!ctx || !d_q || !d_k || !d_v || !d_out) return PTENC_ERR_INVALID_ARG;
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
-  hipError_t e = pt_launch_step_prologue(ctx->dev, true, true, ctx->encode_kernel, d_k, d_v, d_active, nullptr,
-                                         S(stream));
-  if (e != hipSuccess) return PTENC_ERR_HIP;
+  if (ctx->attn_kernel == 1) {
+    if (((uintptr_t)d_q | (uintptr_t)d_out | (uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
+    return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, true, true, true, d_q, d_k, d_v, d_out,
+                                               d_active, nullptr, S(stream)));
+  }
+  if (advanced(ctx, pt_launch_step_prologue(ctx->dev, true, true, ctx->encode_kernel, d_k, d_v, d_active, nullptr,
+                                            S(stream))) != PTENC_OK)
+    return PTENC_ERR_HIP;
   return ptenc_decode_attn(ctx, d_q, d_out, d_active, stream);
 }
 

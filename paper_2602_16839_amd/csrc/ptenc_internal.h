@@ -22,12 +22,21 @@ struct PtDev {
   float* S;           // [B, G, r]
   float* Qa;          // [G, r]
   float* S0;          // [G, r]
-  long long* len;     // [B]
+  long long* len;     // [B]  counters as the next kernel finds them
   long long* base;    // [B]
+  long long* len_nx;  // [B]  where a kernel that advances the counters writes them (all rollouts,
+  long long* base_nx; //      changed or not); the host swaps the pairs after such a launch
   int* err;           // sticky error word
   float* partial;     // [rows][n_splits][2 + d]: (m, l, unnormalised out) per window split
   const void* WaK;    // [H_kv*d, r] borrowed
   const void* WaV;    // [H_kv*d, r] borrowed
+  // MFMA path only
+  int n_rt;           // ceil(r / 16): 16-column tiles of the latent space
+  int* tick_rollout;  // [B]      arrival counters, zero between kernels
+  int* tick_slab;     // [B*H_kv]
+  void* WKp;          // W^a_K, W^a_V repacked as MFMA B operands: [H_kv][4][4][64 lanes][8] bf16
+  void* WVp;
+  float* enc_part;    // [B*H_kv][2][C][16 n_rt]: each KV head's share of K_a and V_a
 };
 
 struct ptenc_ctx {
@@ -124,5 +133,7 @@ hipError_t pt_launch_encoder_init(const PtDev& c, const void* qg, const void* Wa
 hipError_t pt_launch_attn_generic(const PtDev& c, const void* q, void* out, const uint8_t* active,
                                   hipStream_t s);
 hipError_t pt_launch_combine(const PtDev& c, void* out, const uint8_t* active, hipStream_t s);
-hipError_t pt_launch_attn_mfma(const PtDev& c, bool nontemporal, const void* q, void* out, const uint8_t* active,
-                               hipStream_t s);
+hipError_t pt_launch_pack_weights(const PtDev& c, hipStream_t s);
+hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, bool do_evict, bool do_append, bool do_attend,
+                                 const void* q, const void* k, const void* v, void* out, const uint8_t* active,
+                                 void* dbg_chunk, hipStream_t s);

@@ -76,7 +76,7 @@ def test_create_checks_pointers_and_order_of_calls():
     assert L.ptenc_set_option(h, ptenc.OPT_SPLITS, ptenc.MAX_SPLITS + 1) == ptenc.ERR_INVALID_ARG
     assert L.ptenc_set_option(h, 99, 0) == ptenc.ERR_INVALID_ARG
     assert L.ptenc_set_option(h, ptenc.OPT_SPLITS, 3) == ptenc.OK
-    assert ptenc.ptenc_get_plan(h) == (1, 3, 0)
+    assert ptenc.ptenc_get_plan(h) == (1, 3, 1)
     assert L.ptenc_destroy(h) == ptenc.OK
     assert L.ptenc_destroy(None) == ptenc.ERR_INVALID_ARG
     assert ptenc.status_string(ptenc.ERR_UNSUPPORTED) == "unsupported configuration"
