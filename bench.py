@@ -9,7 +9,7 @@ Qwen2.5-7B-shaped layer (bf16, 28 query / 4 KV heads, head_dim 128, window 4096,
 128 rollouts) decoded for 8192 steps from an empty cache; inputs are synthetic, seeded, and
 resident in HBM before the timed region starts.
 
-Prints ONE JSON line: whole-job decode tokens/s, the HBM roofline of the attention kernel
+Prints ONE JSON line: whole-job decode tokens/s, the HBM roofline of the step kernel
 (algorithmic bytes per launch / mean launch time measured with HIP events on the launch
 stream), and the CPU oracle timed on the host cores on a bounded sample of the same workload.
 """
@@ -118,6 +118,8 @@ def main() -> int:
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the per-launch HIP-event pass")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also launch the plain copy / read kernels on 1 GiB (scale for the profiler's byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this path runs on ONE GPU (rollouts are independent; several GPUs would each take a "
@@ -187,28 +189,41 @@ def main() -> int:
     value = tokens / (total_ms * 1e-3)
     all_bytes = float(abytes.sum()) + prologue_bytes_total(wl, lengths, K)
 
-    # ---- per-launch timing of the attention kernel (second pass over the same steps) ----
+    # ---- per-launch timing of the step kernel with HIP events on the launch stream (second pass
+    #      over the same steps; on the MFMA path one launch is one whole decode step) ----
     roofline = None
+    fused = attn_kernel == 1
     if not args.no_kernel_timing:
         layer.reset()
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
         for t in range(K):
             a = None if active is None else active[t]
-            layer.evict_encode(a)
-            layer.append(k[t], v[t], a)
-            evs[t][0].record()
-            layer.attend(q[t], out[t], a)
-            evs[t][1].record()
+            if fused:
+                evs[t][0].record()
+                layer.step(q[t], k[t], v[t], out[t], a)
+                evs[t][1].record()
+            else:
+                layer.evict_encode(a)
+                layer.append(k[t], v[t], a)
+                evs[t][0].record()
+                layer.attend(q[t], out[t], a)
+                evs[t][1].record()
         torch.cuda.synchronize()
-        attn_ms = float(sum(a.elapsed_time(b) for a, b in evs))
-        mean_s = attn_ms * 1e-3 / K
-        achieved = float(abytes.mean()) / mean_s / 1e9
+        kern_ms = float(sum(a.elapsed_time(b) for a, b in evs))
+        mean_s = kern_ms * 1e-3 / K
+        launch_bytes = (all_bytes if fused else float(abytes.sum())) / K
+        achieved = launch_bytes / mean_s / 1e9
+        traffic = None
+        tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % wl.name)
+        if os.path.exists(tpath) and K == wl.steps:
+            with open(tpath) as fh:
+                traffic = json.load(fh).get("traffic_bytes_per_launch")
         roofline = {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-            "kernel": "attn_mfma_kernel" if attn_kernel == 1 else "attn_generic_kernel",
-            "launches": K, "mean_launch_us": mean_s * 1e6, "algorithmic_bytes_per_launch": float(abytes.mean()),
-            "includes_combine_kernel": bool(n_splits > 1),
+            "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+            "kernel": "decode_mfma_kernel (evict-encode + append + attention in one launch)" if fused
+                      else "attn_generic_kernel + combine_kernel",
+            "launches": K, "mean_launch_us": mean_s * 1e6, "algorithmic_bytes_per_launch": launch_bytes,
         }
 
     res = {
@@ -230,6 +245,17 @@ def main() -> int:
         "algorithmic_gbytes": all_bytes / 1e9,
         "roofline": roofline,
     }
+    if args.calibrate:
+        nbytes = 1 << 30
+        src = torch.randint(0, 255, (nbytes,), dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        sink = torch.zeros(4, dtype=torch.uint8, device=dev)
+        for _ in range(5):
+            ptenc.ptenc_util_copy(dst, src, nbytes, 2048)
+            ptenc.ptenc_util_stream_read(src, nbytes, sink, 2048)
+        torch.cuda.synchronize()
+        res["calibration"] = {"copy_kernel_bytes_read": nbytes, "copy_kernel_bytes_written": nbytes,
+                              "read_kernel_bytes_read": nbytes, "launches_each": 5}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(res), flush=True)
