@@ -1,0 +1,125 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times
+(ptenc_decode_run over step-major buffers, default plan): the whole run is decoded on the GPU
+and sampled outputs, ring contents and states are recomputed one by one by the CPU oracle from
+the stateless input generator.  Counters are checked in full against the closed forms."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import pte_oracle as po
+from oracle.ring_model import evicted_closed_form
+from paper_2602_16839_amd import inputs as I
+from paper_2602_16839_amd import ptenc
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_full(wl, sample_steps, seg_steps):
+    """Decode the whole workload in segments; returns (layer, lengths, {t: out[t-1] on the host})."""
+    dev = torch.device("cuda:0")
+    enc = I.encoder_params(wl, device=dev)
+    layer = ptenc.Layer(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
+                        dtype=wl.torch_dtype, n_global=wl.n_global, rank=wl.rank, poison_cache=True)
+    layer.set_encoder(enc["q_g"], enc["WaQ"], enc["WaK"], enc["WaV"], enc["k_g"], enc["v_g"])
+    layer.reset()
+    lengths = I.rollout_lengths(wl)
+    T = int(lengths.max())
+    len_dev = torch.from_numpy(lengths).to(dev).view(1, -1)
+    kept = {}
+    for t0 in range(0, T, seg_steps):
+        t1 = min(T, t0 + seg_steps)
+        q, k, v = I.qkv_steps(wl, t0, t1, device=dev)
+        active = None
+        if wl.ragged:
+            tt = torch.arange(t0, t1, device=dev).view(-1, 1)
+            active = (tt < len_dev).to(torch.uint8).contiguous()
+        out = layer.run(q, k, v, active=active)
+        for t in sample_steps:
+            if t0 < t <= t1:
+                kept[t] = out[t - 1 - t0].cpu()
+        del q, k, v, out
+    torch.cuda.synchronize()
+    return layer, lengths, kept, T
+
+
+def _oracle_out(wl, b, t, L):
+    """Attention output of rollout b at decode step t (1-based), from regenerated inputs."""
+    if t > L:
+        return np.zeros((wl.n_q_heads, wl.head_dim))
+    E = evicted_closed_form(t, wl.window, wl.chunk)
+    q, k, v = I.qkv_steps(wl, E, t, b0=b, b1=b + 1)
+    return po.attend(H.f64(q[-1, 0]), list(H.f64(k[:, 0])), list(H.f64(v[:, 0])))
+
+
+def _oracle_state(wl, b, L, enc):
+    """S of rollout b after L decode steps: every eviction replayed from regenerated inputs."""
+    e = {k: H.f64(v) for k, v in enc.items()}
+    Q_a, S = po.init_state(e["q_g"], e["WaQ"], e["WaK"], e["WaV"], e["k_g"], e["v_g"])
+    E = evicted_closed_form(L, wl.window, wl.chunk)
+    if E:
+        _, k, v = I.qkv_steps(wl, 0, E, b0=b, b1=b + 1)
+        k, v = H.f64(k[:, 0]).reshape(E, -1), H.f64(v[:, 0]).reshape(E, -1)
+        for c0 in range(0, E, wl.chunk):
+            S = po.normalize(S + po.encode_chunk(Q_a, k[c0:c0 + wl.chunk], v[c0:c0 + wl.chunk], e["WaK"], e["WaV"]))
+    return S
+
+
+def _check(wl, sample_b, sample_t, seg_steps):
+    layer, lengths, kept, T = _run_full(wl, sample_t, seg_steps)
+    assert layer.poll_error() == 0
+    # counters, all rollouts, against the closed forms
+    ln, base = layer.counters()
+    assert np.array_equal(ln, lengths)
+    assert np.array_equal(base, np.array([evicted_closed_form(int(L), wl.window, wl.chunk) for L in lengths]))
+    # sampled outputs
+    for t in sample_t:
+        got = H.f64(kept[t])
+        for b in sample_b:
+            ref = _oracle_out(wl, b, t, int(lengths[b]))
+            H.assert_close(got[b], ref, H.BF16_ABS, H.BF16_REL, "%s out b=%d t=%d" % (wl.name, b, t))
+    # sampled ring contents (bit exact) and states
+    Kw, Vw = layer.gather_window()
+    S = layer.get_state()
+    enc = I.encoder_params(wl)
+    for b in sample_b:
+        L = int(lengths[b])
+        E, n = int(base[b]), int(ln[b] - base[b])
+        _, k, v = I.qkv_steps(wl, E, L, b0=b, b1=b + 1)
+        assert torch.equal(Kw[b, :, :n].cpu(), k[:, 0].transpose(0, 1)), "ring K of rollout %d" % b
+        assert torch.equal(Vw[b, :, :n].cpu(), v[:, 0].transpose(0, 1)), "ring V of rollout %d" % b
+        H.assert_close(S[b], _oracle_state(wl, b, L, enc), H.S_ABS, H.S_REL, "%s S b=%d" % (wl.name, b))
+    return layer
+
+
+def test_qwen3b_full_run_sampled():
+    wl = I.WORKLOADS["qwen3b"]
+    W, C, T = wl.window, wl.chunk, wl.steps
+    layer = _check(wl, [0, 37, 63], [1, 33, W, W + 1, W + C // 2, T - 1, T], seg_steps=1024)
+    assert layer.plan()[0] == 1
+
+
+def test_qwen7b_full_run_sampled():
+    # the configuration the benchmark is quoted on
+    wl = I.WORKLOADS["qwen7b"]
+    W, C, T = wl.window, wl.chunk, wl.steps
+    layer = _check(wl, [0, 77, 127], [1, 31, 1000, W, W + 1, W + C, 6001, T], seg_steps=1024)
+    assert layer.plan() == (1, 1, 1)
+
+
+def test_llama8b_full_run_sampled():
+    wl = I.WORKLOADS["llama8b"]
+    W, C, T = wl.window, wl.chunk, wl.steps
+    _check(wl, [3, 255], [W, W + 1, T], seg_steps=512)
+
+
+def test_ragged_full_run_sampled():
+    wl = I.WORKLOADS["ragged"]
+    lengths = I.rollout_lengths(wl)
+    order = np.argsort(lengths)
+    b_short, b_med, b_long = int(order[0]), int(order[len(order) // 2]), int(order[-1])
+    never_full = [int(b) for b in np.where(lengths < wl.window)[0][:1]]
+    sample_b = sorted(set([b_short, b_med, b_long] + never_full))
+    Lm = int(lengths[b_med])
+    sample_t = sorted(set([1, int(lengths[b_short]), wl.window + 1, Lm, Lm + 1, int(lengths[b_long])]))
+    _check(wl, sample_b, sample_t, seg_steps=1024)
