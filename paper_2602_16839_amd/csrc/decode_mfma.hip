@@ -194,6 +194,16 @@ __device__ inline float ld_agent(const float* p) {
 __device__ inline void st_agent(float* p, float v) {
   __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// two adjacent floats (8-byte aligned) as one 64-bit access
+__device__ inline void st_agent2(float* p, float a, float b) {
+  const unsigned long long u = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
+  __hip_atomic_store((unsigned long long*)p, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void ld_agent2(const float* p, float& a, float& b) {
+  const unsigned long long u = __hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  a = __uint_as_float((unsigned)u);
+  b = __uint_as_float((unsigned)(u >> 32));
+}
 
 struct StepArgs {
   const uint16_t* q;       // [B, H_q, 128]
@@ -446,9 +456,9 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(PtDev c, St
       // park this split's (M, L, o); the last split to arrive merges all of them in split order
       if (has_row) {
         float* po = c.partial + (row * c.n_splits + split) * (128 + 2);
-        if (part == 0) { st_agent(po, M); st_agent(po + 1, L); }
+        if (part == 0) st_agent2(po, M, L);
 #pragma unroll
-        for (int x = 0; x < 8; ++x) st_agent(po + 2 + part * 8 + x, o[x]);
+        for (int x = 0; x < 4; ++x) st_agent2(po + 2 + part * 8 + 2 * x, o[2 * x], o[2 * x + 1]);
       }
       __threadfence_block();
       __syncthreads();
@@ -459,19 +469,44 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(PtDev c, St
       if (last) {
         if (has_row) {
           const float* pp = c.partial + row * c.n_splits * (128 + 2);
-          M = -INFINITY;
-          for (int s = 0; s < c.n_splits; ++s) M = fmaxf(M, ld_agent(pp + (size_t)s * 130));
-          L = 0.f;
+          // statistics: lane `part` of the row's 16 lanes takes splits part and part + 16, all loads in
+          // flight at once, then the 16 lanes exchange by shuffle
+          float Ms[2], Ls[2];
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            const int s = part + 16 * j;
+            Ms[j] = -INFINITY; Ls[j] = 0.f;
+            if (s < c.n_splits) ld_agent2(pp + (size_t)s * 130, Ms[j], Ls[j]);
+          }
+          M = fmaxf(Ms[0], Ms[1]);
+#pragma unroll
+          for (int off = 1; off < 16; off <<= 1) M = fmaxf(M, __shfl_xor(M, off, 16));
+          float fs[2];
+#pragma unroll
+          for (int j = 0; j < 2; ++j) fs[j] = M == -INFINITY ? 0.f : exp2f(Ms[j] - M);
+          L = fs[0] * Ls[0] + fs[1] * Ls[1];
+#pragma unroll
+          for (int off = 1; off < 16; off <<= 1) L += __shfl_xor(L, off, 16);
 #pragma unroll
           for (int x = 0; x < 8; ++x) o[x] = 0.f;
-          if (M != -INFINITY) {
-            for (int s = 0; s < c.n_splits; ++s) {
-              const float* p = pp + (size_t)s * 130;
-              const float fw = exp2f(ld_agent(p) - M);
-              L = fmaf(fw, ld_agent(p + 1), L);
+          for (int s0 = 0; s0 < c.n_splits; s0 += 4) {
+            float t[4][8];
 #pragma unroll
-              for (int x = 0; x < 8; ++x) o[x] = fmaf(fw, ld_agent(p + 2 + part * 8 + x), o[x]);
-            }
+            for (int j = 0; j < 4; ++j)
+              if (s0 + j < c.n_splits) {
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+                  ld_agent2(pp + (size_t)(s0 + j) * 130 + 2 + part * 8 + 2 * x, t[j][2 * x], t[j][2 * x + 1]);
+              }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              if (s0 + j < c.n_splits) {
+                const int s = s0 + j;
+                const float f0 = __shfl(fs[0], s & 15, 16), f1 = __shfl(fs[1], s & 15, 16);
+                const float fw = (s >> 4) ? f1 : f0;
+#pragma unroll
+                for (int x = 0; x < 8; ++x) o[x] = fmaf(fw, t[j][x], o[x]);
+              }
           }
         }
         if (tid == 0) c.tick_slab[slab] = 0;

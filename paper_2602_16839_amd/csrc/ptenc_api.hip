@@ -66,12 +66,15 @@ bool mfma_attn_applies(const ptenc_config& c) {
          c.n_q_heads / c.n_kv_heads <= 16;
 }
 
-// window splits: two workgroups per CU (256 CUs) if the rows alone do not give that; no split
-// shorter than 256 tokens
+// Window splits.  Splitting a (rollout, KV head) row over several workgroups costs a round trip
+// through memory for the partial results, and measured on MI355X one workgroup per row wins as
+// soon as there are about a hundred rows (even with half the CUs idle).  Below that, split until
+// about 128 workgroups exist, but never below 256 tokens per split.
 int heuristic_splits(const ptenc_ctx* x) {
   const ptenc_config& c = x->cfg;
   const long rows = (long)c.batch * (x->attn_kernel ? c.n_kv_heads : c.n_q_heads);
-  long want = (512 + rows - 1) / rows;
+  if (rows >= 96) return 1;
+  long want = (128 + rows - 1) / rows;
   long cap = c.window / 256;
   if (cap < 1) cap = 1;
   if (want > cap) want = cap;

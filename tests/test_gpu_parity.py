@@ -34,6 +34,14 @@ def test_bf16_mfma_path_small_window(splits):
     assert layer.plan()[:2] == (1, splits)
 
 
+@pytest.mark.parametrize("splits", [5, 17, 32])
+def test_many_window_splits_merge_in_kernel(splits):
+    # 33 groups of 32 slots: every split count leaves some splits empty and some with one group
+    wl = small("qwen7b", batch=2, n_q_heads=14, n_kv_heads=2, window=1056, chunk=96, steps=1200)
+    layer, _ = H.run_both(wl, wl.steps, splits=splits, check_every=37)
+    assert layer.plan()[:2] == (1, splits)
+
+
 def test_bf16_generic_path_small_window():
     wl = small("qwen3b", batch=2, n_q_heads=8, n_kv_heads=2, window=96, chunk=40, steps=250)
     layer, _ = H.run_both(wl, wl.steps, force_generic=True, splits=2)
