@@ -21,6 +21,9 @@ What follows the paper, and where:
 * ``OracleLayer.step``  -- decode until the cache is full, then evict the oldest chunk (sliding window
                            over thinking tokens; Our Approach, first paragraph and "The selection of D
                            during training") and fold it into S before decoding continues.
+* ``OracleLayer.prefill`` -- question tokens are kept in the cache permanently and only thinking tokens
+                           slide ("The selection of D during training"; the response-length analysis
+                           quotes a cache of 768 = 512 sink tokens + 256 in the sliding window).
 
 Readings taken where the paper is silent or inconsistent (same list as the design notes):
 
@@ -37,6 +40,10 @@ Readings taken where the paper is silent or inconsistent (same list as the desig
    identity are selectable.
 8. S_0 is not normalised; Normalize first applies at the first eviction.
 13. Attention of an inactive rollout, or over an empty window, returns zeros.
+15. Pinned question tokens: of the W cache slots, n_sink are reserved for a rollout's question
+    tokens (at most n_sink of them, any number per rollout); the sliding window over thinking
+    tokens holds W - n_sink.  Question tokens are attended to at every step, never evicted and
+    never encoded; "full" means the sliding part is full.
 
 End-to-end values are PARITY UNPINNED against the paper: it prints no number for any
 intermediate or output of this path.  The pins in tests/ are closed forms, invariants, library
@@ -122,7 +129,9 @@ class OracleRollout:
     """One rollout's bounded cache and context state."""
 
     def __init__(self, S0: np.ndarray):
-        self.win_k: List[np.ndarray] = []     # logical order, oldest first; each [H_kv, d]
+        self.sink_k: List[np.ndarray] = []    # question tokens, kept for good; each [H_kv, d]
+        self.sink_v: List[np.ndarray] = []
+        self.win_k: List[np.ndarray] = []     # thinking tokens, logical order, oldest first
         self.win_v: List[np.ndarray] = []
         self.appended = 0                     # tokens appended so far
         self.evicted = 0                      # tokens evicted so far
@@ -134,16 +143,18 @@ class OracleLayer:
     """Batched decode of B independent rollouts through one attention layer under a bounded window.
 
     ``window`` W is the cache capacity in tokens, ``chunk`` C the number of oldest tokens evicted
-    at once when the window is full.
+    at once when the window is full.  ``n_sink`` of the W slots are reserved for question tokens
+    (see ``prefill``); the sliding window over thinking tokens then holds W - n_sink.
     """
 
     def __init__(self, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, window: int,
                  chunk: int, q_g, WaQ, WaK, WaV, k_g=None, v_g=None,
                  norm_mode: int = NORM_FROBENIUS, norm_eps: float = 1e-12,
-                 softmax_scale: Optional[float] = None, keep_chunks: bool = False):
-        assert n_q_heads % n_kv_heads == 0 and 1 <= chunk <= window
+                 softmax_scale: Optional[float] = None, keep_chunks: bool = False, n_sink: int = 0):
+        assert n_q_heads % n_kv_heads == 0 and 0 <= n_sink < window and 1 <= chunk <= window - n_sink
         self.B, self.H_q, self.H_kv, self.d = batch, n_q_heads, n_kv_heads, head_dim
-        self.W, self.C = window, chunk
+        self.W, self.C, self.n_sink = window, chunk, n_sink
+        self.ring = window - n_sink           # capacity of the sliding part
         self.WaK = np.asarray(WaK, dtype=np.float64)
         self.WaV = np.asarray(WaV, dtype=np.float64)
         self.Q_a, self.S0 = init_state(q_g, WaQ, WaK, WaV, k_g, v_g)
@@ -156,7 +167,7 @@ class OracleLayer:
     def evict_encode(self, b: int) -> bool:
         """If rollout b's window is full: fold its C oldest tokens into S and drop them."""
         r = self.rollouts[b]
-        if len(r.win_k) < self.W:
+        if len(r.win_k) < self.ring:
             return False
         C = self.C
         K_e = np.stack([k.reshape(-1) for k in r.win_k[:C]])     # [C, d_kv], heads concatenated
@@ -172,14 +183,22 @@ class OracleLayer:
 
     def append(self, b: int, k: np.ndarray, v: np.ndarray) -> None:
         r = self.rollouts[b]
-        assert len(r.win_k) < self.W, "append on a full window"
+        assert len(r.win_k) < self.ring, "append on a full window"
         r.win_k.append(np.array(k, dtype=np.float64))
         r.win_v.append(np.array(v, dtype=np.float64))
         r.appended += 1
 
     def attend(self, b: int, q: np.ndarray) -> np.ndarray:
         r = self.rollouts[b]
-        return attend(q, r.win_k, r.win_v, self.scale)
+        return attend(q, r.sink_k + r.win_k, r.sink_v + r.win_v, self.scale)
+
+    def prefill(self, b: int, K_p: np.ndarray, V_p: np.ndarray) -> None:
+        """Question tokens of rollout b, ``[P, H_kv, d]`` each with P <= n_sink: kept permanently."""
+        r = self.rollouts[b]
+        assert len(K_p) == len(V_p) and len(r.sink_k) + len(K_p) <= self.n_sink, "more question tokens than n_sink"
+        for kk, vv in zip(K_p, V_p):
+            r.sink_k.append(np.array(kk, dtype=np.float64))
+            r.sink_v.append(np.array(vv, dtype=np.float64))
 
     # -- one batched decode step ------------------------------------------------------------
     def step(self, q: np.ndarray, k: np.ndarray, v: np.ndarray,
@@ -203,8 +222,13 @@ class OracleLayer:
                 np.array([r.evicted for r in self.rollouts], dtype=np.int64))
 
     def window_kv(self, b: int):
+        """Everything rollout b attends over: question tokens first, then the sliding window."""
         r = self.rollouts[b]
-        if not r.win_k:
+        ks, vs = r.sink_k + r.win_k, r.sink_v + r.win_v
+        if not ks:
             z = np.zeros((0, self.H_kv, self.d))
             return z, z.copy()
-        return np.stack(r.win_k), np.stack(r.win_v)
+        return np.stack(ks), np.stack(vs)
+
+    def prompt_lengths(self) -> np.ndarray:
+        return np.array([len(r.sink_k) for r in self.rollouts], dtype=np.int64)

@@ -353,6 +353,57 @@ def test_inactive_rollouts_are_untouched_and_return_zeros():
 
 
 # ---------------------------------------------------------------------------------------------
+# pinned question tokens ("The selection of D during training": question tokens are kept for good,
+# only thinking tokens slide; e.g. a cache of 768 = 512 sink tokens + 256 in the sliding window)
+# ---------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("W,n_sink,C,P", [(12, 4, 3, (4, 2)), (10, 6, 4, (0, 6)), (9, 1, 8, (1, 1))])
+def test_question_tokens_stay_and_only_thinking_tokens_slide(W, n_sink, C, P):
+    B, H_q, H_kv, d = 2, 4, 2, 4
+    R = W - n_sink
+    T = 3 * R + 4
+    enc = dict(q_g=rand(3, H_q * d), WaQ=rand(H_q * d, 5), WaK=rand(H_kv * d, 5), WaV=rand(H_kv * d, 5),
+               k_g=rand(3, H_kv * d), v_g=rand(3, H_kv * d))
+    layer = po.OracleLayer(B, H_q, H_kv, d, W, C, n_sink=n_sink, keep_chunks=True, **enc)
+    plain = po.OracleLayer(B, H_q, H_kv, d, R, C, keep_chunks=True, **enc)     # no question tokens, window R
+    pk = [rand(P[b], H_kv, d) for b in range(B)]
+    pv = [rand(P[b], H_kv, d) for b in range(B)]
+    for b in range(B):
+        layer.prefill(b, pk[b], pv[b])
+    assert layer.prompt_lengths().tolist() == list(P)
+    q, k, v = rand(T, B, H_q, d), rand(T, B, H_kv, d), rand(T, B, H_kv, d)
+    for t in range(1, T + 1):
+        out = layer.step(q[t - 1], k[t - 1], v[t - 1])
+        plain.step(q[t - 1], k[t - 1], v[t - 1])
+        E = evicted_closed_form(t, R, C)
+        assert n_live_closed_form(t, R, C) == t - E
+        for b in range(B):
+            Kall = np.concatenate([pk[b], k[E:t, b]])
+            Vall = np.concatenate([pv[b], v[E:t, b]])
+            assert np.allclose(out[b], direct_attention(q[t - 1, b], Kall, Vall, H_q // H_kv), atol=1e-13)
+            Kw, Vw = layer.window_kv(b)
+            assert np.array_equal(Kw, Kall) and np.array_equal(Vw, Vall)
+    # eviction schedule, evicted chunks and the state are those of the plain window of R thinking tokens
+    assert np.array_equal(layer.counters()[0], plain.counters()[0])
+    assert np.array_equal(layer.counters()[1], plain.counters()[1])
+    assert np.array_equal(layer.state(), plain.state())
+    for b in range(B):
+        for (Ka, Va), (Kb, Vb) in zip(layer.rollouts[b].evicted_chunks, plain.rollouts[b].evicted_chunks):
+            assert np.array_equal(Ka, Kb) and np.array_equal(Va, Vb)
+    with pytest.raises(AssertionError):
+        layer.prefill(0, rand(n_sink + 1, H_kv, d), rand(n_sink + 1, H_kv, d))
+
+
+def test_ring_model_with_reserved_question_slots():
+    ring = RingModel(1, 12, 3, n_sink=4)
+    slots = [int(ring.step()[0]) for _ in range(20)]
+    assert slots[:9] == [4, 5, 6, 7, 8, 9, 10, 11, 4]                 # ring of 8 behind 4 reserved slots
+    assert ring.base[0] == 3 * -(-(20 - 8) // 3) and min(slots) >= 4
+    assert ring.evictions[0][0].tolist() == [4, 5, 6]
+    assert ring.live_slots(0).tolist() == [4 + p % 8 for p in range(int(ring.base[0]), 20)]
+
+
+# ---------------------------------------------------------------------------------------------
 # ring model against a brute-force deque, incl. C not dividing W, C = 1, C = W, rotated start
 # ---------------------------------------------------------------------------------------------
 
