@@ -2,9 +2,11 @@
  * ptenc -- bounded-cache rollout decode for Progressive Thought Encoding on one MI355X (gfx950).
  *
  * One context = one attention layer decoding B independent rollouts.  Per rollout the library
- * keeps a ring-buffer KV cache of W token slots, two counters (len = tokens appended, base =
- * tokens evicted; live positions are [base, len), position p lives in slot p mod W) and the
- * fixed-size context state S (G x r, fp32).
+ * keeps a KV cache of W token slots -- n_sink slots reserved for the rollout's question tokens,
+ * which are never evicted, and a ring of W - n_sink slots for thinking tokens -- two counters
+ * (len = thinking tokens appended, base = thinking tokens evicted; live positions are
+ * [base, len), position p lives in slot n_sink + p mod (W - n_sink)) and the fixed-size context
+ * state S (G x r, fp32).
  *
  * The calls follow the paper's problem statement:
  *   - a cache policy that prunes the KV cache online during decoding, so that every token is
@@ -15,7 +17,10 @@
  *   - when the cache is full the earliest thinking tokens are evicted as a chunk and folded
  *     into the context state: S' = ((q_g W^a_Q)(K_e W^a_K)^T)(V_e W^a_V), then
  *     S <- Normalize(S + S') (Our Approach, the Delta-W equation and the update rule); S starts
- *     from the same contraction applied to the global tokens' own k_g, v_g (same section).
+ *     from the same contraction applied to the global tokens' own k_g, v_g (same section);
+ *   - question tokens stay in the cache for good and only thinking tokens slide (Our Approach,
+ *     "The selection of D during training"; the response-length analysis quotes a cache of
+ *     768 = 512 sink tokens + 256 in the sliding window).
  *
  * Conventions for every entry point
  *   - All "d_" pointers are DEVICE pointers, all "h_" pointers are HOST pointers.
@@ -82,9 +87,9 @@ typedef struct {
   int32_t n_q_heads;      /* H_q */
   int32_t n_kv_heads;     /* H_kv, divides H_q */
   int32_t head_dim;       /* d, 1..256 */
-  int32_t window;         /* W ring slots */
-  int32_t chunk;          /* C tokens evicted at once, 1 <= C <= W */
-  int32_t n_sink;         /* permanently retained prompt tokens: reserved, must be 0 */
+  int32_t window;         /* W cache slots per rollout, question tokens included */
+  int32_t chunk;          /* C tokens evicted at once, 1 <= C <= W - n_sink */
+  int32_t n_sink;         /* slots reserved for permanently retained question tokens, 0 <= n_sink < W */
   int32_t n_global;       /* G global tokens, 1..64 */
   int32_t rank;           /* r latent width, 1..64 */
   int32_t dtype;          /* ptenc_dtype */
@@ -114,23 +119,32 @@ ptenc_status ptenc_set_option(ptenc_ctx* ctx, int32_t option, int32_t value);
 ptenc_status ptenc_set_encoder(ptenc_ctx* ctx, const void* d_qg, const void* d_WaQ, const void* d_WaK,
                                const void* d_WaV, const void* d_kg, const void* d_vg, void* stream);
 
-/* len = base = 0 and S = S_0 for the rollouts selected by d_mask (uint8[B], NULL = all);
+/* len = base = 0, no question tokens, and S = S_0 for the rollouts selected by d_mask (uint8[B], NULL = all);
  * clears the error word when d_mask is NULL.  Cache contents are left as they are (dead slots
  * are never read). */
 ptenc_status ptenc_reset(ptenc_ctx* ctx, const uint8_t* d_mask, void* stream);
 
-/* Writes k, v [B, H_kv, d] of every active rollout to slot len mod W, then len += 1
+/* Question tokens of every rollout into its reserved slots (bulk append): d_k, d_v are
+ * [B, p_max, H_kv, d] of cfg.dtype, h_prompt_len is a HOST array of B lengths, each
+ * 0 <= len <= min(n_sink, p_max); rollout b's tokens 0 .. len-1 are taken, replacing whatever
+ * question tokens it held.  They are attended to at every step and never evicted or encoded.
+ * Synchronises the stream (the host array is consumed before return). */
+ptenc_status ptenc_prefill(ptenc_ctx* ctx, const void* d_k, const void* d_v, const int32_t* h_prompt_len,
+                           int32_t p_max, void* stream);
+ptenc_status ptenc_get_prompt_len(ptenc_ctx* ctx, int32_t* h_prompt_len, void* stream);
+
+/* Writes k, v [B, H_kv, d] of every active rollout to the ring slot of position len, then len += 1
  * (Notation and Preliminaries: the cache is extended by k_{t+1}, v_{t+1} before attending). */
 ptenc_status ptenc_cache_append(ptenc_ctx* ctx, const void* d_k, const void* d_v,
                                 const uint8_t* d_active, void* stream);
 
-/* out[b, h] = softmax(q[b, h] . K_live / sqrt(d)) V_live over rollout b's live positions,
+/* out[b, h] = softmax(q[b, h] . K_live / sqrt(d)) V_live over rollout b's question tokens and live positions,
  * query head h reading KV head h / (H_q / H_kv); q and out are [B, H_q, d]
  * (Notation and Preliminaries, attention equation, restricted to the pruned context). */
 ptenc_status ptenc_decode_attn(ptenc_ctx* ctx, const void* d_q, void* d_out, const uint8_t* d_active,
                                void* stream);
 
-/* For every active rollout whose window is full (len - base == W): takes its C oldest
+/* For every active rollout whose ring is full (len - base == W - n_sink): takes its C oldest
  * positions [base, base + C), oldest first, folds them into S as defined above, and
  * base += C.  Other rollouts are untouched.  d_dbg_chunk is NULL, or [B, 2, C, H_kv*d] of
  * cfg.dtype receiving K_e (index 0) and V_e (index 1) of each evicting rollout in logical
@@ -148,7 +162,7 @@ ptenc_status ptenc_decode_run(ptenc_ctx* ctx, const void* d_q, const void* d_k, 
                               void* d_out, const uint8_t* d_active, int64_t n_steps, void* stream);
 
 /* Counters to / from host arrays of B int64 each.  set_counters requires
- * 0 <= base <= len <= base + W for every rollout (used for resume and rotation tests). */
+ * 0 <= base <= len <= base + W - n_sink for every rollout (used for resume and rotation tests). */
 ptenc_status ptenc_get_counters(ptenc_ctx* ctx, int64_t* h_len, int64_t* h_base, void* stream);
 ptenc_status ptenc_set_counters(ptenc_ctx* ctx, const int64_t* h_len, const int64_t* h_base, void* stream);
 
@@ -159,8 +173,9 @@ ptenc_status ptenc_set_state(ptenc_ctx* ctx, const float* h_S, void* stream);
 /* Q_a [G, r] and S_0 [G, r] (fp32) as computed by ptenc_set_encoder; either may be NULL. */
 ptenc_status ptenc_get_encoder_state(ptenc_ctx* ctx, float* h_Qa, float* h_S0, void* stream);
 
-/* Live window in logical order (oldest first) into d_K, d_V [B, H_kv, W, d] of cfg.dtype; rows
- * at and beyond len - base are zero-filled.  Debug / checkpoint helper. */
+/* Everything a rollout attends over, in logical order (question tokens, then live positions oldest
+ * first) into d_K, d_V [B, H_kv, W, d] of cfg.dtype; the remaining rows are zero-filled.
+ * Debug / checkpoint helper. */
 ptenc_status ptenc_gather_window(ptenc_ctx* ctx, void* d_K, void* d_V, void* stream);
 
 /* Element offset, within d_cache, of element i of the key (which = 0) or value (which = 1) of

@@ -36,10 +36,12 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(PtDev c, const T
   float* po = c.partial + ((size_t)bh * c.n_splits + split) * (c.d + 2);
   const bool act = !active || active[b];
   const long long len = c.len[b], base = c.base[b];
-  const int n_live = act ? (int)(len - base) : 0;
+  // logical order: the P question tokens (slots 0 .. P-1), then the live ring positions
+  const int P = act ? c.n_prompt[b] : 0;
+  const int n_live = act ? P + (int)(len - base) : 0;
   const int per = (n_live + c.n_splits - 1) / c.n_splits;
   const int j0 = split * per, j1 = min(n_live, j0 + per);
-  const int s0 = (int)(base % c.W);
+  const int s0 = (int)(base % c.Wr);
   const T* slab = (const T*)c.cache + (size_t)(b * c.Hkv + h / c.group) * pt_slab_elems(c.W, c.d);
 
   for (int i = t; i < c.d; i += kThreads) qs[i] = pt_ld<T>(q + (size_t)bh * c.d + i);
@@ -51,7 +53,8 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(PtDev c, const T
     float s = -INFINITY;
     int slot = 0;
     if (j < j1) {
-      slot = s0 + j; if (slot >= c.W) slot -= c.W;
+      slot = j;
+      if (j >= P) { slot = s0 + (j - P); if (slot >= c.Wr) slot -= c.Wr; slot += c.n_sink; }
       float dot = 0.f;
       for (int i = 0; i < c.d; ++i) dot = fmaf(qs[i], pt_ld<T>(slab + pt_k_off(c.tiled, c.W, c.d, slot, i)), dot);
       s = dot * c.scale_log2;

@@ -19,10 +19,11 @@ constexpr int kMaxGR = kEncMaxGR; // max G and r
 
 // ---- token sources ---------------------------------------------------------------------------
 template <typename T>
-struct CacheChunk {   // the C oldest live tokens of rollout b, logical order
-  const T* cache; int b, Hkv, d, W, tiled, s0;
+struct CacheChunk {   // the C oldest live thinking tokens of rollout b, logical order
+  const T* cache; int b, Hkv, d, W, tiled, s0, n_sink, Wr;
   __device__ float get(int which, int tok, int kk) const {
-    int slot = s0 + tok; if (slot >= W) slot -= W;
+    int slot = s0 + tok; if (slot >= Wr) slot -= Wr;
+    slot += n_sink;
     const int h = kk / d, i = kk - h * d;
     const T* slab = cache + (size_t)(b * Hkv + h) * pt_slab_elems(W, d);
     const size_t off = which == 0 ? pt_k_off(tiled, W, d, slot, i) : pt_v_off(tiled, W, d, slot, i);
@@ -115,8 +116,8 @@ __global__ __launch_bounds__(kThreads) void step_prologue_kernel(PtDev c, int do
   T* cache = (T*)c.cache;
   const bool act = !active || active[b];
 
-  if (act && do_evict && len - base == c.W) {
-    CacheChunk<T> src{cache, b, c.Hkv, c.d, c.W, c.tiled, (int)(base % c.W)};
+  if (act && do_evict && len - base == c.Wr) {
+    CacheChunk<T> src{cache, b, c.Hkv, c.d, c.W, c.tiled, (int)(base % c.Wr), c.n_sink, c.Wr};
     float sacc[16];
     T* dbg = dbg_chunk ? dbg_chunk + (size_t)b * 2 * c.C * dkv : nullptr;
     encode_chunk<T>(sm, src, c.C, dkv, c.G, c.r, c.Qa, (const T*)c.WaK, (const T*)c.WaV, dbg, sacc);
@@ -127,10 +128,10 @@ __global__ __launch_bounds__(kThreads) void step_prologue_kernel(PtDev c, int do
   }
 
   if (act && do_append) {
-    if (len - base >= c.W) {
+    if (len - base >= c.Wr) {
       if (t == 0) atomicOr(c.err, PTENC_DEVERR_APPEND_FULL);
     } else {
-      const int slot = (int)(len % c.W);
+      const int slot = c.n_sink + (int)(len % c.Wr);
       for (int idx = t; idx < dkv; idx += kThreads) {
         const int h = idx / c.d, i = idx - h * c.d;
         T* slab = cache + (size_t)(b * c.Hkv + h) * pt_slab_elems(c.W, c.d);
@@ -155,26 +156,73 @@ __global__ void reset_kernel(PtDev c, const uint8_t* __restrict__ mask, int clea
   if (mask && !mask[b]) return;
   const int n = c.G * c.r;
   for (int i = threadIdx.x; i < n; i += blockDim.x) c.S[(size_t)b * n + i] = c.S0[i];
-  if (threadIdx.x == 0) { c.len[b] = 0; c.base[b] = 0; }
+  if (threadIdx.x == 0) { c.len[b] = 0; c.base[b] = 0; c.n_prompt[b] = 0; }
 }
 
 template <typename T>
 __global__ void gather_kernel(PtDev c, T* __restrict__ Kout, T* __restrict__ Vout) {
   const int slab = blockIdx.x, b = slab / c.Hkv;
   const long long len = c.len[b], base = c.base[b];
-  const int n_live = (int)(len - base), s0 = (int)(base % c.W);
+  const int n_live = (int)(len - base), s0 = (int)(base % c.Wr), P = c.n_prompt[b];
   const T* src = (const T*)c.cache + (size_t)slab * pt_slab_elems(c.W, c.d);
   for (int j = blockIdx.y; j < c.W; j += gridDim.y) {
-    int slot = s0 + j; if (slot >= c.W) slot -= c.W;
+    int slot = j;                                  // question tokens first ...
+    if (j >= P) { slot = s0 + (j - P); if (slot >= c.Wr) slot -= c.Wr; slot += c.n_sink; }   // ... then the ring
     for (int i = threadIdx.x; i < c.d; i += blockDim.x) {
       const size_t o = ((size_t)slab * c.W + j) * c.d + i;
-      if (j < n_live) {
+      if (j < P + n_live) {
         Kout[o] = src[pt_k_off(c.tiled, c.W, c.d, slot, i)];
         Vout[o] = src[pt_v_off(c.tiled, c.W, c.d, slot, i)];
       } else {
         Kout[o] = (T)0; Vout[o] = (T)0;
       }
     }
+  }
+}
+
+// Question tokens [B, p_max, H_kv, d] into the reserved slots: one workgroup per (slab, 32 tokens).
+// The 32 x d tile is staged in LDS so that the tiled layout is written in whole 16-byte vectors.
+template <typename T>
+__global__ __launch_bounds__(256) void prefill_kernel(PtDev c, const T* __restrict__ kin, const T* __restrict__ vin,
+                                                      int p_max) {
+  __shared__ T tile[32][256 + 8];
+  const int slab = blockIdx.x, b = slab / c.Hkv, h = slab - b * c.Hkv, j0 = blockIdx.y * 32;
+  const int P = c.n_prompt[b];
+  if (j0 >= P) return;
+  const int n = min(32, P - j0);
+  T* dst = (T*)c.cache + (size_t)slab * pt_slab_elems(c.W, c.d);
+  for (int which = 0; which < 2; ++which) {
+    const T* in = which == 0 ? kin : vin;
+    for (int idx = threadIdx.x; idx < 32 * c.d; idx += blockDim.x) {
+      const int tk = idx / c.d, i = idx - tk * c.d;
+      tile[tk][i] = tk < n ? in[(((size_t)b * p_max + j0 + tk) * c.Hkv + h) * c.d + i] : (T)0;
+    }
+    __syncthreads();
+    if (c.tiled) {
+      // d = 128: 512 vectors of 8 elements for the two K tiles, 512 for the token-minor V part
+      typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+      union { u32x4 u; uint16_t s[8]; } vec;
+      uint16_t* g = (uint16_t*)dst + (size_t)(j0 >> 5) * PT_GROUP_ELEMS + which * 4096;
+      for (int vi = threadIdx.x; vi < 512; vi += blockDim.x) {
+        if (which == 0) {
+          const int t = vi >> 8, cc = (vi >> 6) & 3, kgrp = (vi >> 4) & 3, m = vi & 15;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) vec.s[e] = (uint16_t)tile[16 * t + m][32 * cc + 8 * kgrp + e];
+        } else {
+          const int it = vi >> 6, kgrp = (vi >> 4) & 3, m = vi & 15;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) vec.s[e] = (uint16_t)tile[(e >> 2) * 16 + 4 * kgrp + (e & 3)][16 * it + m];
+        }
+        *(u32x4*)(g + (size_t)vi * 8) = vec.u;
+      }
+    } else {
+      for (int idx = threadIdx.x; idx < n * c.d; idx += blockDim.x) {
+        const int tk = idx / c.d, i = idx - tk * c.d;
+        const size_t off = which == 0 ? pt_k_off(0, c.W, c.d, j0 + tk, i) : pt_v_off(0, c.W, c.d, j0 + tk, i);
+        dst[off] = tile[tk][i];
+      }
+    }
+    __syncthreads();
   }
 }
 
@@ -234,6 +282,15 @@ hipError_t pt_launch_gather(const PtDev& c, void* K, void* V, hipStream_t s) {
     hipLaunchKernelGGL(gather_kernel<float>, grid, dim3(threads), 0, s, c, (float*)K, (float*)V);
   else
     hipLaunchKernelGGL(gather_kernel<uint16_t>, grid, dim3(threads), 0, s, c, (uint16_t*)K, (uint16_t*)V);
+  return hipGetLastError();
+}
+
+hipError_t pt_launch_prefill(const PtDev& c, const void* k, const void* v, int p_max, hipStream_t s) {
+  dim3 grid(c.B * c.Hkv, (c.n_sink + 31) / 32);
+  if (c.dtype == PTENC_F32)
+    hipLaunchKernelGGL(prefill_kernel<float>, grid, dim3(256), 0, s, c, (const float*)k, (const float*)v, p_max);
+  else
+    hipLaunchKernelGGL(prefill_kernel<uint16_t>, grid, dim3(256), 0, s, c, (const uint16_t*)k, (const uint16_t*)v, p_max);
   return hipGetLastError();
 }
 

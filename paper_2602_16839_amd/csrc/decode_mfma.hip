@@ -75,7 +75,9 @@ struct Acc {
   float m, l;      // running max (base-2 domain) and this lane's share of the running sum
 };
 
-__device__ inline void process_group(Frag& f, const Op q[4], Acc& a, int visit, int off0, int n_live,
+// jg = logical index of the group's first slot within its region (question tokens or ring walk),
+// n_live = number of live logical indices of that region.
+__device__ inline void process_group(Frag& f, const Op q[4], Acc& a, int jg, int n_live,
                                      float scale_log2, int kgrp) {
   f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -83,8 +85,6 @@ __device__ inline void process_group(Frag& f, const Op q[4], Acc& a, int visit, 
     s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.k0[c].h, q[c].h, s0, 0, 0, 0);
     s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.k1[c].h, q[c].h, s1, 0, 0, 0);
   }
-  // logical index of the group's first slot relative to the oldest live token
-  const int jg = visit * PT_GROUP_TOKENS - off0;
   const bool interior = jg >= 0 && jg + PT_GROUP_TOKENS <= n_live;   // wave-uniform
   float s[8];
   if (interior) {
@@ -228,7 +228,7 @@ union StepSmem {
 __device__ inline void encode_head_share(const PtDev& c, StepSmem& sm, const u32x4* __restrict__ slab_p, int slab,
                                          int hkv, int s0, int lane, int wave) {
   const int n = lane & 15, kgrp = lane >> 4;
-  const int g0 = s0 >> 5, off0 = s0 & 31, NG = c.W >> 5;
+  const int g0 = s0 >> 5, off0 = s0 & 31, NG = c.Wr >> 5, gs = c.n_sink >> 5;   // s0: ring-relative slot
   const int n_vis = (off0 + c.C + PT_GROUP_TOKENS - 1) >> 5;
   const int RP = c.n_rt * 16;
   float* partK = c.enc_part + (size_t)slab * 2 * c.C * RP;
@@ -240,7 +240,7 @@ __device__ inline void encode_head_share(const PtDev& c, StepSmem& sm, const u32
     int pg = g0 + vis;
     if (pg >= NG) pg -= NG;
     if (pg >= NG) pg -= NG;
-    const u32x4* grp = slab_p + (size_t)pg * (PT_GROUP_ELEMS / 8);
+    const u32x4* grp = slab_p + (size_t)(gs + pg) * (PT_GROUP_ELEMS / 8);
     // V part -> LDS as stored (the operand needs 8 consecutive columns of one token, which the
     // token-minor layout scatters)
 #pragma unroll
@@ -325,18 +325,21 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(PtDev c, St
 
   // counters as the step finds them, and as it leaves them
   const long long len0 = c.len[b], base0 = c.base[b];
-  const bool evicting = act && a.do_evict && (len0 - base0 == c.W);
+  const bool evicting = act && a.do_evict && (len0 - base0 == c.Wr);
   const long long base1 = base0 + (evicting ? c.C : 0);
-  const bool append_full = act && a.do_append && (len0 - base1 >= c.W);
+  const bool append_full = act && a.do_append && (len0 - base1 >= c.Wr);
   const bool appending = act && a.do_append && !append_full;
   const long long len1 = len0 + (appending ? 1 : 0);
 
-  // the live window this step attends over, as a walk over 32-slot groups
+  // what this step attends over, as a walk over 32-slot groups: first the groups of the question
+  // tokens (slots 0 .. P-1), then the ring of thinking tokens from its oldest live slot
+  const int P = act ? c.n_prompt[b] : 0;
   const int n_live = act ? (int)(len1 - base1) : 0;
-  const int s0 = (int)(base1 % c.W);
+  const int s0 = (int)(base1 % c.Wr);            // ring-relative slot of the oldest live position
   const int g0 = s0 >> 5, off0 = s0 & 31;
-  const int NG = c.W >> 5;
-  const int n_visits = n_live > 0 ? (off0 + n_live + PT_GROUP_TOKENS - 1) >> 5 : 0;
+  const int NG = c.Wr >> 5, gs = c.n_sink >> 5;
+  const int n_sink_vis = (P + PT_GROUP_TOKENS - 1) >> 5;
+  const int n_visits = n_sink_vis + (n_live > 0 ? (off0 + n_live + PT_GROUP_TOKENS - 1) >> 5 : 0);
   const int per = (n_visits + c.n_splits - 1) / c.n_splits;
   const int v0 = split * per, v1 = min(n_visits, v0 + per);
   // the split whose range ends with the newest position evicts / appends for this KV head
@@ -346,7 +349,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(PtDev c, St
 
   if (owner && (evicting || appending)) {
     if (evicting) {
-      const int s0e = (int)(base0 % c.W);   // slot of the oldest token of the chunk
+      const int s0e = (int)(base0 % c.Wr);  // ring-relative slot of the oldest token of the chunk
       encode_head_share(c, sm, slab_p, slab, hkv, s0e, lane, wave);
       if (a.dbg_chunk) {
         const int dkv = c.Hkv * 128;
@@ -355,7 +358,8 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(PtDev c, St
         uint16_t* dV = dK + (size_t)c.C * dkv;
         for (int idx = tid; idx < c.C * 128; idx += kWaves * 64) {
           const int j = idx >> 7, i = idx & 127;
-          int slot = s0e + j; if (slot >= c.W) slot -= c.W;
+          int slot = s0e + j; if (slot >= c.Wr) slot -= c.Wr;
+          slot += c.n_sink;
           dK[(size_t)j * dkv + i] = src[pt_k_off(1, c.W, 128, slot, i)];
           dV[(size_t)j * dkv + i] = src[pt_v_off(1, c.W, 128, slot, i)];
         }
@@ -368,7 +372,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(PtDev c, St
       Op kp[4];
       uint16_t vp[8];
       load_newest(kp, vp, a.knew, a.vnew, ((size_t)b * c.Hkv + hkv) * 128, n, kgrp);
-      store_newest((uint16_t*)slab_p, c.W, (int)(len0 % c.W), kp, vp, n, kgrp);
+      store_newest((uint16_t*)slab_p, c.W, c.n_sink + (int)(len0 % c.Wr), kp, vp, n, kgrp);
     }
   }
   if (append_full && owner && hkv == 0 && tid == 0) atomicOr(c.err, PTENC_DEVERR_APPEND_FULL);
@@ -382,7 +386,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(PtDev c, St
 
     if (v0 < v1) {
       const bool patch = appending && owner;       // this workgroup's range ends with the new token
-      const int p_visit = n_visits - 1, p_tl = (int)(len0 % c.W) & 31;
+      const int p_visit = n_visits - 1, p_tl = (int)(len0 % c.Wr) & 31;
       Op kp[4];
       uint16_t vp[8];
       if (patch) load_newest(kp, vp, a.knew, a.vnew, ((size_t)b * c.Hkv + hkv) * 128, n, kgrp);
@@ -396,11 +400,20 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(PtDev c, St
         for (int cc = 0; cc < 4; ++cc) qf[cc].u = u32x4{0u, 0u, 0u, 0u};
       }
       auto grp_ptr = [&](int visit) {
-        int pg = g0 + visit;
-        if (pg >= NG) pg -= NG;
-        if (pg >= NG) pg -= NG;   // a full ring that starts mid-group visits its first group twice
+        int pg = visit;                       // question tokens: group `visit`
+        if (visit >= n_sink_vis) {
+          pg = g0 + visit - n_sink_vis;
+          if (pg >= NG) pg -= NG;
+          if (pg >= NG) pg -= NG;             // a full ring that starts mid-group visits its first group twice
+          pg += gs;
+        }
         return (const u32x4*)slab_p + (size_t)pg * (PT_GROUP_ELEMS / 8);
       };
+      // logical index of a visit's first slot within its region, and that region's live count
+      auto visit_jg = [&](int visit) {
+        return visit < n_sink_vis ? visit * PT_GROUP_TOKENS : (visit - n_sink_vis) * PT_GROUP_TOKENS - off0;
+      };
+      auto visit_lim = [&](int visit) { return visit < n_sink_vis ? P : n_live; };
       int i = v0 + wave;
       Frag fa, fb;
       if (i < v1) load_group<NT>(fa, grp_ptr(i), lane);
@@ -408,18 +421,19 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(PtDev c, St
         int nx = i + kWaves;
         if (nx < v1) load_group<NT>(fb, grp_ptr(nx), lane);
         if (patch && i == p_visit) patch_newest(fa, kp, vp, p_tl, n, kgrp);
-        process_group(fa, qf, acc, i, off0, n_live, c.scale_log2, kgrp);
+        process_group(fa, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp);
         i = nx;
         if (i >= v1) break;
         nx = i + kWaves;
         if (nx < v1) load_group<NT>(fa, grp_ptr(nx), lane);
         if (patch && i == p_visit) patch_newest(fb, kp, vp, p_tl, n, kgrp);
-        process_group(fb, qf, acc, i, off0, n_live, c.scale_log2, kgrp);
+        process_group(fb, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp);
         i = nx;
       }
       // the store of the new token rides behind the walk: its inputs arrived long ago, and the
       // chunk of an evicting step was read before anything could overwrite its oldest slot
-      if (patch && wave == 0) store_newest((uint16_t*)slab_p, c.W, (int)(len0 % c.W), kp, vp, n, kgrp);
+      if (patch && wave == 0)
+        store_newest((uint16_t*)slab_p, c.W, c.n_sink + (int)(len0 % c.Wr), kp, vp, n, kgrp);
     }
 
     // ---- merge the 4 wavefronts through LDS ----
@@ -518,7 +532,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(PtDev c, St
 #pragma unroll
       for (int x = 0; x < 8; ++x) r.h[x] = (__bf16)(o[x] * inv);
       *(u32x4*)(a.out + row * 128 + part * 8) = r.u;
-      if (act && n_live == 0 && part == 0 && qn == 0 && hkv == 0) atomicOr(c.err, PTENC_DEVERR_ATTEND_EMPTY);
+      if (act && n_live + P == 0 && part == 0 && qn == 0 && hkv == 0) atomicOr(c.err, PTENC_DEVERR_ATTEND_EMPTY);
     }
   }
 

@@ -11,7 +11,7 @@ namespace {
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct StateLayout {
-  size_t S, Qa, S0, len, base, len2, base2, err, tick_rollout, tick_slab, WKp, WVp, total;
+  size_t S, Qa, S0, len, base, len2, base2, n_prompt, err, tick_rollout, tick_slab, WKp, WVp, total;
 };
 
 StateLayout state_layout(const ptenc_config& c) {
@@ -25,6 +25,7 @@ StateLayout state_layout(const ptenc_config& c) {
   L.base = off; off = align256(off + sizeof(long long) * c.batch);
   L.len2 = off;  off = align256(off + sizeof(long long) * c.batch);
   L.base2 = off; off = align256(off + sizeof(long long) * c.batch);
+  L.n_prompt = off; off = align256(off + sizeof(int) * c.batch);
   L.err = off;  off = align256(off + sizeof(int));
   L.tick_rollout = off; off = align256(off + sizeof(int) * c.batch);
   L.tick_slab = off;    off = align256(off + sizeof(int) * c.batch * c.n_kv_heads);
@@ -39,12 +40,12 @@ ptenc_status check_config(const ptenc_config* c) {
   if (!c) return PTENC_ERR_INVALID_ARG;
   if (c->batch < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 1) return PTENC_ERR_INVALID_ARG;
   if (c->n_q_heads % c->n_kv_heads != 0) return PTENC_ERR_INVALID_ARG;
-  if (c->window < 1 || c->chunk < 1 || c->chunk > c->window) return PTENC_ERR_INVALID_ARG;
+  if (c->window < 1 || c->n_sink < 0 || c->n_sink >= c->window) return PTENC_ERR_INVALID_ARG;
+  if (c->chunk < 1 || c->chunk > c->window - c->n_sink) return PTENC_ERR_INVALID_ARG;
   if (c->n_global < 1 || c->rank < 1) return PTENC_ERR_INVALID_ARG;
   if (c->dtype != PTENC_F32 && c->dtype != PTENC_BF16) return PTENC_ERR_INVALID_ARG;
   if (c->norm_mode < PTENC_NORM_FROBENIUS || c->norm_mode > PTENC_NORM_NONE) return PTENC_ERR_INVALID_ARG;
   if (!(c->norm_eps >= 0.f) || !(c->softmax_scale >= 0.f) || isinf(c->softmax_scale)) return PTENC_ERR_INVALID_ARG;
-  if (c->n_sink != 0) return PTENC_ERR_UNSUPPORTED;
   if (c->head_dim > 256 || c->n_global > 64 || c->rank > 64) return PTENC_ERR_UNSUPPORTED;
   if ((size_t)c->batch * c->n_q_heads > 0x7fffffffu / PTENC_MAX_SPLITS) return PTENC_ERR_UNSUPPORTED;
   return PTENC_OK;
@@ -62,7 +63,7 @@ size_t enc_part_bytes(const ptenc_config& c) {
 }
 
 bool mfma_attn_applies(const ptenc_config& c) {
-  return c.dtype == PTENC_BF16 && c.head_dim == 128 && c.window % 32 == 0 &&
+  return c.dtype == PTENC_BF16 && c.head_dim == 128 && c.window % 32 == 0 && c.n_sink % 32 == 0 &&
          c.n_q_heads / c.n_kv_heads <= 16;
 }
 
@@ -139,6 +140,7 @@ ptenc_status ptenc_create(const ptenc_config* cfg, void* d_cache, void* d_state,
   PtDev& d = x->dev;
   d.B = cfg->batch; d.Hq = cfg->n_q_heads; d.Hkv = cfg->n_kv_heads; d.d = cfg->head_dim;
   d.W = cfg->window; d.C = cfg->chunk; d.G = cfg->n_global; d.r = cfg->rank;
+  d.n_sink = cfg->n_sink; d.Wr = cfg->window - cfg->n_sink;
   d.group = cfg->n_q_heads / cfg->n_kv_heads;
   d.dtype = cfg->dtype;
   d.tiled = mfma_attn_applies(*cfg) ? 1 : 0;
@@ -150,6 +152,7 @@ ptenc_status ptenc_create(const ptenc_config* cfg, void* d_cache, void* d_state,
   d.S = (float*)(sp + L.S); d.Qa = (float*)(sp + L.Qa); d.S0 = (float*)(sp + L.S0);
   d.len = (long long*)(sp + L.len); d.base = (long long*)(sp + L.base); d.err = (int*)(sp + L.err);
   d.len_nx = (long long*)(sp + L.len2); d.base_nx = (long long*)(sp + L.base2);
+  d.n_prompt = (int*)(sp + L.n_prompt);
   d.partial = (float*)d_scratch;
   d.enc_part = (float*)((char*)d_scratch + partial_bytes(*cfg));
   d.WaK = nullptr; d.WaV = nullptr;
@@ -218,6 +221,31 @@ ptenc_status ptenc_reset(ptenc_ctx* ctx, const uint8_t* d_mask, void* stream) {
   if (!ctx) return PTENC_ERR_INVALID_ARG;
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
   return hip_status(pt_launch_reset(ctx->dev, d_mask, d_mask == nullptr, S(stream)));
+}
+
+ptenc_status ptenc_prefill(ptenc_ctx* ctx, const void* d_k, const void* d_v, const int32_t* h_prompt_len,
+                           int32_t p_max, void* stream) {
+  if (!ctx || !d_k || !d_v || !h_prompt_len || p_max < 1) return PTENC_ERR_INVALID_ARG;
+  if (!ctx->encoder_set) return PTENC_ERR_STATE;
+  for (int b = 0; b < ctx->cfg.batch; ++b)
+    if (h_prompt_len[b] < 0 || h_prompt_len[b] > ctx->cfg.n_sink || h_prompt_len[b] > p_max) return PTENC_ERR_INVALID_ARG;
+  if (hipMemcpyAsync(ctx->dev.n_prompt, h_prompt_len, sizeof(int) * ctx->cfg.batch, hipMemcpyHostToDevice, S(stream)) !=
+      hipSuccess)
+    return PTENC_ERR_HIP;
+  if (ctx->cfg.n_sink > 0) {
+    hipError_t e = pt_launch_prefill(ctx->dev, d_k, d_v, p_max, S(stream));
+    if (e != hipSuccess) return PTENC_ERR_HIP;
+  }
+  // the host array may be pageable and reused by the caller right after return
+  return hip_status(hipStreamSynchronize(S(stream)));
+}
+
+ptenc_status ptenc_get_prompt_len(ptenc_ctx* ctx, int32_t* h_prompt_len, void* stream) {
+  if (!ctx || !h_prompt_len) return PTENC_ERR_INVALID_ARG;
+  if (hipMemcpyAsync(h_prompt_len, ctx->dev.n_prompt, sizeof(int) * ctx->cfg.batch, hipMemcpyDeviceToHost, S(stream)) !=
+      hipSuccess)
+    return PTENC_ERR_HIP;
+  return hip_status(hipStreamSynchronize(S(stream)));
 }
 
 ptenc_status ptenc_cache_append(ptenc_ctx* ctx, const void* d_k, const void* d_v, const uint8_t* d_active,
@@ -297,7 +325,7 @@ ptenc_status ptenc_get_counters(ptenc_ctx* ctx, int64_t* h_len, int64_t* h_base,
 ptenc_status ptenc_set_counters(ptenc_ctx* ctx, const int64_t* h_len, const int64_t* h_base, void* stream) {
   if (!ctx || !h_len || !h_base) return PTENC_ERR_INVALID_ARG;
   for (int b = 0; b < ctx->cfg.batch; ++b)
-    if (h_base[b] < 0 || h_len[b] < h_base[b] || h_len[b] - h_base[b] > ctx->cfg.window) return PTENC_ERR_INVALID_ARG;
+    if (h_base[b] < 0 || h_len[b] < h_base[b] || h_len[b] - h_base[b] > ctx->dev.Wr) return PTENC_ERR_INVALID_ARG;
   const size_t n = sizeof(long long) * ctx->cfg.batch;
   if (hipMemcpyAsync(ctx->dev.len, h_len, n, hipMemcpyHostToDevice, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
   if (hipMemcpyAsync(ctx->dev.base, h_base, n, hipMemcpyHostToDevice, S(stream)) != hipSuccess) return PTENC_ERR_HIP;

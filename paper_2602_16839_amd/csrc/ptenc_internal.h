@@ -11,6 +11,8 @@
 // ------------------------------------------------------------------------------------------
 struct PtDev {
   int B, Hq, Hkv, d, W, C, G, r;
+  int n_sink;         // slots 0 .. n_sink-1 of every slab hold question tokens (kept for good)
+  int Wr;             // W - n_sink: capacity of the ring of thinking tokens behind them
   int group;          // H_q / H_kv
   int dtype;          // ptenc_dtype
   int tiled;          // 1: bf16 d=128 MFMA-tiled cache layout, 0: row-major
@@ -26,6 +28,7 @@ struct PtDev {
   long long* base;    // [B]
   long long* len_nx;  // [B]  where a kernel that advances the counters writes them (all rollouts,
   long long* base_nx; //      changed or not); the host swaps the pairs after such a launch
+  int* n_prompt;      // [B]  question tokens held in the reserved slots
   int* err;           // sticky error word
   float* partial;     // [rows][n_splits][2 + d]: (m, l, unnormalised out) per window split
   const void* WaK;    // [H_kv*d, r] borrowed
@@ -56,7 +59,8 @@ struct ptenc_ctx {
 // Physical cache layout.
 //
 // The cache is an array of slabs, one per (rollout b, KV head h): slab = b * H_kv + h, each of
-// 2 * W * d elements.
+// 2 * W * d elements, W slots.  Slots 0 .. n_sink-1 hold the rollout's question tokens (token j in
+// slot j); thinking-token position p lives in slot n_sink + p mod (W - n_sink).
 //
 // Row-major layout (fp32, or bf16 shapes the MFMA kernel does not take):
 //   K[slot][i] at slot * d + i,  V[slot][i] at W * d + slot * d + i.
@@ -128,6 +132,7 @@ hipError_t pt_launch_step_prologue(const PtDev& c, bool do_evict, bool do_append
                                    const void* k, const void* v, const uint8_t* active, void* dbg_chunk,
                                    hipStream_t s);
 hipError_t pt_launch_gather(const PtDev& c, void* K, void* V, hipStream_t s);
+hipError_t pt_launch_prefill(const PtDev& c, const void* k, const void* v, int p_max, hipStream_t s);
 hipError_t pt_launch_encoder_init(const PtDev& c, const void* qg, const void* WaQ, const void* kg,
                                   const void* vg, hipStream_t s);
 hipError_t pt_launch_attn_generic(const PtDev& c, const void* q, void* out, const uint8_t* active,

@@ -44,6 +44,7 @@ STREAM_Q, STREAM_K, STREAM_V = 0, 1, 2
 STREAM_QG, STREAM_KG, STREAM_VG = 3, 4, 5
 STREAM_WAQ, STREAM_WAK, STREAM_WAV = 6, 7, 8
 STREAM_HEAD_SCALE_Q, STREAM_HEAD_SCALE_K, STREAM_HEAD_SCALE_V = 9, 10, 11
+STREAM_PROMPT_K, STREAM_PROMPT_V, STREAM_PROMPT_LEN = 12, 13, 14
 
 
 def _signed(x: int) -> int:
@@ -149,6 +150,7 @@ class Workload:
     seed: int
     per_head_scale: bool = False   # per-head factor U(0.5, 1.5), independent for q, k and v heads
     ragged: bool = False           # per-rollout length lognormal(median 3000, sigma 0.8), capped at `steps`
+    n_sink: int = 0                # cache slots reserved for question tokens (kept for good); part of `window`
     n_global: int = 32             # G global tokens (paper, Experimental Setup: 32 global tokens)
     rank: int = 32                 # r latent width (paper, Experimental Setup: LoRA rank 32)
 
@@ -179,6 +181,9 @@ WORKLOADS = {
     "qwen7b": Workload("qwen7b", "bf16", 128, 28, 4, 128, 4096, 128, 8192, 0.088, 1003, per_head_scale=True),
     "llama8b": Workload("llama8b", "bf16", 256, 32, 8, 128, 8192, 256, 16384, 0.088, 1004),
     "ragged": Workload("ragged", "bf16", 512, 16, 2, 128, 1024, 64, 16384, 0.088, 1005, ragged=True),
+    # the qwen7b shape with 512 slots reserved for question tokens in front of the same 4096-token window
+    "qwen7b_sink": Workload("qwen7b_sink", "bf16", 128, 28, 4, 128, 4096 + 512, 128, 8192, 0.088, 1006,
+                            per_head_scale=True, n_sink=512),
 }
 
 
@@ -222,6 +227,24 @@ def encoder_params(wl: Workload, device="cpu", with_global_kv: bool = True):
         p["k_g"] = g2(STREAM_KG, G, wl.d_kv, wl.scale)
         p["v_g"] = g2(STREAM_VG, G, wl.d_kv, wl.scale)
     return p
+
+
+def prompt_lengths(wl: Workload) -> np.ndarray:
+    """Question length per rollout (int32 ``[B]``), uniform in [n_sink/4, n_sink], seeded; zeros without a sink."""
+    if wl.n_sink == 0:
+        return np.zeros(wl.batch, dtype=np.int32)
+    lo = max(1, wl.n_sink // 4)
+    u = np.array([uniform01_int(wl.seed, STREAM_PROMPT_LEN, b) for b in range(wl.batch)])
+    return np.minimum(lo + np.floor(u * (wl.n_sink - lo + 1)), wl.n_sink).astype(np.int32)
+
+
+def prompt_kv(wl: Workload, device="cpu"):
+    """Question keys and values ``[B, n_sink, H_kv, d]`` (rows beyond a rollout's length are simply unused)."""
+    sq, sk, sv = qkv_head_scales(wl)
+    kw = dict(dtype=wl.torch_dtype, device=device)
+    k = gaussian(wl.seed, STREAM_PROMPT_K, 0, wl.batch, wl.n_sink, wl.n_kv_heads, wl.head_dim, wl.scale, sk, **kw)
+    v = gaussian(wl.seed, STREAM_PROMPT_V, 0, wl.batch, wl.n_sink, wl.n_kv_heads, wl.head_dim, wl.scale, sv, **kw)
+    return k, v
 
 
 def rollout_lengths(wl: Workload) -> np.ndarray:

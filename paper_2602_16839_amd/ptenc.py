@@ -29,6 +29,7 @@ EXPORTS = [
     "ptenc_decode_run", "ptenc_get_counters", "ptenc_set_counters", "ptenc_get_state", "ptenc_set_state",
     "ptenc_get_encoder_state", "ptenc_gather_window", "ptenc_cache_offset", "ptenc_poll_error",
     "ptenc_get_plan", "ptenc_status_string", "ptenc_util_stream_read", "ptenc_util_copy",
+    "ptenc_prefill", "ptenc_get_prompt_len",
 ]
 
 
@@ -83,6 +84,8 @@ def lib() -> C.CDLL:
             "ptenc_get_plan": [vp, P(i32), P(i32), P(i32)],
             "ptenc_util_stream_read": [vp, sz, vp, i32, vp],
             "ptenc_util_copy": [vp, vp, sz, i32, vp],
+            "ptenc_prefill": [vp, vp, vp, vp, i32, vp],
+            "ptenc_get_prompt_len": [vp, vp, vp],
         }
         for name, args in sig.items():
             fn = getattr(L, name)
@@ -143,6 +146,19 @@ def ptenc_set_encoder(ctx, q_g, WaQ, WaK, WaV, k_g=None, v_g=None):
 
 def ptenc_reset(ctx, mask=None):
     _check(lib().ptenc_reset(ctx, _ptr(mask), _stream()), "ptenc_reset")
+
+
+def ptenc_prefill(ctx, k, v, prompt_len):
+    """k, v: [B, p_max, H_kv, d] device tensors; prompt_len: B host integers."""
+    pl = np.ascontiguousarray(prompt_len, dtype=np.int32)
+    _check(lib().ptenc_prefill(ctx, _ptr(k), _ptr(v), pl.ctypes.data_as(C.c_void_p), int(k.shape[1]), _stream()),
+           "ptenc_prefill")
+
+
+def ptenc_get_prompt_len(ctx, batch: int):
+    pl = np.zeros(batch, dtype=np.int32)
+    _check(lib().ptenc_get_prompt_len(ctx, pl.ctypes.data_as(C.c_void_p), _stream()), "ptenc_get_prompt_len")
+    return pl
 
 
 def ptenc_cache_append(ctx, k, v, active=None):
@@ -238,8 +254,8 @@ class Layer:
 
     def __init__(self, batch, n_q_heads, n_kv_heads, head_dim, window, chunk, dtype=torch.bfloat16,
                  n_global=32, rank=32, norm_mode=NORM_FROBENIUS, norm_eps=0.0, softmax_scale=0.0,
-                 device="cuda:0", poison_cache=False):
-        self.cfg = Config(batch, n_q_heads, n_kv_heads, head_dim, window, chunk, 0, n_global, rank,
+                 device="cuda:0", poison_cache=False, n_sink=0):
+        self.cfg = Config(batch, n_q_heads, n_kv_heads, head_dim, window, chunk, n_sink, n_global, rank,
                           F32 if dtype == torch.float32 else BF16, norm_mode, norm_eps, softmax_scale)
         self.dtype, self.device = dtype, torch.device(device)
         cb, sb, xb = ptenc_query_sizes(self.cfg)
@@ -272,6 +288,12 @@ class Layer:
 
     def reset(self, mask=None):
         ptenc_reset(self.ctx, mask)
+
+    def prefill(self, k, v, prompt_len):
+        ptenc_prefill(self.ctx, k, v, prompt_len)
+
+    def prompt_len(self):
+        return ptenc_get_prompt_len(self.ctx, self.B)
 
     def append(self, k, v, active=None):
         ptenc_cache_append(self.ctx, k, v, active)

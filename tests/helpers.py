@@ -45,14 +45,15 @@ def make_oracle(wl, enc, norm_mode=po.NORM_FROBENIUS, keep_chunks=False, softmax
     e = {k: f64(v) for k, v in enc.items()}
     return po.OracleLayer(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
                           e["q_g"], e["WaQ"], e["WaK"], e["WaV"], e.get("k_g"), e.get("v_g"),
-                          norm_mode=norm_mode, keep_chunks=keep_chunks, softmax_scale=softmax_scale)
+                          norm_mode=norm_mode, keep_chunks=keep_chunks, softmax_scale=softmax_scale,
+                          n_sink=wl.n_sink)
 
 
 def make_layer(wl, enc, norm_mode=0, splits=0, force_generic=False, poison=True, softmax_scale=0.0):
     from paper_2602_16839_amd import ptenc
     layer = ptenc.Layer(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
                         dtype=wl.torch_dtype, n_global=wl.n_global, rank=wl.rank, norm_mode=norm_mode,
-                        softmax_scale=softmax_scale, poison_cache=poison)
+                        softmax_scale=softmax_scale, poison_cache=poison, n_sink=wl.n_sink)
     if force_generic:
         layer.set_option(ptenc.OPT_FORCE_GENERIC, 1)
     if splits:
@@ -63,13 +64,26 @@ def make_layer(wl, enc, norm_mode=0, splits=0, force_generic=False, poison=True,
     return layer
 
 
+def prefill_both(wl, orc, layer, prompt_len=None):
+    """Question tokens into both sides; returns the lengths used."""
+    pl = I.prompt_lengths(wl) if prompt_len is None else np.asarray(prompt_len, dtype=np.int32)
+    pk, pv = I.prompt_kv(wl)
+    for b in range(wl.batch):
+        orc.prefill(b, f64(pk[b, :pl[b]]), f64(pv[b, :pl[b]]))
+    layer.prefill(pk.cuda(), pv.cuda(), pl)
+    assert np.array_equal(layer.prompt_len(), pl)
+    return pl
+
+
 def run_both(wl, T, norm_mode=0, splits=0, force_generic=False, lengths=None, with_global_kv=True,
-             q_gain=1.0, check_every=1):
+             q_gain=1.0, check_every=1, prompt_len=None):
     """Decode T steps on the oracle and on the HIP layer; compare outputs every `check_every` steps,
     counters every step, and the state at the end.  Returns (layer, oracle)."""
     enc = I.encoder_params(wl, with_global_kv=with_global_kv)
     orc = make_oracle(wl, enc, norm_mode=norm_mode)
     layer = make_layer(wl, enc, norm_mode=norm_mode, splits=splits, force_generic=force_generic)
+    if wl.n_sink:
+        prefill_both(wl, orc, layer, prompt_len)
     q, k, v = I.qkv_steps(wl, 0, T)
     if q_gain != 1.0:
         q = (q.float() * q_gain).to(q.dtype)

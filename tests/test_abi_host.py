@@ -44,7 +44,9 @@ def test_query_sizes():
     (dict(dtype=7), ptenc.ERR_INVALID_ARG),
     (dict(norm_mode=3), ptenc.ERR_INVALID_ARG),
     (dict(softmax_scale=-1.0), ptenc.ERR_INVALID_ARG),
-    (dict(n_sink=4), ptenc.ERR_UNSUPPORTED),
+    (dict(n_sink=64), ptenc.ERR_INVALID_ARG),
+    (dict(n_sink=-1), ptenc.ERR_INVALID_ARG),
+    (dict(n_sink=56, chunk=16), ptenc.ERR_INVALID_ARG),
     (dict(head_dim=512), ptenc.ERR_UNSUPPORTED),
     (dict(rank=65), ptenc.ERR_UNSUPPORTED),
     (dict(n_global=128), ptenc.ERR_UNSUPPORTED),
@@ -102,6 +104,18 @@ def test_cache_layout_is_a_bijection(c):
     with pytest.raises(ptenc.PtencError):
         ptenc.ptenc_cache_offset(h, 0, 0, c.window, 0, 0)
     ptenc.ptenc_destroy(h)
+
+
+def test_reserved_question_slots_choose_the_plan():
+    # the MFMA path needs whole 32-slot groups on both sides of the boundary
+    for n_sink, kernel in ((0, 1), (32, 1), (4, 0), (16, 0)):
+        st, h = _host_ctx(cfg(window=96, n_sink=n_sink))
+        assert st == ptenc.OK
+        assert ptenc.ptenc_get_plan(h)[0] == kernel
+        L = ptenc.lib()
+        assert L.ptenc_prefill(h, C.c_void_p(256), C.c_void_p(256), None, 8, None) == ptenc.ERR_INVALID_ARG
+        assert L.ptenc_prefill(h, C.c_void_p(256), C.c_void_p(256), C.c_void_p(256), 8, None) == ptenc.ERR_STATE
+        ptenc.ptenc_destroy(h)
 
 
 def test_tiled_layout_matches_its_documented_formula():

@@ -20,9 +20,12 @@ def _run_full(wl, sample_steps, seg_steps):
     dev = torch.device("cuda:0")
     enc = I.encoder_params(wl, device=dev)
     layer = ptenc.Layer(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
-                        dtype=wl.torch_dtype, n_global=wl.n_global, rank=wl.rank, poison_cache=True)
+                        dtype=wl.torch_dtype, n_global=wl.n_global, rank=wl.rank, poison_cache=True, n_sink=wl.n_sink)
     layer.set_encoder(enc["q_g"], enc["WaQ"], enc["WaK"], enc["WaV"], enc["k_g"], enc["v_g"])
     layer.reset()
+    if wl.n_sink:
+        pk, pv = I.prompt_kv(wl, device=dev)
+        layer.prefill(pk, pv, I.prompt_lengths(wl))
     lengths = I.rollout_lengths(wl)
     T = int(lengths.max())
     len_dev = torch.from_numpy(lengths).to(dev).view(1, -1)
@@ -47,16 +50,21 @@ def _oracle_out(wl, b, t, L):
     """Attention output of rollout b at decode step t (1-based), from regenerated inputs."""
     if t > L:
         return np.zeros((wl.n_q_heads, wl.head_dim))
-    E = evicted_closed_form(t, wl.window, wl.chunk)
+    E = evicted_closed_form(t, wl.window - wl.n_sink, wl.chunk)
     q, k, v = I.qkv_steps(wl, E, t, b0=b, b1=b + 1)
-    return po.attend(H.f64(q[-1, 0]), list(H.f64(k[:, 0])), list(H.f64(v[:, 0])))
+    keys, values = list(H.f64(k[:, 0])), list(H.f64(v[:, 0]))
+    if wl.n_sink:                                   # question tokens come first and never leave
+        P = int(I.prompt_lengths(wl)[b])
+        pk, pv = I.prompt_kv(wl)
+        keys, values = list(H.f64(pk[b, :P])) + keys, list(H.f64(pv[b, :P])) + values
+    return po.attend(H.f64(q[-1, 0]), keys, values)
 
 
 def _oracle_state(wl, b, L, enc):
     """S of rollout b after L decode steps: every eviction replayed from regenerated inputs."""
     e = {k: H.f64(v) for k, v in enc.items()}
     Q_a, S = po.init_state(e["q_g"], e["WaQ"], e["WaK"], e["WaV"], e["k_g"], e["v_g"])
-    E = evicted_closed_form(L, wl.window, wl.chunk)
+    E = evicted_closed_form(L, wl.window - wl.n_sink, wl.chunk)
     if E:
         _, k, v = I.qkv_steps(wl, 0, E, b0=b, b1=b + 1)
         k, v = H.f64(k[:, 0]).reshape(E, -1), H.f64(v[:, 0]).reshape(E, -1)
@@ -71,7 +79,7 @@ def _check(wl, sample_b, sample_t, seg_steps):
     # counters, all rollouts, against the closed forms
     ln, base = layer.counters()
     assert np.array_equal(ln, lengths)
-    assert np.array_equal(base, np.array([evicted_closed_form(int(L), wl.window, wl.chunk) for L in lengths]))
+    assert np.array_equal(base, np.array([evicted_closed_form(int(L), wl.window - wl.n_sink, wl.chunk) for L in lengths]))
     # sampled outputs
     for t in sample_t:
         got = H.f64(kept[t])
@@ -85,9 +93,10 @@ def _check(wl, sample_b, sample_t, seg_steps):
     for b in sample_b:
         L = int(lengths[b])
         E, n = int(base[b]), int(ln[b] - base[b])
+        P = int(I.prompt_lengths(wl)[b])
         _, k, v = I.qkv_steps(wl, E, L, b0=b, b1=b + 1)
-        assert torch.equal(Kw[b, :, :n].cpu(), k[:, 0].transpose(0, 1)), "ring K of rollout %d" % b
-        assert torch.equal(Vw[b, :, :n].cpu(), v[:, 0].transpose(0, 1)), "ring V of rollout %d" % b
+        assert torch.equal(Kw[b, :, P:P + n].cpu(), k[:, 0].transpose(0, 1)), "ring K of rollout %d" % b
+        assert torch.equal(Vw[b, :, P:P + n].cpu(), v[:, 0].transpose(0, 1)), "ring V of rollout %d" % b
         H.assert_close(S[b], _oracle_state(wl, b, L, enc), H.S_ABS, H.S_REL, "%s S b=%d" % (wl.name, b))
     return layer
 
@@ -105,6 +114,15 @@ def test_qwen7b_full_run_sampled():
     W, C, T = wl.window, wl.chunk, wl.steps
     layer = _check(wl, [0, 77, 127], [1, 31, 1000, W, W + 1, W + C, 6001, T], seg_steps=1024)
     assert layer.plan() == (1, 1, 1)
+
+
+def test_qwen7b_with_question_tokens_full_run_sampled():
+    # 512 reserved slots (ragged question lengths 128..512) in front of the same 4096-token window
+    wl = I.WORKLOADS["qwen7b_sink"]
+    R, C, T = wl.window - wl.n_sink, wl.chunk, wl.steps
+    pl = I.prompt_lengths(wl)
+    assert pl.min() >= 128 and pl.max() <= 512 and len(set(pl.tolist())) > 32
+    _check(wl, [0, 64, 127], [1, R, R + 1, T], seg_steps=1024)
 
 
 def test_llama8b_full_run_sampled():

@@ -103,20 +103,69 @@ def test_init_state_matches_oracle():
 
 
 # ------------------------------------------------------------------------------------------------
+# pinned question tokens in front of the sliding window
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("splits", [1, 3])
+def test_question_tokens_mfma_path(splits):
+    # 64 reserved slots + a ring of 96; question lengths: full, one token, mid-group, none
+    wl = small("qwen7b", batch=4, n_q_heads=14, n_kv_heads=2, window=160, n_sink=64, chunk=40, steps=260)
+    layer, orc = H.run_both(wl, wl.steps, splits=splits, prompt_len=[64, 1, 37, 0])
+    assert layer.plan()[:2] == (1, splits)
+    Kw, Vw = layer.gather_window()
+    for b in range(wl.batch):
+        Ko, Vo = orc.window_kv(b)
+        n = Ko.shape[0]
+        assert np.array_equal(H.f64(Kw[b, :, :n]), Ko.transpose(1, 0, 2)) and not Kw[b, :, n:].any()
+        assert np.array_equal(H.f64(Vw[b, :, :n]), Vo.transpose(1, 0, 2)) and not Vw[b, :, n:].any()
+
+
+def test_question_tokens_generic_paths():
+    # fp32, and bf16 with reserved slots that are not whole groups (row-major layout)
+    wl = small("tiny_f32", batch=3, window=40, n_sink=8, chunk=5, steps=100)
+    layer, _ = H.run_both(wl, wl.steps, prompt_len=[8, 0, 3])
+    assert layer.plan()[0] == 0
+    wl = small("qwen3b", batch=2, n_q_heads=4, n_kv_heads=2, window=69, n_sink=5, chunk=16, steps=150)
+    layer, _ = H.run_both(wl, wl.steps, splits=2, prompt_len=[5, 2])
+    assert layer.plan()[0] == 0
+
+
+def test_question_tokens_only_no_thinking_tokens_yet():
+    # attention right after prefill, before any append: softmax over the question tokens alone
+    wl = small("qwen3b", batch=2, n_q_heads=8, n_kv_heads=2, window=96, n_sink=32, chunk=16, steps=4)
+    enc = I.encoder_params(wl)
+    orc, layer = H.make_oracle(wl, enc), H.make_layer(wl, enc)
+    H.prefill_both(wl, orc, layer, [32, 7])
+    q, _, _ = I.qkv_steps(wl, 0, 1)
+    out = layer.attend(q[0].cuda())
+    for b in range(2):
+        H.assert_close(H.f64(out[b]), orc.attend(b, H.f64(q[0, b])), H.BF16_ABS, H.BF16_REL, "prompt-only b=%d" % b)
+    assert layer.poll_error() == 0
+    layer.reset()                                  # reset forgets the question tokens
+    assert layer.prompt_len().tolist() == [0, 0]
+
+
+# ------------------------------------------------------------------------------------------------
 # integer / byte work: bit exact
 # ------------------------------------------------------------------------------------------------
 
-@pytest.mark.parametrize("name,W,C", [("tiny_f32", 24, 5), ("qwen3b", 64, 24), ("qwen3b", 40, 40)])
-def test_ring_contents_and_eviction_order_are_bit_exact(name, W, C):
-    wl = small(name, batch=3, window=W, chunk=C, steps=3 * W + 5)
+@pytest.mark.parametrize("name,W,C,n_sink", [("tiny_f32", 24, 5, 0), ("qwen3b", 64, 24, 0), ("qwen3b", 40, 40, 0),
+                                             ("qwen3b", 96, 24, 32), ("tiny_f32", 30, 4, 7)])
+def test_ring_contents_and_eviction_order_are_bit_exact(name, W, C, n_sink):
+    wl = small(name, batch=3, window=W, chunk=C, steps=3 * W + 5, n_sink=n_sink)
     if name != "tiny_f32":
         wl = wl.replace(n_q_heads=4, n_kv_heads=2)
     enc = I.encoder_params(wl)
     layer = H.make_layer(wl, enc)
-    ring = RingModel(wl.batch, W, C)
+    ring = RingModel(wl.batch, W, C, n_sink=n_sink)
     q, k, v = I.qkv_steps(wl, 0, wl.steps)
     kd, vd = k.cuda(), v.cuda()
     dkv = wl.d_kv
+    pl = np.zeros(wl.batch, dtype=np.int64)
+    if n_sink:
+        pl = I.prompt_lengths(wl)
+        pk, pv = I.prompt_kv(wl)
+        layer.prefill(pk.cuda(), pv.cuda(), pl)
     for t in range(wl.steps):
         dbg = torch.zeros((wl.batch, 2, C, dkv), dtype=wl.torch_dtype, device="cuda")
         layer.evict_encode(dbg_chunk=dbg)
@@ -138,11 +187,15 @@ def test_ring_contents_and_eviction_order_are_bit_exact(name, W, C):
             for b in range(wl.batch):
                 n = int(ring.n_live()[b])
                 p0 = int(ring.base[b])
-                assert torch.equal(Kw[b, :, :n].cpu(), k[p0:p0 + n, b].transpose(0, 1))
-                assert torch.equal(Vw[b, :, :n].cpu(), v[p0:p0 + n, b].transpose(0, 1))
-                assert not Kw[b, :, n:].any() and not Vw[b, :, n:].any()
+                P = int(pl[b])
+                if P:
+                    assert torch.equal(Kw[b, :, :P].cpu(), pk[b, :P].transpose(0, 1))
+                    assert torch.equal(Vw[b, :, :P].cpu(), pv[b, :P].transpose(0, 1))
+                assert torch.equal(Kw[b, :, P:P + n].cpu(), k[p0:p0 + n, b].transpose(0, 1))
+                assert torch.equal(Vw[b, :, P:P + n].cpu(), v[p0:p0 + n, b].transpose(0, 1))
+                assert not Kw[b, :, P + n:].any() and not Vw[b, :, P + n:].any()
                 # physical slots: slot s holds position slot_pos[b, s] (documented offset function)
-                for s in (0, W // 2, W - 1):
+                for s in (n_sink, n_sink + (W - n_sink) // 2, W - 1):
                     p = int(ring.slot_pos[b, s])
                     if p >= 0:
                         off = layer.cache_offset(b, 1 if wl.n_kv_heads > 1 else 0, s, 3, 0)
