@@ -34,9 +34,9 @@ def n_live_at(t: int, W: int, C: int) -> int:
     return t if t <= W else W - C + ((t - W - 1) % C) + 1
 
 
-def attention_bytes_per_step(wl, lengths, steps: int):
-    """Algorithmic bytes of the attention launch of every step: K and V stream over the live
-    window plus q in and out out, for every active rollout."""
+def attention_bytes_per_step(wl, lengths, steps: int, prompt_len=None):
+    """Algorithmic bytes of the attention launch of every step: K and V stream over the question
+    tokens and the live window plus q in and out out, for every active rollout."""
     import numpy as np
     s = wl.elem_bytes
     per_tok = 2 * wl.d_kv * s
@@ -44,12 +44,13 @@ def attention_bytes_per_step(wl, lengths, steps: int):
     out = np.zeros(steps, dtype=np.float64)
     act = np.zeros(steps, dtype=np.int64)
     uniq = {}
-    for L in lengths.tolist():
-        uniq[L] = uniq.get(L, 0) + 1
-    nl = np.array([n_live_at(t, wl.window, wl.chunk) for t in range(1, steps + 1)], dtype=np.float64)
-    for L, cnt in uniq.items():
+    pls = [0] * len(lengths) if prompt_len is None else prompt_len.tolist()
+    for L, P in zip(lengths.tolist(), pls):
+        uniq[(L, P)] = uniq.get((L, P), 0) + 1
+    nl = np.array([n_live_at(t, wl.window - wl.n_sink, wl.chunk) for t in range(1, steps + 1)], dtype=np.float64)
+    for (L, P), cnt in uniq.items():
         n = min(L, steps)
-        out[:n] += cnt * (per_tok * nl[:n] + qo)
+        out[:n] += cnt * (per_tok * (nl[:n] + P) + qo)
         act[:n] += cnt
     return out, act
 
@@ -62,7 +63,8 @@ def prologue_bytes_total(wl, lengths, steps: int) -> float:
     for L in lengths.tolist():
         n = min(L, steps)
         tot += n * 2 * wl.d_kv * s
-        ev = 0 if n <= wl.window else math.ceil((n - wl.window) / wl.chunk)
+        ring = wl.window - wl.n_sink
+        ev = 0 if n <= ring else math.ceil((n - ring) / wl.chunk)
         tot += ev * (2 * wl.chunk * wl.d_kv * s + 2 * wl.n_global * wl.rank * 4)
     return tot
 
@@ -159,17 +161,27 @@ def main() -> int:
     enc = I.encoder_params(wl, device=dev)
 
     layer = ptenc.Layer(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
-                        dtype=wl.torch_dtype, n_global=wl.n_global, rank=wl.rank)
+                        dtype=wl.torch_dtype, n_global=wl.n_global, rank=wl.rank, n_sink=wl.n_sink)
+    prompt_len = I.prompt_lengths(wl) if wl.n_sink else None
+    if wl.n_sink:
+        pk, pv = I.prompt_kv(wl, device=dev)
+
+    def start_run():
+        # an empty cache, question tokens (if the workload has any) prefilled: not part of the timed steps
+        layer.reset()
+        if wl.n_sink:
+            layer.prefill(pk, pv, prompt_len)
+
     if args.splits:
         layer.set_option(ptenc.OPT_SPLITS, args.splits)
     layer.set_encoder(enc["q_g"], enc["WaQ"], enc["WaK"], enc["WaV"], enc["k_g"], enc["v_g"])
     attn_kernel, n_splits, _ = layer.plan()
 
     # ---- warmup, then the timed run from an empty cache ----
-    layer.reset()
+    start_run()
     if Wu:
         layer.run(q[:Wu], k[:Wu], v[:Wu], out[:Wu], None if active is None else active[:Wu])
-    layer.reset()
+    start_run()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     w0 = time.perf_counter()
@@ -184,7 +196,7 @@ def main() -> int:
     ln, base = layer.counters()
     assert np.array_equal(ln, np.minimum(lengths, K)), "counters after the run are not the step count"
 
-    abytes, act = attention_bytes_per_step(wl, lengths, K)
+    abytes, act = attention_bytes_per_step(wl, lengths, K, prompt_len)
     tokens = int(act.sum())
     value = tokens / (total_ms * 1e-3)
     all_bytes = float(abytes.sum()) + prologue_bytes_total(wl, lengths, K)
@@ -194,7 +206,7 @@ def main() -> int:
     roofline = None
     fused = attn_kernel == 1
     if not args.no_kernel_timing:
-        layer.reset()
+        start_run()
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
         for t in range(K):
             a = None if active is None else active[t]
@@ -233,9 +245,11 @@ def main() -> int:
         "dtype": wl.dtype, "data": "synthetic",
         "config": {
             "workload": "%s-shaped layer: B %d rollouts, %d Q / %d KV heads, head_dim %d, window %d, chunk %d, "
-                        "%d decode steps from an empty cache%s" % (
+                        "%d decode steps from an empty cache%s%s" % (
                             wl.name, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk, K,
-                            ", ragged lengths" if wl.ragged else ""),
+                            ", ragged lengths" if wl.ragged else "",
+                            ", %d slots reserved for question tokens (128..%d per rollout, prefilled)" % (
+                                wl.n_sink, wl.n_sink) if wl.n_sink else ""),
             "name": wl.name, "batch": wl.batch, "window": wl.window, "chunk": wl.chunk, "tokens": tokens,
             "attn_kernel": "mfma" if attn_kernel == 1 else "generic", "window_splits": n_splits,
             "parallelism": "single GPU",
