@@ -76,6 +76,8 @@ enum { PTENC_DEVERR_APPEND_FULL = 1, PTENC_DEVERR_ATTEND_EMPTY = 2 };
 typedef enum {
   PTENC_OPT_SPLITS = 0,       /* window splits per (rollout, KV head); 1..PTENC_MAX_SPLITS; 0 = heuristic */
   PTENC_OPT_FORCE_GENERIC = 1,/* 1 = use the plain ALU attention kernel even where the MFMA one applies */
+  PTENC_OPT_WAVES = 3,        /* wavefronts per workgroup of the MFMA kernel: 4, or 8 (taken only with at most
+                                 8 query heads per KV head); 0 = heuristic */
   PTENC_OPT_NONTEMPORAL = 2   /* K/V stream with non-temporal loads: 1 / 0; -1 = heuristic (on when the cache
                                  exceeds the memory-side cache) */
 } ptenc_option;

@@ -96,7 +96,7 @@ __device__ void encode_chunk(EncSmem& sm, const Src& src, int n_tok, int dkv, in
       }
     }
     __syncthreads();
-    pt_encode_accumulate(sm.tail, Qa, G, r, ntok, sacc);
+    pt_encode_accumulate<kThreads>(sm.tail, Qa, G, r, ntok, sacc);
   }
 }
 
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(kThreads) void step_prologue_kernel(PtDev c, int do
     T* dbg = dbg_chunk ? dbg_chunk + (size_t)b * 2 * c.C * dkv : nullptr;
     encode_chunk<T>(sm, src, c.C, dkv, c.G, c.r, c.Qa, (const T*)c.WaK, (const T*)c.WaV, dbg, sacc);
     // S <- Normalize(S + S')   (Our Approach, the update rule)
-    pt_state_update(c, b, sacc, &sm.Ws[0][0], sm.tail.red);
+    pt_state_update<kThreads>(c, b, sacc, &sm.Ws[0][0], sm.tail.red);
     base += c.C;
     __syncthreads();   // every read of the evicted slots is done before the append below
   }

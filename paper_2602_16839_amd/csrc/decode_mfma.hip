@@ -49,7 +49,7 @@ struct Frag {   // one 32-token group in registers: 64 VGPRs
   Op k0[4], k1[4], v[8];
 };
 
-constexpr int kWaves = 4;
+constexpr int kEncWaves = 4;   // wavefronts of a workgroup that take part in the encoder's MFMA share
 constexpr int kORow = 132;   // padded fp32 row of the cross-wave merge buffer
 
 // NT = non-temporal loads: the stream is read once per step, so it should not displace anything
@@ -215,18 +215,22 @@ struct StepArgs {
   int do_evict, do_append, do_attend;
 };
 
+// WAVES wavefronts per workgroup: 4 (up to 16 query heads per KV head) or 8 (up to 8), the same LDS.
+template <int WAVES>
 union StepSmem {
   struct {
-    float o[kWaves][16][kORow];
-    float m[kWaves][16], l[kWaves][16];
+    float o[WAVES][64 / WAVES][kORow];
+    float m[WAVES][64 / WAVES], l[WAVES][64 / WAVES];
   } merge;
-  uint16_t vstage[kWaves][4096];   // one group's V part per wavefront (encoder operand transposition)
+  uint16_t vstage[kEncWaves][4096];   // one group's V part per wavefront (encoder operand transposition)
   EncTailSmem enc;   // Ka and Va (contiguous, >= G*r floats) double as the row-norm staging area
 };
 
 // This head's share of K_a and V_a for the chunk [base, base + C): rows j = logical token, RP columns.
-__device__ inline void encode_head_share(const PtDev& c, StepSmem& sm, const u32x4* __restrict__ slab_p, int slab,
-                                         int hkv, int s0, int lane, int wave) {
+template <int WAVES>
+__device__ inline void encode_head_share(const PtDev& c, StepSmem<WAVES>& sm, const u32x4* __restrict__ slab_p,
+                                         int slab, int hkv, int s0, int lane, int wave) {
+  if (wave >= kEncWaves) return;
   const int n = lane & 15, kgrp = lane >> 4;
   const int g0 = s0 >> 5, off0 = s0 & 31, NG = c.Wr >> 5, gs = c.n_sink >> 5;   // s0: ring-relative slot
   const int n_vis = (off0 + c.C + PT_GROUP_TOKENS - 1) >> 5;
@@ -236,7 +240,7 @@ __device__ inline void encode_head_share(const PtDev& c, StepSmem& sm, const u32
   const u32x4* WKp = (const u32x4*)c.WKp + (size_t)hkv * 4 * 4 * 64;
   const u32x4* WVp = (const u32x4*)c.WVp + (size_t)hkv * 4 * 4 * 64;
   uint16_t* vs = sm.vstage[wave];
-  for (int vis = wave; vis < n_vis; vis += kWaves) {
+  for (int vis = wave; vis < n_vis; vis += kEncWaves) {
     int pg = g0 + vis;
     if (pg >= NG) pg -= NG;
     if (pg >= NG) pg -= NG;
@@ -287,7 +291,9 @@ __device__ inline void encode_head_share(const PtDev& c, StepSmem& sm, const u32
 
 // Last workgroup of a rollout: K_a, V_a = sum of the heads' shares (head order), S' = (Q_a K_a^T) V_a,
 // S <- Normalize(S + S').
-__device__ inline void encode_finish(const PtDev& c, StepSmem& sm, int b) {
+template <int WAVES>
+__device__ inline void encode_finish(const PtDev& c, StepSmem<WAVES>& sm, int b) {
+  constexpr int THREADS = WAVES * 64;
   const int t = threadIdx.x;
   const int RP = c.n_rt * 16;
   float sacc[16];
@@ -296,7 +302,7 @@ __device__ inline void encode_finish(const PtDev& c, StepSmem& sm, int b) {
   const float* part0 = c.enc_part + (size_t)b * c.Hkv * 2 * c.C * RP;
   for (int sub0 = 0; sub0 < c.C; sub0 += kEncSub) {
     const int ntok = min(kEncSub, c.C - sub0);
-    for (int idx = t; idx < 2 * kEncSub * RP; idx += kEncThreads) {
+    for (int idx = t; idx < 2 * kEncSub * RP; idx += THREADS) {
       const int which = idx / (kEncSub * RP), rem = idx - which * (kEncSub * RP);
       const int tk = rem / RP, col = rem - tk * RP;
       float v = 0.f;
@@ -306,19 +312,22 @@ __device__ inline void encode_finish(const PtDev& c, StepSmem& sm, int b) {
       (which == 0 ? sm.enc.Ka : sm.enc.Va)[tk][col] = v;
     }
     __syncthreads();
-    pt_encode_accumulate(sm.enc, c.Qa, c.G, c.r, ntok, sacc);
+    pt_encode_accumulate<THREADS>(sm.enc, c.Qa, c.G, c.r, ntok, sacc);
   }
-  pt_state_update(c, b, sacc, &sm.enc.Ka[0][0], sm.enc.red);
+  pt_state_update<THREADS>(c, b, sacc, &sm.enc.Ka[0][0], sm.enc.red);
 }
 
-template <bool NT>
-__global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(PtDev c, StepArgs a) {
-  __shared__ StepSmem sm;
+template <bool NT, int WAVES>
+__global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, StepArgs a) {
+  constexpr int kWaves = WAVES;
+  __shared__ StepSmem<WAVES> sm;
   __shared__ int sm_ticket;
 
   const int slab = blockIdx.x, split = blockIdx.y;
   const int b = slab / c.Hkv, hkv = slab - b * c.Hkv;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+  const int ns = c.n_splits;   // window splits
   const int n = lane & 15, kgrp = lane >> 4;
   const int g = c.group;
   const bool act = !a.active || a.active[b];
@@ -340,7 +349,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(PtDev c, St
   const int NG = c.Wr >> 5, gs = c.n_sink >> 5;
   const int n_sink_vis = (P + PT_GROUP_TOKENS - 1) >> 5;
   const int n_visits = n_sink_vis + (n_live > 0 ? (off0 + n_live + PT_GROUP_TOKENS - 1) >> 5 : 0);
-  const int per = (n_visits + c.n_splits - 1) / c.n_splits;
+  const int per = (n_visits + ns - 1) / ns;
   const int v0 = split * per, v1 = min(n_visits, v0 + per);
   // the split whose range ends with the newest position evicts / appends for this KV head
   const bool owner = split == (n_visits > 0 ? (n_visits - 1) / per : 0);
@@ -466,10 +475,10 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(PtDev c, St
       }
     }
     bool write_out = has_row;
-    if (c.n_splits > 1) {
+    if (ns > 1) {
       // park this split's (M, L, o); the last split to arrive merges all of them in split order
       if (has_row) {
-        float* po = c.partial + (row * c.n_splits + split) * (128 + 2);
+        float* po = c.partial + (row * ns + split) * (128 + 2);
         if (part == 0) st_agent2(po, M, L);
 #pragma unroll
         for (int x = 0; x < 4; ++x) st_agent2(po + 2 + part * 8 + 2 * x, o[2 * x], o[2 * x + 1]);
@@ -478,11 +487,11 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(PtDev c, St
       __syncthreads();
       if (tid == 0) sm_ticket = atomicAdd(c.tick_slab + slab, 1);
       __syncthreads();
-      const bool last = sm_ticket == c.n_splits - 1;
+      const bool last = sm_ticket == ns - 1;
       write_out = has_row && last;
       if (last) {
         if (has_row) {
-          const float* pp = c.partial + row * c.n_splits * (128 + 2);
+          const float* pp = c.partial + row * ns * (128 + 2);
           // statistics: lane `part` of the row's 16 lanes takes splits part and part + 16, all loads in
           // flight at once, then the 16 lanes exchange by shuffle
           float Ms[2], Ls[2];
@@ -490,7 +499,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(PtDev c, St
           for (int j = 0; j < 2; ++j) {
             const int s = part + 16 * j;
             Ms[j] = -INFINITY; Ls[j] = 0.f;
-            if (s < c.n_splits) ld_agent2(pp + (size_t)s * 130, Ms[j], Ls[j]);
+            if (s < ns) ld_agent2(pp + (size_t)s * 130, Ms[j], Ls[j]);
           }
           M = fmaxf(Ms[0], Ms[1]);
 #pragma unroll
@@ -503,18 +512,18 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(PtDev c, St
           for (int off = 1; off < 16; off <<= 1) L += __shfl_xor(L, off, 16);
 #pragma unroll
           for (int x = 0; x < 8; ++x) o[x] = 0.f;
-          for (int s0 = 0; s0 < c.n_splits; s0 += 4) {
+          for (int s0 = 0; s0 < ns; s0 += 4) {
             float t[4][8];
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-              if (s0 + j < c.n_splits) {
+              if (s0 + j < ns) {
 #pragma unroll
                 for (int x = 0; x < 4; ++x)
                   ld_agent2(pp + (size_t)(s0 + j) * 130 + 2 + part * 8 + 2 * x, t[j][2 * x], t[j][2 * x + 1]);
               }
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-              if (s0 + j < c.n_splits) {
+              if (s0 + j < ns) {
                 const int s = s0 + j;
                 const float f0 = __shfl(fs[0], s & 15, 16), f1 = __shfl(fs[1], s & 15, 16);
                 const float fw = (s >> 4) ? f1 : f0;
@@ -548,7 +557,7 @@ __global__ __launch_bounds__(kWaves * 64, 2) void decode_mfma_kernel(PtDev c, St
     __syncthreads();
     if (tid == 0) sm_ticket = atomicAdd(c.tick_rollout + b, 1);
     __syncthreads();
-    if (sm_ticket == c.Hkv * c.n_splits - 1) {
+    if (sm_ticket == c.Hkv * ns - 1) {
       encode_finish(c, sm, b);
       if (tid == 0) c.tick_rollout[b] = 0;
     }
@@ -578,7 +587,7 @@ hipError_t pt_launch_pack_weights(const PtDev& c, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, bool do_evict, bool do_append, bool do_attend,
+hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bool do_evict, bool do_append, bool do_attend,
                                  const void* q, const void* k, const void* v, void* out, const uint8_t* active,
                                  void* dbg_chunk, hipStream_t s) {
   StepArgs a;
@@ -587,12 +596,16 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, bool do_evict
   a.active = active; a.dbg_chunk = (uint16_t*)dbg_chunk;
   a.do_evict = do_evict; a.do_append = do_append; a.do_attend = do_attend;
   // without attention there is nothing to split
+  // without attention there is nothing to split
   PtDev cc = c;
   if (!do_attend) cc.n_splits = 1;
   dim3 grid(cc.B * cc.Hkv, cc.n_splits);
-  if (nontemporal)
-    hipLaunchKernelGGL(decode_mfma_kernel<true>, grid, dim3(kWaves * 64), 0, s, cc, a);
-  else
-    hipLaunchKernelGGL(decode_mfma_kernel<false>, grid, dim3(kWaves * 64), 0, s, cc, a);
+  if (waves == 8) {
+    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 8>), grid, dim3(512), 0, s, cc, a);
+    else hipLaunchKernelGGL((decode_mfma_kernel<false, 8>), grid, dim3(512), 0, s, cc, a);
+  } else {
+    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 4>), grid, dim3(256), 0, s, cc, a);
+    else hipLaunchKernelGGL((decode_mfma_kernel<false, 4>), grid, dim3(256), 0, s, cc, a);
+  }
   return hipGetLastError();
 }

@@ -89,6 +89,13 @@ void replan(ptenc_ctx* x) {
   x->encode_kernel = x->attn_kernel;
   x->dev.n_splits = x->opt_splits > 0 ? x->opt_splits : heuristic_splits(x);
   // a cache that fits the 256 MiB memory-side cache is better served by ordinary loads
+  // 8 wavefronts per workgroup need the query group to fit 8 rows of the merge buffer; measured
+  // worth ~3 % when there is at most one workgroup per CU, a loss of as much when there are more
+  {
+    const long rows = (long)x->cfg.batch * x->cfg.n_kv_heads * x->dev.n_splits;
+    const int want = x->opt_waves ? x->opt_waves : (rows <= 256 ? 8 : 4);
+    x->waves = (want == 8 && x->dev.group <= 8) ? 8 : 4;
+  }
   x->nontemporal = x->opt_nontemporal >= 0 ? x->opt_nontemporal : (x->cache_bytes > ((size_t)192 << 20) ? 1 : 0);
 }
 
@@ -181,6 +188,10 @@ ptenc_status ptenc_set_option(ptenc_ctx* ctx, int32_t option, int32_t value) {
       if (value < -1 || value > 1) return PTENC_ERR_INVALID_ARG;
       ctx->opt_nontemporal = value;
       break;
+    case PTENC_OPT_WAVES:
+      if (value != 0 && value != 4 && value != 8) return PTENC_ERR_INVALID_ARG;
+      ctx->opt_waves = value;
+      break;
     case PTENC_OPT_FORCE_GENERIC:
       if (value != 0 && value != 1) return PTENC_ERR_INVALID_ARG;
       ctx->opt_force_generic = value;
@@ -254,7 +265,7 @@ ptenc_status ptenc_cache_append(ptenc_ctx* ctx, const void* d_k, const void* d_v
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
-    return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, false, true, false, nullptr, d_k, d_v,
+    return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, false, true, false, nullptr, d_k, d_v,
                                                nullptr, d_active, nullptr, S(stream)));
   }
   return advanced(ctx, pt_launch_step_prologue(ctx->dev, false, true, ctx->encode_kernel, d_k, d_v, d_active,
@@ -265,7 +276,7 @@ ptenc_status ptenc_evict_encode(ptenc_ctx* ctx, const uint8_t* d_active, void* d
   if (!ctx) return PTENC_ERR_INVALID_ARG;
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
   if (ctx->attn_kernel == 1)
-    return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, true, false, false, nullptr, nullptr,
+    return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, true, false, false, nullptr, nullptr,
                                                nullptr, nullptr, d_active, d_dbg_chunk, S(stream)));
   return advanced(ctx, pt_launch_step_prologue(ctx->dev, true, false, ctx->encode_kernel, nullptr, nullptr,
                                                d_active, d_dbg_chunk, S(stream)));
@@ -277,7 +288,7 @@ ptenc_status ptenc_decode_attn(ptenc_ctx* ctx, const void* d_q, void* d_out, con
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_q | (uintptr_t)d_out) & 15) return PTENC_ERR_INVALID_ARG;
-    return hip_status(pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, false, false, true, d_q, nullptr,
+    return hip_status(pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, false, false, true, d_q, nullptr,
                                             nullptr, d_out, d_active, nullptr, S(stream)));
   }
   return hip_status(pt_launch_attn_generic(ctx->dev, d_q, d_out, d_active, S(stream)));
@@ -289,7 +300,7 @@ ptenc_status ptenc_decode_step(ptenc_ctx* ctx, const void* d_q, const void* d_k,
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_q | (uintptr_t)d_out | (uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
-    return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, true, true, true, d_q, d_k, d_v, d_out,
+    return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, true, true, true, d_q, d_k, d_v, d_out,
                                                d_active, nullptr, S(stream)));
   }
   if (advanced(ctx, pt_launch_step_prologue(ctx->dev, true, true, ctx->encode_kernel, d_k, d_v, d_active, nullptr,

@@ -51,6 +51,8 @@ struct ptenc_ctx {
   int opt_force_generic;
   int opt_nontemporal;   // -1 = heuristic, 0, 1
   int nontemporal;       // resolved
+  int opt_waves;         // 0 = heuristic, 4, 8
+  int waves;             // resolved: wavefronts per workgroup of the MFMA kernel
   int attn_kernel;       // 0 generic, 1 mfma
   int encode_kernel;     // 0 generic, 1 mfma
 };
@@ -139,6 +141,6 @@ hipError_t pt_launch_attn_generic(const PtDev& c, const void* q, void* out, cons
                                   hipStream_t s);
 hipError_t pt_launch_combine(const PtDev& c, void* out, const uint8_t* active, hipStream_t s);
 hipError_t pt_launch_pack_weights(const PtDev& c, hipStream_t s);
-hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, bool do_evict, bool do_append, bool do_attend,
+hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bool do_evict, bool do_append, bool do_attend,
                                  const void* q, const void* k, const void* v, void* out, const uint8_t* active,
                                  void* dbg_chunk, hipStream_t s);

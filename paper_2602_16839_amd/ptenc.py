@@ -20,7 +20,7 @@ OK, ERR_INVALID_ARG, ERR_STATE, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM = range(6)
 F32, BF16 = 0, 1
 NORM_FROBENIUS, NORM_ROW_L2, NORM_NONE = 0, 1, 2
 DEVERR_APPEND_FULL, DEVERR_ATTEND_EMPTY = 1, 2
-OPT_SPLITS, OPT_FORCE_GENERIC, OPT_NONTEMPORAL = 0, 1, 2
+OPT_SPLITS, OPT_FORCE_GENERIC, OPT_NONTEMPORAL, OPT_WAVES = 0, 1, 2, 3
 MAX_SPLITS = 32
 
 EXPORTS = [

@@ -42,6 +42,17 @@ def test_many_window_splits_merge_in_kernel(splits):
     assert layer.plan()[:2] == (1, splits)
 
 
+@pytest.mark.parametrize("splits", [1, 2])
+def test_eight_wavefront_workgroups(splits):
+    # the 512-thread variant (query groups of at most 8): evictions, question tokens, splits
+    wl = small("qwen3b", batch=3, n_q_heads=16, n_kv_heads=2, window=352, n_sink=32, chunk=72, steps=800)
+    layer, _ = H.run_both(wl, wl.steps, splits=splits, waves=8, check_every=23, prompt_len=[32, 0, 9])
+    assert layer.plan()[:2] == (1, splits)
+    # a query group of 14 does not fit 8 rows: the request falls back to 4 wavefronts and still works
+    wl = small("qwen7b", batch=2, n_q_heads=28, n_kv_heads=2, window=96, chunk=32, steps=150)
+    H.run_both(wl, wl.steps, waves=8, check_every=11)
+
+
 def test_bf16_generic_path_small_window():
     wl = small("qwen3b", batch=2, n_q_heads=8, n_kv_heads=2, window=96, chunk=40, steps=250)
     layer, _ = H.run_both(wl, wl.steps, force_generic=True, splits=2)
