@@ -70,7 +70,7 @@ typedef enum { PTENC_F32 = 0, PTENC_BF16 = 1 } ptenc_dtype;
 typedef enum { PTENC_NORM_FROBENIUS = 0, PTENC_NORM_ROW_L2 = 1, PTENC_NORM_NONE = 2 } ptenc_norm;
 
 /* Bits of the sticky device error word. */
-enum { PTENC_DEVERR_APPEND_FULL = 1, PTENC_DEVERR_ATTEND_EMPTY = 2 };
+enum { PTENC_DEVERR_APPEND_FULL = 1, PTENC_DEVERR_ATTEND_EMPTY = 2, PTENC_DEVERR_BAD_ID = 4 };
 
 /* Tunables for ptenc_set_option. */
 typedef enum {
@@ -162,6 +162,21 @@ ptenc_status ptenc_decode_step(ptenc_ctx* ctx, const void* d_q, const void* d_k,
  * ptenc_decode_step; the loop runs on the host without synchronising. */
 ptenc_status ptenc_decode_run(ptenc_ctx* ctx, const void* d_q, const void* d_k, const void* d_v,
                               void* d_out, const uint8_t* d_active, int64_t n_steps, void* stream);
+
+/* One decode step for a compact list of rollouts (a rollout engine drops finished rollouts from its
+ * batch instead of masking them): d_ids is int32[n] on the DEVICE, distinct rollout indices in
+ * [0, B); q and out are [n, H_q, d], k and v [n, H_kv, d], row j belonging to rollout d_ids[j].
+ * Rollouts not listed are untouched.  Same result per listed rollout as ptenc_decode_step.  An id
+ * out of range sets PTENC_DEVERR_BAD_ID and its row is skipped; duplicate ids race.  0 <= n <= B. */
+ptenc_status ptenc_decode_step_ids(ptenc_ctx* ctx, const void* d_q, const void* d_k, const void* d_v,
+                                   void* d_out, const int32_t* d_ids, int32_t n, void* stream);
+
+/* n_steps such steps from concatenated buffers: step t uses rows h_row_offsets[t] ..
+ * h_row_offsets[t+1]-1 of q, k, v, out and d_ids (h_row_offsets: HOST int64[n_steps + 1],
+ * non-decreasing, starting at 0).  The loop runs on the host without synchronising. */
+ptenc_status ptenc_decode_run_ids(ptenc_ctx* ctx, const void* d_q, const void* d_k, const void* d_v,
+                                  void* d_out, const int32_t* d_ids, const int64_t* h_row_offsets,
+                                  int64_t n_steps, void* stream);
 
 /* Counters to / from host arrays of B int64 each.  set_counters requires
  * 0 <= base <= len <= base + W - n_sink for every rollout (used for resume and rotation tests). */

@@ -27,14 +27,19 @@ __device__ inline float block_reduce(float v, float* red, bool is_max) {
 
 template <typename T>
 __global__ __launch_bounds__(kThreads) void attn_generic_kernel(PtDev c, const T* __restrict__ q,
-                                                               const uint8_t* __restrict__ active) {
+                                                               const uint8_t* __restrict__ active,
+                                                               const int* __restrict__ ids) {
   __shared__ float qs[256];
   __shared__ float ps[kThreads];
   __shared__ int slots[kThreads];
   __shared__ float red[kThreads / 64];
-  const int bh = blockIdx.x, b = bh / c.Hq, h = bh - b * c.Hq, split = blockIdx.y, t = threadIdx.x;
+  // bh = (row of q and out, query head); the row's rollout is b = row, or ids[row]
+  const int bh = blockIdx.x, j_row = bh / c.Hq, h = bh - j_row * c.Hq, split = blockIdx.y, t = threadIdx.x;
   float* po = c.partial + ((size_t)bh * c.n_splits + split) * (c.d + 2);
-  const bool act = !active || active[b];
+  int b = j_row;
+  bool bad = false;
+  if (ids) { b = ids[j_row]; bad = (unsigned)b >= (unsigned)c.B; if (bad) b = 0; }
+  const bool act = !bad && (!active || active[b]);
   const long long len = c.len[b], base = c.base[b];
   // logical order: the P question tokens (slots 0 .. P-1), then the live ring positions
   const int P = act ? c.n_prompt[b] : 0;
@@ -82,16 +87,21 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(PtDev c, const T
 
 // Merge the window splits of one (rollout, query head) and write the output row.
 template <typename T>
-__global__ void combine_kernel(PtDev c, T* __restrict__ out, const uint8_t* __restrict__ active) {
-  const int bh = blockIdx.x, b = bh / c.Hq;
+__global__ void combine_kernel(PtDev c, T* __restrict__ out, const uint8_t* __restrict__ active,
+                               const int* __restrict__ ids) {
+  const int bh = blockIdx.x;
+  int b = bh / c.Hq;
+  bool bad = false;
+  if (ids) { b = ids[b]; bad = (unsigned)b >= (unsigned)c.B; if (bad) b = 0; }
   const float* pp = c.partial + (size_t)bh * c.n_splits * (c.d + 2);
-  const bool act = !active || active[b];
+  const bool act = !bad && (!active || active[b]);
   float M = -INFINITY;
   if (act)
     for (int s = 0; s < c.n_splits; ++s) M = fmaxf(M, pp[(size_t)s * (c.d + 2)]);
   if (M == -INFINITY) {
     for (int i = threadIdx.x; i < c.d; i += blockDim.x) pt_st<T>(out + (size_t)bh * c.d + i, 0.f);
     if (act && threadIdx.x == 0) atomicOr(c.err, PTENC_DEVERR_ATTEND_EMPTY);
+    if (bad && threadIdx.x == 0) atomicOr(c.err, PTENC_DEVERR_BAD_ID);
     return;
   }
   float L = 0.f;
@@ -112,23 +122,17 @@ __global__ void combine_kernel(PtDev c, T* __restrict__ out, const uint8_t* __re
 
 }  // namespace
 
-hipError_t pt_launch_combine(const PtDev& c, void* out, const uint8_t* active, hipStream_t s) {
-  const int threads = c.d <= 64 ? 64 : 128;
-  if (c.dtype == PTENC_F32)
-    hipLaunchKernelGGL(combine_kernel<float>, dim3(c.B * c.Hq), dim3(threads), 0, s, c, (float*)out, active);
-  else
-    hipLaunchKernelGGL(combine_kernel<uint16_t>, dim3(c.B * c.Hq), dim3(threads), 0, s, c, (uint16_t*)out, active);
-  return hipGetLastError();
-}
-
 hipError_t pt_launch_attn_generic(const PtDev& c, const void* q, void* out, const uint8_t* active,
-                                  hipStream_t s) {
-  dim3 grid(c.B * c.Hq, c.n_splits);
-  if (c.dtype == PTENC_F32)
-    hipLaunchKernelGGL(attn_generic_kernel<float>, grid, dim3(kThreads), 0, s, c, (const float*)q, active);
-  else
-    hipLaunchKernelGGL(attn_generic_kernel<uint16_t>, grid, dim3(kThreads), 0, s, c, (const uint16_t*)q, active);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  return pt_launch_combine(c, out, active, s);
+                                  const int* ids, int n_rows, hipStream_t s) {
+  const int rows = (ids ? n_rows : c.B) * c.Hq;
+  dim3 grid(rows, c.n_splits);
+  const int cthreads = c.d <= 64 ? 64 : 128;
+  if (c.dtype == PTENC_F32) {
+    hipLaunchKernelGGL(attn_generic_kernel<float>, grid, dim3(kThreads), 0, s, c, (const float*)q, active, ids);
+    hipLaunchKernelGGL(combine_kernel<float>, dim3(rows), dim3(cthreads), 0, s, c, (float*)out, active, ids);
+  } else {
+    hipLaunchKernelGGL(attn_generic_kernel<uint16_t>, grid, dim3(kThreads), 0, s, c, (const uint16_t*)q, active, ids);
+    hipLaunchKernelGGL(combine_kernel<uint16_t>, dim3(rows), dim3(cthreads), 0, s, c, (uint16_t*)out, active, ids);
+  }
+  return hipGetLastError();
 }

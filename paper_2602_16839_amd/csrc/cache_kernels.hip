@@ -106,9 +106,17 @@ __global__ __launch_bounds__(kThreads) void step_prologue_kernel(PtDev c, int do
                                                                 const T* __restrict__ knew,
                                                                 const T* __restrict__ vnew,
                                                                 const uint8_t* __restrict__ active,
-                                                                T* dbg_chunk) {
+                                                                T* dbg_chunk, const int* __restrict__ ids) {
   __shared__ EncSmem sm;
-  const int b = blockIdx.x, t = threadIdx.x;
+  const int j_row = blockIdx.x, t = threadIdx.x;   // row of k / v; rollout b = j_row, or ids[j_row]
+  int b = j_row;
+  if (ids) {
+    b = ids[j_row];
+    if ((unsigned)b >= (unsigned)c.B) {
+      if (t == 0) atomicOr(c.err, PTENC_DEVERR_BAD_ID);
+      return;
+    }
+  }
   const long long len = c.len[b];
   long long base = c.base[b];
   long long len1 = len;
@@ -135,15 +143,20 @@ __global__ __launch_bounds__(kThreads) void step_prologue_kernel(PtDev c, int do
       for (int idx = t; idx < dkv; idx += kThreads) {
         const int h = idx / c.d, i = idx - h * c.d;
         T* slab = cache + (size_t)(b * c.Hkv + h) * pt_slab_elems(c.W, c.d);
-        const size_t src = (size_t)b * dkv + idx;
+        const size_t src = (size_t)j_row * dkv + idx;
         slab[pt_k_off(c.tiled, c.W, c.d, slot, i)] = knew[src];
         slab[pt_v_off(c.tiled, c.W, c.d, slot, i)] = vnew[src];
       }
       len1 = len + 1;
     }
   }
-  // counters go to the other buffer, for every rollout, changed or not
-  if (t == 0) { c.len_nx[b] = len1; c.base_nx[b] = base; }
+  // counters go to the other buffer, for every rollout, changed or not; with a compact list (which
+  // would leave the unlisted rollouts out) they are written in place: this workgroup is the only
+  // one that touches rollout b in this kernel
+  if (t == 0) {
+    if (ids) { c.len[b] = len1; c.base[b] = base; }
+    else { c.len_nx[b] = len1; c.base_nx[b] = base; }
+  }
 }
 
 // ---- reset / gather -----------------------------------------------------------------------------
@@ -262,16 +275,16 @@ hipError_t pt_launch_reset(const PtDev& c, const uint8_t* mask, bool clear_err, 
   return hipGetLastError();
 }
 
-hipError_t pt_launch_step_prologue(const PtDev& c, bool do_evict, bool do_append, int encode_kernel,
+hipError_t pt_launch_step_prologue(const PtDev& c, bool do_evict, bool do_append,
                                    const void* k, const void* v, const uint8_t* active, void* dbg_chunk,
-                                   hipStream_t s) {
-  (void)encode_kernel;
+                                   const int* ids, int n_rows, hipStream_t s) {
+  const dim3 grid(ids ? n_rows : c.B);
   if (c.dtype == PTENC_F32)
-    hipLaunchKernelGGL(step_prologue_kernel<float>, dim3(c.B), dim3(kThreads), 0, s, c, do_evict ? 1 : 0,
-                       do_append ? 1 : 0, (const float*)k, (const float*)v, active, (float*)dbg_chunk);
+    hipLaunchKernelGGL(step_prologue_kernel<float>, grid, dim3(kThreads), 0, s, c, do_evict ? 1 : 0,
+                       do_append ? 1 : 0, (const float*)k, (const float*)v, active, (float*)dbg_chunk, ids);
   else
-    hipLaunchKernelGGL(step_prologue_kernel<uint16_t>, dim3(c.B), dim3(kThreads), 0, s, c, do_evict ? 1 : 0,
-                       do_append ? 1 : 0, (const uint16_t*)k, (const uint16_t*)v, active, (uint16_t*)dbg_chunk);
+    hipLaunchKernelGGL(step_prologue_kernel<uint16_t>, grid, dim3(kThreads), 0, s, c, do_evict ? 1 : 0,
+                       do_append ? 1 : 0, (const uint16_t*)k, (const uint16_t*)v, active, (uint16_t*)dbg_chunk, ids);
   return hipGetLastError();
 }
 

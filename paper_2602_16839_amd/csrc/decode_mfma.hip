@@ -212,6 +212,7 @@ struct StepArgs {
   const uint16_t* vnew;
   const uint8_t* active;   // [B] or null
   uint16_t* dbg_chunk;     // [B, 2, C, H_kv*128] or null
+  const int* ids;          // null, or the rollouts this launch works on: row j of q/k/v/out is rollout ids[j]
   int do_evict, do_append, do_attend;
 };
 
@@ -323,8 +324,17 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
   __shared__ StepSmem<WAVES> sm;
   __shared__ int sm_ticket;
 
-  const int slab = blockIdx.x, split = blockIdx.y;
-  const int b = slab / c.Hkv, hkv = slab - b * c.Hkv;
+  // row j of the launch (and of q / k / v / out) is rollout b: j itself, or ids[j] for a compact list
+  const int j_row = blockIdx.x / c.Hkv, hkv = blockIdx.x - j_row * c.Hkv, split = blockIdx.y;
+  int b = j_row;
+  if (a.ids) {
+    b = a.ids[j_row];
+    if ((unsigned)b >= (unsigned)c.B) {            // never index with a bad id: flag it and leave
+      if (threadIdx.x == 0 && hkv == 0 && split == 0) atomicOr(c.err, PTENC_DEVERR_BAD_ID);
+      return;
+    }
+  }
+  const int slab = b * c.Hkv + hkv;                // cache slab, scratch and arrival counters go by rollout
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
   const int ns = c.n_splits;   // window splits
@@ -380,7 +390,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
       // the walk, from the registers that also patch the last group)
       Op kp[4];
       uint16_t vp[8];
-      load_newest(kp, vp, a.knew, a.vnew, ((size_t)b * c.Hkv + hkv) * 128, n, kgrp);
+      load_newest(kp, vp, a.knew, a.vnew, ((size_t)j_row * c.Hkv + hkv) * 128, n, kgrp);
       store_newest((uint16_t*)slab_p, c.W, c.n_sink + (int)(len0 % c.Wr), kp, vp, n, kgrp);
     }
   }
@@ -398,10 +408,10 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
       const int p_visit = n_visits - 1, p_tl = (int)(len0 % c.Wr) & 31;
       Op kp[4];
       uint16_t vp[8];
-      if (patch) load_newest(kp, vp, a.knew, a.vnew, ((size_t)b * c.Hkv + hkv) * 128, n, kgrp);
+      if (patch) load_newest(kp, vp, a.knew, a.vnew, ((size_t)j_row * c.Hkv + hkv) * 128, n, kgrp);
       Op qf[4];
       if (n < g) {
-        const u32x4* qp = (const u32x4*)(a.q + ((size_t)b * c.Hq + hkv * g + n) * 128);
+        const u32x4* qp = (const u32x4*)(a.q + ((size_t)j_row * c.Hq + hkv * g + n) * 128);
 #pragma unroll
         for (int cc = 0; cc < 4; ++cc) qf[cc].u = qp[cc * 4 + kgrp];
       } else {
@@ -457,7 +467,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
 
     const int qn = tid >> 4, part = tid & 15;   // 16 threads per query, 8 columns each
     const bool has_row = qn < g;
-    const size_t row = (size_t)b * c.Hq + hkv * g + (has_row ? qn : 0);
+    const size_t row = (size_t)b * c.Hq + hkv * g + (has_row ? qn : 0);          // scratch row
+    const size_t row_io = (size_t)j_row * c.Hq + hkv * g + (has_row ? qn : 0);   // row of out
     float M = -INFINITY, L = 0.f, o[8];
 #pragma unroll
     for (int x = 0; x < 8; ++x) o[x] = 0.f;
@@ -540,26 +551,34 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
       Op r;
 #pragma unroll
       for (int x = 0; x < 8; ++x) r.h[x] = (__bf16)(o[x] * inv);
-      *(u32x4*)(a.out + row * 128 + part * 8) = r.u;
+      *(u32x4*)(a.out + row_io * 128 + part * 8) = r.u;
       if (act && n_live + P == 0 && part == 0 && qn == 0 && hkv == 0) atomicOr(c.err, PTENC_DEVERR_ATTEND_EMPTY);
     }
   }
 
-  // ---- counters go to the other buffer (nobody reads that one in this kernel) ----
-  if ((a.do_evict || a.do_append) && hkv == 0 && split == 0 && tid == 0) {
+  // ---- counters ----
+  // Full batch: they go to the other buffer (nobody reads that one in this kernel), so no workgroup
+  // waits for the rest of its rollout.  Compact list: the other buffer would miss the unlisted
+  // rollouts, so the last workgroup of the rollout to arrive writes them in place.
+  const bool advancing = a.do_evict || a.do_append;
+  const bool in_place = a.ids != nullptr;
+  if (advancing && !in_place && hkv == 0 && split == 0 && tid == 0) {
     c.len_nx[b] = len1;
     c.base_nx[b] = base1;
   }
 
   // ---- whoever finishes last for this rollout completes the encoding ----
-  if (evicting) {
+  if (evicting || (in_place && appending)) {
     __threadfence_block();
     __syncthreads();
     if (tid == 0) sm_ticket = atomicAdd(c.tick_rollout + b, 1);
     __syncthreads();
     if (sm_ticket == c.Hkv * ns - 1) {
-      encode_finish(c, sm, b);
-      if (tid == 0) c.tick_rollout[b] = 0;
+      if (evicting) encode_finish(c, sm, b);
+      if (tid == 0) {
+        if (in_place) { c.len[b] = len1; c.base[b] = base1; }
+        c.tick_rollout[b] = 0;
+      }
     }
   }
 }
@@ -589,8 +608,9 @@ hipError_t pt_launch_pack_weights(const PtDev& c, hipStream_t s) {
 
 hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bool do_evict, bool do_append, bool do_attend,
                                  const void* q, const void* k, const void* v, void* out, const uint8_t* active,
-                                 void* dbg_chunk, hipStream_t s) {
+                                 void* dbg_chunk, const int* ids, int n_rows, hipStream_t s) {
   StepArgs a;
+  a.ids = ids;
   a.q = (const uint16_t*)q; a.out = (uint16_t*)out;
   a.knew = (const uint16_t*)k; a.vnew = (const uint16_t*)v;
   a.active = active; a.dbg_chunk = (uint16_t*)dbg_chunk;
@@ -599,7 +619,7 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bo
   // without attention there is nothing to split
   PtDev cc = c;
   if (!do_attend) cc.n_splits = 1;
-  dim3 grid(cc.B * cc.Hkv, cc.n_splits);
+  dim3 grid((ids ? n_rows : cc.B) * cc.Hkv, cc.n_splits);
   if (waves == 8) {
     if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 8>), grid, dim3(512), 0, s, cc, a);
     else hipLaunchKernelGGL((decode_mfma_kernel<false, 8>), grid, dim3(512), 0, s, cc, a);

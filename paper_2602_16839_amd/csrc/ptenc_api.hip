@@ -71,12 +71,12 @@ bool mfma_attn_applies(const ptenc_config& c) {
 // through memory for the partial results, and measured on MI355X one workgroup per row wins as
 // soon as there are about a hundred rows (even with half the CUs idle).  Below that, split until
 // about 128 workgroups exist, but never below 256 tokens per split.
-int heuristic_splits(const ptenc_ctx* x) {
+int heuristic_splits(const ptenc_ctx* x, long n_rollouts) {
   const ptenc_config& c = x->cfg;
-  const long rows = (long)c.batch * (x->attn_kernel ? c.n_kv_heads : c.n_q_heads);
+  const long rows = n_rollouts * (x->attn_kernel ? c.n_kv_heads : c.n_q_heads);
   if (rows >= 96) return 1;
   long want = (128 + rows - 1) / rows;
-  long cap = c.window / 256;
+  long cap = (c.window - c.n_sink) / 256;
   if (cap < 1) cap = 1;
   if (want > cap) want = cap;
   if (want > PTENC_MAX_SPLITS) want = PTENC_MAX_SPLITS;
@@ -84,18 +84,20 @@ int heuristic_splits(const ptenc_ctx* x) {
   return (int)want;
 }
 
+// 8 wavefronts per workgroup need the query group to fit 8 rows of the merge buffer; measured
+// worth ~3 % when there is at most one workgroup per CU, a loss of as much when there are more
+int pick_waves(const ptenc_ctx* x, long n_rollouts, int splits) {
+  const long wgs = n_rollouts * x->cfg.n_kv_heads * splits;
+  const int want = x->opt_waves ? x->opt_waves : (wgs <= 256 ? 8 : 4);
+  return (want == 8 && x->dev.group <= 8) ? 8 : 4;
+}
+
 void replan(ptenc_ctx* x) {
   x->attn_kernel = (x->dev.tiled && !x->opt_force_generic) ? 1 : 0;
   x->encode_kernel = x->attn_kernel;
-  x->dev.n_splits = x->opt_splits > 0 ? x->opt_splits : heuristic_splits(x);
+  x->dev.n_splits = x->opt_splits > 0 ? x->opt_splits : heuristic_splits(x, x->cfg.batch);
+  x->waves = pick_waves(x, x->cfg.batch, x->dev.n_splits);
   // a cache that fits the 256 MiB memory-side cache is better served by ordinary loads
-  // 8 wavefronts per workgroup need the query group to fit 8 rows of the merge buffer; measured
-  // worth ~3 % when there is at most one workgroup per CU, a loss of as much when there are more
-  {
-    const long rows = (long)x->cfg.batch * x->cfg.n_kv_heads * x->dev.n_splits;
-    const int want = x->opt_waves ? x->opt_waves : (rows <= 256 ? 8 : 4);
-    x->waves = (want == 8 && x->dev.group <= 8) ? 8 : 4;
-  }
   x->nontemporal = x->opt_nontemporal >= 0 ? x->opt_nontemporal : (x->cache_bytes > ((size_t)192 << 20) ? 1 : 0);
 }
 
@@ -266,10 +268,10 @@ ptenc_status ptenc_cache_append(ptenc_ctx* ctx, const void* d_k, const void* d_v
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
     return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, false, true, false, nullptr, d_k, d_v,
-                                               nullptr, d_active, nullptr, S(stream)));
+                                               nullptr, d_active, nullptr, nullptr, 0, S(stream)));
   }
-  return advanced(ctx, pt_launch_step_prologue(ctx->dev, false, true, ctx->encode_kernel, d_k, d_v, d_active,
-                                               nullptr, S(stream)));
+  return advanced(ctx, pt_launch_step_prologue(ctx->dev, false, true, d_k, d_v, d_active, nullptr, nullptr, 0,
+                                               S(stream)));
 }
 
 ptenc_status ptenc_evict_encode(ptenc_ctx* ctx, const uint8_t* d_active, void* d_dbg_chunk, void* stream) {
@@ -277,9 +279,9 @@ ptenc_status ptenc_evict_encode(ptenc_ctx* ctx, const uint8_t* d_active, void* d
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
   if (ctx->attn_kernel == 1)
     return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, true, false, false, nullptr, nullptr,
-                                               nullptr, nullptr, d_active, d_dbg_chunk, S(stream)));
-  return advanced(ctx, pt_launch_step_prologue(ctx->dev, true, false, ctx->encode_kernel, nullptr, nullptr,
-                                               d_active, d_dbg_chunk, S(stream)));
+                                               nullptr, nullptr, d_active, d_dbg_chunk, nullptr, 0, S(stream)));
+  return advanced(ctx, pt_launch_step_prologue(ctx->dev, true, false, nullptr, nullptr, d_active, d_dbg_chunk,
+                                               nullptr, 0, S(stream)));
 }
 
 ptenc_status ptenc_decode_attn(ptenc_ctx* ctx, const void* d_q, void* d_out, const uint8_t* d_active,
@@ -289,9 +291,9 @@ ptenc_status ptenc_decode_attn(ptenc_ctx* ctx, const void* d_q, void* d_out, con
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_q | (uintptr_t)d_out) & 15) return PTENC_ERR_INVALID_ARG;
     return hip_status(pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, false, false, true, d_q, nullptr,
-                                            nullptr, d_out, d_active, nullptr, S(stream)));
+                                            nullptr, d_out, d_active, nullptr, nullptr, 0, S(stream)));
   }
-  return hip_status(pt_launch_attn_generic(ctx->dev, d_q, d_out, d_active, S(stream)));
+  return hip_status(pt_launch_attn_generic(ctx->dev, d_q, d_out, d_active, nullptr, 0, S(stream)));
 }
 
 ptenc_status ptenc_decode_step(ptenc_ctx* ctx, const void* d_q, const void* d_k, const void* d_v, void* d_out,
@@ -301,12 +303,54 @@ ptenc_status ptenc_decode_step(ptenc_ctx* ctx, const void* d_q, const void* d_k,
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_q | (uintptr_t)d_out | (uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
     return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, true, true, true, d_q, d_k, d_v, d_out,
-                                               d_active, nullptr, S(stream)));
+                                               d_active, nullptr, nullptr, 0, S(stream)));
   }
-  if (advanced(ctx, pt_launch_step_prologue(ctx->dev, true, true, ctx->encode_kernel, d_k, d_v, d_active, nullptr,
+  if (advanced(ctx, pt_launch_step_prologue(ctx->dev, true, true, d_k, d_v, d_active, nullptr, nullptr, 0,
                                             S(stream))) != PTENC_OK)
     return PTENC_ERR_HIP;
   return ptenc_decode_attn(ctx, d_q, d_out, d_active, stream);
+}
+
+ptenc_status ptenc_decode_step_ids(ptenc_ctx* ctx, const void* d_q, const void* d_k, const void* d_v, void* d_out,
+                                   const int32_t* d_ids, int32_t n, void* stream) {
+  if (!ctx || n < 0 || n > ctx->cfg.batch) return PTENC_ERR_INVALID_ARG;
+  if (!ctx->encoder_set) return PTENC_ERR_STATE;
+  if (n == 0) return PTENC_OK;
+  if (!d_q || !d_k || !d_v || !d_out || !d_ids) return PTENC_ERR_INVALID_ARG;
+  // the plan follows the number of rollouts actually decoded
+  PtDev d = ctx->dev;
+  d.n_splits = ctx->opt_splits > 0 ? ctx->opt_splits : heuristic_splits(ctx, n);
+  if (ctx->attn_kernel == 1) {
+    if (((uintptr_t)d_q | (uintptr_t)d_out | (uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
+    // counters are written in place by this launch: no buffer rotation
+    return hip_status(pt_launch_decode_mfma(d, ctx->nontemporal != 0, pick_waves(ctx, n, d.n_splits), true, true, true,
+                                            d_q, d_k, d_v, d_out, nullptr, nullptr, d_ids, n, S(stream)));
+  }
+  hipError_t e = pt_launch_step_prologue(d, true, true, d_k, d_v, nullptr, nullptr, d_ids, n, S(stream));
+  if (e != hipSuccess) return PTENC_ERR_HIP;
+  return hip_status(pt_launch_attn_generic(d, d_q, d_out, nullptr, d_ids, n, S(stream)));
+}
+
+ptenc_status ptenc_decode_run_ids(ptenc_ctx* ctx, const void* d_q, const void* d_k, const void* d_v, void* d_out,
+                                  const int32_t* d_ids, const int64_t* h_row_offsets, int64_t n_steps, void* stream) {
+  if (!ctx || !h_row_offsets || n_steps < 0 || h_row_offsets[0] != 0) return PTENC_ERR_INVALID_ARG;
+  const ptenc_config& c = ctx->cfg;
+  for (int64_t t = 0; t < n_steps; ++t) {
+    const int64_t n = h_row_offsets[t + 1] - h_row_offsets[t];
+    if (n < 0 || n > c.batch) return PTENC_ERR_INVALID_ARG;
+  }
+  const size_t es = elem_bytes(c.dtype);
+  const size_t qb = (size_t)c.n_q_heads * c.head_dim * es, kb = (size_t)c.n_kv_heads * c.head_dim * es;
+  for (int64_t t = 0; t < n_steps; ++t) {
+    const int64_t r0 = h_row_offsets[t], n = h_row_offsets[t + 1] - r0;
+    if (n == 0) continue;
+    if (!d_q || !d_k || !d_v || !d_out || !d_ids) return PTENC_ERR_INVALID_ARG;
+    ptenc_status st = ptenc_decode_step_ids(ctx, (const char*)d_q + r0 * qb, (const char*)d_k + r0 * kb,
+                                            (const char*)d_v + r0 * kb, (char*)d_out + r0 * qb, d_ids + r0, (int32_t)n,
+                                            stream);
+    if (st != PTENC_OK) return st;
+  }
+  return PTENC_OK;
 }
 
 ptenc_status ptenc_decode_run(ptenc_ctx* ctx, const void* d_q, const void* d_k, const void* d_v, void* d_out,

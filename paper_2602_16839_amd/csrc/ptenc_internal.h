@@ -130,17 +130,16 @@ template <> __device__ inline void pt_st<uint16_t>(uint16_t* p, float v) { *p = 
 // Launchers implemented in the kernel files (host side, return hipError_t).
 // ------------------------------------------------------------------------------------------
 hipError_t pt_launch_reset(const PtDev& c, const uint8_t* mask, bool clear_err, hipStream_t s);
-hipError_t pt_launch_step_prologue(const PtDev& c, bool do_evict, bool do_append, int encode_kernel,
+hipError_t pt_launch_step_prologue(const PtDev& c, bool do_evict, bool do_append,
                                    const void* k, const void* v, const uint8_t* active, void* dbg_chunk,
-                                   hipStream_t s);
+                                   const int* ids, int n_rows, hipStream_t s);
 hipError_t pt_launch_gather(const PtDev& c, void* K, void* V, hipStream_t s);
 hipError_t pt_launch_prefill(const PtDev& c, const void* k, const void* v, int p_max, hipStream_t s);
 hipError_t pt_launch_encoder_init(const PtDev& c, const void* qg, const void* WaQ, const void* kg,
                                   const void* vg, hipStream_t s);
 hipError_t pt_launch_attn_generic(const PtDev& c, const void* q, void* out, const uint8_t* active,
-                                  hipStream_t s);
-hipError_t pt_launch_combine(const PtDev& c, void* out, const uint8_t* active, hipStream_t s);
+                                  const int* ids, int n_rows, hipStream_t s);
 hipError_t pt_launch_pack_weights(const PtDev& c, hipStream_t s);
 hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bool do_evict, bool do_append, bool do_attend,
                                  const void* q, const void* k, const void* v, void* out, const uint8_t* active,
-                                 void* dbg_chunk, hipStream_t s);
+                                 void* dbg_chunk, const int* ids, int n_rows, hipStream_t s);

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_PKG_DIR, "libptenc.so")
 OK, ERR_INVALID_ARG, ERR_STATE, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM = range(6)
 F32, BF16 = 0, 1
 NORM_FROBENIUS, NORM_ROW_L2, NORM_NONE = 0, 1, 2
-DEVERR_APPEND_FULL, DEVERR_ATTEND_EMPTY = 1, 2
+DEVERR_APPEND_FULL, DEVERR_ATTEND_EMPTY, DEVERR_BAD_ID = 1, 2, 4
 OPT_SPLITS, OPT_FORCE_GENERIC, OPT_NONTEMPORAL, OPT_WAVES = 0, 1, 2, 3
 MAX_SPLITS = 32
 
@@ -29,7 +29,7 @@ EXPORTS = [
     "ptenc_decode_run", "ptenc_get_counters", "ptenc_set_counters", "ptenc_get_state", "ptenc_set_state",
     "ptenc_get_encoder_state", "ptenc_gather_window", "ptenc_cache_offset", "ptenc_poll_error",
     "ptenc_get_plan", "ptenc_status_string", "ptenc_util_stream_read", "ptenc_util_copy",
-    "ptenc_prefill", "ptenc_get_prompt_len",
+    "ptenc_prefill", "ptenc_get_prompt_len", "ptenc_decode_step_ids", "ptenc_decode_run_ids",
 ]
 
 
@@ -86,6 +86,8 @@ def lib() -> C.CDLL:
             "ptenc_util_copy": [vp, vp, sz, i32, vp],
             "ptenc_prefill": [vp, vp, vp, vp, i32, vp],
             "ptenc_get_prompt_len": [vp, vp, vp],
+            "ptenc_decode_step_ids": [vp, vp, vp, vp, vp, vp, i32, vp],
+            "ptenc_decode_run_ids": [vp, vp, vp, vp, vp, vp, vp, i64, vp],
         }
         for name, args in sig.items():
             fn = getattr(L, name)
@@ -181,6 +183,21 @@ def ptenc_decode_step(ctx, q, k, v, out, active=None):
 def ptenc_decode_run(ctx, q, k, v, out, active, n_steps: int):
     _check(lib().ptenc_decode_run(ctx, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(active), n_steps, _stream()),
            "ptenc_decode_run")
+
+
+def ptenc_decode_step_ids(ctx, q, k, v, out, ids):
+    """q, out [n, H_q, d]; k, v [n, H_kv, d]; ids int32 [n] device tensor of distinct rollout indices."""
+    assert ids.dtype == torch.int32
+    _check(lib().ptenc_decode_step_ids(ctx, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(ids), int(ids.numel()), _stream()),
+           "ptenc_decode_step_ids")
+
+
+def ptenc_decode_run_ids(ctx, q, k, v, out, ids, row_offsets):
+    """Concatenated compact buffers; row_offsets: host int64 [n_steps + 1]."""
+    assert ids.dtype == torch.int32
+    ro = np.ascontiguousarray(row_offsets, dtype=np.int64)
+    _check(lib().ptenc_decode_run_ids(ctx, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(ids),
+                                      ro.ctypes.data_as(C.c_void_p), len(ro) - 1, _stream()), "ptenc_decode_run_ids")
 
 
 def ptenc_get_counters(ctx, batch: int):
@@ -311,6 +328,18 @@ class Layer:
         if out is None:
             out = torch.empty_like(q)
         ptenc_decode_step(self.ctx, q, k, v, out, active)
+        return out
+
+    def step_ids(self, q, k, v, ids, out=None):
+        if out is None:
+            out = torch.empty_like(q)
+        ptenc_decode_step_ids(self.ctx, q, k, v, out, ids)
+        return out
+
+    def run_ids(self, q, k, v, ids, row_offsets, out=None):
+        if out is None:
+            out = torch.empty_like(q)
+        ptenc_decode_run_ids(self.ctx, q, k, v, out, ids, row_offsets)
         return out
 
     def run(self, q, k, v, out=None, active=None):

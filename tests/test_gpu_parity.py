@@ -100,6 +100,66 @@ def test_ragged_rollouts_are_masked():
     assert ln.tolist() == lengths.tolist()
 
 
+def _compact_run(wl, lengths, T, **layer_kw):
+    """Decode with compact id lists (finished rollouts dropped from the batch) next to the oracle's masked run."""
+    enc = I.encoder_params(wl)
+    orc = H.make_oracle(wl, enc)
+    layer = H.make_layer(wl, enc, **layer_kw)
+    q, k, v = I.qkv_steps(wl, 0, T)
+    rows_q, rows_k, rows_v, ids, offs, refs = [], [], [], [], [0], []
+    for t in range(T):
+        act = I.active_mask(lengths, t)
+        ref = orc.step(H.f64(q[t]), H.f64(k[t]), H.f64(v[t]), act)
+        idx = np.nonzero(act)[0]
+        it = torch.from_numpy(idx)
+        rows_q.append(q[t][it]); rows_k.append(k[t][it]); rows_v.append(v[t][it])
+        ids.append(it.to(torch.int32)); offs.append(offs[-1] + len(idx)); refs.append(ref[idx])
+    cq, ck, cv = (torch.cat(x).cuda() for x in (rows_q, rows_k, rows_v))
+    cid = torch.cat(ids).cuda()
+    return layer, orc, cq, ck, cv, cid, np.array(offs), np.concatenate(refs)
+
+
+@pytest.mark.parametrize("kind", ["mfma", "generic_bf16", "f32"])
+def test_compact_rollout_lists_equal_masked_decoding(kind):
+    lengths = np.array([90, 1, 31, 32, 33, 70, 0, 90])
+    if kind == "f32":
+        wl = small("tiny_f32", batch=8, window=32, chunk=8, steps=90)
+        kw = {}
+    else:
+        wl = small("ragged", batch=8, n_q_heads=8, n_kv_heads=2, window=32, chunk=8, steps=90)
+        kw = dict(force_generic=(kind == "generic_bf16"))
+    layer, orc, cq, ck, cv, cid, offs, ref = _compact_run(wl, lengths, wl.steps, **kw)
+    out = layer.run_ids(cq, ck, cv, cid, offs)
+    abs_tol, rel_tol = H.tolerances(wl)
+    H.assert_close(H.f64(out), ref, abs_tol, rel_tol, "compact outputs")
+    ln, base = layer.counters()
+    oln, obase = orc.counters()
+    assert np.array_equal(ln, oln) and np.array_equal(base, obase) and ln.tolist() == lengths.tolist()
+    H.assert_close(layer.get_state(), orc.state(), H.S_ABS, H.S_REL, "state S")
+    assert layer.poll_error() == 0
+    # step by step gives the same bits as the batched call; so does mixing in a full-batch masked step
+    layer2 = H.make_layer(wl, I.encoder_params(wl), **kw)
+    outs = []
+    for t in range(wl.steps):
+        r0, r1 = int(offs[t]), int(offs[t + 1])
+        if r1 > r0:
+            outs.append(layer2.step_ids(cq[r0:r1], ck[r0:r1], cv[r0:r1], cid[r0:r1]))
+    assert torch.equal(torch.cat(outs), out) and np.array_equal(layer2.get_state(), layer.get_state())
+
+
+def test_bad_rollout_id_is_flagged_and_skipped():
+    from paper_2602_16839_amd import ptenc
+    wl = small("ragged", batch=4, n_q_heads=8, n_kv_heads=2, window=32, chunk=8, steps=4)
+    layer = H.make_layer(wl, I.encoder_params(wl))
+    q, k, v = (x.cuda() for x in I.qkv_steps(wl, 0, 1))
+    ids = torch.tensor([2, 9, 0], dtype=torch.int32, device="cuda")
+    out = layer.step_ids(q[0][:3].contiguous(), k[0][:3].contiguous(), v[0][:3].contiguous(), ids)
+    assert layer.poll_error() == ptenc.DEVERR_BAD_ID
+    ln, _ = layer.counters()
+    assert ln.tolist() == [1, 0, 1, 0]
+    assert out[0].any() and out[2].any()
+
+
 def test_init_state_matches_oracle():
     for name in ("tiny_f32", "qwen7b"):
         wl = I.WORKLOADS[name].replace(batch=2)
