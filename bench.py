@@ -118,6 +118,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--workload", default="qwen7b")
     ap.add_argument("--splits", type=int, default=0)
+    ap.add_argument("--ragged-mode", choices=["compact", "masked"], default="compact",
+                    help="ragged workloads: drop finished rollouts from the batch (rollout-id lists) or mask them")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the per-launch HIP-event pass")
     ap.add_argument("--calibrate", action="store_true",
@@ -153,11 +155,21 @@ def main() -> int:
     for t0 in range(0, T_gen, blk):
         t1 = min(T_gen, t0 + blk)
         q[t0:t1], k[t0:t1], v[t0:t1] = I.qkv_steps(wl, t0, t1, device=dev)
-    out = torch.empty_like(q)
     active = None
+    compact = wl.ragged and args.ragged_mode == "compact"
+    row_offsets = None
     if wl.ragged:
         tt = torch.arange(T_gen, device=dev).view(-1, 1)
-        active = (tt < torch.from_numpy(lengths).to(dev).view(1, -1)).to(torch.uint8).contiguous()
+        alive = tt < torch.from_numpy(lengths).to(dev).view(1, -1)          # [T, B]
+        if compact:
+            # what a rollout engine feeds: only the rollouts still running, with their ids
+            ids = torch.nonzero(alive)[:, 1].to(torch.int32).contiguous()
+            q, k, v = q[alive].contiguous(), k[alive].contiguous(), v[alive].contiguous()
+            counts = np.array([(lengths > t).sum() for t in range(T_gen)], dtype=np.int64)
+            row_offsets = np.concatenate([[0], np.cumsum(counts)])
+        else:
+            active = alive.to(torch.uint8).contiguous()
+    out = torch.empty_like(q)
     enc = I.encoder_params(wl, device=dev)
 
     layer = ptenc.Layer(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
@@ -178,15 +190,22 @@ def main() -> int:
     attn_kernel, n_splits, _ = layer.plan()
 
     # ---- warmup, then the timed run from an empty cache ----
+    def run_steps(t0, t1):
+        if compact:
+            r0, r1 = int(row_offsets[t0]), int(row_offsets[t1])
+            layer.run_ids(q[r0:r1], k[r0:r1], v[r0:r1], ids[r0:r1], row_offsets[t0:t1 + 1] - r0, out[r0:r1])
+        else:
+            layer.run(q[t0:t1], k[t0:t1], v[t0:t1], out[t0:t1], None if active is None else active[t0:t1])
+
     start_run()
     if Wu:
-        layer.run(q[:Wu], k[:Wu], v[:Wu], out[:Wu], None if active is None else active[:Wu])
+        run_steps(0, Wu)
     start_run()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     w0 = time.perf_counter()
     e0.record()
-    layer.run(q[:K], k[:K], v[:K], out[:K], None if active is None else active[:K])
+    run_steps(0, K)
     e1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - w0) * 1e3
@@ -210,7 +229,13 @@ def main() -> int:
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
         for t in range(K):
             a = None if active is None else active[t]
-            if fused:
+            if compact:
+                r0, r1 = int(row_offsets[t]), int(row_offsets[t + 1])
+                evs[t][0].record()
+                if r1 > r0:
+                    layer.step_ids(q[r0:r1], k[r0:r1], v[r0:r1], ids[r0:r1], out[r0:r1])
+                evs[t][1].record()
+            elif fused:
                 evs[t][0].record()
                 layer.step(q[t], k[t], v[t], out[t], a)
                 evs[t][1].record()
@@ -247,7 +272,8 @@ def main() -> int:
             "workload": "%s-shaped layer: B %d rollouts, %d Q / %d KV heads, head_dim %d, window %d, chunk %d, "
                         "%d decode steps from an empty cache%s%s" % (
                             wl.name, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk, K,
-                            ", ragged lengths" if wl.ragged else "",
+                            (", ragged lengths, finished rollouts %s" % ("dropped from the batch (rollout-id lists)"
+                                                                        if compact else "masked")) if wl.ragged else "",
                             ", %d slots reserved for question tokens (128..%d per rollout, prefilled)" % (
                                 wl.n_sink, wl.n_sink) if wl.n_sink else ""),
             "name": wl.name, "batch": wl.batch, "window": wl.window, "chunk": wl.chunk, "tokens": tokens,
