@@ -21,6 +21,9 @@ What follows the paper, and where:
 * ``OracleLayer.step``  -- decode until the cache is full, then evict the oldest chunk (sliding window
                            over thinking tokens; Our Approach, first paragraph and "The selection of D
                            during training") and fold it into S before decoding continues.
+* ``apply_delta``       -- the context state used as a weight delta: Delta-W = A S B, theta' = theta + Delta-W
+                           (Our Approach, the Delta-W equation and the sentence after the update rule),
+                           applied to one token's activations: y + ((x A) S) B.
 * ``OracleLayer.prefill`` -- question tokens are kept in the cache permanently and only thinking tokens
                            slide ("The selection of D during training"; the response-length analysis
                            quotes a cache of 768 = 512 sink tokens + 256 in the sliding window).
@@ -40,6 +43,9 @@ Readings taken where the paper is silent or inconsistent (same list as the desig
    identity are selectable.
 8. S_0 is not normalised; Normalize first applies at the first eviction.
 13. Attention of an inactive rollout, or over an empty window, returns zeros.
+14. Delta-W = A S B in the row convention of reading 2: a projection y = x W (x a row, W d_in x d_out)
+    becomes y = x (W + A S B) with A d_in x G and B r x d_out.  Which projections receive it is not
+    stated; the operation is the same for any.
 15. Pinned question tokens: of the W cache slots, n_sink are reserved for a rollout's question
     tokens (at most n_sink of them, any number per rollout); the sliding window over thinking
     tokens holds W - n_sink.  Question tokens are attended to at every step, never evicted and
@@ -111,6 +117,12 @@ def init_state(q_g, WaQ, WaK, WaV, k_g=None, v_g=None):
     if k_g is None or v_g is None:
         return Q_a, np.zeros((Q_a.shape[0], np.asarray(WaV).shape[1]), dtype=np.float64)
     return Q_a, encode_chunk(Q_a, k_g, v_g, WaK, WaV)
+
+
+def apply_delta(x: np.ndarray, A: np.ndarray, S: np.ndarray, B: np.ndarray, y: np.ndarray) -> np.ndarray:
+    """y + x (A S B) for one rollout: x ``[d_in]``, A ``[d_in, G]``, S ``[G, r]``, B ``[r, d_out]``, y ``[d_out]``."""
+    dW = np.asarray(A, dtype=np.float64) @ np.asarray(S, dtype=np.float64) @ np.asarray(B, dtype=np.float64)
+    return np.asarray(y, dtype=np.float64) + np.asarray(x, dtype=np.float64) @ dW
 
 
 def normalize(X: np.ndarray, mode: int = NORM_FROBENIUS, eps: float = 1e-12) -> np.ndarray:

@@ -231,6 +231,31 @@ def test_init_state_is_encoding_of_global_tokens_unnormalised():
 
 
 # ---------------------------------------------------------------------------------------------
+# the state as a weight delta (Our Approach: Delta-W = A S B, theta' = theta + Delta-W)
+# ---------------------------------------------------------------------------------------------
+
+def test_apply_delta_hand_worked_and_structure():
+    # x = (1, 2), A = [[1, 0], [0, 1]], S = [[0, 1], [2, 0]], B = [[1, 1, 0], [0, 1, 1]], y = (10, 20, 30):
+    # x A = (1, 2); (x A) S = (2*2, 1*1) = (4, 1); ((x A) S) B = (4, 4 + 1, 1) = (4, 5, 1) => y' = (14, 25, 31)
+    x, A = np.array([1.0, 2.0]), np.eye(2)
+    S, B = np.array([[0.0, 1.0], [2.0, 0.0]]), np.array([[1.0, 1.0, 0.0], [0.0, 1.0, 1.0]])
+    y = np.array([10.0, 20.0, 30.0])
+    assert np.array_equal(po.apply_delta(x, A, S, B, y), np.array([14.0, 25.0, 31.0]))
+    # transposing S would give (x A) S^T = (2, 2) -> (2, 4, 2): visibly different
+    assert not np.array_equal(po.apply_delta(x, A, S.T, B, y), np.array([14.0, 25.0, 31.0]))
+    # random shapes: left-to-right evaluation, zero state, linearity in S, brute force
+    d_in, G, r, d_out = 7, 3, 4, 5
+    x, A, S, B, y = rand(d_in), rand(d_in, G), rand(G, r), rand(r, d_out), rand(d_out)
+    out = po.apply_delta(x, A, S, B, y)
+    assert np.allclose(out, y + ((x @ A) @ S) @ B, atol=1e-12)
+    assert np.array_equal(po.apply_delta(x, A, np.zeros((G, r)), B, y), y)
+    assert np.allclose(po.apply_delta(x, A, 3.0 * S, B, y) - y, 3.0 * (out - y), atol=1e-12)
+    for j in range(d_out):
+        tot = sum(x[i] * A[i][g] * S[g][c] * B[c][j] for i in range(d_in) for g in range(G) for c in range(r))
+        assert abs(out[j] - y[j] - tot) < 1e-12
+
+
+# ---------------------------------------------------------------------------------------------
 # Normalize (Our Approach: S <- Normalize(S + S')) -- the choice of norm is parity-unpinned
 # ---------------------------------------------------------------------------------------------
 
