@@ -122,6 +122,8 @@ def main() -> int:
                     help="ragged workloads: drop finished rollouts from the batch (rollout-id lists) or mask them")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the per-launch HIP-event pass")
+    ap.add_argument("--extras", action="store_true",
+                    help="also time the state-as-weight-delta application (and the question-token prefill)")
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch the plain copy / read kernels on 1 GiB (scale for the profiler's byte counters)")
     args = ap.parse_args()
@@ -285,6 +287,37 @@ def main() -> int:
         "algorithmic_gbytes": all_bytes / 1e9,
         "roofline": roofline,
     }
+    if args.extras:
+        # y += ((x A) S) B at the model's hidden size (the query projection width stands in for it)
+        ex = {}
+        d_h = wl.d_q
+        ad = I.adapter_inputs(wl, d_h, d_h, device=dev)
+        yb = ad["y"].clone()
+        for _ in range(10):
+            layer.apply_delta(ad["x"], ad["At"], ad["Bt"], yb)
+        torch.cuda.synchronize()
+        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a0.record()
+        for _ in range(200):
+            layer.apply_delta(ad["x"], ad["At"], ad["Bt"], yb)
+        a1.record()
+        torch.cuda.synchronize()
+        us = a0.elapsed_time(a1) * 1e3 / 200
+        s_ = wl.elem_bytes
+        nbytes_ad = wl.batch * (d_h * s_ + 2 * d_h * s_ + wl.n_global * wl.rank * 4) + (wl.n_global + wl.rank) * d_h * s_
+        ex["apply_delta"] = {"d_in": d_h, "d_out": d_h, "us_per_call": us, "algorithmic_bytes": nbytes_ad,
+                             "GB_per_s": nbytes_ad / us / 1e3, "hbm_frac": nbytes_ad / us / 1e3 / HBM_PEAK_GBS}
+        if wl.n_sink:
+            torch.cuda.synchronize()
+            a0.record()
+            for _ in range(20):
+                layer.prefill(pk, pv, prompt_len)
+            a1.record()
+            torch.cuda.synchronize()
+            us = a0.elapsed_time(a1) * 1e3 / 20
+            nb = float(prompt_len.sum()) * 2 * wl.d_kv * s_ * 2          # read once, written once
+            ex["prefill"] = {"us_per_call": us, "algorithmic_bytes": nb, "GB_per_s": nb / us / 1e3}
+        res["extras"] = ex
     if args.calibrate:
         nbytes = 1 << 30
         src = torch.randint(0, 255, (nbytes,), dtype=torch.uint8, device=dev)

@@ -178,6 +178,17 @@ ptenc_status ptenc_decode_run_ids(ptenc_ctx* ctx, const void* d_q, const void* d
                                   void* d_out, const int32_t* d_ids, const int64_t* h_row_offsets,
                                   int64_t n_steps, void* stream);
 
+/* The context state used as a per-rollout low-rank weight delta (Our Approach: Delta-W = A S B,
+ * theta' = theta + Delta-W; which projections receive it is the caller's choice):
+ *     y[j] += ((x[j] A) S_b) B        for every row j, b = j (or d_ids[j])
+ * x is [rows, d_in], y [rows, d_out] (updated in place), both cfg.dtype; A (d_in x G) is given
+ * transposed, d_At [G, d_in]; B (r x d_out) is given transposed, d_Bt [d_out, r]; fp32
+ * accumulation.  rows = B with d_ids NULL (d_active may mask rollouts: their rows of y are left
+ * as they are), else rows = n with rollout ids as in ptenc_decode_step_ids. */
+ptenc_status ptenc_apply_delta(ptenc_ctx* ctx, const void* d_x, const void* d_At, const void* d_Bt, void* d_y,
+                               int32_t d_in, int32_t d_out, const uint8_t* d_active, const int32_t* d_ids, int32_t n,
+                               void* stream);
+
 /* Counters to / from host arrays of B int64 each.  set_counters requires
  * 0 <= base <= len <= base + W - n_sink for every rollout (used for resume and rotation tests). */
 ptenc_status ptenc_get_counters(ptenc_ctx* ctx, int64_t* h_len, int64_t* h_base, void* stream);

@@ -353,6 +353,16 @@ ptenc_status ptenc_decode_run_ids(ptenc_ctx* ctx, const void* d_q, const void* d
   return PTENC_OK;
 }
 
+ptenc_status ptenc_apply_delta(ptenc_ctx* ctx, const void* d_x, const void* d_At, const void* d_Bt, void* d_y,
+                               int32_t d_in, int32_t d_out, const uint8_t* d_active, const int32_t* d_ids, int32_t n,
+                               void* stream) {
+  if (!ctx || !d_x || !d_At || !d_Bt || !d_y || d_in < 1 || d_out < 1) return PTENC_ERR_INVALID_ARG;
+  if (d_ids && (n < 0 || n > ctx->cfg.batch)) return PTENC_ERR_INVALID_ARG;
+  if (!ctx->encoder_set) return PTENC_ERR_STATE;
+  if (d_ids && n == 0) return PTENC_OK;
+  return hip_status(pt_launch_apply_delta(ctx->dev, d_x, d_At, d_Bt, d_y, d_in, d_out, d_active, d_ids, n, S(stream)));
+}
+
 ptenc_status ptenc_decode_run(ptenc_ctx* ctx, const void* d_q, const void* d_k, const void* d_v, void* d_out,
                               const uint8_t* d_active, int64_t n_steps, void* stream) {
   if (!ctx || !d_q || !d_k || !d_v || !d_out || n_steps < 0) return PTENC_ERR_INVALID_ARG;

@@ -45,6 +45,7 @@ STREAM_QG, STREAM_KG, STREAM_VG = 3, 4, 5
 STREAM_WAQ, STREAM_WAK, STREAM_WAV = 6, 7, 8
 STREAM_HEAD_SCALE_Q, STREAM_HEAD_SCALE_K, STREAM_HEAD_SCALE_V = 9, 10, 11
 STREAM_PROMPT_K, STREAM_PROMPT_V, STREAM_PROMPT_LEN = 12, 13, 14
+STREAM_ADAPT_A, STREAM_ADAPT_B, STREAM_ADAPT_X, STREAM_ADAPT_Y = 15, 16, 17, 18
 
 
 def _signed(x: int) -> int:
@@ -245,6 +246,21 @@ def prompt_kv(wl: Workload, device="cpu"):
     k = gaussian(wl.seed, STREAM_PROMPT_K, 0, wl.batch, wl.n_sink, wl.n_kv_heads, wl.head_dim, wl.scale, sk, **kw)
     v = gaussian(wl.seed, STREAM_PROMPT_V, 0, wl.batch, wl.n_sink, wl.n_kv_heads, wl.head_dim, wl.scale, sv, **kw)
     return k, v
+
+
+def adapter_inputs(wl: Workload, d_in: int, d_out: int, device="cpu"):
+    """Inputs of the weight-delta application: x [B, d_in], y [B, d_out] activations of unit scale, and the
+    maps A^T [G, d_in], B^T [d_out, r] with std 1/sqrt(fan_in) (A maps d_in -> G, B maps r -> d_out)."""
+    dt = wl.torch_dtype
+
+    def g2(stream, rows, cols, scale):
+        return gaussian(wl.seed, stream, 0, 1, 1, rows, cols, scale, dtype=dt, device=device).view(rows, cols)
+
+    return {
+        "x": g2(STREAM_ADAPT_X, wl.batch, d_in, 1.0), "y": g2(STREAM_ADAPT_Y, wl.batch, d_out, 1.0),
+        "At": g2(STREAM_ADAPT_A, wl.n_global, d_in, 1.0 / math.sqrt(d_in)),
+        "Bt": g2(STREAM_ADAPT_B, d_out, wl.rank, 1.0 / math.sqrt(wl.rank)),
+    }
 
 
 def rollout_lengths(wl: Workload) -> np.ndarray:

@@ -30,6 +30,7 @@ EXPORTS = [
     "ptenc_get_encoder_state", "ptenc_gather_window", "ptenc_cache_offset", "ptenc_poll_error",
     "ptenc_get_plan", "ptenc_status_string", "ptenc_util_stream_read", "ptenc_util_copy",
     "ptenc_prefill", "ptenc_get_prompt_len", "ptenc_decode_step_ids", "ptenc_decode_run_ids",
+    "ptenc_apply_delta",
 ]
 
 
@@ -88,6 +89,7 @@ def lib() -> C.CDLL:
             "ptenc_get_prompt_len": [vp, vp, vp],
             "ptenc_decode_step_ids": [vp, vp, vp, vp, vp, vp, i32, vp],
             "ptenc_decode_run_ids": [vp, vp, vp, vp, vp, vp, vp, i64, vp],
+            "ptenc_apply_delta": [vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp],
         }
         for name, args in sig.items():
             fn = getattr(L, name)
@@ -198,6 +200,13 @@ def ptenc_decode_run_ids(ctx, q, k, v, out, ids, row_offsets):
     ro = np.ascontiguousarray(row_offsets, dtype=np.int64)
     _check(lib().ptenc_decode_run_ids(ctx, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(ids),
                                       ro.ctypes.data_as(C.c_void_p), len(ro) - 1, _stream()), "ptenc_decode_run_ids")
+
+
+def ptenc_apply_delta(ctx, x, At, Bt, y, active=None, ids=None):
+    """y += ((x A) S) B in place; At = A^T [G, d_in], Bt = B^T [d_out, r]."""
+    n = 0 if ids is None else int(ids.numel())
+    _check(lib().ptenc_apply_delta(ctx, _ptr(x), _ptr(At), _ptr(Bt), _ptr(y), int(x.shape[-1]), int(y.shape[-1]),
+                                   _ptr(active), _ptr(ids), n, _stream()), "ptenc_apply_delta")
 
 
 def ptenc_get_counters(ctx, batch: int):
@@ -341,6 +350,10 @@ class Layer:
             out = torch.empty_like(q)
         ptenc_decode_run_ids(self.ctx, q, k, v, out, ids, row_offsets)
         return out
+
+    def apply_delta(self, x, At, Bt, y, active=None, ids=None):
+        ptenc_apply_delta(self.ctx, x, At, Bt, y, active, ids)
+        return y
 
     def run(self, q, k, v, out=None, active=None):
         if out is None:

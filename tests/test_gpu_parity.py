@@ -160,6 +160,36 @@ def test_bad_rollout_id_is_flagged_and_skipped():
     assert out[0].any() and out[2].any()
 
 
+@pytest.mark.parametrize("name,d_in,d_out,G,r", [("qwen3b", 512, 384, 32, 32), ("qwen3b", 260, 77, 16, 24),
+                                                 ("tiny_f32", 96, 130, 32, 32)])
+def test_state_applied_as_weight_delta(name, d_in, d_out, G, r):
+    wl = small(name, batch=5, window=32, chunk=8, steps=60, n_global=G, rank=r)
+    if name != "tiny_f32":
+        wl = wl.replace(n_q_heads=4, n_kv_heads=2)
+    layer, orc = H.run_both(wl, wl.steps, check_every=20)          # leaves 4 evictions' worth of state in S
+    ad = I.adapter_inputs(wl, d_in, d_out)
+    x, y0, At, Bt = (H.f64(ad[k]) for k in ("x", "y", "At", "Bt"))
+    S = orc.state()
+    ref = np.stack([po.apply_delta(x[b], At.T, S[b], Bt.T, y0[b]) for b in range(wl.batch)])
+    dev = {k: v.cuda() for k, v in ad.items()}
+    y = dev["y"].clone()
+    layer.apply_delta(dev["x"], dev["At"], dev["Bt"], y)
+    abs_tol, rel_tol = H.tolerances(wl)
+    H.assert_close(H.f64(y), ref, max(abs_tol, 2e-5), rel_tol, "y + x (A S B)")
+    assert np.abs(ref - y0).max() > 0.02                           # the delta is not lost in the tolerance
+    # masked rollouts keep their rows; a compact id list touches only the listed rows
+    y = dev["y"].clone()
+    mask = torch.tensor([1, 0, 1, 1, 0], dtype=torch.uint8, device="cuda")
+    layer.apply_delta(dev["x"], dev["At"], dev["Bt"], y, active=mask)
+    assert torch.equal(y[1], dev["y"][1]) and torch.equal(y[4], dev["y"][4])
+    H.assert_close(H.f64(y[[0, 2, 3]]), ref[[0, 2, 3]], max(abs_tol, 2e-5), rel_tol, "masked")
+    ids = torch.tensor([3, 0], dtype=torch.int32, device="cuda")
+    yc = dev["y"][[3, 0]].contiguous()
+    layer.apply_delta(dev["x"][[3, 0]].contiguous(), dev["At"], dev["Bt"], yc, ids=ids)
+    H.assert_close(H.f64(yc), ref[[3, 0]], max(abs_tol, 2e-5), rel_tol, "compact")
+    assert layer.poll_error() == 0
+
+
 def test_init_state_matches_oracle():
     for name in ("tiny_f32", "qwen7b"):
         wl = I.WORKLOADS[name].replace(batch=2)
