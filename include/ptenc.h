@@ -42,6 +42,9 @@
  *   - Element type: q, k, v, out, the cache and the encoder parameters all have cfg.dtype.
  *     Scores, softmax statistics, accumulators and S are fp32.
  *   - Overlapping calls on one context from different streams race; serialise them.
+ *   - HIP graphs: every decode entry point only launches kernels (no allocation, copy or memset),
+ *     so it can be captured; set PTENC_OPT_COUNTERS_IN_PLACE first, and give the graph fixed
+ *     input / output buffers that are refilled between replays.
  */
 #ifndef PTENC_H
 #define PTENC_H
@@ -76,10 +79,14 @@ enum { PTENC_DEVERR_APPEND_FULL = 1, PTENC_DEVERR_ATTEND_EMPTY = 2, PTENC_DEVERR
 typedef enum {
   PTENC_OPT_SPLITS = 0,       /* window splits per (rollout, KV head); 1..PTENC_MAX_SPLITS; 0 = heuristic */
   PTENC_OPT_FORCE_GENERIC = 1,/* 1 = use the plain ALU attention kernel even where the MFMA one applies */
+  PTENC_OPT_NONTEMPORAL = 2,  /* K/V stream with non-temporal loads: 1 / 0; -1 = heuristic (on when the cache
+                                 exceeds the memory-side cache) */
   PTENC_OPT_WAVES = 3,        /* wavefronts per workgroup of the MFMA kernel: 4, or 8 (taken only with at most
                                  8 query heads per KV head); 0 = heuristic */
-  PTENC_OPT_NONTEMPORAL = 2   /* K/V stream with non-temporal loads: 1 / 0; -1 = heuristic (on when the cache
-                                 exceeds the memory-side cache) */
+  PTENC_OPT_COUNTERS_IN_PLACE = 4 /* 1 = steps update len / base in place instead of alternating between two
+                                 buffers on the host.  Needed when a step is captured into a HIP graph and
+                                 replayed (the alternation would be frozen into the graph); costs one extra
+                                 arrival counter per rollout and step.  Default 0. */
 } ptenc_option;
 
 #define PTENC_MAX_SPLITS 32

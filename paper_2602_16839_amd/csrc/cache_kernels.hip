@@ -106,7 +106,8 @@ __global__ __launch_bounds__(kThreads) void step_prologue_kernel(PtDev c, int do
                                                                 const T* __restrict__ knew,
                                                                 const T* __restrict__ vnew,
                                                                 const uint8_t* __restrict__ active,
-                                                                T* dbg_chunk, const int* __restrict__ ids) {
+                                                                T* dbg_chunk, const int* __restrict__ ids,
+                                                                int in_place) {
   __shared__ EncSmem sm;
   const int j_row = blockIdx.x, t = threadIdx.x;   // row of k / v; rollout b = j_row, or ids[j_row]
   int b = j_row;
@@ -154,7 +155,7 @@ __global__ __launch_bounds__(kThreads) void step_prologue_kernel(PtDev c, int do
   // would leave the unlisted rollouts out) they are written in place: this workgroup is the only
   // one that touches rollout b in this kernel
   if (t == 0) {
-    if (ids) { c.len[b] = len1; c.base[b] = base; }
+    if (in_place) { c.len[b] = len1; c.base[b] = base; }
     else { c.len_nx[b] = len1; c.base_nx[b] = base; }
   }
 }
@@ -277,14 +278,15 @@ hipError_t pt_launch_reset(const PtDev& c, const uint8_t* mask, bool clear_err, 
 
 hipError_t pt_launch_step_prologue(const PtDev& c, bool do_evict, bool do_append,
                                    const void* k, const void* v, const uint8_t* active, void* dbg_chunk,
-                                   const int* ids, int n_rows, hipStream_t s) {
+                                   const int* ids, int n_rows, bool in_place, hipStream_t s) {
   const dim3 grid(ids ? n_rows : c.B);
+  const int ip = (ids != nullptr || in_place) ? 1 : 0;
   if (c.dtype == PTENC_F32)
     hipLaunchKernelGGL(step_prologue_kernel<float>, grid, dim3(kThreads), 0, s, c, do_evict ? 1 : 0,
-                       do_append ? 1 : 0, (const float*)k, (const float*)v, active, (float*)dbg_chunk, ids);
+                       do_append ? 1 : 0, (const float*)k, (const float*)v, active, (float*)dbg_chunk, ids, ip);
   else
     hipLaunchKernelGGL(step_prologue_kernel<uint16_t>, grid, dim3(kThreads), 0, s, c, do_evict ? 1 : 0,
-                       do_append ? 1 : 0, (const uint16_t*)k, (const uint16_t*)v, active, (uint16_t*)dbg_chunk, ids);
+                       do_append ? 1 : 0, (const uint16_t*)k, (const uint16_t*)v, active, (uint16_t*)dbg_chunk, ids, ip);
   return hipGetLastError();
 }
 

@@ -214,6 +214,7 @@ struct StepArgs {
   uint16_t* dbg_chunk;     // [B, 2, C, H_kv*128] or null
   const int* ids;          // null, or the rollouts this launch works on: row j of q/k/v/out is rollout ids[j]
   int do_evict, do_append, do_attend;
+  int in_place;            // counters written in place by the rollout's last workgroup (compact lists; graph replay)
 };
 
 // WAVES wavefronts per workgroup: 4 (up to 16 query heads per KV head) or 8 (up to 8), the same LDS.
@@ -561,7 +562,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
   // waits for the rest of its rollout.  Compact list: the other buffer would miss the unlisted
   // rollouts, so the last workgroup of the rollout to arrive writes them in place.
   const bool advancing = a.do_evict || a.do_append;
-  const bool in_place = a.ids != nullptr;
+  const bool in_place = a.in_place != 0;
   if (advancing && !in_place && hkv == 0 && split == 0 && tid == 0) {
     c.len_nx[b] = len1;
     c.base_nx[b] = base1;
@@ -608,9 +609,10 @@ hipError_t pt_launch_pack_weights(const PtDev& c, hipStream_t s) {
 
 hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bool do_evict, bool do_append, bool do_attend,
                                  const void* q, const void* k, const void* v, void* out, const uint8_t* active,
-                                 void* dbg_chunk, const int* ids, int n_rows, hipStream_t s) {
+                                 void* dbg_chunk, const int* ids, int n_rows, bool in_place, hipStream_t s) {
   StepArgs a;
   a.ids = ids;
+  a.in_place = (ids != nullptr || in_place) ? 1 : 0;
   a.q = (const uint16_t*)q; a.out = (uint16_t*)out;
   a.knew = (const uint16_t*)k; a.vnew = (const uint16_t*)v;
   a.active = active; a.dbg_chunk = (uint16_t*)dbg_chunk;

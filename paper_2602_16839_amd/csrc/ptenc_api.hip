@@ -106,6 +106,7 @@ inline hipStream_t S(void* s) { return (hipStream_t)s; }
 // after a launch that advanced the counters: the buffer it wrote becomes the current one
 ptenc_status advanced(ptenc_ctx* x, hipError_t e) {
   if (e != hipSuccess) return PTENC_ERR_HIP;
+  if (x->opt_in_place) return PTENC_OK;
   long long* t = x->dev.len; x->dev.len = x->dev.len_nx; x->dev.len_nx = t;
   t = x->dev.base; x->dev.base = x->dev.base_nx; x->dev.base_nx = t;
   return PTENC_OK;
@@ -194,6 +195,10 @@ ptenc_status ptenc_set_option(ptenc_ctx* ctx, int32_t option, int32_t value) {
       if (value != 0 && value != 4 && value != 8) return PTENC_ERR_INVALID_ARG;
       ctx->opt_waves = value;
       break;
+    case PTENC_OPT_COUNTERS_IN_PLACE:
+      if (value != 0 && value != 1) return PTENC_ERR_INVALID_ARG;
+      ctx->opt_in_place = value;
+      break;
     case PTENC_OPT_FORCE_GENERIC:
       if (value != 0 && value != 1) return PTENC_ERR_INVALID_ARG;
       ctx->opt_force_generic = value;
@@ -268,10 +273,10 @@ ptenc_status ptenc_cache_append(ptenc_ctx* ctx, const void* d_k, const void* d_v
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
     return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, false, true, false, nullptr, d_k, d_v,
-                                               nullptr, d_active, nullptr, nullptr, 0, S(stream)));
+                                               nullptr, d_active, nullptr, nullptr, 0, ctx->opt_in_place != 0, S(stream)));
   }
   return advanced(ctx, pt_launch_step_prologue(ctx->dev, false, true, d_k, d_v, d_active, nullptr, nullptr, 0,
-                                               S(stream)));
+                                               ctx->opt_in_place != 0, S(stream)));
 }
 
 ptenc_status ptenc_evict_encode(ptenc_ctx* ctx, const uint8_t* d_active, void* d_dbg_chunk, void* stream) {
@@ -279,9 +284,9 @@ ptenc_status ptenc_evict_encode(ptenc_ctx* ctx, const uint8_t* d_active, void* d
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
   if (ctx->attn_kernel == 1)
     return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, true, false, false, nullptr, nullptr,
-                                               nullptr, nullptr, d_active, d_dbg_chunk, nullptr, 0, S(stream)));
+                                               nullptr, nullptr, d_active, d_dbg_chunk, nullptr, 0, ctx->opt_in_place != 0, S(stream)));
   return advanced(ctx, pt_launch_step_prologue(ctx->dev, true, false, nullptr, nullptr, d_active, d_dbg_chunk,
-                                               nullptr, 0, S(stream)));
+                                               nullptr, 0, ctx->opt_in_place != 0, S(stream)));
 }
 
 ptenc_status ptenc_decode_attn(ptenc_ctx* ctx, const void* d_q, void* d_out, const uint8_t* d_active,
@@ -291,7 +296,7 @@ ptenc_status ptenc_decode_attn(ptenc_ctx* ctx, const void* d_q, void* d_out, con
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_q | (uintptr_t)d_out) & 15) return PTENC_ERR_INVALID_ARG;
     return hip_status(pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, false, false, true, d_q, nullptr,
-                                            nullptr, d_out, d_active, nullptr, nullptr, 0, S(stream)));
+                                            nullptr, d_out, d_active, nullptr, nullptr, 0, false, S(stream)));
   }
   return hip_status(pt_launch_attn_generic(ctx->dev, d_q, d_out, d_active, nullptr, 0, S(stream)));
 }
@@ -303,10 +308,10 @@ ptenc_status ptenc_decode_step(ptenc_ctx* ctx, const void* d_q, const void* d_k,
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_q | (uintptr_t)d_out | (uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
     return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, true, true, true, d_q, d_k, d_v, d_out,
-                                               d_active, nullptr, nullptr, 0, S(stream)));
+                                               d_active, nullptr, nullptr, 0, ctx->opt_in_place != 0, S(stream)));
   }
   if (advanced(ctx, pt_launch_step_prologue(ctx->dev, true, true, d_k, d_v, d_active, nullptr, nullptr, 0,
-                                            S(stream))) != PTENC_OK)
+                                            ctx->opt_in_place != 0, S(stream))) != PTENC_OK)
     return PTENC_ERR_HIP;
   return ptenc_decode_attn(ctx, d_q, d_out, d_active, stream);
 }
@@ -324,9 +329,9 @@ ptenc_status ptenc_decode_step_ids(ptenc_ctx* ctx, const void* d_q, const void* 
     if (((uintptr_t)d_q | (uintptr_t)d_out | (uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
     // counters are written in place by this launch: no buffer rotation
     return hip_status(pt_launch_decode_mfma(d, ctx->nontemporal != 0, pick_waves(ctx, n, d.n_splits), true, true, true,
-                                            d_q, d_k, d_v, d_out, nullptr, nullptr, d_ids, n, S(stream)));
+                                            d_q, d_k, d_v, d_out, nullptr, nullptr, d_ids, n, true, S(stream)));
   }
-  hipError_t e = pt_launch_step_prologue(d, true, true, d_k, d_v, nullptr, nullptr, d_ids, n, S(stream));
+  hipError_t e = pt_launch_step_prologue(d, true, true, d_k, d_v, nullptr, nullptr, d_ids, n, true, S(stream));
   if (e != hipSuccess) return PTENC_ERR_HIP;
   return hip_status(pt_launch_attn_generic(d, d_q, d_out, nullptr, d_ids, n, S(stream)));
 }

@@ -52,6 +52,7 @@ struct ptenc_ctx {
   int opt_nontemporal;   // -1 = heuristic, 0, 1
   int nontemporal;       // resolved
   int opt_waves;         // 0 = heuristic, 4, 8
+  int opt_in_place;      // 1 = counters are updated in place (no buffer rotation on the host)
   int waves;             // resolved: wavefronts per workgroup of the MFMA kernel
   int attn_kernel;       // 0 generic, 1 mfma
   int encode_kernel;     // 0 generic, 1 mfma
@@ -132,7 +133,7 @@ template <> __device__ inline void pt_st<uint16_t>(uint16_t* p, float v) { *p = 
 hipError_t pt_launch_reset(const PtDev& c, const uint8_t* mask, bool clear_err, hipStream_t s);
 hipError_t pt_launch_step_prologue(const PtDev& c, bool do_evict, bool do_append,
                                    const void* k, const void* v, const uint8_t* active, void* dbg_chunk,
-                                   const int* ids, int n_rows, hipStream_t s);
+                                   const int* ids, int n_rows, bool in_place, hipStream_t s);
 hipError_t pt_launch_gather(const PtDev& c, void* K, void* V, hipStream_t s);
 hipError_t pt_launch_prefill(const PtDev& c, const void* k, const void* v, int p_max, hipStream_t s);
 hipError_t pt_launch_encoder_init(const PtDev& c, const void* qg, const void* WaQ, const void* kg,
@@ -144,4 +145,4 @@ hipError_t pt_launch_apply_delta(const PtDev& c, const void* x, const void* At, 
 hipError_t pt_launch_pack_weights(const PtDev& c, hipStream_t s);
 hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bool do_evict, bool do_append, bool do_attend,
                                  const void* q, const void* k, const void* v, void* out, const uint8_t* active,
-                                 void* dbg_chunk, const int* ids, int n_rows, hipStream_t s);
+                                 void* dbg_chunk, const int* ids, int n_rows, bool in_place, hipStream_t s);

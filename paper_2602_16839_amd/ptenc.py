@@ -20,7 +20,7 @@ OK, ERR_INVALID_ARG, ERR_STATE, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM = range(6)
 F32, BF16 = 0, 1
 NORM_FROBENIUS, NORM_ROW_L2, NORM_NONE = 0, 1, 2
 DEVERR_APPEND_FULL, DEVERR_ATTEND_EMPTY, DEVERR_BAD_ID = 1, 2, 4
-OPT_SPLITS, OPT_FORCE_GENERIC, OPT_NONTEMPORAL, OPT_WAVES = 0, 1, 2, 3
+OPT_SPLITS, OPT_FORCE_GENERIC, OPT_NONTEMPORAL, OPT_WAVES, OPT_COUNTERS_IN_PLACE = 0, 1, 2, 3, 4
 MAX_SPLITS = 32
 
 EXPORTS = [

@@ -190,6 +190,40 @@ def test_state_applied_as_weight_delta(name, d_in, d_out, G, r):
     assert layer.poll_error() == 0
 
 
+@pytest.mark.parametrize("kind", ["mfma", "f32"])
+def test_a_captured_step_replays_like_eager_steps(kind):
+    # one decode step captured into a HIP graph (counters updated in place) and replayed with refilled
+    # inputs, with eager work and synchronisation between replays; every replay is checked
+    from paper_2602_16839_amd import ptenc
+    if kind == "mfma":
+        wl = small("qwen7b", batch=3, n_q_heads=14, n_kv_heads=2, window=96, chunk=32, steps=150)
+    else:
+        wl = small("tiny_f32", batch=3, window=24, chunk=8, steps=60)
+    enc = I.encoder_params(wl)
+    q, k, v = (x.cuda() for x in I.qkv_steps(wl, 0, wl.steps))
+    eager = H.make_layer(wl, enc)
+    ref = eager.run(q, k, v)
+    layer = H.make_layer(wl, enc)
+    layer.set_option(ptenc.OPT_COUNTERS_IN_PLACE, 1)
+    qs, ks, vs = torch.empty_like(q[0]), torch.empty_like(k[0]), torch.empty_like(v[0])
+    outs = torch.empty_like(q[0])
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        layer.step(qs, ks, vs, outs)
+    for t in range(wl.steps):
+        qs.copy_(q[t]); ks.copy_(k[t]); vs.copy_(v[t])
+        g.replay()
+        if t % 7 == 0:
+            torch.cuda.synchronize()
+            _ = (q[t].float() * 2).sum().item()          # unrelated eager work between replays
+        assert torch.equal(outs, ref[t]), "replay %d" % t
+    ln, base = layer.counters()
+    eln, ebase = eager.counters()
+    assert np.array_equal(ln, eln) and np.array_equal(base, ebase)
+    assert np.array_equal(layer.get_state(), eager.get_state())
+    assert layer.poll_error() == 0
+
+
 def test_init_state_matches_oracle():
     for name in ("tiny_f32", "qwen7b"):
         wl = I.WORKLOADS[name].replace(batch=2)
