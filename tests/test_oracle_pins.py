@@ -345,8 +345,10 @@ def test_state_update_normalises_after_every_eviction_and_starts_from_S0():
     layer, enc = _layer(B, H_q, H_kv, d, W, C)
     T = 11
     q, k, v = rand(T, B, H_q, d), rand(T, B, H_kv, d), rand(T, B, H_kv, d)
-    S = layer.S0.copy()
     Q_a = enc["q_g"] @ enc["WaQ"]
+    # the starting state, by an independent route: the global tokens' own encoding, NOT normalised
+    S = np.linalg.multi_dot([Q_a, (enc["k_g"] @ enc["WaK"]).T, enc["v_g"] @ enc["WaV"]])
+    assert np.allclose(layer.rollouts[0].S, S, atol=1e-13) and abs(np.linalg.norm(S) - 1.0) > 1e-3
     for t in range(T):
         before = layer.rollouts[0].evicted
         layer.step(q[t], k[t], v[t])
