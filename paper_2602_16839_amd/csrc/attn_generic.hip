@@ -3,8 +3,8 @@
 // out[b,h] = softmax(q[b,h] . K_live * scale) V_live over the live positions of rollout b
 // (Notation and Preliminaries, attention equation, over the pruned context).  One workgroup per
 // (rollout, query head, window split): a thread scores one token, the block reduces max and sum,
-// then one thread per output column accumulates the values.  Partial results are
-// (m, l, unnormalised out) in the base-2 domain and are merged by combine_kernel.
+// then one thread per output column accumulates the values.  With several splits the partial
+// results (m, l, unnormalised out; base-2 domain) are merged by combine_kernel.
 #include "ptenc_internal.h"
 
 namespace {
@@ -27,6 +27,7 @@ __device__ inline float block_reduce(float v, float* red, bool is_max) {
 
 template <typename T>
 __global__ __launch_bounds__(kThreads) void attn_generic_kernel(PtDev c, const T* __restrict__ q,
+                                                               T* __restrict__ out,
                                                                const uint8_t* __restrict__ active,
                                                                const int* __restrict__ ids) {
   __shared__ float qs[256];
@@ -81,6 +82,13 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(PtDev c, const T
     m_run = m_new;
     __syncthreads();
   }
+  if (c.n_splits == 1) {
+    // nothing to merge: normalise and write the output row here
+    if (t < c.d) pt_st<T>(out + (size_t)bh * c.d + t, l_run > 0.f ? acc / l_run : 0.f);
+    if (t == 0 && act && n_live == 0) atomicOr(c.err, PTENC_DEVERR_ATTEND_EMPTY);
+    if (t == 0 && bad) atomicOr(c.err, PTENC_DEVERR_BAD_ID);
+    return;
+  }
   if (t == 0) { po[0] = m_run; po[1] = l_run; }
   if (t < c.d) po[2 + t] = acc;
 }
@@ -128,11 +136,14 @@ hipError_t pt_launch_attn_generic(const PtDev& c, const void* q, void* out, cons
   dim3 grid(rows, c.n_splits);
   const int cthreads = c.d <= 64 ? 64 : 128;
   if (c.dtype == PTENC_F32) {
-    hipLaunchKernelGGL(attn_generic_kernel<float>, grid, dim3(kThreads), 0, s, c, (const float*)q, active, ids);
-    hipLaunchKernelGGL(combine_kernel<float>, dim3(rows), dim3(cthreads), 0, s, c, (float*)out, active, ids);
+    hipLaunchKernelGGL(attn_generic_kernel<float>, grid, dim3(kThreads), 0, s, c, (const float*)q, (float*)out, active, ids);
+    if (c.n_splits > 1)
+      hipLaunchKernelGGL(combine_kernel<float>, dim3(rows), dim3(cthreads), 0, s, c, (float*)out, active, ids);
   } else {
-    hipLaunchKernelGGL(attn_generic_kernel<uint16_t>, grid, dim3(kThreads), 0, s, c, (const uint16_t*)q, active, ids);
-    hipLaunchKernelGGL(combine_kernel<uint16_t>, dim3(rows), dim3(cthreads), 0, s, c, (uint16_t*)out, active, ids);
+    hipLaunchKernelGGL(attn_generic_kernel<uint16_t>, grid, dim3(kThreads), 0, s, c, (const uint16_t*)q, (uint16_t*)out,
+                       active, ids);
+    if (c.n_splits > 1)
+      hipLaunchKernelGGL(combine_kernel<uint16_t>, dim3(rows), dim3(cthreads), 0, s, c, (uint16_t*)out, active, ids);
   }
   return hipGetLastError();
 }

@@ -131,3 +131,27 @@ def test_tiled_layout_matches_its_documented_formula():
         kgv, ev = (tl % 16) // 4, (tl // 16) * 4 + tl % 4
         assert ptenc.ptenc_cache_offset(h, 0, 0, slot, i, 1) == grp * 8192 + 4096 + ((it * 4 + kgv) * 16 + mm) * 8 + ev
     ptenc.ptenc_destroy(h)
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    # no CPU fallback: without the shared library the binding raises instead of computing anything
+    monkeypatch.setattr(ptenc, "_LIB", None)
+    monkeypatch.setattr(ptenc, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libptenc.so"))
+    with pytest.raises(FileNotFoundError):
+        ptenc.lib()
+    with pytest.raises(FileNotFoundError):
+        ptenc.ptenc_query_sizes(cfg())
+
+
+def test_oracle_and_product_do_not_import_each_other():
+    pkg = os.path.join(ROOT, "paper_2602_16839_amd")
+    for root, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(root, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle|oracle[./]pte_oracle|oracle[./]ring_model", text, re.M), \
+                    "%s reaches into the oracle" % f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith(".py"):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2602_16839_amd" not in text and "ptenc" not in text and "import torch" not in text

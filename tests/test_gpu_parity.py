@@ -84,6 +84,14 @@ def test_norm_modes_and_zero_initialised_state(norm):
     H.run_both(wl, wl.steps, norm_mode=norm, with_global_kv=(norm != po.NORM_NONE), check_every=7)
 
 
+@pytest.mark.parametrize("G,r", [(48, 64), (64, 16), (1, 1)])
+def test_global_token_counts_and_latent_widths(G, r):
+    # the global-token ablation sizes (16 / 32 / 48 / 64) and latent widths up to 64, on the MFMA encoder
+    wl = small("qwen7b", batch=2, n_q_heads=14, n_kv_heads=2, window=64, chunk=40, steps=150, n_global=G, rank=r)
+    layer, _ = H.run_both(wl, wl.steps, check_every=13)
+    assert layer.plan() == (1, 4, 1) or layer.plan()[2] == 1
+
+
 def test_peaky_softmax_exercises_the_online_rescale():
     # queries scaled x64: scores ~ 4 N(0,1), i.e. a range of ~30 base-2 units across the window, so
     # the running max keeps moving; values stay O(0.25) so that the absolute bar is not spent on
