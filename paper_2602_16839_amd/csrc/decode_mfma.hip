@@ -236,9 +236,12 @@ __device__ inline void encode_head_share(const PtDev& c, StepSmem<WAVES>& sm, co
   const int n = lane & 15, kgrp = lane >> 4;
   const int g0 = s0 >> 5, off0 = s0 & 31, NG = c.Wr >> 5, gs = c.n_sink >> 5;   // s0: ring-relative slot
   const int n_vis = (off0 + c.C + PT_GROUP_TOKENS - 1) >> 5;
-  const int RP = c.n_rt * 16;
-  float* partK = c.enc_part + (size_t)slab * 2 * c.C * RP;
-  float* partV = partK + (size_t)c.C * RP;
+  // The share is indexed by p = 32 * visit + slot-in-group (logical token j = p - off0) and stored as
+  // [p / 4][column][p % 4], so that the 4 accumulator rows a lane holds for its column are 16
+  // contiguous bytes and a wavefront's store covers whole cache lines.
+  const int RP = c.n_rt * 16, PR = pt_share_rows(c.C);
+  float* partK = c.enc_part + (size_t)slab * 2 * PR * RP;
+  float* partV = partK + (size_t)PR * RP;
   const u32x4* WKp = (const u32x4*)c.WKp + (size_t)hkv * 4 * 4 * 64;
   const u32x4* WVp = (const u32x4*)c.WVp + (size_t)hkv * 4 * 4 * 64;
   uint16_t* vs = sm.vstage[wave];
@@ -276,15 +279,13 @@ __device__ inline void encode_head_share(const PtDev& c, StepSmem<WAVES>& sm, co
           dk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[cc].h, wk.h, dk, 0, 0, 0);
           dv = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[cc].h, wv.h, dv, 0, 0, 0);
         }
-        // D[token 4 kgrp + e][column n] -> rows by logical token index
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int j = vis * PT_GROUP_TOKENS + t * 16 + 4 * kgrp + e - off0;
-          if ((unsigned)j < (unsigned)c.C) {
-            st_agent(partK + (size_t)j * RP + rt * 16 + n, dk[e]);
-            st_agent(partV + (size_t)j * RP + rt * 16 + n, dv[e]);
-          }
-        }
+        // D[token 4 kgrp + e][column n]: rows p = 32 vis + 16 t + 4 kgrp + e (rows outside the chunk are
+        // written too and never read)
+        const size_t o = ((size_t)(vis * 8 + t * 4 + kgrp) * RP + rt * 16 + n) * 4;
+        st_agent2(partK + o, dk[0], dk[1]);
+        st_agent2(partK + o + 2, dk[2], dk[3]);
+        st_agent2(partV + o, dv[0], dv[1]);
+        st_agent2(partV + o + 2, dv[2], dv[3]);
       }
     }
     __builtin_amdgcn_wave_barrier();
@@ -294,27 +295,48 @@ __device__ inline void encode_head_share(const PtDev& c, StepSmem<WAVES>& sm, co
 // Last workgroup of a rollout: K_a, V_a = sum of the heads' shares (head order), S' = (Q_a K_a^T) V_a,
 // S <- Normalize(S + S').
 template <int WAVES>
-__device__ inline void encode_finish(const PtDev& c, StepSmem<WAVES>& sm, int b) {
+__device__ inline void encode_finish(const PtDev& c, StepSmem<WAVES>& sm, int b, int off0) {
   constexpr int THREADS = WAVES * 64;
   const int t = threadIdx.x;
-  const int RP = c.n_rt * 16;
+  const int RP = c.n_rt * 16, PR = pt_share_rows(c.C);
   float sacc[16];
 #pragma unroll
   for (int x = 0; x < 16; ++x) sacc[x] = 0.f;
-  const float* part0 = c.enc_part + (size_t)b * c.Hkv * 2 * c.C * RP;
-  for (int sub0 = 0; sub0 < c.C; sub0 += kEncSub) {
-    const int ntok = min(kEncSub, c.C - sub0);
-    for (int idx = t; idx < 2 * kEncSub * RP; idx += THREADS) {
-      const int which = idx / (kEncSub * RP), rem = idx - which * (kEncSub * RP);
-      const int tk = rem / RP, col = rem - tk * RP;
-      float v = 0.f;
-      if (tk < ntok)
-        for (int h = 0; h < c.Hkv; ++h)
-          v += ld_agent(part0 + ((size_t)(h * 2 + which) * c.C + sub0 + tk) * RP + col);
-      (which == 0 ? sm.enc.Ka : sm.enc.Va)[tk][col] = v;
+  const float* part0 = c.enc_part + (size_t)b * c.Hkv * 2 * PR * RP;
+  // 32 rows of p at a time, from a multiple of 4; rows outside the chunk [off0, off0 + C) count as zero
+  for (int ps = off0 & ~3; ps < off0 + c.C; ps += kEncSub) {
+    // one item = (K_a or V_a, block of 4 rows, column): 16 bytes per head, all heads' loads in flight together
+    for (int idx = t; idx < 2 * 8 * RP; idx += THREADS) {
+      const int which = idx / (8 * RP), rem = idx - which * (8 * RP);
+      const int blk = rem / RP, col = rem - blk * RP;
+      float v[4] = {0.f, 0.f, 0.f, 0.f};
+      if (ps + 4 * blk < off0 + c.C) {
+        const size_t o = ((size_t)((ps >> 2) + blk) * RP + col) * 4;
+        for (int h0 = 0; h0 < c.Hkv; h0 += 4) {
+          float x[4][4];
+#pragma unroll
+          for (int hh = 0; hh < 4; ++hh) {
+            const int h = h0 + hh < c.Hkv ? h0 + hh : c.Hkv - 1;       // clamp: loaded, not added
+            const float* sp = part0 + (size_t)(h * 2 + which) * PR * RP + o;
+            ld_agent2(sp, x[hh][0], x[hh][1]);
+            ld_agent2(sp + 2, x[hh][2], x[hh][3]);
+          }
+#pragma unroll
+          for (int hh = 0; hh < 4; ++hh)
+            if (h0 + hh < c.Hkv) {
+#pragma unroll
+              for (int e = 0; e < 4; ++e) v[e] += x[hh][e];
+            }
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int p = ps + 4 * blk + e;
+        (which == 0 ? sm.enc.Ka : sm.enc.Va)[4 * blk + e][col] = (p >= off0 && p < off0 + c.C) ? v[e] : 0.f;
+      }
     }
     __syncthreads();
-    pt_encode_accumulate<THREADS>(sm.enc, c.Qa, c.G, c.r, ntok, sacc);
+    pt_encode_accumulate<THREADS>(sm.enc, c.Qa, c.G, c.r, kEncSub, sacc);
   }
   pt_state_update<THREADS>(c, b, sacc, &sm.enc.Ka[0][0], sm.enc.red);
 }
@@ -575,7 +597,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
     if (tid == 0) sm_ticket = atomicAdd(c.tick_rollout + b, 1);
     __syncthreads();
     if (sm_ticket == c.Hkv * ns - 1) {
-      if (evicting) encode_finish(c, sm, b);
+      if (evicting) encode_finish(c, sm, b, (int)(base0 % c.Wr) & 31);
       if (tid == 0) {
         if (in_place) { c.len[b] = len1; c.base[b] = base1; }
         c.tick_rollout[b] = 0;

@@ -59,7 +59,7 @@ size_t partial_bytes(const ptenc_config& c) {
 
 size_t enc_part_bytes(const ptenc_config& c) {
   const size_t n_rt = (c.rank + 15) / 16;
-  return align256((size_t)c.batch * c.n_kv_heads * 2 * c.chunk * 16 * n_rt * sizeof(float));
+  return align256((size_t)c.batch * c.n_kv_heads * 2 * pt_share_rows(c.chunk) * 16 * n_rt * sizeof(float));
 }
 
 bool mfma_attn_applies(const ptenc_config& c) {
