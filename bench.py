@@ -118,12 +118,17 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--workload", default="qwen7b")
     ap.add_argument("--splits", type=int, default=0)
+    ap.add_argument("--chunk", type=int, default=0,
+                    help="override the workload's eviction chunk C (eviction-ratio sweeps; 0 = the workload's own)")
     ap.add_argument("--ragged-mode", choices=["compact", "masked"], default="compact",
                     help="ragged workloads: drop finished rollouts from the batch (rollout-id lists) or mask them")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the per-launch HIP-event pass")
     ap.add_argument("--extras", action="store_true",
                     help="also time the state-as-weight-delta application (and the question-token prefill)")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="also time a stack of this many layers (each with its own cache) over the same steps: "
+                         "eager launches, then replays of the recorded one-step HIP graph")
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch the plain copy / read kernels on 1 GiB (scale for the profiler's byte counters)")
     args = ap.parse_args()
@@ -142,6 +147,8 @@ def main() -> int:
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
     wl = I.WORKLOADS[args.workload]
+    if args.chunk:
+        wl = wl.replace(chunk=args.chunk)
     K = args.steps if args.steps > 0 else wl.steps
     Wu = max(0, args.warmup)
     lengths = I.rollout_lengths(wl)
@@ -318,6 +325,61 @@ def main() -> int:
             nb = float(prompt_len.sum()) * 2 * wl.d_kv * s_ * 2          # read once, written once
             ex["prefill"] = {"us_per_call": us, "algorithmic_bytes": nb, "GB_per_s": nb / us / 1e3}
         res["extras"] = ex
+    if args.layers > 0 and not wl.ragged:
+        # L layers, each with its own cache, counters and state; layer l reads the inputs of step t + 7 l
+        L = args.layers
+        del layer
+        st = ptenc.Stack(L, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
+                         dtype=wl.torch_dtype, n_global=wl.n_global, rank=wl.rank, n_sink=wl.n_sink)
+        for lay in st.layers:
+            lay.set_encoder(enc["q_g"], enc["WaQ"], enc["WaK"], enc["WaV"], enc["k_g"], enc["v_g"])
+            if args.splits:
+                lay.set_option(ptenc.OPT_SPLITS, args.splits)
+
+        def stack_start():
+            st.reset()
+            if wl.n_sink:
+                for lay in st.layers:
+                    lay.prefill(pk, pv, prompt_len)
+
+        outs = [out[l % T_gen] for l in range(L)]
+
+        def eager(t):
+            idx = [(t + 7 * l) % T_gen for l in range(L)]
+            st.step([q[i] for i in idx], [k[i] for i in idx], [v[i] for i in idx], outs)
+
+        def timed(fn):
+            stack_start()
+            for t in range(min(Wu, 8)):
+                fn(t)
+            stack_start()
+            torch.cuda.synchronize()
+            s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            c0 = time.perf_counter()
+            s0.record()
+            for t in range(K):
+                fn(t)
+            s1.record()
+            torch.cuda.synchronize()
+            return max(s0.elapsed_time(s1), (time.perf_counter() - c0) * 1e3)
+
+        ms_eager = timed(eager)
+        ln0, _ = st.layers[L - 1].counters()
+        assert np.array_equal(ln0, np.full(wl.batch, K)) and st.layers[0].poll_error() == 0
+        st.graph_capture([q[l % T_gen] for l in range(L)], [k[l % T_gen] for l in range(L)],
+                         [v[l % T_gen] for l in range(L)], outs)
+        ms_graph = timed(lambda t: st.graph_launch())
+        ln0, _ = st.layers[L - 1].counters()
+        assert np.array_equal(ln0, np.full(wl.batch, K)) and st.layers[0].poll_error() == 0
+        best = min(ms_eager, ms_graph)
+        res["stack"] = {
+            "layers": L, "cache_gbytes": st.cache.numel() / 1e9, "plan": list(st.layers[0].plan()),
+            "metric": "rollout decode tokens/s per model of %d layers (bounded window)" % L,
+            "value": tokens / (best * 1e-3), "unit": "tokens/s",
+            "ms_per_step_eager": ms_eager / K, "ms_per_step_graph": ms_graph / K,
+            "hbm_frac_whole_path": L * all_bytes / (best * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        }
+        del st
     if args.calibrate:
         nbytes = 1 << 30
         src = torch.randint(0, 255, (nbytes,), dtype=torch.uint8, device=dev)

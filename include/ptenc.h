@@ -226,6 +226,50 @@ ptenc_status ptenc_poll_error(ptenc_ctx* ctx, int32_t* h_flags, void* stream);
  * splits in use; *encode_kernel likewise. Any pointer may be NULL. */
 ptenc_status ptenc_get_plan(ptenc_ctx* ctx, int32_t* attn_kernel, int32_t* n_splits, int32_t* encode_kernel);
 
+/* ---- Multi-layer driver -------------------------------------------------------------------------
+ * A stack is L contexts with one configuration -- the L attention layers of one model decoding the
+ * same B rollouts (Experiment setup: the evaluated models are stacks of identical attention layers,
+ * each with its own KV cache; the rollout stage pays the bounded-cache step once per layer and
+ * token).  d_cache and d_state hold L consecutive per-layer slices of the sizes ptenc_query_sizes
+ * reports (layer l starts at l times that size); d_scratch is ONE layer's scratch, shared, which is
+ * safe because the layers of a stack run in stream order -- all calls on a stack and on its
+ * layers must be issued to one stream, or be serialised by the caller.  Layers are created with
+ * PTENC_OPT_COUNTERS_IN_PLACE = 1, and with non-temporal K/V loads when the L caches together
+ * exceed the memory-side cache.  Everything per layer (ptenc_set_encoder, ptenc_prefill,
+ * ptenc_get_state, ...) goes through the borrowed context ptenc_stack_layer returns; it dies with
+ * the stack. */
+typedef struct ptenc_stack ptenc_stack; /* opaque, host side */
+#define PTENC_MAX_LAYERS 1024
+
+ptenc_status ptenc_stack_query_sizes(const ptenc_config* cfg, int32_t n_layers, size_t* cache_bytes,
+                                     size_t* state_bytes, size_t* scratch_bytes);
+ptenc_status ptenc_stack_create(const ptenc_config* cfg, int32_t n_layers, void* d_cache, void* d_state,
+                                void* d_scratch, ptenc_stack** out);
+ptenc_status ptenc_stack_destroy(ptenc_stack* stack);
+ptenc_status ptenc_stack_layer(ptenc_stack* stack, int32_t layer, ptenc_ctx** out);
+/* ptenc_reset of every layer. */
+ptenc_status ptenc_stack_reset(ptenc_stack* stack, const uint8_t* d_mask, void* stream);
+
+/* One decode step of every layer, in layer order: ptenc_decode_step(layer l, h_q[l], h_k[l], h_v[l],
+ * h_out[l], d_active).  h_q, h_k, h_v, h_out are HOST arrays of L DEVICE pointers (a model computes
+ * layer l's q, k, v from layer l-1's output, so they live in per-layer buffers anyway); shapes per
+ * layer as for ptenc_decode_step.  Stops at the first layer that returns an error and returns it. */
+ptenc_status ptenc_stack_decode_step(ptenc_stack* stack, const void* const* h_q, const void* const* h_k,
+                                     const void* const* h_v, void* const* h_out, const uint8_t* d_active,
+                                     void* stream);
+
+/* Records one ptenc_stack_decode_step over the given buffers into a HIP graph kept by the stack
+ * (replacing an earlier one); nothing is executed.  The pointers are frozen into the graph: refill
+ * the same buffers between replays.  Every layer's encoder must be set (else PTENC_ERR_STATE).
+ * The recording uses a stream of the library's own, so the caller's stream can be the default one.
+ * A graph holds whatever kernel plan the layers had when it was recorded: record again after
+ * ptenc_set_option. */
+ptenc_status ptenc_stack_graph_capture(ptenc_stack* stack, const void* const* h_q, const void* const* h_k,
+                                       const void* const* h_v, void* const* h_out, const uint8_t* d_active);
+/* Replays the recorded step on `stream` (PTENC_ERR_STATE if none was recorded): one call = one
+ * decode step of all layers.  Allocates nothing. */
+ptenc_status ptenc_stack_graph_launch(ptenc_stack* stack, void* stream);
+
 /* Calibration helpers (no context needed): a plain streaming read of `bytes` (whole 16 KiB units,
  * a multiple of 16384 is read; d_sink is 4 bytes that are practically never written) and a
  * plain copy of `bytes` (multiple of 16), each on n_blocks workgroups of 256 threads.  They

@@ -1,0 +1,148 @@
+// Multi-layer driver: L attention layers of one model decoding the same B rollouts, one context
+// per layer over slices of three caller-owned buffers, and one decode step of the whole stack
+// either as L launches or as a replay of a HIP graph that holds them.
+//
+// Every layer keeps its own bounded cache, counters and context state (the paper's models have
+// one KV cache and one adapted projection per layer: Experiment setup, model descriptions); the
+// layers of a step run one after another on one stream, so they share a single scratch buffer.
+#include <hip/hip_runtime.h>
+
+#include <new>
+#include <vector>
+
+#include "ptenc.h"
+#include "ptenc_internal.h"
+
+struct ptenc_stack {
+  std::vector<ptenc_ctx*> layers;
+  hipStream_t capture_stream = nullptr;
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+};
+
+namespace {
+
+void drop_graph(ptenc_stack* s) {
+  if (s->exec) { (void)hipGraphExecDestroy(s->exec); s->exec = nullptr; }
+  if (s->graph) { (void)hipGraphDestroy(s->graph); s->graph = nullptr; }
+}
+
+ptenc_status launch_layers(ptenc_stack* s, const void* const* h_q, const void* const* h_k, const void* const* h_v,
+                           void* const* h_out, const uint8_t* d_active, void* stream) {
+  for (size_t l = 0; l < s->layers.size(); ++l) {
+    ptenc_status st = ptenc_decode_step(s->layers[l], h_q[l], h_k[l], h_v[l], h_out[l], d_active, stream);
+    if (st != PTENC_OK) return st;
+  }
+  return PTENC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+ptenc_status ptenc_stack_query_sizes(const ptenc_config* cfg, int32_t n_layers, size_t* cache_bytes,
+                                     size_t* state_bytes, size_t* scratch_bytes) {
+  if (n_layers < 1 || n_layers > PTENC_MAX_LAYERS) return PTENC_ERR_INVALID_ARG;
+  size_t cb = 0, sb = 0, xb = 0;
+  ptenc_status st = ptenc_query_sizes(cfg, &cb, &sb, &xb);
+  if (st != PTENC_OK) return st;
+  if (cache_bytes) *cache_bytes = cb * (size_t)n_layers;
+  if (state_bytes) *state_bytes = sb * (size_t)n_layers;
+  if (scratch_bytes) *scratch_bytes = xb;
+  return PTENC_OK;
+}
+
+ptenc_status ptenc_stack_create(const ptenc_config* cfg, int32_t n_layers, void* d_cache, void* d_state,
+                                void* d_scratch, ptenc_stack** out) {
+  if (!out) return PTENC_ERR_INVALID_ARG;
+  *out = nullptr;
+  size_t cb = 0, sb = 0, xb = 0;
+  ptenc_status st = ptenc_stack_query_sizes(cfg, n_layers, &cb, &sb, &xb);
+  if (st != PTENC_OK) return st;
+  cb /= (size_t)n_layers;
+  sb /= (size_t)n_layers;
+  ptenc_stack* s = new (std::nothrow) ptenc_stack;
+  if (!s) return PTENC_ERR_NOMEM;
+  for (int l = 0; l < n_layers; ++l) {
+    ptenc_ctx* x = nullptr;
+    st = ptenc_create(cfg, (char*)d_cache + cb * l, (char*)d_state + sb * l, d_scratch, &x);
+    // counters in place: a step of the stack may be replayed from a graph at any time
+    if (st == PTENC_OK) st = ptenc_set_option(x, PTENC_OPT_COUNTERS_IN_PLACE, 1);
+    // the layers' caches together decide whether the memory-side cache can hold the stream
+    if (st == PTENC_OK && cb * (size_t)n_layers > ((size_t)192 << 20)) st = ptenc_set_option(x, PTENC_OPT_NONTEMPORAL, 1);
+    if (x) s->layers.push_back(x);
+    if (st != PTENC_OK) {
+      (void)ptenc_stack_destroy(s);
+      return st;
+    }
+  }
+  *out = s;
+  return PTENC_OK;
+}
+
+ptenc_status ptenc_stack_destroy(ptenc_stack* s) {
+  if (!s) return PTENC_ERR_INVALID_ARG;
+  drop_graph(s);
+  if (s->capture_stream) (void)hipStreamDestroy(s->capture_stream);
+  for (ptenc_ctx* x : s->layers) (void)ptenc_destroy(x);
+  delete s;
+  return PTENC_OK;
+}
+
+ptenc_status ptenc_stack_layer(ptenc_stack* s, int32_t layer, ptenc_ctx** out) {
+  if (!s || !out || layer < 0 || (size_t)layer >= s->layers.size()) return PTENC_ERR_INVALID_ARG;
+  *out = s->layers[layer];
+  return PTENC_OK;
+}
+
+ptenc_status ptenc_stack_reset(ptenc_stack* s, const uint8_t* d_mask, void* stream) {
+  if (!s) return PTENC_ERR_INVALID_ARG;
+  for (ptenc_ctx* x : s->layers) {
+    ptenc_status st = ptenc_reset(x, d_mask, stream);
+    if (st != PTENC_OK) return st;
+  }
+  return PTENC_OK;
+}
+
+ptenc_status ptenc_stack_decode_step(ptenc_stack* s, const void* const* h_q, const void* const* h_k,
+                                     const void* const* h_v, void* const* h_out, const uint8_t* d_active,
+                                     void* stream) {
+  if (!s || !h_q || !h_k || !h_v || !h_out) return PTENC_ERR_INVALID_ARG;
+  return launch_layers(s, h_q, h_k, h_v, h_out, d_active, stream);
+}
+
+ptenc_status ptenc_stack_graph_capture(ptenc_stack* s, const void* const* h_q, const void* const* h_k,
+                                       const void* const* h_v, void* const* h_out, const uint8_t* d_active) {
+  if (!s || !h_q || !h_k || !h_v || !h_out) return PTENC_ERR_INVALID_ARG;
+  for (size_t l = 0; l < s->layers.size(); ++l) {
+    if (!h_q[l] || !h_k[l] || !h_v[l] || !h_out[l]) return PTENC_ERR_INVALID_ARG;
+    if (!s->layers[l]->encoder_set) return PTENC_ERR_STATE;
+  }
+  drop_graph(s);
+  // a stream of the library's own (default priority) records the launches; nothing runs on it
+  if (!s->capture_stream && hipStreamCreateWithFlags(&s->capture_stream, hipStreamNonBlocking) != hipSuccess)
+    return PTENC_ERR_HIP;
+  if (hipStreamBeginCapture(s->capture_stream, hipStreamCaptureModeThreadLocal) != hipSuccess) return PTENC_ERR_HIP;
+  ptenc_status st = launch_layers(s, h_q, h_k, h_v, h_out, d_active, s->capture_stream);
+  hipGraph_t g = nullptr;
+  hipError_t e = hipStreamEndCapture(s->capture_stream, &g);   // always ends the capture
+  if (st != PTENC_OK || e != hipSuccess || !g) {
+    if (g) (void)hipGraphDestroy(g);
+    return st != PTENC_OK ? st : PTENC_ERR_HIP;
+  }
+  s->graph = g;
+  if (hipGraphInstantiate(&s->exec, g, nullptr, nullptr, 0) != hipSuccess) {
+    s->exec = nullptr;
+    drop_graph(s);
+    return PTENC_ERR_HIP;
+  }
+  return PTENC_OK;
+}
+
+ptenc_status ptenc_stack_graph_launch(ptenc_stack* s, void* stream) {
+  if (!s) return PTENC_ERR_INVALID_ARG;
+  if (!s->exec) return PTENC_ERR_STATE;
+  return hipGraphLaunch(s->exec, (hipStream_t)stream) == hipSuccess ? PTENC_OK : PTENC_ERR_HIP;
+}
+
+}  // extern "C"

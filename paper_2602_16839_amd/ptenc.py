@@ -31,6 +31,8 @@ EXPORTS = [
     "ptenc_get_plan", "ptenc_status_string", "ptenc_util_stream_read", "ptenc_util_copy",
     "ptenc_prefill", "ptenc_get_prompt_len", "ptenc_decode_step_ids", "ptenc_decode_run_ids",
     "ptenc_apply_delta",
+    "ptenc_stack_query_sizes", "ptenc_stack_create", "ptenc_stack_destroy", "ptenc_stack_layer",
+    "ptenc_stack_reset", "ptenc_stack_decode_step", "ptenc_stack_graph_capture", "ptenc_stack_graph_launch",
 ]
 
 
@@ -90,6 +92,14 @@ def lib() -> C.CDLL:
             "ptenc_decode_step_ids": [vp, vp, vp, vp, vp, vp, i32, vp],
             "ptenc_decode_run_ids": [vp, vp, vp, vp, vp, vp, vp, i64, vp],
             "ptenc_apply_delta": [vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp],
+            "ptenc_stack_query_sizes": [P(Config), i32, P(sz), P(sz), P(sz)],
+            "ptenc_stack_create": [P(Config), i32, vp, vp, vp, P(vp)],
+            "ptenc_stack_destroy": [vp],
+            "ptenc_stack_layer": [vp, i32, P(vp)],
+            "ptenc_stack_reset": [vp, vp, vp],
+            "ptenc_stack_decode_step": [vp, P(vp), P(vp), P(vp), P(vp), vp, vp],
+            "ptenc_stack_graph_capture": [vp, P(vp), P(vp), P(vp), P(vp), vp],
+            "ptenc_stack_graph_launch": [vp, vp],
         }
         for name, args in sig.items():
             fn = getattr(L, name)
@@ -273,6 +283,57 @@ def ptenc_util_copy(dst, src, nbytes: int, n_blocks: int):
     _check(lib().ptenc_util_copy(_ptr(dst), _ptr(src), nbytes, n_blocks, _stream()), "ptenc_util_copy")
 
 
+def ptenc_stack_query_sizes(cfg: Config, n_layers: int):
+    a, b, c = C.c_size_t(), C.c_size_t(), C.c_size_t()
+    _check(lib().ptenc_stack_query_sizes(C.byref(cfg), n_layers, C.byref(a), C.byref(b), C.byref(c)),
+           "ptenc_stack_query_sizes")
+    return a.value, b.value, c.value
+
+
+def ptenc_stack_create(cfg: Config, n_layers: int, d_cache, d_state, d_scratch):
+    h = C.c_void_p()
+    _check(lib().ptenc_stack_create(C.byref(cfg), n_layers, _ptr(d_cache), _ptr(d_state), _ptr(d_scratch), C.byref(h)),
+           "ptenc_stack_create")
+    return h
+
+
+def ptenc_stack_destroy(stack):
+    _check(lib().ptenc_stack_destroy(stack), "ptenc_stack_destroy")
+
+
+def ptenc_stack_layer(stack, layer: int):
+    h = C.c_void_p()
+    _check(lib().ptenc_stack_layer(stack, layer, C.byref(h)), "ptenc_stack_layer")
+    return h
+
+
+def ptenc_stack_reset(stack, mask=None):
+    _check(lib().ptenc_stack_reset(stack, _ptr(mask), _stream()), "ptenc_stack_reset")
+
+
+def _ptr_array(tensors):
+    """Host array of device pointers, one per layer."""
+    arr = (C.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = _ptr(t)
+    return arr
+
+
+def ptenc_stack_decode_step(stack, q, k, v, out, active=None):
+    """q, k, v, out: sequences of L per-layer device tensors."""
+    _check(lib().ptenc_stack_decode_step(stack, _ptr_array(q), _ptr_array(k), _ptr_array(v), _ptr_array(out),
+                                         _ptr(active), _stream()), "ptenc_stack_decode_step")
+
+
+def ptenc_stack_graph_capture(stack, q, k, v, out, active=None):
+    _check(lib().ptenc_stack_graph_capture(stack, _ptr_array(q), _ptr_array(k), _ptr_array(v), _ptr_array(out),
+                                           _ptr(active)), "ptenc_stack_graph_capture")
+
+
+def ptenc_stack_graph_launch(stack):
+    _check(lib().ptenc_stack_graph_launch(stack, _stream()), "ptenc_stack_graph_launch")
+
+
 # ---- convenience owner of the device buffers (plumbing only) ---------------------------------
 
 class Layer:
@@ -292,11 +353,21 @@ class Layer:
         self.scratch = torch.empty(xb, dtype=torch.uint8, device=self.device)
         self.ctx = ptenc_create(self.cfg, self.cache, self.state, self.scratch)
         self._enc = None
+        self._owns_ctx = True
+
+    @classmethod
+    def _borrowed(cls, cfg, dtype, device, ctx, keep_alive):
+        """A layer of a Stack: same methods, context and buffers owned by the stack."""
+        self = cls.__new__(cls)
+        self.cfg, self.dtype, self.device, self.ctx = cfg, dtype, device, ctx
+        self.cache = self.state = self.scratch = None
+        self._enc, self._owns_ctx, self._stack = None, False, keep_alive
+        return self
 
     def close(self):
-        if self.ctx is not None:
+        if self.ctx is not None and self._owns_ctx:
             ptenc_destroy(self.ctx)
-            self.ctx = None
+        self.ctx = None
 
     def __del__(self):
         try:
@@ -398,3 +469,54 @@ class Layer:
 
     def set_option(self, option, value):
         ptenc_set_option(self.ctx, option, value)
+
+
+class Stack:
+    """L layers over one cache / state allocation and one shared scratch buffer; forwards to the
+    ptenc_stack_* calls.  ``layers[l]`` is a Layer view of layer l (encoder, prefill, read-back)."""
+
+    def __init__(self, n_layers, batch, n_q_heads, n_kv_heads, head_dim, window, chunk, dtype=torch.bfloat16,
+                 n_global=32, rank=32, norm_mode=NORM_FROBENIUS, norm_eps=0.0, softmax_scale=0.0,
+                 device="cuda:0", poison_cache=False, n_sink=0):
+        self.cfg = Config(batch, n_q_heads, n_kv_heads, head_dim, window, chunk, n_sink, n_global, rank,
+                          F32 if dtype == torch.float32 else BF16, norm_mode, norm_eps, softmax_scale)
+        self.dtype, self.device, self.n_layers = dtype, torch.device(device), n_layers
+        cb, sb, xb = ptenc_stack_query_sizes(self.cfg, n_layers)
+        self.cache = torch.empty(cb, dtype=torch.uint8, device=self.device)
+        if poison_cache:
+            self.cache.fill_(0xFF)
+        self.state = torch.zeros(sb, dtype=torch.uint8, device=self.device)
+        self.scratch = torch.empty(xb, dtype=torch.uint8, device=self.device)
+        self.stack = ptenc_stack_create(self.cfg, n_layers, self.cache, self.state, self.scratch)
+        self.layers = [Layer._borrowed(self.cfg, dtype, self.device, ptenc_stack_layer(self.stack, l), self)
+                       for l in range(n_layers)]
+        self._graph_bufs = None
+
+    def close(self):
+        if self.stack is not None:
+            for layer in self.layers:
+                layer.ctx = None
+            ptenc_stack_destroy(self.stack)
+            self.stack = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def reset(self, mask=None):
+        ptenc_stack_reset(self.stack, mask)
+
+    def step(self, q, k, v, out=None, active=None):
+        if out is None:
+            out = [torch.empty_like(x) for x in q]
+        ptenc_stack_decode_step(self.stack, q, k, v, out, active)
+        return out
+
+    def graph_capture(self, q, k, v, out, active=None):
+        self._graph_bufs = (list(q), list(k), list(v), list(out), active)    # frozen into the graph: keep alive
+        ptenc_stack_graph_capture(self.stack, q, k, v, out, active)
+
+    def graph_launch(self):
+        ptenc_stack_graph_launch(self.stack)

@@ -84,6 +84,27 @@ def test_create_checks_pointers_and_order_of_calls():
     assert ptenc.status_string(ptenc.ERR_UNSUPPORTED) == "unsupported configuration"
 
 
+def test_stack_sizes_and_argument_checks():
+    L = ptenc.lib()
+    c = cfg()
+    one = ptenc.ptenc_query_sizes(c)
+    cb, sb, xb = ptenc.ptenc_stack_query_sizes(c, 5)
+    assert (cb, sb, xb) == (5 * one[0], 5 * one[1], one[2])        # scratch is shared by the layers
+    a = C.c_size_t()
+    for n in (0, -1, 1025):
+        assert L.ptenc_stack_query_sizes(C.byref(c), n, C.byref(a), None, None) == ptenc.ERR_INVALID_ARG
+    h = C.c_void_p()
+    assert L.ptenc_stack_create(C.byref(c), 2, None, C.c_void_p(0x20000), C.c_void_p(0x30000), C.byref(h)) == ptenc.ERR_INVALID_ARG
+    assert L.ptenc_stack_create(C.byref(c), 2, C.c_void_p(0x1000000), C.c_void_p(0x2000000), C.c_void_p(0x3000000), C.byref(h)) == ptenc.OK
+    x = C.c_void_p()
+    assert L.ptenc_stack_layer(h, 2, C.byref(x)) == ptenc.ERR_INVALID_ARG
+    assert L.ptenc_stack_layer(h, 1, C.byref(x)) == ptenc.OK and x.value
+    assert L.ptenc_stack_graph_launch(h, None) == ptenc.ERR_STATE   # nothing recorded
+    assert L.ptenc_stack_decode_step(h, None, None, None, None, None, None) == ptenc.ERR_INVALID_ARG
+    assert L.ptenc_stack_destroy(h) == ptenc.OK
+    assert L.ptenc_stack_destroy(None) == ptenc.ERR_INVALID_ARG
+
+
 @pytest.mark.parametrize("c", [cfg(), cfg(dtype=ptenc.F32, head_dim=64, window=48, chunk=5),
                                cfg(window=40)])   # window 40 is not a multiple of 32: row-major bf16
 def test_cache_layout_is_a_bijection(c):

@@ -125,6 +125,14 @@ def test_qwen7b_with_question_tokens_full_run_sampled():
     _check(wl, [0, 64, 127], [1, R, R + 1, T], seg_steps=1024)
 
 
+def test_qwen7b_quarter_window_chunks_full_run_sampled():
+    # the paper's own eviction ratio (a quarter of the window leaves on saturation), with a chunk
+    # that is not a whole number of 32-slot groups
+    wl = I.WORKLOADS["qwen7b"].replace(chunk=1000)
+    W, C, T = wl.window, wl.chunk, wl.steps
+    _check(wl, [5, 126], [W, W + 1, W + C + 1, T], seg_steps=1024)
+
+
 def test_llama8b_full_run_sampled():
     wl = I.WORKLOADS["llama8b"]
     W, C, T = wl.window, wl.chunk, wl.steps
