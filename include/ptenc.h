@@ -83,11 +83,37 @@ typedef enum {
                                  exceeds the memory-side cache) */
   PTENC_OPT_WAVES = 3,        /* wavefronts per workgroup of the MFMA kernel: 4, or 8 (taken only with at most
                                  8 query heads per KV head); 0 = heuristic */
-  PTENC_OPT_COUNTERS_IN_PLACE = 4 /* 1 = steps update len / base in place instead of alternating between two
+  PTENC_OPT_COUNTERS_IN_PLACE = 4, /* 1 = steps update len / base in place instead of alternating between two
                                  buffers on the host.  Needed when a step is captured into a HIP graph and
                                  replayed (the alternation would be frozen into the graph); costs one extra
                                  arrival counter per rollout and step.  Default 0. */
+  PTENC_OPT_EVICT_POLICY = 5, /* ptenc_policy: which tokens an eviction takes.  Set it before the first step after
+                                 a reset (scores are kept only while it is PTENC_POLICY_SCORED). */
+  PTENC_OPT_RECENT = 6        /* scored policy: the n most recent ring entries are never taken; 0 .. W - n_sink - C;
+                                 -1 = default (half the ring, at most W - n_sink - C) */
 } ptenc_option;
+
+/* Which tokens leave when the sliding part of the cache is full.
+ * SLIDING: the C oldest thinking tokens (Our Approach, "The selection of D during training").
+ * SCORED:  importance-based token dropping (Ablation studies, "Integration with inference-time token
+ *          dropping strategy": the paper finds it more accurate but 37 % slower in rollouts and leaves an
+ *          efficient integration open).  Here the score is the heavy-hitter one -- the attention
+ *          probability a token has received, summed over decode steps and over all query heads -- and
+ *          it is a by-product of ptenc_decode_step: the probabilities of a step are recomputed, from
+ *          that step's saved queries and softmax statistics, while the NEXT step of the rollout streams
+ *          the same keys, so they join the scores one step late and cost no extra pass over the cache.
+ *          When the ring is full, the C lowest-scored entries among all but the PTENC_OPT_RECENT most
+ *          recent ones leave (ties: the older ring entry first), are encoded oldest-first into S exactly
+ *          as a sliding chunk would be, and the survivors of the oldest C ring places move into the
+ *          victims' places beyond them, so the ring stays one contiguous run (attention does not depend
+ *          on the order of the cache).  Question tokens are never scored or taken.  With
+ *          PTENC_OPT_RECENT = W - n_sink - C the policy is the sliding window.
+ *          Needs the MFMA path (bf16, head_dim 128, W and n_sink multiples of 32) and at most 12288
+ *          eligible entries; else PTENC_ERR_UNSUPPORTED.  Scores advance only through
+ *          ptenc_decode_step / ptenc_decode_run / ptenc_decode_step_ids / ptenc_decode_run_ids (a
+ *          separate ptenc_decode_attn leaves them alone); ptenc_set_counters accepts only empty
+ *          windows.  Per step it costs one extra small launch that returns at once unless a ring is full. */
+typedef enum { PTENC_POLICY_SLIDING = 0, PTENC_POLICY_SCORED = 1 } ptenc_policy;
 
 #define PTENC_MAX_SPLITS 32
 
@@ -218,6 +244,19 @@ ptenc_status ptenc_gather_window(ptenc_ctx* ctx, void* d_K, void* d_V, void* str
  * that poison or inspect raw slots. */
 ptenc_status ptenc_cache_offset(ptenc_ctx* ctx, int32_t b, int32_t h, int32_t slot, int32_t i,
                                 int32_t which, size_t* elem_offset);
+
+/* Scored policy only (else PTENC_ERR_STATE).
+ * ptenc_get_scores: the folded scores (float [B][W]) and the positions (int64 [B][W], position = the
+ *   token's 0-based append index within its rollout) of the live ring entries, in ring order, oldest
+ *   ring entry first; entries past the live count read 0 and -1.  Either output may be NULL.  Device
+ *   pointers; asynchronous.
+ * ptenc_set_scores: overwrites the scores of the live ring entries (same layout) and drops the
+ *   probabilities of the latest step that were still waiting to be folded.
+ * ptenc_get_victims: the positions the last eviction of every rollout took (int64 [B][C], ring order;
+ *   -1 where none happened since the reset).  Host pointer; synchronises. */
+ptenc_status ptenc_get_scores(ptenc_ctx* ctx, float* d_score, int64_t* d_pos, void* stream);
+ptenc_status ptenc_set_scores(ptenc_ctx* ctx, const float* d_score, void* stream);
+ptenc_status ptenc_get_victims(ptenc_ctx* ctx, int64_t* h_pos, void* stream);
 
 /* Reads and returns the sticky device error word (does not clear it; ptenc_reset(NULL) does). */
 ptenc_status ptenc_poll_error(ptenc_ctx* ctx, int32_t* h_flags, void* stream);

@@ -10,7 +10,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libptenc.so")
 SOURCES = ["ptenc_api.hip", "cache_kernels.hip", "attn_generic.hip", "decode_mfma.hip", "util_kernels.hip", "adapter_kernels.hip",
-           "stack_api.hip"]
+           "stack_api.hip", "scored_kernels.hip"]
 # packed-fp32 instruction selection is switched off for all device code
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -8,14 +8,11 @@
 // The encoder here is the general one (any dtype, layout, G and r up to 64).  It evaluates
 // S' = (Q_a (K_e W^a_K)^T)(V_e W^a_V) (Our Approach, the Delta-W equation) in the paper's
 // association, 32 tokens at a time, with fp32 accumulation.
-#include "pt_encode_tail.h"
+#include "pt_encode_alu.h"
 
 namespace {
 
 constexpr int kThreads = kEncThreads;
-constexpr int kSub = kEncSub;     // tokens per sub-chunk
-constexpr int kKB = 64;           // contraction block over d_kv
-constexpr int kMaxGR = kEncMaxGR; // max G and r
 
 // ---- token sources ---------------------------------------------------------------------------
 template <typename T>
@@ -38,67 +35,6 @@ struct GlobalTokens { // k_g, v_g: row-major [G, d_kv]
     return pt_ld<T>((which == 0 ? kg : vg) + (size_t)tok * dkv + kk);
   }
 };
-
-struct EncSmem {
-  float Ks[kSub][kKB + 1];
-  float Ws[kKB][kMaxGR];       // reused as the G x r staging area of the state update
-  EncTailSmem tail;
-};
-
-// S' of a chunk of n_tok tokens; thread t ends up with entries t, t+256, ... of the row-major
-// G x r result in sacc[].  dbg (may be null) receives the raw chunk [2][n_tok][d_kv].
-template <typename T, typename Src>
-__device__ void encode_chunk(EncSmem& sm, const Src& src, int n_tok, int dkv, int G, int r,
-                             const float* __restrict__ Qa, const T* __restrict__ WaK,
-                             const T* __restrict__ WaV, T* dbg, float sacc[16]) {
-  const int t = threadIdx.x;
-  const int tok = t & (kSub - 1), cg = t >> 5;   // 8 column groups
-#pragma unroll
-  for (int x = 0; x < 16; ++x) sacc[x] = 0.f;
-
-  for (int sub0 = 0; sub0 < n_tok; sub0 += kSub) {
-    const int ntok = min(kSub, n_tok - sub0);
-    for (int which = 0; which < 2; ++which) {
-      const T* Wsrc = which == 0 ? WaK : WaV;
-      float acc[8];
-#pragma unroll
-      for (int x = 0; x < 8; ++x) acc[x] = 0.f;
-      for (int kb = 0; kb < dkv; kb += kKB) {
-        const int nk = min(kKB, dkv - kb);
-        for (int idx = t; idx < kSub * kKB; idx += kThreads) {
-          const int tk = idx / kKB, kk = idx - tk * kKB;
-          float val = 0.f;
-          if (tk < ntok && kk < nk) {
-            val = src.get(which, sub0 + tk, kb + kk);
-            if (dbg) pt_st<T>(dbg + ((size_t)which * n_tok + sub0 + tk) * dkv + kb + kk, val);
-          }
-          sm.Ks[tk][kk] = val;
-        }
-        for (int idx = t; idx < kKB * r; idx += kThreads) {
-          const int kk = idx / r, col = idx - kk * r;
-          sm.Ws[kk][col] = kk < nk ? pt_ld<T>(Wsrc + (size_t)(kb + kk) * r + col) : 0.f;
-        }
-        __syncthreads();
-        for (int kk = 0; kk < kKB; ++kk) {
-          const float kv = sm.Ks[tok][kk];
-#pragma unroll
-          for (int x = 0; x < 8; ++x) {
-            const int col = cg + 8 * x;
-            if (col < r) acc[x] = fmaf(kv, sm.Ws[kk][col], acc[x]);
-          }
-        }
-        __syncthreads();
-      }
-#pragma unroll
-      for (int x = 0; x < 8; ++x) {
-        const int col = cg + 8 * x;
-        if (col < r) (which == 0 ? sm.tail.Ka : sm.tail.Va)[tok][col] = acc[x];
-      }
-    }
-    __syncthreads();
-    pt_encode_accumulate<kThreads>(sm.tail, Qa, G, r, ntok, sacc);
-  }
-}
 
 // ---- step prologue ----------------------------------------------------------------------------
 template <typename T>
@@ -171,6 +107,9 @@ __global__ void reset_kernel(PtDev c, const uint8_t* __restrict__ mask, int clea
   const int n = c.G * c.r;
   for (int i = threadIdx.x; i < n; i += blockDim.x) c.S[(size_t)b * n + i] = c.S0[i];
   if (threadIdx.x == 0) { c.len[b] = 0; c.base[b] = 0; c.n_prompt[b] = 0; }
+  // importance scores: nothing waits to be folded, no eviction has happened
+  for (int h = threadIdx.x; h < c.Hkv; h += blockDim.x) c.mtag[b * c.Hkv + h] = -1;
+  for (int i = threadIdx.x; i < c.C; i += blockDim.x) c.victims[(size_t)b * c.C + i] = -1;
 }
 
 template <typename T>

@@ -135,6 +135,42 @@ __device__ inline void process_group(Frag& f, const Op q[4], Acc& a, int jg, int
   for (int i = 0; i < 8; ++i) a.o[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.v[i].h, pf.h, a.o[i], 0, 0, 0);
 }
 
+// Importance scores: the probability every token of a group received in the rollout's PREVIOUS step,
+// recomputed from that step's saved queries and softmax statistics while the group's keys are in
+// registers anyway (the ablation on token dropping strategies; accumulated attention probability is
+// the heavy-hitter score).  Heads ride in the M dimension here, so that the sum over heads is a sum
+// over a lane's 4 accumulator rows and two xor-shuffles:
+//   D[head 4 kgrp + e][token n] = Q_prev (16 x 32k) * K_tile^T (32k x 16)
+// mp / il = that step's maximum (base-2 domain) and 1 / sum for heads 4 kgrp + e (il = 0 beyond the
+// query group).  Returns this lane's token's probability mass: lanes 0..15 token n of the first 16,
+// lanes 16..31 token n of the second 16 (the other lanes hold copies).  jg, n_valid as in process_group.
+struct Lagged {
+  Op q[4];
+  float mp[4], il[4];
+};
+
+__device__ inline float lagged_mass(const Frag& f, const Lagged& g, int jg, int n_valid, float scale_log2,
+                                    int n, int kgrp) {
+  f32x4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(g.q[c].h, f.k0[c].h, d0, 0, 0, 0);
+    d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(g.q[c].h, f.k1[c].h, d1, 0, 0, 0);
+  }
+  float t0 = 0.f, t1 = 0.f;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    t0 = fmaf(g.il[e], __builtin_amdgcn_exp2f(d0[e] * scale_log2 - g.mp[e]), t0);
+    t1 = fmaf(g.il[e], __builtin_amdgcn_exp2f(d1[e] * scale_log2 - g.mp[e]), t1);
+  }
+  // a dead slot's key may be anything: its column is garbage, but columns never mix
+  t0 += __shfl_xor(t0, 16, 64); t0 += __shfl_xor(t0, 32, 64);
+  t1 += __shfl_xor(t1, 16, 64); t1 += __shfl_xor(t1, 32, 64);
+  const int j = jg + (kgrp & 1) * 16 + n;
+  const float t = (kgrp & 1) ? t1 : t0;
+  return (unsigned)j < (unsigned)n_valid ? t : 0.f;
+}
+
 // kp[c] = this lane's 16 bytes of the new key (k-chunk c), vp[i] = new value column 16 i + (lane % 16).
 __device__ inline void load_newest(Op kp[4], uint16_t vp[8], const uint16_t* __restrict__ knew,
                                    const uint16_t* __restrict__ vnew, size_t src, int n, int kgrp) {
@@ -341,7 +377,7 @@ __device__ inline void encode_finish(const PtDev& c, StepSmem<WAVES>& sm, int b,
   pt_state_update<THREADS>(c, b, sacc, &sm.enc.Ka[0][0], sm.enc.red);
 }
 
-template <bool NT, int WAVES>
+template <bool NT, int WAVES, bool MASS>
 __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, StepArgs a) {
   constexpr int kWaves = WAVES;
   __shared__ StepSmem<WAVES> sm;
@@ -415,6 +451,11 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
       uint16_t vp[8];
       load_newest(kp, vp, a.knew, a.vnew, ((size_t)j_row * c.Hkv + hkv) * 128, n, kgrp);
       store_newest((uint16_t*)slab_p, c.W, c.n_sink + (int)(len0 % c.Wr), kp, vp, n, kgrp);
+      if (c.scored && lane == 0) {            // a new token starts with no score
+        const int slot = c.n_sink + (int)(len0 % c.Wr);
+        c.mass[(size_t)slab * c.W + slot] = 0.f;
+        if (hkv == 0) c.pos[(size_t)b * c.W + slot] = len0;
+      }
     }
   }
   if (append_full && owner && hkv == 0 && tid == 0) atomicOr(c.err, PTENC_DEVERR_APPEND_FULL);
@@ -441,6 +482,33 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
 #pragma unroll
         for (int cc = 0; cc < 4; ++cc) qf[cc].u = u32x4{0u, 0u, 0u, 0u};
       }
+      // the previous step's queries and statistics, if they wait to be folded into the scores
+      // (saved by the step that left len == len0, in the buffer of that parity)
+      Lagged lg;
+      bool fold = false;
+      float* mass_slab = nullptr;
+      if constexpr (MASS) {
+        mass_slab = c.mass + (size_t)slab * c.W;
+        fold = appending && c.mtag[slab] == len0;
+        const int par = (int)(len0 & 1);
+        const uint16_t* qb = c.qprev + ((size_t)par * c.B + b) * c.Hq * 128;
+        const float* mlb = c.mlprev + ((size_t)par * c.B + b) * c.Hq * 2;
+        if (fold && n < g) {
+          const u32x4* qp = (const u32x4*)(qb + (size_t)(hkv * g + n) * 128);
+#pragma unroll
+          for (int cc = 0; cc < 4; ++cc) lg.q[cc].u = qp[cc * 4 + kgrp];
+        } else {
+#pragma unroll
+          for (int cc = 0; cc < 4; ++cc) lg.q[cc].u = u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int hh = 4 * kgrp + e;
+          const bool ok = fold && hh < g;
+          lg.mp[e] = ok ? mlb[(hkv * g + hh) * 2] : 0.f;
+          lg.il[e] = ok ? mlb[(hkv * g + hh) * 2 + 1] : 0.f;
+        }
+      }
       auto grp_ptr = [&](int visit) {
         int pg = visit;                       // question tokens: group `visit`
         if (visit >= n_sink_vis) {
@@ -456,19 +524,47 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
         return visit < n_sink_vis ? visit * PT_GROUP_TOKENS : (visit - n_sink_vis) * PT_GROUP_TOKENS - off0;
       };
       auto visit_lim = [&](int visit) { return visit < n_sink_vis ? P : n_live; };
+      // scores: lanes 0..31 own the group's 32 accumulators (slot = lane); the old value is loaded with
+      // the group, the new one stored after it.  The token appended by this step starts at zero and
+      // takes no part in the previous step; question tokens are not scored.
+      auto mass_ptr = [&](int visit) {
+        return mass_slab + ((const uint16_t*)grp_ptr(visit) - (const uint16_t*)slab_p) / (PT_GROUP_ELEMS / PT_GROUP_TOKENS) + (lane & 31);
+      };
+      auto mass_load = [&](int visit) { return (visit >= n_sink_vis && lane < 32) ? *mass_ptr(visit) : 0.f; };
+      auto mass_fold = [&](const Frag& f, int visit, float old) {
+        if (visit < n_sink_vis) return;
+        const int jg = visit_jg(visit), j = jg + (lane & 31);
+        const float add = fold ? lagged_mass(f, lg, jg, n_live - 1, c.scale_log2, n, kgrp) : 0.f;
+        if (lane < 32) {
+          if (j == n_live - 1 && appending) *mass_ptr(visit) = 0.f;
+          else if (fold && (unsigned)j < (unsigned)(n_live - 1)) *mass_ptr(visit) = old + add;
+        }
+      };
       int i = v0 + wave;
       Frag fa, fb;
-      if (i < v1) load_group<NT>(fa, grp_ptr(i), lane);
+      float ma = 0.f, mb = 0.f;
+      if (i < v1) {
+        load_group<NT>(fa, grp_ptr(i), lane);
+        if constexpr (MASS) ma = mass_load(i);
+      }
       while (i < v1) {
         int nx = i + kWaves;
-        if (nx < v1) load_group<NT>(fb, grp_ptr(nx), lane);
+        if (nx < v1) {
+          load_group<NT>(fb, grp_ptr(nx), lane);
+          if constexpr (MASS) mb = mass_load(nx);
+        }
         if (patch && i == p_visit) patch_newest(fa, kp, vp, p_tl, n, kgrp);
+        if constexpr (MASS) mass_fold(fa, i, ma);
         process_group(fa, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp);
         i = nx;
         if (i >= v1) break;
         nx = i + kWaves;
-        if (nx < v1) load_group<NT>(fa, grp_ptr(nx), lane);
+        if (nx < v1) {
+          load_group<NT>(fa, grp_ptr(nx), lane);
+          if constexpr (MASS) ma = mass_load(nx);
+        }
         if (patch && i == p_visit) patch_newest(fb, kp, vp, p_tl, n, kgrp);
+        if constexpr (MASS) mass_fold(fb, i, mb);
         process_group(fb, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp);
         i = nx;
       }
@@ -476,6 +572,17 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
       // chunk of an evicting step was read before anything could overwrite its oldest slot
       if (patch && wave == 0)
         store_newest((uint16_t*)slab_p, c.W, c.n_sink + (int)(len0 % c.Wr), kp, vp, n, kgrp);
+      if constexpr (MASS) {
+        if (patch && wave == 0) {
+          // this step's queries wait for the next step, in the buffer of the parity of the length it leaves
+          if (n < g) {
+            u32x4* qs = (u32x4*)(c.qprev + (((size_t)(len1 & 1) * c.B + b) * c.Hq + hkv * g + n) * 128);
+#pragma unroll
+            for (int cc = 0; cc < 4; ++cc) qs[cc * 4 + kgrp] = qf[cc].u;
+          }
+          if (hkv == 0 && lane == 0) c.pos[(size_t)b * c.W + c.n_sink + (int)(len0 % c.Wr)] = len0;
+        }
+      }
     }
 
     // ---- merge the 4 wavefronts through LDS ----
@@ -569,6 +676,16 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
         if (tid == 0) c.tick_slab[slab] = 0;
       }
     }
+    if constexpr (MASS) {
+      if (write_out && appending) {
+        if (part == 0) {
+          float* ml = c.mlprev + (((size_t)(len1 & 1) * c.B + b) * c.Hq + hkv * g + qn) * 2;
+          ml[0] = M;
+          ml[1] = L > 0.f ? 1.f / L : 0.f;
+        }
+        if (tid == 0) c.mtag[slab] = len1;
+      }
+    }
     if (write_out) {
       const float inv = L > 0.f ? 1.f / L : 0.f;
       Op r;
@@ -644,12 +761,17 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bo
   PtDev cc = c;
   if (!do_attend) cc.n_splits = 1;
   dim3 grid((ids ? n_rows : cc.B) * cc.Hkv, cc.n_splits);
-  if (waves == 8) {
-    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 8>), grid, dim3(512), 0, s, cc, a);
-    else hipLaunchKernelGGL((decode_mfma_kernel<false, 8>), grid, dim3(512), 0, s, cc, a);
+  // scores are maintained by whole steps only (append + attention) under the scored policy
+  const bool mass = cc.scored && do_append && do_attend;
+  if (mass) {
+    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 4, true>), grid, dim3(256), 0, s, cc, a);
+    else hipLaunchKernelGGL((decode_mfma_kernel<false, 4, true>), grid, dim3(256), 0, s, cc, a);
+  } else if (waves == 8) {
+    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 8, false>), grid, dim3(512), 0, s, cc, a);
+    else hipLaunchKernelGGL((decode_mfma_kernel<false, 8, false>), grid, dim3(512), 0, s, cc, a);
   } else {
-    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 4>), grid, dim3(256), 0, s, cc, a);
-    else hipLaunchKernelGGL((decode_mfma_kernel<false, 4>), grid, dim3(256), 0, s, cc, a);
+    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 4, false>), grid, dim3(256), 0, s, cc, a);
+    else hipLaunchKernelGGL((decode_mfma_kernel<false, 4, false>), grid, dim3(256), 0, s, cc, a);
   }
   return hipGetLastError();
 }

@@ -11,7 +11,8 @@ namespace {
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct StateLayout {
-  size_t S, Qa, S0, len, base, len2, base2, n_prompt, err, tick_rollout, tick_slab, WKp, WVp, total;
+  size_t S, Qa, S0, len, base, len2, base2, n_prompt, err, tick_rollout, tick_slab, WKp, WVp;
+  size_t mass, pos, victims, vidx, qprev, mlprev, mtag, total;   // importance-based eviction
 };
 
 StateLayout state_layout(const ptenc_config& c) {
@@ -32,6 +33,14 @@ StateLayout state_layout(const ptenc_config& c) {
   const size_t packed = (size_t)c.n_kv_heads * 4 * 4 * 64 * 8 * 2;   // MFMA operand form of W^a_K / W^a_V
   L.WKp = off;  off = align256(off + packed);
   L.WVp = off;  off = align256(off + packed);
+  const size_t slabs = (size_t)c.batch * c.n_kv_heads, rows = (size_t)c.batch * c.n_q_heads;
+  L.mass = off;    off = align256(off + slabs * c.window * sizeof(float));
+  L.pos = off;     off = align256(off + (size_t)c.batch * c.window * sizeof(long long));
+  L.victims = off; off = align256(off + (size_t)c.batch * c.chunk * sizeof(long long));
+  L.vidx = off;    off = align256(off + (size_t)c.batch * c.chunk * sizeof(int));
+  L.qprev = off;   off = align256(off + 2 * rows * c.head_dim * 2);
+  L.mlprev = off;  off = align256(off + 2 * rows * 2 * sizeof(float));
+  L.mtag = off;    off = align256(off + slabs * sizeof(long long));
   L.total = off;
   return L;
 }
@@ -92,8 +101,19 @@ int pick_waves(const ptenc_ctx* x, long n_rollouts, int splits) {
   return (want == 8 && x->dev.group <= 8) ? 8 : 4;
 }
 
+// most recent ring entries the scored policy protects: the caller's value, else half the ring,
+// never so many that fewer than a chunk stay eligible
+int resolved_recent(const ptenc_ctx* x) {
+  const int Wr = x->dev.Wr, C = x->dev.C;
+  int r = x->opt_recent >= 0 ? x->opt_recent : Wr / 2;
+  if (r > Wr - C) r = Wr - C;
+  return r;
+}
+
 void replan(ptenc_ctx* x) {
   x->attn_kernel = (x->dev.tiled && !x->opt_force_generic) ? 1 : 0;
+  x->dev.scored = (x->opt_policy == PTENC_POLICY_SCORED && x->attn_kernel == 1) ? 1 : 0;
+  x->dev.n_recent = resolved_recent(x);
   x->encode_kernel = x->attn_kernel;
   x->dev.n_splits = x->opt_splits > 0 ? x->opt_splits : heuristic_splits(x, x->cfg.batch);
   x->waves = pick_waves(x, x->cfg.batch, x->dev.n_splits);
@@ -169,6 +189,11 @@ ptenc_status ptenc_create(const ptenc_config* cfg, void* d_cache, void* d_state,
   d.n_rt = (cfg->rank + 15) / 16;
   d.tick_rollout = (int*)(sp + L.tick_rollout); d.tick_slab = (int*)(sp + L.tick_slab);
   d.WKp = sp + L.WKp; d.WVp = sp + L.WVp;
+  d.scored = 0; d.n_recent = 0;
+  d.mass = (float*)(sp + L.mass); d.pos = (long long*)(sp + L.pos); d.victims = (long long*)(sp + L.victims);
+  d.vidx = (int*)(sp + L.vidx); d.qprev = (uint16_t*)(sp + L.qprev); d.mlprev = (float*)(sp + L.mlprev);
+  d.mtag = (long long*)(sp + L.mtag);
+  x->opt_recent = -1;
   replan(x);
   *out = x;
   return PTENC_OK;
@@ -201,7 +226,23 @@ ptenc_status ptenc_set_option(ptenc_ctx* ctx, int32_t option, int32_t value) {
       break;
     case PTENC_OPT_FORCE_GENERIC:
       if (value != 0 && value != 1) return PTENC_ERR_INVALID_ARG;
+      if (value == 1 && ctx->opt_policy == PTENC_POLICY_SCORED) return PTENC_ERR_UNSUPPORTED;
       ctx->opt_force_generic = value;
+      break;
+    case PTENC_OPT_EVICT_POLICY:
+      if (value != PTENC_POLICY_SLIDING && value != PTENC_POLICY_SCORED) return PTENC_ERR_INVALID_ARG;
+      if (value == PTENC_POLICY_SCORED) {
+        // the scores are a by-product of the MFMA step kernel, and the selection ranks in LDS
+        if (!ctx->dev.tiled || ctx->opt_force_generic) return PTENC_ERR_UNSUPPORTED;
+        if (ctx->dev.Wr - resolved_recent(ctx) > PT_SCORED_MAX_ELIGIBLE) return PTENC_ERR_UNSUPPORTED;
+      }
+      ctx->opt_policy = value;
+      break;
+    case PTENC_OPT_RECENT:
+      if (value < -1 || (value >= 0 && value > ctx->dev.Wr - ctx->dev.C)) return PTENC_ERR_INVALID_ARG;
+      if (ctx->opt_policy == PTENC_POLICY_SCORED && value >= 0 && ctx->dev.Wr - value > PT_SCORED_MAX_ELIGIBLE)
+        return PTENC_ERR_UNSUPPORTED;
+      ctx->opt_recent = value;
       break;
     default:
       return PTENC_ERR_INVALID_ARG;
@@ -282,6 +323,8 @@ ptenc_status ptenc_cache_append(ptenc_ctx* ctx, const void* d_k, const void* d_v
 ptenc_status ptenc_evict_encode(ptenc_ctx* ctx, const uint8_t* d_active, void* d_dbg_chunk, void* stream) {
   if (!ctx) return PTENC_ERR_INVALID_ARG;
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
+  if (ctx->dev.scored)   // moves base in place: no buffer rotation
+    return hip_status(pt_launch_scored_evict(ctx->dev, d_active, d_dbg_chunk, nullptr, 0, S(stream)));
   if (ctx->attn_kernel == 1)
     return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, true, false, false, nullptr, nullptr,
                                                nullptr, nullptr, d_active, d_dbg_chunk, nullptr, 0, ctx->opt_in_place != 0, S(stream)));
@@ -307,8 +350,10 @@ ptenc_status ptenc_decode_step(ptenc_ctx* ctx, const void* d_q, const void* d_k,
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_q | (uintptr_t)d_out | (uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
-    return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, true, true, true, d_q, d_k, d_v, d_out,
-                                               d_active, nullptr, nullptr, 0, ctx->opt_in_place != 0, S(stream)));
+    if (ctx->dev.scored && pt_launch_scored_evict(ctx->dev, d_active, nullptr, nullptr, 0, S(stream)) != hipSuccess)
+      return PTENC_ERR_HIP;
+    return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, !ctx->dev.scored, true, true, d_q, d_k,
+                                               d_v, d_out, d_active, nullptr, nullptr, 0, ctx->opt_in_place != 0, S(stream)));
   }
   if (advanced(ctx, pt_launch_step_prologue(ctx->dev, true, true, d_k, d_v, d_active, nullptr, nullptr, 0,
                                             ctx->opt_in_place != 0, S(stream))) != PTENC_OK)
@@ -327,8 +372,9 @@ ptenc_status ptenc_decode_step_ids(ptenc_ctx* ctx, const void* d_q, const void* 
   d.n_splits = ctx->opt_splits > 0 ? ctx->opt_splits : heuristic_splits(ctx, n);
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_q | (uintptr_t)d_out | (uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
+    if (d.scored && pt_launch_scored_evict(d, nullptr, nullptr, d_ids, n, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
     // counters are written in place by this launch: no buffer rotation
-    return hip_status(pt_launch_decode_mfma(d, ctx->nontemporal != 0, pick_waves(ctx, n, d.n_splits), true, true, true,
+    return hip_status(pt_launch_decode_mfma(d, ctx->nontemporal != 0, pick_waves(ctx, n, d.n_splits), !d.scored, true, true,
                                             d_q, d_k, d_v, d_out, nullptr, nullptr, d_ids, n, true, S(stream)));
   }
   hipError_t e = pt_launch_step_prologue(d, true, true, d_k, d_v, nullptr, nullptr, d_ids, n, true, S(stream));
@@ -396,6 +442,13 @@ ptenc_status ptenc_set_counters(ptenc_ctx* ctx, const int64_t* h_len, const int6
   if (!ctx || !h_len || !h_base) return PTENC_ERR_INVALID_ARG;
   for (int b = 0; b < ctx->cfg.batch; ++b)
     if (h_base[b] < 0 || h_len[b] < h_base[b] || h_len[b] - h_base[b] > ctx->dev.Wr) return PTENC_ERR_INVALID_ARG;
+  if (ctx->dev.scored) {
+    // live tokens would need scores and position tags that nobody supplies: only empty windows may be re-based
+    for (int b = 0; b < ctx->cfg.batch; ++b)
+      if (h_len[b] != h_base[b]) return PTENC_ERR_UNSUPPORTED;
+    if (hipMemsetAsync(ctx->dev.mtag, 0xff, sizeof(long long) * ctx->cfg.batch * ctx->cfg.n_kv_heads, S(stream)) != hipSuccess)
+      return PTENC_ERR_HIP;
+  }
   const size_t n = sizeof(long long) * ctx->cfg.batch;
   if (hipMemcpyAsync(ctx->dev.len, h_len, n, hipMemcpyHostToDevice, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
   if (hipMemcpyAsync(ctx->dev.base, h_base, n, hipMemcpyHostToDevice, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
@@ -423,6 +476,26 @@ ptenc_status ptenc_get_encoder_state(ptenc_ctx* ctx, float* h_Qa, float* h_S0, v
   const size_t n = sizeof(float) * ctx->cfg.n_global * ctx->cfg.rank;
   if (h_Qa && hipMemcpyAsync(h_Qa, ctx->dev.Qa, n, hipMemcpyDeviceToHost, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
   if (h_S0 && hipMemcpyAsync(h_S0, ctx->dev.S0, n, hipMemcpyDeviceToHost, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
+  return hip_status(hipStreamSynchronize(S(stream)));
+}
+
+ptenc_status ptenc_get_scores(ptenc_ctx* ctx, float* d_score, int64_t* d_pos, void* stream) {
+  if (!ctx || (!d_score && !d_pos)) return PTENC_ERR_INVALID_ARG;
+  if (!ctx->dev.scored) return PTENC_ERR_STATE;
+  return hip_status(pt_launch_scores_get(ctx->dev, d_score, (long long*)d_pos, S(stream)));
+}
+
+ptenc_status ptenc_set_scores(ptenc_ctx* ctx, const float* d_score, void* stream) {
+  if (!ctx || !d_score) return PTENC_ERR_INVALID_ARG;
+  if (!ctx->dev.scored) return PTENC_ERR_STATE;
+  return hip_status(pt_launch_scores_set(ctx->dev, d_score, S(stream)));
+}
+
+ptenc_status ptenc_get_victims(ptenc_ctx* ctx, int64_t* h_pos, void* stream) {
+  if (!ctx || !h_pos) return PTENC_ERR_INVALID_ARG;
+  if (!ctx->dev.scored) return PTENC_ERR_STATE;
+  const size_t n = sizeof(long long) * ctx->cfg.batch * ctx->cfg.chunk;
+  if (hipMemcpyAsync(h_pos, ctx->dev.victims, n, hipMemcpyDeviceToHost, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
   return hip_status(hipStreamSynchronize(S(stream)));
 }
 

@@ -40,6 +40,17 @@ struct PtDev {
   void* WKp;          // W^a_K, W^a_V repacked as MFMA B operands: [H_kv][4][4][64 lanes][8] bf16
   void* WVp;
   float* enc_part;    // [B*H_kv][2][pt_share_rows(C)][16 n_rt]: each KV head's share of K_a and V_a
+  // importance-based eviction (MFMA path only)
+  int scored;         // 1: an eviction takes the lowest-scored tokens instead of the oldest
+  int n_recent;       // most recent ring entries an eviction never takes
+  float* mass;        // [B*H_kv][W] by physical slot: attention probability the token has received from
+                      //   this KV head's query heads, all folded steps summed
+  long long* pos;     // [B][W] by physical slot: position (append index) of the token stored there
+  long long* victims; // [B][C] positions the rollout's last eviction took, ring order (-1: none yet)
+  int* vidx;          // [B][C] selection scratch: ring indices of the victims
+  uint16_t* qprev;    // [2][B][H_q][128] the latest step's queries, buffer = parity of the length it left
+  float* mlprev;      // [2][B][H_q][2]   that step's softmax maximum (base-2 domain) and 1 / sum
+  long long* mtag;    // [B*H_kv] the length that step left (its data waits to be folded); -1: none
 };
 
 struct ptenc_ctx {
@@ -53,6 +64,8 @@ struct ptenc_ctx {
   int nontemporal;       // resolved
   int opt_waves;         // 0 = heuristic, 4, 8
   int opt_in_place;      // 1 = counters are updated in place (no buffer rotation on the host)
+  int opt_policy;        // 0 sliding window, 1 scored
+  int opt_recent;        // -1 = default
   int waves;             // resolved: wavefronts per workgroup of the MFMA kernel
   int attn_kernel;       // 0 generic, 1 mfma
   int encode_kernel;     // 0 generic, 1 mfma
@@ -150,3 +163,9 @@ hipError_t pt_launch_pack_weights(const PtDev& c, hipStream_t s);
 hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bool do_evict, bool do_append, bool do_attend,
                                  const void* q, const void* k, const void* v, void* out, const uint8_t* active,
                                  void* dbg_chunk, const int* ids, int n_rows, bool in_place, hipStream_t s);
+// importance-based eviction (scored_kernels.hip)
+hipError_t pt_launch_scored_evict(const PtDev& c, const uint8_t* active, void* dbg_chunk, const int* ids, int n_rows,
+                                  hipStream_t s);
+hipError_t pt_launch_scores_get(const PtDev& c, float* d_score, long long* d_pos, hipStream_t s);
+hipError_t pt_launch_scores_set(const PtDev& c, const float* d_score, hipStream_t s);
+#define PT_SCORED_MAX_ELIGIBLE 12288   // eligible ring entries the selection can rank (48 KiB of LDS)

@@ -21,6 +21,8 @@ F32, BF16 = 0, 1
 NORM_FROBENIUS, NORM_ROW_L2, NORM_NONE = 0, 1, 2
 DEVERR_APPEND_FULL, DEVERR_ATTEND_EMPTY, DEVERR_BAD_ID = 1, 2, 4
 OPT_SPLITS, OPT_FORCE_GENERIC, OPT_NONTEMPORAL, OPT_WAVES, OPT_COUNTERS_IN_PLACE = 0, 1, 2, 3, 4
+OPT_EVICT_POLICY, OPT_RECENT = 5, 6
+POLICY_SLIDING, POLICY_SCORED = 0, 1
 MAX_SPLITS = 32
 
 EXPORTS = [
@@ -31,6 +33,7 @@ EXPORTS = [
     "ptenc_get_plan", "ptenc_status_string", "ptenc_util_stream_read", "ptenc_util_copy",
     "ptenc_prefill", "ptenc_get_prompt_len", "ptenc_decode_step_ids", "ptenc_decode_run_ids",
     "ptenc_apply_delta",
+    "ptenc_get_scores", "ptenc_set_scores", "ptenc_get_victims",
     "ptenc_stack_query_sizes", "ptenc_stack_create", "ptenc_stack_destroy", "ptenc_stack_layer",
     "ptenc_stack_reset", "ptenc_stack_decode_step", "ptenc_stack_graph_capture", "ptenc_stack_graph_launch",
 ]
@@ -92,6 +95,9 @@ def lib() -> C.CDLL:
             "ptenc_decode_step_ids": [vp, vp, vp, vp, vp, vp, i32, vp],
             "ptenc_decode_run_ids": [vp, vp, vp, vp, vp, vp, vp, i64, vp],
             "ptenc_apply_delta": [vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp],
+            "ptenc_get_scores": [vp, vp, vp, vp],
+            "ptenc_set_scores": [vp, vp, vp],
+            "ptenc_get_victims": [vp, vp, vp],
             "ptenc_stack_query_sizes": [P(Config), i32, P(sz), P(sz), P(sz)],
             "ptenc_stack_create": [P(Config), i32, vp, vp, vp, P(vp)],
             "ptenc_stack_destroy": [vp],
@@ -283,6 +289,22 @@ def ptenc_util_copy(dst, src, nbytes: int, n_blocks: int):
     _check(lib().ptenc_util_copy(_ptr(dst), _ptr(src), nbytes, n_blocks, _stream()), "ptenc_util_copy")
 
 
+def ptenc_get_scores(ctx, score, pos):
+    """score float32 [B, W], pos int64 [B, W] device tensors (either may be None)."""
+    _check(lib().ptenc_get_scores(ctx, _ptr(score), _ptr(pos), _stream()), "ptenc_get_scores")
+
+
+def ptenc_set_scores(ctx, score):
+    assert score.dtype == torch.float32
+    _check(lib().ptenc_set_scores(ctx, _ptr(score), _stream()), "ptenc_set_scores")
+
+
+def ptenc_get_victims(ctx, batch: int, chunk: int):
+    pos = np.zeros((batch, chunk), dtype=np.int64)
+    _check(lib().ptenc_get_victims(ctx, pos.ctypes.data_as(C.c_void_p), _stream()), "ptenc_get_victims")
+    return pos
+
+
 def ptenc_stack_query_sizes(cfg: Config, n_layers: int):
     a, b, c = C.c_size_t(), C.c_size_t(), C.c_size_t()
     _check(lib().ptenc_stack_query_sizes(C.byref(cfg), n_layers, C.byref(a), C.byref(b), C.byref(c)),
@@ -469,6 +491,22 @@ class Layer:
 
     def set_option(self, option, value):
         ptenc_set_option(self.ctx, option, value)
+
+    def scores(self):
+        """(scores float32 [B, W], positions int64 [B, W]) of the live ring entries, ring order, on the host."""
+        sc = torch.empty((self.B, self.cfg.window), dtype=torch.float32, device=self.device)
+        ps = torch.empty((self.B, self.cfg.window), dtype=torch.int64, device=self.device)
+        ptenc_get_scores(self.ctx, sc, ps)
+        return sc.cpu().numpy(), ps.cpu().numpy()
+
+    def set_scores(self, scores):
+        sc = torch.as_tensor(np.ascontiguousarray(scores, dtype=np.float32)).to(self.device)
+        assert tuple(sc.shape) == (self.B, self.cfg.window)
+        ptenc_set_scores(self.ctx, sc)
+        torch.cuda.current_stream().synchronize()
+
+    def victims(self):
+        return ptenc_get_victims(self.ctx, self.B, self.cfg.chunk)
 
 
 class Stack:

@@ -1,0 +1,201 @@
+"""Importance-based eviction on the GPU against the scored oracle.
+
+The scores are floating point (compared with a tolerance); which tokens leave is an integer
+decision taken on them.  Two kinds of test keep the two apart: selection on INJECTED scores (the
+same float32 values on both sides, many ties) must agree bit for bit, and end-to-end runs use
+inputs whose oracle-side margin between the last victim and the best survivor is far above the
+score tolerance at every eviction (asserted), so both sides must pick the same tokens."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import scored_oracle as so
+from paper_2602_16839_amd import inputs as I
+from paper_2602_16839_amd import ptenc
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+SCORE_ABS, SCORE_REL = 1e-4, 1e-3      # fp32 exp2 / accumulation against fp64
+MIN_MARGIN = 2e-2                      # relative gap the end-to-end inputs must keep at every selection
+
+
+def small(**kw):
+    base = dict(batch=3, n_q_heads=14, n_kv_heads=2, window=96, chunk=32, steps=200)
+    base.update(kw)
+    return I.WORKLOADS["qwen7b"].replace(**base)
+
+
+def make_both(wl, n_recent, splits=0):
+    enc = I.encoder_params(wl)
+    e = {k: H.f64(v) for k, v in enc.items()}
+    orc = so.ScoredOracleLayer(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk, n_recent,
+                               e["q_g"], e["WaQ"], e["WaK"], e["WaV"], e["k_g"], e["v_g"], n_sink=wl.n_sink)
+    layer = ptenc.Layer(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
+                        dtype=wl.torch_dtype, n_global=wl.n_global, rank=wl.rank, poison_cache=True, n_sink=wl.n_sink)
+    layer.set_option(ptenc.OPT_RECENT, n_recent)
+    layer.set_option(ptenc.OPT_EVICT_POLICY, ptenc.POLICY_SCORED)
+    if splits:
+        layer.set_option(ptenc.OPT_SPLITS, splits)
+    dev = {k: v.cuda() for k, v in enc.items()}
+    layer.set_encoder(dev["q_g"], dev["WaQ"], dev["WaK"], dev["WaV"], dev["k_g"], dev["v_g"])
+    layer.reset()
+    return orc, layer
+
+
+def check_scores(wl, orc, layer, what):
+    sc, ps = layer.scores()
+    for b in range(wl.batch):
+        n = len(orc.win[b])
+        assert np.array_equal(ps[b, :n], orc.positions(b)), "%s: ring positions of rollout %d" % (what, b)
+        assert (ps[b, n:] == -1).all() and (sc[b, n:] == 0).all()
+        ref = orc.scores(b)
+        err = np.abs(sc[b, :n] - ref)
+        assert (err <= SCORE_ABS + SCORE_REL * np.abs(ref)).all(), "%s: scores of rollout %d off by %.3e" % (what, b, err.max())
+
+
+def run_both(wl, T, n_recent, q_gain, splits=0, lengths=None, prompt_len=None, score_every=17):
+    orc, layer = make_both(wl, n_recent, splits)
+    if wl.n_sink:
+        pl = np.asarray(prompt_len, dtype=np.int32)
+        pk, pv = I.prompt_kv(wl)
+        for b in range(wl.batch):
+            orc.prefill(b, H.f64(pk[b, :pl[b]]), H.f64(pv[b, :pl[b]]))
+        layer.prefill(pk.cuda(), pv.cuda(), pl)
+    q, k, v = I.qkv_steps(wl, 0, T)
+    q = (q.float() * q_gain).to(q.dtype)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    qn, kn, vn = H.f64(q), H.f64(k), H.f64(v)
+    n_evictions = 0
+    for t in range(T):
+        act = None if lengths is None else I.active_mask(lengths, t)
+        before = list(orc.evicted)
+        ref = orc.step(qn[t], kn[t], vn[t], act)
+        out = layer.step(qd[t], kd[t], vd[t], active=None if act is None else torch.from_numpy(act).cuda())
+        H.assert_close(H.f64(out), ref, H.BF16_ABS, H.BF16_REL, "out at step %d" % t)
+        if list(orc.evicted) != before:
+            n_evictions += 1
+            vic = layer.victims()
+            for b in range(wl.batch):
+                if orc.evicted[b] != before[b]:
+                    assert vic[b].tolist() == orc.last_victims[b], "victims of rollout %d at step %d" % (b, t)
+        ln, base = layer.counters()
+        oln, obase = orc.counters()
+        assert np.array_equal(ln, oln) and np.array_equal(base, obase), "counters differ at step %d" % t
+        if t % score_every == 0 or t == T - 1:
+            check_scores(wl, orc, layer, "step %d" % t)
+    assert orc.min_margin >= MIN_MARGIN, "inputs leave a selection too close to call (%.2e): pick others" % orc.min_margin
+    assert n_evictions >= 3
+    H.assert_close(layer.get_state(), orc.state(), H.S_ABS, H.S_REL, "state S")
+    assert layer.poll_error() == 0
+    return orc, layer
+
+
+@pytest.mark.parametrize("splits", [1, 3])
+def test_scored_run_matches_oracle(splits):
+    wl = small()
+    orc, layer = run_both(wl, wl.steps, n_recent=24, q_gain=48.0, splits=splits)
+    # the policy did something other than slide: some evicted chunk was not the oldest one
+    assert any(list(orc.positions(b)) != list(range(orc.evicted[b], orc.appended[b])) for b in range(wl.batch))
+
+
+def test_scored_run_with_question_tokens_and_ragged_lengths():
+    wl = small(batch=4, window=160, n_sink=64, chunk=40, steps=260, seed=2006)    # a seed with wide margins
+    lengths = np.array([260, 90, 200, 131])
+    run_both(wl, wl.steps, n_recent=16, q_gain=48.0, lengths=lengths, prompt_len=[64, 1, 37, 0])
+
+
+def test_with_only_the_oldest_chunk_eligible_outputs_equal_the_sliding_window_bitwise():
+    wl = small(batch=2, window=128, chunk=32, steps=300)
+    enc = I.encoder_params(wl)
+    plain = H.make_layer(wl, enc)
+    _, scored = make_both(wl, n_recent=wl.window - wl.chunk)
+    q, k, v = (x.cuda() for x in I.qkv_steps(wl, 0, wl.steps))
+    for t in range(wl.steps):
+        assert torch.equal(scored.step(q[t], k[t], v[t]), plain.step(q[t], k[t], v[t])), "step %d" % t
+    assert all(np.array_equal(a, b) for a, b in zip(scored.counters(), plain.counters()))
+    # the two encoders (plain ALU here, MFMA there) agree to fp32 rounding
+    H.assert_close(scored.get_state(), plain.get_state(), 1e-5, 1e-4, "state")
+    Ks, Vs = scored.gather_window()
+    Kp, Vp = plain.gather_window()
+    n = int(plain.counters()[0][0] - plain.counters()[1][0])
+    assert torch.equal(Ks[:, :, :n], Kp[:, :, :n]) and torch.equal(Vs[:, :, :n], Vp[:, :, :n])
+
+
+@pytest.mark.parametrize("W,C,n_recent,n_sink", [(96, 32, 24, 0), (160, 40, 0, 32), (128, 7, 100, 0), (64, 64, 0, 0)])
+def test_selection_on_injected_scores_is_bit_exact(W, C, n_recent, n_sink):
+    # scores with few distinct values (plenty of ties), the same float32 numbers on both sides
+    wl = small(batch=3, window=W, chunk=C, n_sink=n_sink, steps=W - n_sink + 6 * C)
+    orc, layer = make_both(wl, n_recent)
+    Wr = W - n_sink
+    q, k, v = I.qkv_steps(wl, 0, wl.steps)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    qn, kn, vn = H.f64(q), H.f64(k), H.f64(v)
+    rng = np.random.default_rng(7)
+    n_checked = 0
+    for t in range(wl.steps):
+        if len(orc.win[0]) == Wr:                      # the next step evicts: plant the scores
+            sc = np.zeros((wl.batch, W), dtype=np.float32)
+            levels = rng.integers(2, 9)
+            sc[:, :Wr] = (rng.integers(0, levels, (wl.batch, Wr)) / np.float32(levels)).astype(np.float32)
+            layer.set_scores(sc)
+            for b in range(wl.batch):
+                orc.set_scores(b, sc[b, :Wr].astype(np.float64))
+        before = list(orc.evicted)
+        ref = orc.step(qn[t], kn[t], vn[t])
+        out = layer.step(qd[t], kd[t], vd[t])
+        H.assert_close(H.f64(out), ref, H.BF16_ABS, H.BF16_REL, "out at step %d" % t)
+        if list(orc.evicted) != before:
+            vic = layer.victims()
+            _, ps = layer.scores()
+            for b in range(wl.batch):
+                assert vic[b].tolist() == orc.last_victims[b], "victims of rollout %d at step %d" % (b, t)
+                n = len(orc.win[b])
+                assert np.array_equal(ps[b, :n], orc.positions(b)), "ring order of rollout %d after step %d" % (b, t)
+            n_checked += 1
+    assert n_checked >= 5
+    H.assert_close(layer.get_state(), orc.state(), H.S_ABS, H.S_REL, "state S")
+    # what the cache holds is what the oracle's ring holds, token for token
+    Kw, Vw = layer.gather_window()
+    for b in range(wl.batch):
+        P = 0
+        ks = torch.stack([torch.from_numpy(e.k) for e in orc.win[b]]).to(torch.bfloat16)     # [n, H_kv, d]
+        assert torch.equal(Kw[b, :, P:P + len(orc.win[b])].cpu(), ks.transpose(0, 1))
+    assert layer.poll_error() == 0
+
+
+def test_scored_compact_id_lists():
+    # finished rollouts dropped from the batch: the selection and the scores follow the id list
+    wl = small(batch=4, window=96, chunk=32, steps=180, seed=2006)
+    lengths = np.array([180, 60, 150, 101])
+    orc, layer = make_both(wl, n_recent=24)
+    q, k, v = I.qkv_steps(wl, 0, wl.steps)
+    q = (q.float() * 48.0).to(q.dtype)
+    qn, kn, vn = H.f64(q), H.f64(k), H.f64(v)
+    for t in range(wl.steps):
+        act = I.active_mask(lengths, t)
+        ids = np.nonzero(act)[0].astype(np.int32)
+        ref = orc.step(qn[t], kn[t], vn[t], act)
+        idt = torch.from_numpy(ids).cuda()
+        out = layer.step_ids(q[t][ids].cuda().contiguous(), k[t][ids].cuda().contiguous(), v[t][ids].cuda().contiguous(), idt)
+        H.assert_close(H.f64(out), ref[ids], H.BF16_ABS, H.BF16_REL, "out at step %d" % t)
+    assert orc.min_margin >= MIN_MARGIN
+    check_scores(wl, orc, layer, "end")
+    assert all(np.array_equal(a, b) for a, b in zip(layer.counters(), orc.counters()))
+    H.assert_close(layer.get_state(), orc.state(), H.S_ABS, H.S_REL, "state S")
+
+
+def test_scored_policy_argument_checks():
+    wl = small()
+    enc = I.encoder_params(wl)
+    plain = H.make_layer(wl, enc)
+    sc = torch.zeros((wl.batch, wl.window), dtype=torch.float32, device="cuda")
+    with pytest.raises(ptenc.PtencError) as ei:
+        ptenc.ptenc_get_scores(plain.ctx, sc, None)         # sliding policy keeps no scores
+    assert ei.value.status == ptenc.ERR_STATE
+    _, layer = make_both(wl, 24)
+    q, k, v = (x.cuda() for x in I.qkv_steps(wl, 0, 4))
+    layer.step(q[0], k[0], v[0])
+    with pytest.raises(ptenc.PtencError) as ei:
+        layer.set_counters(np.full(wl.batch, 5), np.full(wl.batch, 2))    # live tokens without scores
+    assert ei.value.status == ptenc.ERR_UNSUPPORTED
