@@ -126,6 +126,9 @@ def main() -> int:
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the per-launch HIP-event pass")
     ap.add_argument("--extras", action="store_true",
                     help="also time the state-as-weight-delta application (and the question-token prefill)")
+    ap.add_argument("--policy", choices=["sliding", "scored"], default="sliding",
+                    help="which tokens an eviction takes: the oldest chunk, or the lowest accumulated attention probability")
+    ap.add_argument("--recent", type=int, default=-1, help="scored policy: most recent ring entries never taken (-1 = half the ring)")
     ap.add_argument("--layers", type=int, default=0,
                     help="also time a stack of this many layers (each with its own cache) over the same steps: "
                          "eager launches, then replays of the recorded one-step HIP graph")
@@ -195,6 +198,9 @@ def main() -> int:
 
     if args.splits:
         layer.set_option(ptenc.OPT_SPLITS, args.splits)
+    if args.policy == "scored":
+        layer.set_option(ptenc.OPT_RECENT, args.recent)
+        layer.set_option(ptenc.OPT_EVICT_POLICY, ptenc.POLICY_SCORED)
     layer.set_encoder(enc["q_g"], enc["WaQ"], enc["WaK"], enc["WaV"], enc["k_g"], enc["v_g"])
     attn_kernel, n_splits, _ = layer.plan()
 
@@ -287,6 +293,7 @@ def main() -> int:
                                 wl.n_sink, wl.n_sink) if wl.n_sink else ""),
             "name": wl.name, "batch": wl.batch, "window": wl.window, "chunk": wl.chunk, "tokens": tokens,
             "attn_kernel": "mfma" if attn_kernel == 1 else "generic", "window_splits": n_splits,
+            "evict_policy": args.policy,
             "parallelism": "single GPU",
         },
         "gpu_ms": gpu_ms, "wall_ms": wall_ms,

@@ -144,24 +144,30 @@ __device__ inline void process_group(Frag& f, const Op q[4], Acc& a, int jg, int
 // mp / il = that step's maximum (base-2 domain) and 1 / sum for heads 4 kgrp + e (il = 0 beyond the
 // query group).  Returns this lane's token's probability mass: lanes 0..15 token n of the first 16,
 // lanes 16..31 token n of the second 16 (the other lanes hold copies).  jg, n_valid as in process_group.
-struct Lagged {
-  Op q[4];
-  float mp[4], il[4];
+// The operands live in LDS (wavefront-private, written once before the walk): registers are what the
+// walk is short of, and an LDS read does not queue behind the K/V stream the way a spill reload would.
+struct LaggedLds {   // per wavefront
+  u32x4 q[4][64];    // [k-chunk][lane]: A operand rows = heads
+  float mp[4][64];   // [e][lane]
+  float il[4][64];
 };
 
-__device__ inline float lagged_mass(const Frag& f, const Lagged& g, int jg, int n_valid, float scale_log2,
+__device__ inline float lagged_mass(const Frag& f, const LaggedLds& g, int lane, int jg, int n_valid, float scale_log2,
                                     int n, int kgrp) {
   f32x4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
-    d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(g.q[c].h, f.k0[c].h, d0, 0, 0, 0);
-    d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(g.q[c].h, f.k1[c].h, d1, 0, 0, 0);
+    Op q;
+    q.u = g.q[c][lane];
+    d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q.h, f.k0[c].h, d0, 0, 0, 0);
+    d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q.h, f.k1[c].h, d1, 0, 0, 0);
   }
   float t0 = 0.f, t1 = 0.f;
 #pragma unroll
   for (int e = 0; e < 4; ++e) {
-    t0 = fmaf(g.il[e], __builtin_amdgcn_exp2f(d0[e] * scale_log2 - g.mp[e]), t0);
-    t1 = fmaf(g.il[e], __builtin_amdgcn_exp2f(d1[e] * scale_log2 - g.mp[e]), t1);
+    const float mp = g.mp[e][lane], il = g.il[e][lane];
+    t0 = fmaf(il, __builtin_amdgcn_exp2f(d0[e] * scale_log2 - mp), t0);
+    t1 = fmaf(il, __builtin_amdgcn_exp2f(d1[e] * scale_log2 - mp), t1);
   }
   // a dead slot's key may be anything: its column is garbage, but columns never mix
   t0 += __shfl_xor(t0, 16, 64); t0 += __shfl_xor(t0, 32, 64);
@@ -382,6 +388,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
   constexpr int kWaves = WAVES;
   __shared__ StepSmem<WAVES> sm;
   __shared__ int sm_ticket;
+  extern __shared__ __align__(16) float dyn_lds[];   // MASS only: parked masses, then one LaggedLds per wavefront
 
   // row j of the launch (and of q / k / v / out) is rollout b: j itself, or ids[j] for a compact list
   const int j_row = blockIdx.x / c.Hkv, hkv = blockIdx.x - j_row * c.Hkv, split = blockIdx.y;
@@ -484,29 +491,27 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
       }
       // the previous step's queries and statistics, if they wait to be folded into the scores
       // (saved by the step that left len == len0, in the buffer of that parity)
-      Lagged lg;
       bool fold = false;
       float* mass_slab = nullptr;
+      float* park = dyn_lds;                                              // 32 floats per group of this workgroup
+      LaggedLds* lgp = nullptr;
       if constexpr (MASS) {
+        lgp = (LaggedLds*)(dyn_lds + (c.W / PT_GROUP_TOKENS + 2) * PT_GROUP_TOKENS) + wave;
         mass_slab = c.mass + (size_t)slab * c.W;
         fold = appending && c.mtag[slab] == len0;
-        const int par = (int)(len0 & 1);
-        const uint16_t* qb = c.qprev + ((size_t)par * c.B + b) * c.Hq * 128;
-        const float* mlb = c.mlprev + ((size_t)par * c.B + b) * c.Hq * 2;
-        if (fold && n < g) {
-          const u32x4* qp = (const u32x4*)(qb + (size_t)(hkv * g + n) * 128);
+        if (fold) {
+          const int par = (int)(len0 & 1);
+          const uint16_t* qb = c.qprev + ((size_t)par * c.B + b) * c.Hq * 128;
+          const float* mlb = c.mlprev + ((size_t)par * c.B + b) * c.Hq * 2;
+          const u32x4* qp = (const u32x4*)(qb + (size_t)(hkv * g + (n < g ? n : 0)) * 128);
 #pragma unroll
-          for (int cc = 0; cc < 4; ++cc) lg.q[cc].u = qp[cc * 4 + kgrp];
-        } else {
+          for (int cc = 0; cc < 4; ++cc) lgp->q[cc][lane] = n < g ? qp[cc * 4 + kgrp] : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
-          for (int cc = 0; cc < 4; ++cc) lg.q[cc].u = u32x4{0u, 0u, 0u, 0u};
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int hh = 4 * kgrp + e;
-          const bool ok = fold && hh < g;
-          lg.mp[e] = ok ? mlb[(hkv * g + hh) * 2] : 0.f;
-          lg.il[e] = ok ? mlb[(hkv * g + hh) * 2 + 1] : 0.f;
+          for (int e = 0; e < 4; ++e) {
+            const int hh = 4 * kgrp + e;
+            lgp->mp[e][lane] = hh < g ? mlb[(hkv * g + hh) * 2] : 0.f;
+            lgp->il[e][lane] = hh < g ? mlb[(hkv * g + hh) * 2 + 1] : 0.f;
+          }
         }
       }
       auto grp_ptr = [&](int visit) {
@@ -524,49 +529,59 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
         return visit < n_sink_vis ? visit * PT_GROUP_TOKENS : (visit - n_sink_vis) * PT_GROUP_TOKENS - off0;
       };
       auto visit_lim = [&](int visit) { return visit < n_sink_vis ? P : n_live; };
-      // scores: lanes 0..31 own the group's 32 accumulators (slot = lane); the old value is loaded with
-      // the group, the new one stored after it.  The token appended by this step starts at zero and
-      // takes no part in the previous step; question tokens are not scored.
-      auto mass_ptr = [&](int visit) {
-        return mass_slab + ((const uint16_t*)grp_ptr(visit) - (const uint16_t*)slab_p) / (PT_GROUP_ELEMS / PT_GROUP_TOKENS) + (lane & 31);
-      };
-      auto mass_load = [&](int visit) { return (visit >= n_sink_vis && lane < 32) ? *mass_ptr(visit) : 0.f; };
-      auto mass_fold = [&](const Frag& f, int visit, float old) {
-        if (visit < n_sink_vis) return;
-        const int jg = visit_jg(visit), j = jg + (lane & 31);
-        const float add = fold ? lagged_mass(f, lg, jg, n_live - 1, c.scale_log2, n, kgrp) : 0.f;
-        if (lane < 32) {
-          if (j == n_live - 1 && appending) *mass_ptr(visit) = 0.f;
-          else if (fold && (unsigned)j < (unsigned)(n_live - 1)) *mass_ptr(visit) = old + add;
-        }
+      // scores: what a group's tokens received in the previous step is parked in LDS during the walk
+      // (no global store between the loads of the stream) and added to the accumulators afterwards
+      auto mass_park = [&](const Frag& f, int visit) {
+        if (!fold || visit < n_sink_vis) return;
+        const float add = lagged_mass(f, *lgp, lane, visit_jg(visit), n_live - 1, c.scale_log2, n, kgrp);
+        if (lane < 32) park[(visit - v0) * 32 + lane] = add;
       };
       int i = v0 + wave;
       Frag fa, fb;
-      float ma = 0.f, mb = 0.f;
-      if (i < v1) {
-        load_group<NT>(fa, grp_ptr(i), lane);
-        if constexpr (MASS) ma = mass_load(i);
-      }
+      if (i < v1) load_group<NT>(fa, grp_ptr(i), lane);
       while (i < v1) {
         int nx = i + kWaves;
-        if (nx < v1) {
-          load_group<NT>(fb, grp_ptr(nx), lane);
-          if constexpr (MASS) mb = mass_load(nx);
-        }
+        if (nx < v1) load_group<NT>(fb, grp_ptr(nx), lane);
         if (patch && i == p_visit) patch_newest(fa, kp, vp, p_tl, n, kgrp);
-        if constexpr (MASS) mass_fold(fa, i, ma);
+        if constexpr (MASS) mass_park(fa, i);
         process_group(fa, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp);
         i = nx;
         if (i >= v1) break;
         nx = i + kWaves;
-        if (nx < v1) {
-          load_group<NT>(fa, grp_ptr(nx), lane);
-          if constexpr (MASS) ma = mass_load(nx);
-        }
+        if (nx < v1) load_group<NT>(fa, grp_ptr(nx), lane);
         if (patch && i == p_visit) patch_newest(fb, kp, vp, p_tl, n, kgrp);
-        if constexpr (MASS) mass_fold(fb, i, mb);
+        if constexpr (MASS) mass_park(fb, i);
         process_group(fb, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp);
         i = nx;
+      }
+      if constexpr (MASS) {
+        // every wavefront folds the groups it walked: lanes 0..31 own a group's 32 accumulators
+        // (slot = lane).  The token this step appended starts at zero and took no part in the previous
+        // step; question tokens are not scored.  Loads of a batch first, then its stores.
+        auto mass_ptr = [&](int visit) {
+          return mass_slab + ((const uint16_t*)grp_ptr(visit) - (const uint16_t*)slab_p) / (PT_GROUP_ELEMS / PT_GROUP_TOKENS) +
+                 (lane & 31);
+        };
+        for (int i0 = v0 + wave; i0 < v1; i0 += 8 * kWaves) {
+          float old[8];
+          int what[8];   // 0 nothing, 1 add, 2 zero
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int vi = i0 + u * kWaves;
+            what[u] = 0;
+            if (vi < v1 && vi >= n_sink_vis && lane < 32) {
+              const int j = visit_jg(vi) + lane;
+              if (appending && j == n_live - 1) what[u] = 2;
+              else if (fold && (unsigned)j < (unsigned)(n_live - 1)) { what[u] = 1; old[u] = *mass_ptr(vi); }
+            }
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int vi = i0 + u * kWaves;
+            if (what[u] == 1) *mass_ptr(vi) = old[u] + park[(vi - v0) * 32 + lane];
+            else if (what[u] == 2) *mass_ptr(vi) = 0.f;
+          }
+        }
       }
       // the store of the new token rides behind the walk: its inputs arrived long ago, and the
       // chunk of an evicting step was read before anything could overwrite its oldest slot
@@ -764,8 +779,10 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bo
   // scores are maintained by whole steps only (append + attention) under the scored policy
   const bool mass = cc.scored && do_append && do_attend;
   if (mass) {
-    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 4, true>), grid, dim3(256), 0, s, cc, a);
-    else hipLaunchKernelGGL((decode_mfma_kernel<false, 4, true>), grid, dim3(256), 0, s, cc, a);
+    // parked masses of every group a workgroup may walk + the previous step's operands per wavefront
+    const size_t park = (size_t)(cc.W / PT_GROUP_TOKENS + 2) * PT_GROUP_TOKENS * sizeof(float) + 4 * sizeof(LaggedLds);
+    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 4, true>), grid, dim3(256), park, s, cc, a);
+    else hipLaunchKernelGGL((decode_mfma_kernel<false, 4, true>), grid, dim3(256), park, s, cc, a);
   } else if (waves == 8) {
     if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 8, false>), grid, dim3(512), 0, s, cc, a);
     else hipLaunchKernelGGL((decode_mfma_kernel<false, 8, false>), grid, dim3(512), 0, s, cc, a);

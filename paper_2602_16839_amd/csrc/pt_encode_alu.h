@@ -33,18 +33,25 @@ __device__ void encode_chunk(EncSmem& sm, const Src& src, int n_tok, int dkv, in
       for (int x = 0; x < 8; ++x) acc[x] = 0.f;
       for (int kb = 0; kb < dkv; kb += kEncKB) {
         const int nk = min(kEncKB, dkv - kb);
-        for (int idx = t; idx < kEncSub * kEncKB; idx += kEncThreads) {
+        // all loads of the block first (nothing between them that could alias), then the stores
+        constexpr int kPer = kEncSub * kEncKB / kEncThreads;
+        float vals[kPer];
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+          const int idx = t + u * kEncThreads;
           const int tk = idx / kEncKB, kk = idx - tk * kEncKB;
-          float val = 0.f;
-          if (tk < ntok && kk < nk) {
-            val = src.get(which, sub0 + tk, kb + kk);
-            if (dbg) pt_st<T>(dbg + ((size_t)which * n_tok + sub0 + tk) * dkv + kb + kk, val);
-          }
-          sm.Ks[tk][kk] = val;
+          vals[u] = (tk < ntok && kk < nk) ? src.get(which, sub0 + tk, kb + kk) : 0.f;
         }
         for (int idx = t; idx < kEncKB * r; idx += kEncThreads) {
           const int kk = idx / r, col = idx - kk * r;
           sm.Ws[kk][col] = kk < nk ? pt_ld<T>(Wsrc + (size_t)(kb + kk) * r + col) : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < kPer; ++u) {
+          const int idx = t + u * kEncThreads;
+          const int tk = idx / kEncKB, kk = idx - tk * kEncKB;
+          sm.Ks[tk][kk] = vals[u];
+          if (dbg && tk < ntok && kk < nk) pt_st<T>(dbg + ((size_t)which * n_tok + sub0 + tk) * dkv + kb + kk, vals[u]);
         }
         __syncthreads();
         for (int kk = 0; kk < kEncKB; ++kk) {

@@ -172,14 +172,41 @@ __global__ __launch_bounds__(kThreads) void scored_evict_kernel(PtDev c, const u
     if (i >= C && is_victim(i)) sm.u.moves[1][victims_before(i) - v_head] = i;       // k-th place
   }
   __syncthreads();
+  // a token of one KV head = 16 key pieces of 16 bytes + 128 value elements (token-minor): 144 items,
+  // moved in batches of loads followed by stores so that the round trips overlap
   uint16_t* cache = (uint16_t*)c.cache;
-  for (int idx = t; idx < n_mv * c.Hkv * 256; idx += kThreads) {
-    const int mv = idx / (c.Hkv * 256), rem = idx - mv * (c.Hkv * 256);
-    const int h = rem >> 8, which = (rem >> 7) & 1, i = rem & 127;
-    const int src = slot_of(sm.u.moves[0][mv]), dst = slot_of(sm.u.moves[1][mv]);
-    uint16_t* slab = cache + (size_t)(b * c.Hkv + h) * pt_slab_elems(c.W, 128);
-    if (which == 0) slab[pt_k_off(1, c.W, 128, dst, i)] = slab[pt_k_off(1, c.W, 128, src, i)];
-    else slab[pt_v_off(1, c.W, 128, dst, i)] = slab[pt_v_off(1, c.W, 128, src, i)];
+  typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+  const int n_items = n_mv * c.Hkv * 144;
+  for (int i0 = 0; i0 < n_items; i0 += kThreads * 4) {
+    u32x4 kv[4];
+    uint16_t vv[4];
+    size_t dsto[4];
+    int kind[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int idx = i0 + u * kThreads + t;
+      kind[u] = -1;
+      if (idx < n_items) {
+        const int mv = idx / (c.Hkv * 144), rem = idx - mv * (c.Hkv * 144);
+        const int h = rem / 144, it = rem - h * 144;
+        const int src = slot_of(sm.u.moves[0][mv]), dst = slot_of(sm.u.moves[1][mv]);
+        const size_t so = (size_t)(b * c.Hkv + h) * pt_slab_elems(c.W, 128);
+        if (it < 16) {
+          kind[u] = 0;
+          kv[u] = *(const u32x4*)(cache + so + pt_k_off(1, c.W, 128, src, it * 8));
+          dsto[u] = so + pt_k_off(1, c.W, 128, dst, it * 8);
+        } else {
+          kind[u] = 1;
+          vv[u] = cache[so + pt_v_off(1, c.W, 128, src, it - 16)];
+          dsto[u] = so + pt_v_off(1, c.W, 128, dst, it - 16);
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (kind[u] == 0) *(u32x4*)(cache + dsto[u]) = kv[u];
+      else if (kind[u] == 1) cache[dsto[u]] = vv[u];
+    }
   }
   for (int idx = t; idx < n_mv * (c.Hkv + 1); idx += kThreads) {
     const int mv = idx / (c.Hkv + 1), h = idx - mv * (c.Hkv + 1);
