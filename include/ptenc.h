@@ -103,10 +103,12 @@ typedef enum {
  *          that step's saved queries and softmax statistics, while the NEXT step of the rollout streams
  *          the same keys, so they join the scores one step late and cost no extra pass over the cache.
  *          When the ring is full, the C lowest-scored entries among all but the PTENC_OPT_RECENT most
- *          recent ones leave (ties: the older ring entry first), are encoded oldest-first into S exactly
- *          as a sliding chunk would be, and the survivors of the oldest C ring places move into the
- *          victims' places beyond them, so the ring stays one contiguous run (attention does not depend
- *          on the order of the cache).  Question tokens are never scored or taken.  With
+ *          recent ones are chosen (ties: the older ring entry first); the survivors among the oldest C
+ *          ring places trade places with the chosen entries beyond them, so that the oldest C places hold
+ *          exactly the chosen tokens, which then leave and are encoded into S exactly as a sliding chunk
+ *          is, and the ring stays one contiguous run (attention does not depend on the order of the
+ *          cache; d_dbg_chunk of ptenc_evict_encode lists them in the order of those places).
+ *          Question tokens are never scored or taken.  With
  *          PTENC_OPT_RECENT = W - n_sink - C the policy is the sliding window.
  *          Needs the MFMA path (bf16, head_dim 128, W and n_sink multiples of 32) and at most 12288
  *          eligible entries; else PTENC_ERR_UNSUPPORTED.  Scores advance only through

@@ -30,8 +30,8 @@ Readings
       survivor, oldest first, to the k-th such place, oldest first) and the oldest chunk's places
       are dropped.  Attention does not depend on the order of the cache (a key carries its own
       position), so this only decides which entries count as "recent" later on.
-  s5. Victims are encoded in ring order, oldest first (a sum over tokens: the order only matters
-      to rounding), then S <- Normalize(S + S') as for the sliding window.
+  s5. The victims are encoded as one chunk, S <- Normalize(S + S') as for the sliding window.  S' is
+      a sum over tokens, so the order within the chunk matters to rounding only (here: ring order).
   s6. Question tokens are never scored, evicted or moved.
 """
 from __future__ import annotations

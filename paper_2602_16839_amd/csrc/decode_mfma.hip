@@ -170,10 +170,12 @@ __device__ inline float lagged_mass(const Frag& f, const LaggedLds& g, int lane,
     t1 = fmaf(il, __builtin_amdgcn_exp2f(d1[e] * scale_log2 - mp), t1);
   }
   // a dead slot's key may be anything: its column is garbage, but columns never mix
-  t0 += __shfl_xor(t0, 16, 64); t0 += __shfl_xor(t0, 32, 64);
-  t1 += __shfl_xor(t1, 16, 64); t1 += __shfl_xor(t1, 32, 64);
+  // lane groups 0 and 2 collect the first 16 tokens, 1 and 3 the second 16: each hands its neighbour the
+  // half it does not keep, then the two halves of the wavefront are added
+  float t = (kgrp & 1) ? t1 : t0;
+  t += __shfl_xor((kgrp & 1) ? t0 : t1, 16, 64);
+  t += __shfl_xor(t, 32, 64);
   const int j = jg + (kgrp & 1) * 16 + n;
-  const float t = (kgrp & 1) ? t1 : t0;
   return (unsigned)j < (unsigned)n_valid ? t : 0.f;
 }
 
@@ -495,25 +497,6 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
       float* mass_slab = nullptr;
       float* park = dyn_lds;                                              // 32 floats per group of this workgroup
       LaggedLds* lgp = nullptr;
-      if constexpr (MASS) {
-        lgp = (LaggedLds*)(dyn_lds + (c.W / PT_GROUP_TOKENS + 2) * PT_GROUP_TOKENS) + wave;
-        mass_slab = c.mass + (size_t)slab * c.W;
-        fold = appending && c.mtag[slab] == len0;
-        if (fold) {
-          const int par = (int)(len0 & 1);
-          const uint16_t* qb = c.qprev + ((size_t)par * c.B + b) * c.Hq * 128;
-          const float* mlb = c.mlprev + ((size_t)par * c.B + b) * c.Hq * 2;
-          const u32x4* qp = (const u32x4*)(qb + (size_t)(hkv * g + (n < g ? n : 0)) * 128);
-#pragma unroll
-          for (int cc = 0; cc < 4; ++cc) lgp->q[cc][lane] = n < g ? qp[cc * 4 + kgrp] : u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int hh = 4 * kgrp + e;
-            lgp->mp[e][lane] = hh < g ? mlb[(hkv * g + hh) * 2] : 0.f;
-            lgp->il[e][lane] = hh < g ? mlb[(hkv * g + hh) * 2 + 1] : 0.f;
-          }
-        }
-      }
       auto grp_ptr = [&](int visit) {
         int pg = visit;                       // question tokens: group `visit`
         if (visit >= n_sink_vis) {
@@ -539,6 +522,37 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
       int i = v0 + wave;
       Frag fa, fb;
       if (i < v1) load_group<NT>(fa, grp_ptr(i), lane);
+      if constexpr (MASS) {
+        // after the first group's loads are on their way: stage the previous step's operands (the
+        // addresses are valid whether or not anything waits to be folded, so nothing here depends on
+        // the tag's value but the use of the result)
+        lgp = (LaggedLds*)(dyn_lds + (c.W / PT_GROUP_TOKENS + 2) * PT_GROUP_TOKENS) + wave;
+        mass_slab = c.mass + (size_t)slab * c.W;
+        const long long tag = c.mtag[slab];
+        const int par = (int)(len0 & 1);
+        const uint16_t* qb = c.qprev + ((size_t)par * c.B + b) * c.Hq * 128;
+        const float* mlb = c.mlprev + ((size_t)par * c.B + b) * c.Hq * 2;
+        const u32x4* qp = (const u32x4*)(qb + (size_t)(hkv * g + (n < g ? n : 0)) * 128);
+        u32x4 ql[4];
+        float mpl[4], ill[4];
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) ql[cc] = qp[cc * 4 + kgrp];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int hh = 4 * kgrp + e < g ? 4 * kgrp + e : 0;
+          mpl[e] = mlb[(hkv * g + hh) * 2];
+          ill[e] = mlb[(hkv * g + hh) * 2 + 1];
+        }
+        fold = appending && tag == len0;
+#pragma unroll
+        for (int cc = 0; cc < 4; ++cc) lgp->q[cc][lane] = (fold && n < g) ? ql[cc] : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const bool ok = fold && 4 * kgrp + e < g;
+          lgp->mp[e][lane] = ok ? mpl[e] : 0.f;
+          lgp->il[e][lane] = ok ? ill[e] : 0.f;
+        }
+      }
       while (i < v1) {
         int nx = i + kWaves;
         if (nx < v1) load_group<NT>(fb, grp_ptr(nx), lane);
@@ -557,30 +571,18 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
       if constexpr (MASS) {
         // every wavefront folds the groups it walked: lanes 0..31 own a group's 32 accumulators
         // (slot = lane).  The token this step appended starts at zero and took no part in the previous
-        // step; question tokens are not scored.  Loads of a batch first, then its stores.
+        // step; question tokens are not scored.
         auto mass_ptr = [&](int visit) {
           return mass_slab + ((const uint16_t*)grp_ptr(visit) - (const uint16_t*)slab_p) / (PT_GROUP_ELEMS / PT_GROUP_TOKENS) +
                  (lane & 31);
         };
-        for (int i0 = v0 + wave; i0 < v1; i0 += 8 * kWaves) {
-          float old[8];
-          int what[8];   // 0 nothing, 1 add, 2 zero
-#pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            const int vi = i0 + u * kWaves;
-            what[u] = 0;
-            if (vi < v1 && vi >= n_sink_vis && lane < 32) {
-              const int j = visit_jg(vi) + lane;
-              if (appending && j == n_live - 1) what[u] = 2;
-              else if (fold && (unsigned)j < (unsigned)(n_live - 1)) { what[u] = 1; old[u] = *mass_ptr(vi); }
-            }
-          }
-#pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            const int vi = i0 + u * kWaves;
-            if (what[u] == 1) *mass_ptr(vi) = old[u] + park[(vi - v0) * 32 + lane];
-            else if (what[u] == 2) *mass_ptr(vi) = 0.f;
-          }
+        // one lane adds to one accumulator once per step, so a returnless hardware float add gives the same
+        // bits as load-add-store and needs no round trip
+        for (int vi = v0 + wave; vi < v1; vi += kWaves) {
+          if (vi < n_sink_vis || lane >= 32) continue;
+          const int j = visit_jg(vi) + lane;
+          if (appending && j == n_live - 1) *mass_ptr(vi) = 0.f;
+          else if (fold && (unsigned)j < (unsigned)(n_live - 1)) unsafeAtomicAdd(mass_ptr(vi), park[(vi - v0) * 32 + lane]);
         }
       }
       // the store of the new token rides behind the walk: its inputs arrived long ago, and the

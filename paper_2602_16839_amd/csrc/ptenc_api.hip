@@ -12,7 +12,7 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct StateLayout {
   size_t S, Qa, S0, len, base, len2, base2, n_prompt, err, tick_rollout, tick_slab, WKp, WVp;
-  size_t mass, pos, victims, vidx, qprev, mlprev, mtag, total;   // importance-based eviction
+  size_t mass, pos, victims, qprev, mlprev, mtag, total;   // importance-based eviction
 };
 
 StateLayout state_layout(const ptenc_config& c) {
@@ -37,7 +37,6 @@ StateLayout state_layout(const ptenc_config& c) {
   L.mass = off;    off = align256(off + slabs * c.window * sizeof(float));
   L.pos = off;     off = align256(off + (size_t)c.batch * c.window * sizeof(long long));
   L.victims = off; off = align256(off + (size_t)c.batch * c.chunk * sizeof(long long));
-  L.vidx = off;    off = align256(off + (size_t)c.batch * c.chunk * sizeof(int));
   L.qprev = off;   off = align256(off + 2 * rows * c.head_dim * 2);
   L.mlprev = off;  off = align256(off + 2 * rows * 2 * sizeof(float));
   L.mtag = off;    off = align256(off + slabs * sizeof(long long));
@@ -191,7 +190,7 @@ ptenc_status ptenc_create(const ptenc_config* cfg, void* d_cache, void* d_state,
   d.WKp = sp + L.WKp; d.WVp = sp + L.WVp;
   d.scored = 0; d.n_recent = 0;
   d.mass = (float*)(sp + L.mass); d.pos = (long long*)(sp + L.pos); d.victims = (long long*)(sp + L.victims);
-  d.vidx = (int*)(sp + L.vidx); d.qprev = (uint16_t*)(sp + L.qprev); d.mlprev = (float*)(sp + L.mlprev);
+  d.qprev = (uint16_t*)(sp + L.qprev); d.mlprev = (float*)(sp + L.mlprev);
   d.mtag = (long long*)(sp + L.mtag);
   x->opt_recent = -1;
   replan(x);
@@ -323,8 +322,8 @@ ptenc_status ptenc_cache_append(ptenc_ctx* ctx, const void* d_k, const void* d_v
 ptenc_status ptenc_evict_encode(ptenc_ctx* ctx, const uint8_t* d_active, void* d_dbg_chunk, void* stream) {
   if (!ctx) return PTENC_ERR_INVALID_ARG;
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
-  if (ctx->dev.scored)   // moves base in place: no buffer rotation
-    return hip_status(pt_launch_scored_evict(ctx->dev, d_active, d_dbg_chunk, nullptr, 0, S(stream)));
+  // scored policy: the victims are first brought to the front of the ring, then leave as "the oldest chunk"
+  if (ctx->dev.scored && pt_launch_scored_select(ctx->dev, d_active, nullptr, 0, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
   if (ctx->attn_kernel == 1)
     return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, true, false, false, nullptr, nullptr,
                                                nullptr, nullptr, d_active, d_dbg_chunk, nullptr, 0, ctx->opt_in_place != 0, S(stream)));
@@ -350,9 +349,9 @@ ptenc_status ptenc_decode_step(ptenc_ctx* ctx, const void* d_q, const void* d_k,
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_q | (uintptr_t)d_out | (uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
-    if (ctx->dev.scored && pt_launch_scored_evict(ctx->dev, d_active, nullptr, nullptr, 0, S(stream)) != hipSuccess)
+    if (ctx->dev.scored && pt_launch_scored_select(ctx->dev, d_active, nullptr, 0, S(stream)) != hipSuccess)
       return PTENC_ERR_HIP;
-    return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, !ctx->dev.scored, true, true, d_q, d_k,
+    return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, true, true, true, d_q, d_k,
                                                d_v, d_out, d_active, nullptr, nullptr, 0, ctx->opt_in_place != 0, S(stream)));
   }
   if (advanced(ctx, pt_launch_step_prologue(ctx->dev, true, true, d_k, d_v, d_active, nullptr, nullptr, 0,
@@ -372,9 +371,9 @@ ptenc_status ptenc_decode_step_ids(ptenc_ctx* ctx, const void* d_q, const void* 
   d.n_splits = ctx->opt_splits > 0 ? ctx->opt_splits : heuristic_splits(ctx, n);
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_q | (uintptr_t)d_out | (uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
-    if (d.scored && pt_launch_scored_evict(d, nullptr, nullptr, d_ids, n, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
+    if (d.scored && pt_launch_scored_select(d, nullptr, d_ids, n, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
     // counters are written in place by this launch: no buffer rotation
-    return hip_status(pt_launch_decode_mfma(d, ctx->nontemporal != 0, pick_waves(ctx, n, d.n_splits), !d.scored, true, true,
+    return hip_status(pt_launch_decode_mfma(d, ctx->nontemporal != 0, pick_waves(ctx, n, d.n_splits), true, true, true,
                                             d_q, d_k, d_v, d_out, nullptr, nullptr, d_ids, n, true, S(stream)));
   }
   hipError_t e = pt_launch_step_prologue(d, true, true, d_k, d_v, nullptr, nullptr, d_ids, n, true, S(stream));

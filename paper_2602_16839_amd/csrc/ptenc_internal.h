@@ -47,7 +47,6 @@ struct PtDev {
                       //   this KV head's query heads, all folded steps summed
   long long* pos;     // [B][W] by physical slot: position (append index) of the token stored there
   long long* victims; // [B][C] positions the rollout's last eviction took, ring order (-1: none yet)
-  int* vidx;          // [B][C] selection scratch: ring indices of the victims
   uint16_t* qprev;    // [2][B][H_q][128] the latest step's queries, buffer = parity of the length it left
   float* mlprev;      // [2][B][H_q][2]   that step's softmax maximum (base-2 domain) and 1 / sum
   long long* mtag;    // [B*H_kv] the length that step left (its data waits to be folded); -1: none
@@ -164,8 +163,7 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bo
                                  const void* q, const void* k, const void* v, void* out, const uint8_t* active,
                                  void* dbg_chunk, const int* ids, int n_rows, bool in_place, hipStream_t s);
 // importance-based eviction (scored_kernels.hip)
-hipError_t pt_launch_scored_evict(const PtDev& c, const uint8_t* active, void* dbg_chunk, const int* ids, int n_rows,
-                                  hipStream_t s);
+hipError_t pt_launch_scored_select(const PtDev& c, const uint8_t* active, const int* ids, int n_rows, hipStream_t s);
 hipError_t pt_launch_scores_get(const PtDev& c, float* d_score, long long* d_pos, hipStream_t s);
 hipError_t pt_launch_scores_set(const PtDev& c, const float* d_score, hipStream_t s);
 #define PT_SCORED_MAX_ELIGIBLE 12288   // eligible ring entries the selection can rank (48 KiB of LDS)

@@ -1,45 +1,29 @@
 // Importance-based eviction: when a rollout's ring is full, the C tokens with the lowest
 // accumulated attention probability leave instead of the C oldest (the heavy-hitter rule the paper's
-// ablation on token dropping strategies integrates, chunked like its sliding window), and are
-// folded into S by the same encoder (Our Approach, the Delta-W equation and the update rule).
+// ablation on token dropping strategies integrates, chunked like its sliding window).
 //
+// This kernel only CHOOSES them and brings them to the front of the ring; the decode step that
+// follows then evicts "the oldest chunk" exactly as under the sliding window and folds it into S
+// with the same encoder (Our Approach, the Delta-W equation and the update rule).
 // One workgroup per rollout (bf16, head_dim 128, tiled cache only), in this order:
 //   1. score of every eligible ring entry (all but the n_recent newest) = sum over KV heads of the
 //      per-head accumulators the decode step maintains, in head order;
 //   2. the C lowest, ties towards the older entry: a radix select on the float bit patterns
 //      (scores are >= +0, so unsigned order is numeric order), then one ordered pass for the ties;
-//   3. encode the victims, oldest ring entry first, and update S;
-//   4. keep the ring a contiguous run: the survivors of the oldest chunk move into the places of
-//      the victims beyond it (k-th survivor to the k-th such place; key, value, accumulators and
-//      position tag travel together), and base += C drops the oldest chunk's places.
-// Sources (places inside the oldest chunk) and destinations (outside it) are disjoint, and the
-// victims are read before anything moves.
-#include "pt_encode_alu.h"
+//   3. the survivors among the oldest C ring places trade places with the victims beyond them
+//      (k-th survivor with the k-th such victim; key, value, accumulators and position tag travel
+//      together), so the oldest C places hold exactly the victims and the ring stays one run.
+// The pairs are disjoint, so every exchange is independent of the others.
+#include "ptenc_internal.h"
 
 namespace {
 
-constexpr int kThreads = kEncThreads;   // 256
-
-struct VictimChunk {   // the victims of rollout b, oldest ring entry first
-  const uint16_t* cache; const int* vidx; int b, Hkv, W, s0, n_sink, Wr;
-  __device__ int slot_of(int tok) const {
-    int slot = s0 + vidx[tok]; if (slot >= Wr) slot -= Wr;
-    return slot + n_sink;
-  }
-  __device__ float get(int which, int tok, int kk) const {
-    const int slot = slot_of(tok);
-    const int h = kk >> 7, i = kk & 127;
-    const uint16_t* slab = cache + (size_t)(b * Hkv + h) * pt_slab_elems(W, 128);
-    const size_t off = which == 0 ? pt_k_off(1, W, 128, slot, i) : pt_v_off(1, W, 128, slot, i);
-    return pt_bf16_to_f32(slab[off]);
-  }
-};
+constexpr int kThreads = 256;
 
 struct ScoredSmem {
   union {
     float sc[PT_SCORED_MAX_ELIGIBLE];            // phase 1-2: scores by ring index
-    EncSmem enc;                                 // phase 3
-    int moves[2][PT_SCORED_MAX_ELIGIBLE / 2];    // phase 4: source and destination ring indices
+    int moves[2][PT_SCORED_MAX_ELIGIBLE / 2];    // phase 3: the two ring indices of every exchange
   } u;
   uint32_t vmask[PT_SCORED_MAX_ELIGIBLE / 32];   // bit i: ring entry i is a victim
   int wpre[PT_SCORED_MAX_ELIGIBLE / 32];         // victims before word w
@@ -65,8 +49,8 @@ __device__ inline int block_excl_count(bool flag, ScoredSmem& sm, int* total) {
   return before + within;
 }
 
-__global__ __launch_bounds__(kThreads) void scored_evict_kernel(PtDev c, const uint8_t* __restrict__ active,
-                                                               uint16_t* dbg_chunk, const int* __restrict__ ids) {
+__global__ __launch_bounds__(kThreads) void scored_select_kernel(PtDev c, const uint8_t* __restrict__ active,
+                                                                const int* __restrict__ ids) {
   __shared__ ScoredSmem sm;
   const int t = threadIdx.x;
   int b = blockIdx.x;
@@ -143,44 +127,28 @@ __global__ __launch_bounds__(kThreads) void scored_evict_kernel(PtDev c, const u
     return (w < (n_el + 31) / 32 ? sm.wpre[w] + __popc(sm.vmask[w] & ((1u << (i & 31)) - 1u))
                                  : sm.wpre[w - 1] + __popc(sm.vmask[w - 1]));
   };
-  int* vidx = c.vidx + (size_t)b * C;
+  // what leaves, by position, in ring order (before anything trades places)
   for (int i = t; i < n_el; i += kThreads)
-    if (is_victim(i)) {
-      const int ord = victims_before(i);
-      vidx[ord] = i;
-      c.victims[(size_t)b * C + ord] = c.pos[(size_t)b * c.W + slot_of(i)];
-    }
+    if (is_victim(i)) c.victims[(size_t)b * C + victims_before(i)] = c.pos[(size_t)b * c.W + slot_of(i)];
   const int v_head = victims_before(min(C, n_el));      // victims inside the oldest chunk
-  __threadfence_block();
-  __syncthreads();                                      // scores are dead from here on: sm.u is the encoder's
+  __syncthreads();                                      // scores are dead from here on: sm.u holds the pairs
 
-  // ---- 3. encode the victims and update S ----
-  {
-    VictimChunk src{(const uint16_t*)c.cache, vidx, b, c.Hkv, c.W, s0, c.n_sink, c.Wr};
-    const int dkv = c.Hkv * 128;
-    float sacc[16];
-    uint16_t* dbg = dbg_chunk ? dbg_chunk + (size_t)b * 2 * C * dkv : nullptr;
-    encode_chunk<uint16_t>(sm.u.enc, src, C, dkv, c.G, c.r, c.Qa, (const uint16_t*)c.WaK, (const uint16_t*)c.WaV, dbg, sacc);
-    pt_state_update<kThreads>(c, b, sacc, &sm.u.enc.Ws[0][0], sm.u.enc.tail.red);
-  }
-  __syncthreads();                                      // every victim has been read
-
-  // ---- 4. survivors of the oldest chunk into the victims' places beyond it ----
+  // ---- 3. survivors of the oldest chunk <-> victims beyond it ----
   const int n_mv = C - v_head;
   for (int i = t; i < n_el; i += kThreads) {
     if (i < C && !is_victim(i)) sm.u.moves[0][i - victims_before(i)] = i;            // k-th survivor
-    if (i >= C && is_victim(i)) sm.u.moves[1][victims_before(i) - v_head] = i;       // k-th place
+    if (i >= C && is_victim(i)) sm.u.moves[1][victims_before(i) - v_head] = i;       // k-th victim beyond
   }
   __syncthreads();
   // a token of one KV head = 16 key pieces of 16 bytes + 128 value elements (token-minor): 144 items,
-  // moved in batches of loads followed by stores so that the round trips overlap
+  // exchanged in batches of loads followed by stores so that the round trips overlap
   uint16_t* cache = (uint16_t*)c.cache;
   typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
   const int n_items = n_mv * c.Hkv * 144;
   for (int i0 = 0; i0 < n_items; i0 += kThreads * 4) {
-    u32x4 kv[4];
-    uint16_t vv[4];
-    size_t dsto[4];
+    u32x4 ka[4], kb[4];
+    uint16_t va[4], vb[4];
+    size_t oa[4], ob[4];
     int kind[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -189,33 +157,42 @@ __global__ __launch_bounds__(kThreads) void scored_evict_kernel(PtDev c, const u
       if (idx < n_items) {
         const int mv = idx / (c.Hkv * 144), rem = idx - mv * (c.Hkv * 144);
         const int h = rem / 144, it = rem - h * 144;
-        const int src = slot_of(sm.u.moves[0][mv]), dst = slot_of(sm.u.moves[1][mv]);
+        const int sa = slot_of(sm.u.moves[0][mv]), sb = slot_of(sm.u.moves[1][mv]);
         const size_t so = (size_t)(b * c.Hkv + h) * pt_slab_elems(c.W, 128);
         if (it < 16) {
           kind[u] = 0;
-          kv[u] = *(const u32x4*)(cache + so + pt_k_off(1, c.W, 128, src, it * 8));
-          dsto[u] = so + pt_k_off(1, c.W, 128, dst, it * 8);
+          oa[u] = so + pt_k_off(1, c.W, 128, sa, it * 8);
+          ob[u] = so + pt_k_off(1, c.W, 128, sb, it * 8);
+          ka[u] = *(const u32x4*)(cache + oa[u]);
+          kb[u] = *(const u32x4*)(cache + ob[u]);
         } else {
           kind[u] = 1;
-          vv[u] = cache[so + pt_v_off(1, c.W, 128, src, it - 16)];
-          dsto[u] = so + pt_v_off(1, c.W, 128, dst, it - 16);
+          oa[u] = so + pt_v_off(1, c.W, 128, sa, it - 16);
+          ob[u] = so + pt_v_off(1, c.W, 128, sb, it - 16);
+          va[u] = cache[oa[u]];
+          vb[u] = cache[ob[u]];
         }
       }
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      if (kind[u] == 0) *(u32x4*)(cache + dsto[u]) = kv[u];
-      else if (kind[u] == 1) cache[dsto[u]] = vv[u];
+      if (kind[u] == 0) { *(u32x4*)(cache + oa[u]) = kb[u]; *(u32x4*)(cache + ob[u]) = ka[u]; }
+      else if (kind[u] == 1) { cache[oa[u]] = vb[u]; cache[ob[u]] = va[u]; }
     }
   }
   for (int idx = t; idx < n_mv * (c.Hkv + 1); idx += kThreads) {
     const int mv = idx / (c.Hkv + 1), h = idx - mv * (c.Hkv + 1);
-    const int src = slot_of(sm.u.moves[0][mv]), dst = slot_of(sm.u.moves[1][mv]);
-    if (h < c.Hkv) c.mass[(size_t)(b * c.Hkv + h) * c.W + dst] = c.mass[(size_t)(b * c.Hkv + h) * c.W + src];
-    else c.pos[(size_t)b * c.W + dst] = c.pos[(size_t)b * c.W + src];
+    const int sa = slot_of(sm.u.moves[0][mv]), sb = slot_of(sm.u.moves[1][mv]);
+    if (h < c.Hkv) {
+      float* m = c.mass + (size_t)(b * c.Hkv + h) * c.W;
+      const float x = m[sa], y = m[sb];
+      m[sa] = y; m[sb] = x;
+    } else {
+      long long* p = c.pos + (size_t)b * c.W;
+      const long long x = p[sa], y = p[sb];
+      p[sa] = y; p[sb] = x;
+    }
   }
-  // this workgroup is the only one that touches rollout b in this kernel: the counter moves in place
-  if (t == 0) c.base[b] = base + C;
 }
 
 // Scores and position tags of the live ring entries in ring order (oldest ring entry first);
@@ -254,10 +231,8 @@ __global__ void scores_set_kernel(PtDev c, const float* __restrict__ score) {
 
 }  // namespace
 
-hipError_t pt_launch_scored_evict(const PtDev& c, const uint8_t* active, void* dbg_chunk, const int* ids, int n_rows,
-                                  hipStream_t s) {
-  hipLaunchKernelGGL(scored_evict_kernel, dim3(ids ? n_rows : c.B), dim3(kThreads), 0, s, c, active,
-                     (uint16_t*)dbg_chunk, ids);
+hipError_t pt_launch_scored_select(const PtDev& c, const uint8_t* active, const int* ids, int n_rows, hipStream_t s) {
+  hipLaunchKernelGGL(scored_select_kernel, dim3(ids ? n_rows : c.B), dim3(kThreads), 0, s, c, active, ids);
   return hipGetLastError();
 }
 
