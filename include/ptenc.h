@@ -110,7 +110,8 @@ typedef enum {
  *          cache; d_dbg_chunk of ptenc_evict_encode lists them in the order of those places).
  *          Question tokens are never scored or taken.  With
  *          PTENC_OPT_RECENT = W - n_sink - C the policy is the sliding window.
- *          Needs the MFMA path (bf16, head_dim 128, W and n_sink multiples of 32) and at most 12288
+ *          Needs the MFMA path (bf16, head_dim 128, W and n_sink multiples of 32), at most 8 query heads
+ *          per KV head and at most 12288
  *          eligible entries; else PTENC_ERR_UNSUPPORTED.  Scores advance only through
  *          ptenc_decode_step / ptenc_decode_run / ptenc_decode_step_ids / ptenc_decode_run_ids (a
  *          separate ptenc_decode_attn leaves them alone); ptenc_set_counters accepts only empty

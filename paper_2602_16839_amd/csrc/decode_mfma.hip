@@ -77,8 +77,12 @@ struct Acc {
 
 // jg = logical index of the group's first slot within its region (question tokens or ring walk),
 // n_live = number of live logical indices of that region.
+// MASS: lanes with `lag` set carry a query head of the rollout's PREVIOUS step in their column (see
+// the kernel): their running maximum is frozen at that step's final one, so p[] comes out as that
+// step's unnormalised probabilities, returned in p_out for the importance scores.
+template <bool MASS = false>
 __device__ inline void process_group(Frag& f, const Op q[4], Acc& a, int jg, int n_live,
-                                     float scale_log2, int kgrp) {
+                                     float scale_log2, int kgrp, bool lag = false, float* p_out = nullptr) {
   f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
@@ -116,12 +120,17 @@ __device__ inline void process_group(Frag& f, const Op q[4], Acc& a, int jg, int
   float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
   mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
   mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-  const float m_new = fmaxf(a.m, mx);
+  float m_new = fmaxf(a.m, mx);
+  if constexpr (MASS) m_new = lag ? a.m : m_new;
   const float m_use = m_new == -INFINITY ? 0.f : m_new;   // nothing live yet: keep exp2 away from inf - inf
   const float alpha = __builtin_amdgcn_exp2f(a.m - m_use);
   float p[8], psum = 0.f;
 #pragma unroll
   for (int e = 0; e < 8; ++e) { p[e] = __builtin_amdgcn_exp2f(s[e] - m_use); psum += p[e]; }
+  if constexpr (MASS) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) p_out[e] = p[e];
+  }
   a.l = a.l * alpha + psum;
   a.m = m_new;
   if (__any(alpha != 1.f)) {
@@ -135,48 +144,31 @@ __device__ inline void process_group(Frag& f, const Op q[4], Acc& a, int jg, int
   for (int i = 0; i < 8; ++i) a.o[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.v[i].h, pf.h, a.o[i], 0, 0, 0);
 }
 
-// Importance scores: the probability every token of a group received in the rollout's PREVIOUS step,
-// recomputed from that step's saved queries and softmax statistics while the group's keys are in
-// registers anyway (the ablation on token dropping strategies; accumulated attention probability is
-// the heavy-hitter score).  Heads ride in the M dimension here, so that the sum over heads is a sum
-// over a lane's 4 accumulator rows and two xor-shuffles:
-//   D[head 4 kgrp + e][token n] = Q_prev (16 x 32k) * K_tile^T (32k x 16)
-// mp / il = that step's maximum (base-2 domain) and 1 / sum for heads 4 kgrp + e (il = 0 beyond the
-// query group).  Returns this lane's token's probability mass: lanes 0..15 token n of the first 16,
-// lanes 16..31 token n of the second 16 (the other lanes hold copies).  jg, n_valid as in process_group.
-// The operands live in LDS (wavefront-private, written once before the walk): registers are what the
-// walk is short of, and an LDS read does not queue behind the K/V stream the way a spill reload would.
-struct LaggedLds {   // per wavefront
-  u32x4 q[4][64];    // [k-chunk][lane]: A operand rows = heads
-  float mp[4][64];   // [e][lane]
-  float il[4][64];
-};
+// Importance scores (the ablation on token dropping strategies; accumulated attention probability is
+// the heavy-hitter score).  The probability every token received in the rollout's PREVIOUS step is
+// recomputed while this step streams the same keys, at no extra matrix work: with at most 8 query heads
+// per KV head, columns 8..15 of the score MFMA are free, and carry the previous step's queries (saved
+// by that step, with its softmax maximum and 1 / sum).  Lane (kgrp, n >= 8) then holds, in p[], head
+// n - 8's unnormalised probabilities of its 8 tokens; il = 1 / sum (0 in lanes that carry nothing).
+// The sum over heads is a sum over the 16 lanes of a row (four rotate-and-add steps); afterwards lane
+// (kgrp, n < 8) keeps the total of token tl = (n / 4) * 16 + 4 kgrp + n % 4.
+template <int CTRL>
+__device__ inline float row_ror_add(float v) {
+  return v + __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xf, 0xf, true));
+}
 
-__device__ inline float lagged_mass(const Frag& f, const LaggedLds& g, int lane, int jg, int n_valid, float scale_log2,
-                                    int n, int kgrp) {
-  f32x4 d0 = {0.f, 0.f, 0.f, 0.f}, d1 = {0.f, 0.f, 0.f, 0.f};
+__device__ inline void lagged_mass_park(const float p[8], float il, float* park_grp, int n, int kgrp) {
+  float mine = 0.f;
 #pragma unroll
-  for (int c = 0; c < 4; ++c) {
-    Op q;
-    q.u = g.q[c][lane];
-    d0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q.h, f.k0[c].h, d0, 0, 0, 0);
-    d1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(q.h, f.k1[c].h, d1, 0, 0, 0);
+  for (int e = 0; e < 8; ++e) {
+    float v = p[e] * il;                 // 0 in the lanes of this step's own heads
+    v = row_ror_add<0x128>(v);           // row_ror:8
+    v = row_ror_add<0x124>(v);           // row_ror:4
+    v = row_ror_add<0x122>(v);           // row_ror:2
+    v = row_ror_add<0x121>(v);           // row_ror:1
+    mine = n == e ? v : mine;
   }
-  float t0 = 0.f, t1 = 0.f;
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    const float mp = g.mp[e][lane], il = g.il[e][lane];
-    t0 = fmaf(il, __builtin_amdgcn_exp2f(d0[e] * scale_log2 - mp), t0);
-    t1 = fmaf(il, __builtin_amdgcn_exp2f(d1[e] * scale_log2 - mp), t1);
-  }
-  // a dead slot's key may be anything: its column is garbage, but columns never mix
-  // lane groups 0 and 2 collect the first 16 tokens, 1 and 3 the second 16: each hands its neighbour the
-  // half it does not keep, then the two halves of the wavefront are added
-  float t = (kgrp & 1) ? t1 : t0;
-  t += __shfl_xor((kgrp & 1) ? t0 : t1, 16, 64);
-  t += __shfl_xor(t, 32, 64);
-  const int j = jg + (kgrp & 1) * 16 + n;
-  return (unsigned)j < (unsigned)n_valid ? t : 0.f;
+  if (n < 8) park_grp[(n >> 2) * 16 + 4 * kgrp + (n & 3)] = mine;
 }
 
 // kp[c] = this lane's 16 bytes of the new key (k-chunk c), vp[i] = new value column 16 i + (lane % 16).
@@ -390,7 +382,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
   constexpr int kWaves = WAVES;
   __shared__ StepSmem<WAVES> sm;
   __shared__ int sm_ticket;
-  extern __shared__ __align__(16) float dyn_lds[];   // MASS only: parked masses, then one LaggedLds per wavefront
+  extern __shared__ __align__(16) float dyn_lds[];   // MASS only: parked masses
 
   // row j of the launch (and of q / k / v / out) is rollout b: j itself, or ids[j] for a compact list
   const int j_row = blockIdx.x / c.Hkv, hkv = blockIdx.x - j_row * c.Hkv, split = blockIdx.y;
@@ -493,10 +485,10 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
       }
       // the previous step's queries and statistics, if they wait to be folded into the scores
       // (saved by the step that left len == len0, in the buffer of that parity)
-      bool fold = false;
+      bool fold = false, lag = false;      // lag: this lane's column carries a head of the previous step
+      float il = 0.f;                      // that step's 1 / sum for the lane's head
       float* mass_slab = nullptr;
-      float* park = dyn_lds;                                              // 32 floats per group of this workgroup
-      LaggedLds* lgp = nullptr;
+      float* park = dyn_lds;               // MASS: 32 floats per group this workgroup walks
       auto grp_ptr = [&](int visit) {
         int pg = visit;                       // question tokens: group `visit`
         if (visit >= n_sink_vis) {
@@ -512,60 +504,54 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
         return visit < n_sink_vis ? visit * PT_GROUP_TOKENS : (visit - n_sink_vis) * PT_GROUP_TOKENS - off0;
       };
       auto visit_lim = [&](int visit) { return visit < n_sink_vis ? P : n_live; };
-      // scores: what a group's tokens received in the previous step is parked in LDS during the walk
-      // (no global store between the loads of the stream) and added to the accumulators afterwards
-      auto mass_park = [&](const Frag& f, int visit) {
-        if (!fold || visit < n_sink_vis) return;
-        const float add = lagged_mass(f, *lgp, lane, visit_jg(visit), n_live - 1, c.scale_log2, n, kgrp);
-        if (lane < 32) park[(visit - v0) * 32 + lane] = add;
-      };
       int i = v0 + wave;
       Frag fa, fb;
       if (i < v1) load_group<NT>(fa, grp_ptr(i), lane);
       if constexpr (MASS) {
-        // after the first group's loads are on their way: stage the previous step's operands (the
-        // addresses are valid whether or not anything waits to be folded, so nothing here depends on
-        // the tag's value but the use of the result)
-        lgp = (LaggedLds*)(dyn_lds + (c.W / PT_GROUP_TOKENS + 2) * PT_GROUP_TOKENS) + wave;
+        // after the first group's loads are on their way: the previous step's queries into columns 8..15
+        // (saved by the step that left len == len0, in the buffer of that parity; the addresses are valid
+        // whether or not anything waits to be folded)
         mass_slab = c.mass + (size_t)slab * c.W;
         const long long tag = c.mtag[slab];
-        const int par = (int)(len0 & 1);
-        const uint16_t* qb = c.qprev + ((size_t)par * c.B + b) * c.Hq * 128;
-        const float* mlb = c.mlprev + ((size_t)par * c.B + b) * c.Hq * 2;
-        const u32x4* qp = (const u32x4*)(qb + (size_t)(hkv * g + (n < g ? n : 0)) * 128);
+        const int par = (int)(len0 & 1), hl = (n >= 8 && n - 8 < g) ? n - 8 : 0;
+        const uint16_t* qb = c.qprev + (((size_t)par * c.B + b) * c.Hq + hkv * g + hl) * 128;
+        const float* mlb = c.mlprev + (((size_t)par * c.B + b) * c.Hq + hkv * g + hl) * 2;
         u32x4 ql[4];
-        float mpl[4], ill[4];
 #pragma unroll
-        for (int cc = 0; cc < 4; ++cc) ql[cc] = qp[cc * 4 + kgrp];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int hh = 4 * kgrp + e < g ? 4 * kgrp + e : 0;
-          mpl[e] = mlb[(hkv * g + hh) * 2];
-          ill[e] = mlb[(hkv * g + hh) * 2 + 1];
-        }
+        for (int cc = 0; cc < 4; ++cc) ql[cc] = ((const u32x4*)qb)[cc * 4 + kgrp];
+        const float mpl = mlb[0], ill = mlb[1];
         fold = appending && tag == len0;
+        lag = fold && n >= 8 && n - 8 < g;
+        if (lag) {
 #pragma unroll
-        for (int cc = 0; cc < 4; ++cc) lgp->q[cc][lane] = (fold && n < g) ? ql[cc] : u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const bool ok = fold && 4 * kgrp + e < g;
-          lgp->mp[e][lane] = ok ? mpl[e] : 0.f;
-          lgp->il[e][lane] = ok ? ill[e] : 0.f;
+          for (int cc = 0; cc < 4; ++cc) qf[cc].u = ql[cc];
+          acc.m = mpl;                     // frozen: see process_group
+          il = ill;
         }
       }
       while (i < v1) {
         int nx = i + kWaves;
         if (nx < v1) load_group<NT>(fb, grp_ptr(nx), lane);
         if (patch && i == p_visit) patch_newest(fa, kp, vp, p_tl, n, kgrp);
-        if constexpr (MASS) mass_park(fa, i);
-        process_group(fa, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp);
+        if constexpr (MASS) {
+          float pp[8];
+          process_group<true>(fa, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp, lag, pp);
+          if (fold && i >= n_sink_vis) lagged_mass_park(pp, il, park + (i - v0) * 32, n, kgrp);
+        } else {
+          process_group(fa, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp);
+        }
         i = nx;
         if (i >= v1) break;
         nx = i + kWaves;
         if (nx < v1) load_group<NT>(fa, grp_ptr(nx), lane);
         if (patch && i == p_visit) patch_newest(fb, kp, vp, p_tl, n, kgrp);
-        if constexpr (MASS) mass_park(fb, i);
-        process_group(fb, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp);
+        if constexpr (MASS) {
+          float pp[8];
+          process_group<true>(fb, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp, lag, pp);
+          if (fold && i >= n_sink_vis) lagged_mass_park(pp, il, park + (i - v0) * 32, n, kgrp);
+        } else {
+          process_group(fb, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp);
+        }
         i = nx;
       }
       if constexpr (MASS) {
@@ -578,11 +564,21 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
         };
         // one lane adds to one accumulator once per step, so a returnless hardware float add gives the same
         // bits as load-add-store and needs no round trip
-        for (int vi = v0 + wave; vi < v1; vi += kWaves) {
-          if (vi < n_sink_vis || lane >= 32) continue;
-          const int j = visit_jg(vi) + lane;
-          if (appending && j == n_live - 1) *mass_ptr(vi) = 0.f;
-          else if (fold && (unsigned)j < (unsigned)(n_live - 1)) unsafeAtomicAdd(mass_ptr(vi), park[(vi - v0) * 32 + lane]);
+        for (int i0 = v0 + wave; i0 < v1; i0 += 8 * kWaves) {
+          float add[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {          // the LDS reads of a batch together, then its adds
+            const int vi = i0 + u * kWaves;
+            add[u] = (vi < v1 && lane < 32) ? park[(vi - v0) * 32 + lane] : 0.f;
+          }
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            const int vi = i0 + u * kWaves;
+            if (vi >= v1 || vi < n_sink_vis || lane >= 32) continue;
+            const int j = visit_jg(vi) + lane;
+            if (appending && j == n_live - 1) *mass_ptr(vi) = 0.f;
+            else if (fold && (unsigned)j < (unsigned)(n_live - 1)) unsafeAtomicAdd(mass_ptr(vi), add[u]);
+          }
         }
       }
       // the store of the new token rides behind the walk: its inputs arrived long ago, and the
@@ -781,8 +777,8 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bo
   // scores are maintained by whole steps only (append + attention) under the scored policy
   const bool mass = cc.scored && do_append && do_attend;
   if (mass) {
-    // parked masses of every group a workgroup may walk + the previous step's operands per wavefront
-    const size_t park = (size_t)(cc.W / PT_GROUP_TOKENS + 2) * PT_GROUP_TOKENS * sizeof(float) + 4 * sizeof(LaggedLds);
+    // parked masses of every group a workgroup may walk
+    const size_t park = (size_t)(cc.W / PT_GROUP_TOKENS + 2) * PT_GROUP_TOKENS * sizeof(float);
     if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 4, true>), grid, dim3(256), park, s, cc, a);
     else hipLaunchKernelGGL((decode_mfma_kernel<false, 4, true>), grid, dim3(256), park, s, cc, a);
   } else if (waves == 8) {

@@ -232,7 +232,8 @@ ptenc_status ptenc_set_option(ptenc_ctx* ctx, int32_t option, int32_t value) {
       if (value != PTENC_POLICY_SLIDING && value != PTENC_POLICY_SCORED) return PTENC_ERR_INVALID_ARG;
       if (value == PTENC_POLICY_SCORED) {
         // the scores are a by-product of the MFMA step kernel, and the selection ranks in LDS
-        if (!ctx->dev.tiled || ctx->opt_force_generic) return PTENC_ERR_UNSUPPORTED;
+        // (its spare MFMA columns carry the previous step's queries: at most 8 query heads per KV head)
+        if (!ctx->dev.tiled || ctx->opt_force_generic || ctx->dev.group > 8) return PTENC_ERR_UNSUPPORTED;
         if (ctx->dev.Wr - resolved_recent(ctx) > PT_SCORED_MAX_ELIGIBLE) return PTENC_ERR_UNSUPPORTED;
       }
       ctx->opt_policy = value;
