@@ -110,6 +110,7 @@ __global__ void reset_kernel(PtDev c, const uint8_t* __restrict__ mask, int clea
   // importance scores: nothing waits to be folded, no eviction has happened
   for (int h = threadIdx.x; h < c.Hkv; h += blockDim.x) c.mtag[b * c.Hkv + h] = -1;
   for (int i = threadIdx.x; i < c.C; i += blockDim.x) c.victims[(size_t)b * c.C + i] = -1;
+  if (threadIdx.x == 0) c.selected[b] = 0;
 }
 
 template <typename T>

@@ -32,6 +32,7 @@
 // Counters are double-buffered: a step reads (len, base) from one pair of arrays and writes the
 // other, so no workgroup has to wait for the rest of its rollout before the step can end.
 #include "pt_encode_tail.h"
+#include "pt_scored_select.h"
 
 namespace {
 
@@ -262,6 +263,7 @@ union StepSmem {
   } merge;
   uint16_t vstage[kEncWaves][4096];   // one group's V part per wavefront (encoder operand transposition)
   EncTailSmem enc;   // Ka and Va (contiguous, >= G*r floats) double as the row-norm staging area
+  SelSmall sel;      // scored policy: the choice of the next victims, by the rollout's last workgroup
 };
 
 // This head's share of K_a and V_a for the chunk [base, base + C): rows j = logical token, RP columns.
@@ -720,15 +722,28 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
     c.base_nx[b] = base1;
   }
 
-  // ---- whoever finishes last for this rollout completes the encoding ----
-  if (evicting || (in_place && appending)) {
+  // ---- whoever finishes last for this rollout completes the encoding, and, under the scored policy,
+  //      chooses the next victims as soon as this step's append has filled the ring (the scores a
+  //      selection may use are complete then; the step that evicts finds its victims in front) ----
+  const bool will_select = MASS && appending && (len1 - base1 == c.Wr);
+  if (evicting || (in_place && appending) || will_select) {
+    // rare (once per C steps): the other workgroups' new token and score updates must be visible to the
+    // one that selects, whichever XCD each ran on: device-wide release here, acquire there
+    if (will_select) __threadfence();
     __threadfence_block();
     __syncthreads();
     if (tid == 0) sm_ticket = atomicAdd(c.tick_rollout + b, 1);
     __syncthreads();
     if (sm_ticket == c.Hkv * ns - 1) {
       if (evicting) encode_finish(c, sm, b, (int)(base0 % c.Wr) & 31);
+      if constexpr (MASS) {
+        if (will_select) {
+          __threadfence();
+          pt_scored_select(c, b, base1, dyn_lds, sm.sel);
+        }
+      }
       if (tid == 0) {
+        if (evicting && !will_select) c.selected[b] = 0;   // the chosen chunk has left
         if (in_place) { c.len[b] = len1; c.base[b] = base1; }
         c.tick_rollout[b] = 0;
       }

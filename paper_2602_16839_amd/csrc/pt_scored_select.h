@@ -1,0 +1,186 @@
+// Importance-based eviction, the choice: which C ring entries of a full ring leave next, and the
+// exchange that brings them to the front of the ring (the heavy-hitter rule the paper's ablation on
+// token dropping strategies integrates, chunked like its sliding window).  The eviction itself --
+// dropping the oldest C ring places and folding them into S (Our Approach, the Delta-W equation and
+// the update rule) -- is then the sliding window's, unchanged.
+//
+// One workgroup of 256 threads per rollout:
+//   1. score of every eligible ring entry (all but the n_recent newest) = sum over KV heads of the
+//      per-head accumulators the decode step maintains, in head order;
+//   2. the C lowest, ties towards the older entry: a radix select on the float bit patterns
+//      (scores are >= +0, so unsigned order is numeric order), then one ordered pass for the ties;
+//   3. the survivors among the oldest C ring places trade places with the victims beyond them
+//      (k-th survivor with the k-th such victim; key, value, accumulators and position tag travel
+//      together), so the oldest C places hold exactly the victims and the ring stays one run.
+// The pairs are disjoint, so every exchange is independent of the others.
+#pragma once
+
+#include "ptenc_internal.h"
+
+constexpr int kSelThreads = 256;
+
+struct SelSmall {
+  uint32_t vmask[PT_SCORED_MAX_ELIGIBLE / 32];   // bit i: ring entry i is a victim
+  int wpre[PT_SCORED_MAX_ELIGIBLE / 32];         // victims before word w
+  int hist[256];
+  int sh[4];
+  int wsum[kSelThreads / 64];
+};
+
+// exclusive count, over the workgroup's threads in thread order, of a flag; total in *total
+__device__ inline int pt_sel_excl_count(bool flag, SelSmall& sm, int* total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const unsigned long long bal = __ballot(flag);
+  const int within = __popcll(bal & ((1ull << lane) - 1ull));
+  __syncthreads();
+  if (lane == 0) sm.wsum[wave] = __popcll(bal);
+  __syncthreads();
+  int before = 0, tot = 0;
+  for (int w = 0; w < kSelThreads / 64; ++w) {
+    if (w < wave) before += sm.wsum[w];
+    tot += sm.wsum[w];
+  }
+  *total = tot;
+  return before + within;
+}
+
+// Rollout b's ring is full and starts at position `base`.  `work` = LDS for max(n_el floats, n_el ints),
+// n_el = Wr - n_recent: first the scores by ring index, then the two index lists of the exchanges.
+// Called by all 256 threads of a workgroup; starts and ends with a barrier.
+__device__ inline void pt_scored_select(const PtDev& c, int b, long long base, float* work, SelSmall& sm) {
+  const int t = threadIdx.x;
+  const int n_el = c.Wr - c.n_recent, C = c.C;
+  const int s0 = (int)(base % c.Wr);
+  auto slot_of = [&](int i) { int s = s0 + i; if (s >= c.Wr) s -= c.Wr; return s + c.n_sink; };
+  __syncthreads();
+
+  // ---- 1. scores ----
+  for (int i = t; i < n_el; i += kSelThreads) {
+    const int slot = slot_of(i);
+    float s = 0.f;
+    for (int h = 0; h < c.Hkv; ++h) s += c.mass[(size_t)(b * c.Hkv + h) * c.W + slot];
+    work[i] = s;
+  }
+  for (int w = t; w < PT_SCORED_MAX_ELIGIBLE / 32; w += kSelThreads) sm.vmask[w] = 0u;
+  __syncthreads();
+
+  // ---- 2. the C-th smallest bit pattern, one byte at a time from the top ----
+  uint32_t prefix = 0u, pmask = 0u;
+  int k = C;                                            // still to take among the entries matching prefix
+  for (int shift = 24; shift >= 0; shift -= 8) {
+    sm.hist[t] = 0;
+    __syncthreads();
+    for (int i = t; i < n_el; i += kSelThreads) {
+      const uint32_t bits = __float_as_uint(work[i]);
+      if ((bits & pmask) == prefix) atomicAdd(&sm.hist[(bits >> shift) & 255u], 1);
+    }
+    __syncthreads();
+    if (t == 0) {
+      int cum = 0, dgt = 255;
+      for (int x = 0; x < 256; ++x) {
+        if (cum + sm.hist[x] >= k) { dgt = x; break; }
+        cum += sm.hist[x];
+      }
+      sm.sh[0] = dgt;
+      sm.sh[1] = k - cum;
+    }
+    __syncthreads();
+    prefix |= (uint32_t)sm.sh[0] << shift;
+    pmask |= 255u << shift;
+    k = sm.sh[1];
+    __syncthreads();
+  }
+  // prefix = the threshold pattern; k >= 1 of the entries equal to it are taken, oldest first
+  int eq_seen = 0;
+  for (int i0 = 0; i0 < n_el; i0 += kSelThreads) {
+    const int i = i0 + t;
+    const uint32_t bits = i < n_el ? __float_as_uint(work[i]) : 0xffffffffu;
+    const bool eq = i < n_el && bits == prefix;
+    int tot;
+    const int rank = eq_seen + pt_sel_excl_count(eq, sm, &tot);
+    if (i < n_el && (bits < prefix || (eq && rank < k))) atomicOr(&sm.vmask[i >> 5], 1u << (i & 31));
+    eq_seen += tot;
+  }
+  __syncthreads();
+  if (t == 0) {
+    int cum = 0;
+    for (int w = 0; w < (n_el + 31) / 32; ++w) { sm.wpre[w] = cum; cum += __popc(sm.vmask[w]); }
+  }
+  __syncthreads();
+  auto is_victim = [&](int i) { return i < n_el && ((sm.vmask[i >> 5] >> (i & 31)) & 1u); };
+  auto victims_before = [&](int i) {   // victims among ring entries [0, i), i <= n_el
+    const int w = i >> 5;
+    return (w < (n_el + 31) / 32 ? sm.wpre[w] + __popc(sm.vmask[w] & ((1u << (i & 31)) - 1u))
+                                 : sm.wpre[w - 1] + __popc(sm.vmask[w - 1]));
+  };
+  // what leaves, by position, in ring order (before anything trades places)
+  for (int i = t; i < n_el; i += kSelThreads)
+    if (is_victim(i)) c.victims[(size_t)b * C + victims_before(i)] = c.pos[(size_t)b * c.W + slot_of(i)];
+  const int v_head = victims_before(min(C, n_el));      // victims inside the oldest chunk
+  __syncthreads();                                      // scores are dead from here on: `work` holds the pairs
+
+  // ---- 3. survivors of the oldest chunk <-> victims beyond it ----
+  const int n_mv = C - v_head;
+  int* mv_a = (int*)work;                               // k-th survivor of the oldest chunk
+  int* mv_b = mv_a + n_el / 2 + 1;                      // k-th victim beyond it (n_mv <= n_el / 2)
+  for (int i = t; i < n_el; i += kSelThreads) {
+    if (i < C && !is_victim(i)) mv_a[i - victims_before(i)] = i;
+    if (i >= C && is_victim(i)) mv_b[victims_before(i) - v_head] = i;
+  }
+  __syncthreads();
+  // a token of one KV head = 16 key pieces of 16 bytes + 128 value elements (token-minor): 144 items,
+  // exchanged in batches of loads followed by stores so that the round trips overlap
+  uint16_t* cache = (uint16_t*)c.cache;
+  typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+  const int n_items = n_mv * c.Hkv * 144;
+  for (int i0 = 0; i0 < n_items; i0 += kSelThreads * 4) {
+    u32x4 ka[4], kb[4];
+    uint16_t va[4], vb[4];
+    size_t oa[4], ob[4];
+    int kind[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int idx = i0 + u * kSelThreads + t;
+      kind[u] = -1;
+      if (idx < n_items) {
+        const int mv = idx / (c.Hkv * 144), rem = idx - mv * (c.Hkv * 144);
+        const int h = rem / 144, it = rem - h * 144;
+        const int sa = slot_of(mv_a[mv]), sb = slot_of(mv_b[mv]);
+        const size_t so = (size_t)(b * c.Hkv + h) * pt_slab_elems(c.W, 128);
+        if (it < 16) {
+          kind[u] = 0;
+          oa[u] = so + pt_k_off(1, c.W, 128, sa, it * 8);
+          ob[u] = so + pt_k_off(1, c.W, 128, sb, it * 8);
+          ka[u] = *(const u32x4*)(cache + oa[u]);
+          kb[u] = *(const u32x4*)(cache + ob[u]);
+        } else {
+          kind[u] = 1;
+          oa[u] = so + pt_v_off(1, c.W, 128, sa, it - 16);
+          ob[u] = so + pt_v_off(1, c.W, 128, sb, it - 16);
+          va[u] = cache[oa[u]];
+          vb[u] = cache[ob[u]];
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (kind[u] == 0) { *(u32x4*)(cache + oa[u]) = kb[u]; *(u32x4*)(cache + ob[u]) = ka[u]; }
+      else if (kind[u] == 1) { cache[oa[u]] = vb[u]; cache[ob[u]] = va[u]; }
+    }
+  }
+  for (int idx = t; idx < n_mv * (c.Hkv + 1); idx += kSelThreads) {
+    const int mv = idx / (c.Hkv + 1), h = idx - mv * (c.Hkv + 1);
+    const int sa = slot_of(mv_a[mv]), sb = slot_of(mv_b[mv]);
+    if (h < c.Hkv) {
+      float* m = c.mass + (size_t)(b * c.Hkv + h) * c.W;
+      const float x = m[sa], y = m[sb];
+      m[sa] = y; m[sb] = x;
+    } else {
+      long long* p = c.pos + (size_t)b * c.W;
+      const long long x = p[sa], y = p[sb];
+      p[sa] = y; p[sb] = x;
+    }
+  }
+  if (t == 0) c.selected[b] = 1;
+  __syncthreads();
+}

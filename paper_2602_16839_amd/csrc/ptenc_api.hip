@@ -12,7 +12,7 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct StateLayout {
   size_t S, Qa, S0, len, base, len2, base2, n_prompt, err, tick_rollout, tick_slab, WKp, WVp;
-  size_t mass, pos, victims, qprev, mlprev, mtag, total;   // importance-based eviction
+  size_t mass, pos, victims, qprev, mlprev, mtag, selected, total;   // importance-based eviction
 };
 
 StateLayout state_layout(const ptenc_config& c) {
@@ -40,6 +40,7 @@ StateLayout state_layout(const ptenc_config& c) {
   L.qprev = off;   off = align256(off + 2 * rows * c.head_dim * 2);
   L.mlprev = off;  off = align256(off + 2 * rows * 2 * sizeof(float));
   L.mtag = off;    off = align256(off + slabs * sizeof(long long));
+  L.selected = off; off = align256(off + (size_t)c.batch * sizeof(int));
   L.total = off;
   return L;
 }
@@ -132,6 +133,16 @@ ptenc_status advanced(ptenc_ctx* x, hipError_t e) {
 }
 inline ptenc_status hip_status(hipError_t e) { return e == hipSuccess ? PTENC_OK : PTENC_ERR_HIP; }
 
+// Scored policy: a decode step chooses the next victims itself when its append fills a ring.  A ring
+// can also fill up, or lose its selection, in ways that step does not see (a bare ptenc_cache_append,
+// ptenc_set_scores, a change of policy); the next call that may evict then runs the stand-alone
+// selection first, over every rollout (choosing early for one that sits this call out is harmless).
+hipError_t refresh_selection(ptenc_ctx* x, hipStream_t s) {
+  if (!x->dev.scored || !x->select_stale) return hipSuccess;
+  x->select_stale = 0;
+  return pt_launch_scored_select(x->dev, nullptr, nullptr, 0, s);
+}
+
 }  // namespace
 
 extern "C" {
@@ -192,6 +203,8 @@ ptenc_status ptenc_create(const ptenc_config* cfg, void* d_cache, void* d_state,
   d.mass = (float*)(sp + L.mass); d.pos = (long long*)(sp + L.pos); d.victims = (long long*)(sp + L.victims);
   d.qprev = (uint16_t*)(sp + L.qprev); d.mlprev = (float*)(sp + L.mlprev);
   d.mtag = (long long*)(sp + L.mtag);
+  d.selected = (int*)(sp + L.selected);
+  x->select_stale = 1;
   x->opt_recent = -1;
   replan(x);
   *out = x;
@@ -237,6 +250,7 @@ ptenc_status ptenc_set_option(ptenc_ctx* ctx, int32_t option, int32_t value) {
         if (ctx->dev.Wr - resolved_recent(ctx) > PT_SCORED_MAX_ELIGIBLE) return PTENC_ERR_UNSUPPORTED;
       }
       ctx->opt_policy = value;
+      ctx->select_stale = 1;
       break;
     case PTENC_OPT_RECENT:
       if (value < -1 || (value >= 0 && value > ctx->dev.Wr - ctx->dev.C)) return PTENC_ERR_INVALID_ARG;
@@ -311,6 +325,7 @@ ptenc_status ptenc_cache_append(ptenc_ctx* ctx, const void* d_k, const void* d_v
                                 void* stream) {
   if (!ctx || !d_k || !d_v) return PTENC_ERR_INVALID_ARG;
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
+  ctx->select_stale = 1;   // a bare append may fill a ring without choosing its victims
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
     return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, false, true, false, nullptr, d_k, d_v,
@@ -323,8 +338,7 @@ ptenc_status ptenc_cache_append(ptenc_ctx* ctx, const void* d_k, const void* d_v
 ptenc_status ptenc_evict_encode(ptenc_ctx* ctx, const uint8_t* d_active, void* d_dbg_chunk, void* stream) {
   if (!ctx) return PTENC_ERR_INVALID_ARG;
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
-  // scored policy: the victims are first brought to the front of the ring, then leave as "the oldest chunk"
-  if (ctx->dev.scored && pt_launch_scored_select(ctx->dev, d_active, nullptr, 0, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
+  if (refresh_selection(ctx, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
   if (ctx->attn_kernel == 1)
     return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, true, false, false, nullptr, nullptr,
                                                nullptr, nullptr, d_active, d_dbg_chunk, nullptr, 0, ctx->opt_in_place != 0, S(stream)));
@@ -350,8 +364,7 @@ ptenc_status ptenc_decode_step(ptenc_ctx* ctx, const void* d_q, const void* d_k,
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_q | (uintptr_t)d_out | (uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
-    if (ctx->dev.scored && pt_launch_scored_select(ctx->dev, d_active, nullptr, 0, S(stream)) != hipSuccess)
-      return PTENC_ERR_HIP;
+    if (refresh_selection(ctx, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
     return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, true, true, true, d_q, d_k,
                                                d_v, d_out, d_active, nullptr, nullptr, 0, ctx->opt_in_place != 0, S(stream)));
   }
@@ -372,7 +385,7 @@ ptenc_status ptenc_decode_step_ids(ptenc_ctx* ctx, const void* d_q, const void* 
   d.n_splits = ctx->opt_splits > 0 ? ctx->opt_splits : heuristic_splits(ctx, n);
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_q | (uintptr_t)d_out | (uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
-    if (d.scored && pt_launch_scored_select(d, nullptr, d_ids, n, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
+    if (refresh_selection(ctx, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
     // counters are written in place by this launch: no buffer rotation
     return hip_status(pt_launch_decode_mfma(d, ctx->nontemporal != 0, pick_waves(ctx, n, d.n_splits), true, true, true,
                                             d_q, d_k, d_v, d_out, nullptr, nullptr, d_ids, n, true, S(stream)));
@@ -488,6 +501,7 @@ ptenc_status ptenc_get_scores(ptenc_ctx* ctx, float* d_score, int64_t* d_pos, vo
 ptenc_status ptenc_set_scores(ptenc_ctx* ctx, const float* d_score, void* stream) {
   if (!ctx || !d_score) return PTENC_ERR_INVALID_ARG;
   if (!ctx->dev.scored) return PTENC_ERR_STATE;
+  ctx->select_stale = 1;
   return hip_status(pt_launch_scores_set(ctx->dev, d_score, S(stream)));
 }
 

@@ -50,6 +50,7 @@ struct PtDev {
   uint16_t* qprev;    // [2][B][H_q][128] the latest step's queries, buffer = parity of the length it left
   float* mlprev;      // [2][B][H_q][2]   that step's softmax maximum (base-2 domain) and 1 / sum
   long long* mtag;    // [B*H_kv] the length that step left (its data waits to be folded); -1: none
+  int* selected;      // [B] 1: the ring is full and its next victims already sit in its oldest C places
 };
 
 struct ptenc_ctx {
@@ -65,6 +66,7 @@ struct ptenc_ctx {
   int opt_in_place;      // 1 = counters are updated in place (no buffer rotation on the host)
   int opt_policy;        // 0 sliding window, 1 scored
   int opt_recent;        // -1 = default
+  int select_stale;      // scored policy: a ring may be full without a valid selection (see ptenc_api.hip)
   int waves;             // resolved: wavefronts per workgroup of the MFMA kernel
   int attn_kernel;       // 0 generic, 1 mfma
   int encode_kernel;     // 0 generic, 1 mfma

@@ -47,10 +47,15 @@ def check_scores(wl, orc, layer, what):
     sc, ps = layer.scores()
     for b in range(wl.batch):
         n = len(orc.win[b])
-        assert np.array_equal(ps[b, :n], orc.positions(b)), "%s: ring positions of rollout %d" % (what, b)
         assert (ps[b, n:] == -1).all() and (sc[b, n:] == 0).all()
-        ref = orc.scores(b)
-        err = np.abs(sc[b, :n] - ref)
+        got_p, got_s, ref_p, ref = ps[b, :n], sc[b, :n], orc.positions(b), orc.scores(b)
+        if n == wl.window - wl.n_sink:
+            # a full ring: the library has already brought the next victims to the front (the oracle does
+            # it when they leave), so only the tokens and their scores are comparable, not the order
+            og, orf = np.argsort(got_p), np.argsort(ref_p)
+            got_p, got_s, ref_p, ref = got_p[og], got_s[og], ref_p[orf], ref[orf]
+        assert np.array_equal(got_p, ref_p), "%s: ring positions of rollout %d" % (what, b)
+        err = np.abs(got_s - ref)
         assert (err <= SCORE_ABS + SCORE_REL * np.abs(ref)).all(), "%s: scores of rollout %d off by %.3e" % (what, b, err.max())
 
 
@@ -125,7 +130,7 @@ def test_with_only_the_oldest_chunk_eligible_outputs_equal_the_sliding_window_bi
 @pytest.mark.parametrize("W,C,n_recent,n_sink", [(96, 32, 24, 0), (160, 40, 0, 32), (128, 7, 100, 0), (64, 64, 0, 0)])
 def test_selection_on_injected_scores_is_bit_exact(W, C, n_recent, n_sink):
     # scores with few distinct values (plenty of ties), the same float32 numbers on both sides
-    wl = small(batch=3, window=W, chunk=C, n_sink=n_sink, steps=W - n_sink + 6 * C)
+    wl = small(batch=3, window=W, chunk=C, n_sink=n_sink, steps=W - n_sink + 6 * C - 1)    # ends one short of a full ring
     orc, layer = make_both(wl, n_recent)
     Wr = W - n_sink
     q, k, v = I.qkv_steps(wl, 0, wl.steps)
@@ -134,13 +139,13 @@ def test_selection_on_injected_scores_is_bit_exact(W, C, n_recent, n_sink):
     rng = np.random.default_rng(7)
     n_checked = 0
     for t in range(wl.steps):
-        if len(orc.win[0]) == Wr:                      # the next step evicts: plant the scores
+        if len(orc.win[0]) == Wr - 1:                  # the next step fills the ring, the one after evicts: plant the scores
             sc = np.zeros((wl.batch, W), dtype=np.float32)
             levels = rng.integers(2, 9)
-            sc[:, :Wr] = (rng.integers(0, levels, (wl.batch, Wr)) / np.float32(levels)).astype(np.float32)
+            sc[:, :Wr - 1] = (rng.integers(0, levels, (wl.batch, Wr - 1)) / np.float32(levels)).astype(np.float32)
             layer.set_scores(sc)
             for b in range(wl.batch):
-                orc.set_scores(b, sc[b, :Wr].astype(np.float64))
+                orc.set_scores(b, sc[b, :Wr - 1].astype(np.float64))
         before = list(orc.evicted)
         ref = orc.step(qn[t], kn[t], vn[t])
         out = layer.step(qd[t], kd[t], vd[t])
