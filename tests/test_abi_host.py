@@ -84,6 +84,25 @@ def test_create_checks_pointers_and_order_of_calls():
     assert ptenc.status_string(ptenc.ERR_UNSUPPORTED) == "unsupported configuration"
 
 
+def test_scored_policy_options_are_checked_on_the_host():
+    L = ptenc.lib()
+    _, h = _host_ctx(cfg())                                # bf16, head_dim 128: the MFMA path
+    W, Ck = cfg().window, cfg().chunk
+    assert L.ptenc_set_option(h, ptenc.OPT_RECENT, W - Ck + 1) == ptenc.ERR_INVALID_ARG     # fewer than a chunk eligible
+    assert L.ptenc_set_option(h, ptenc.OPT_RECENT, -2) == ptenc.ERR_INVALID_ARG
+    assert L.ptenc_set_option(h, ptenc.OPT_RECENT, W - Ck) == ptenc.OK
+    assert L.ptenc_set_option(h, ptenc.OPT_EVICT_POLICY, 2) == ptenc.ERR_INVALID_ARG
+    assert L.ptenc_get_scores(h, C.c_void_p(256), None, None) == ptenc.ERR_STATE           # sliding policy keeps none
+    assert L.ptenc_set_option(h, ptenc.OPT_EVICT_POLICY, ptenc.POLICY_SCORED) == ptenc.OK
+    assert L.ptenc_set_option(h, ptenc.OPT_FORCE_GENERIC, 1) == ptenc.ERR_UNSUPPORTED      # the scores come from the MFMA kernel
+    assert L.ptenc_get_scores(h, None, None, None) == ptenc.ERR_INVALID_ARG
+    assert L.ptenc_destroy(h) == ptenc.OK
+    for bad in (cfg(dtype=ptenc.F32, head_dim=64), cfg(window=40, chunk=8), cfg(n_q_heads=36, n_kv_heads=2)):
+        _, h = _host_ctx(bad)                               # fp32, untiled window, 18 query heads per KV head
+        assert L.ptenc_set_option(h, ptenc.OPT_EVICT_POLICY, ptenc.POLICY_SCORED) == ptenc.ERR_UNSUPPORTED
+        assert L.ptenc_destroy(h) == ptenc.OK
+
+
 def test_stack_sizes_and_argument_checks():
     L = ptenc.lib()
     c = cfg()

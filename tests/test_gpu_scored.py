@@ -190,6 +190,54 @@ def test_scored_compact_id_lists():
     H.assert_close(layer.get_state(), orc.state(), H.S_ABS, H.S_REL, "state S")
 
 
+def test_scored_full_size_properties():
+    # the benchmark's shape (B 128, 28 / 4 heads, window 4096, chunk 128) through three evictions, in the
+    # launch configuration the benchmark times.  Which tokens leave is a floating-point decision the CPU
+    # cannot replay at this size, so this checks what holds for any correct choice.
+    from oracle.ring_model import evicted_closed_form
+    wl = I.WORKLOADS["qwen7b"]
+    W, C, Hq = wl.window, wl.chunk, wl.n_q_heads
+    T = W + 2 * C + 5
+    n_recent = W // 2
+    dev = torch.device("cuda:0")
+    enc = I.encoder_params(wl, device=dev)
+    layer = ptenc.Layer(wl.batch, Hq, wl.n_kv_heads, wl.head_dim, W, C, dtype=wl.torch_dtype, poison_cache=True)
+    layer.set_option(ptenc.OPT_EVICT_POLICY, ptenc.POLICY_SCORED)
+    layer.set_encoder(enc["q_g"], enc["WaQ"], enc["WaK"], enc["WaV"], enc["k_g"], enc["v_g"])
+    layer.reset()
+    seen_victims = [set() for _ in range(wl.batch)]
+    for t0 in range(0, T, 512):
+        t1 = min(T, t0 + 512)
+        q, k, v = I.qkv_steps(wl, t0, t1, device=dev)
+        out = layer.run(q, k, v)
+        assert torch.isfinite(out.float()).all()
+        vic = layer.victims()
+        for b in range(wl.batch):
+            if vic[b, 0] >= 0:
+                seen_victims[b].update(vic[b].tolist())
+    assert layer.poll_error() == 0
+    ln, base = layer.counters()
+    E = evicted_closed_form(T, W, C)
+    assert (ln == T).all() and (base == E).all() and E == 3 * C
+    sc, ps = layer.scores()
+    n = T - E
+    for b in range(0, wl.batch, 9):
+        live = ps[b, :n]
+        assert (ps[b, n:] == -1).all()
+        assert len(set(live.tolist())) == n and live.min() >= 0 and live.max() == T - 1    # distinct tokens of this rollout
+        assert set(range(T - n_recent, T)) <= set(live.tolist())                           # the recent ones are protected
+        assert not (set(live.tolist()) & seen_victims[b])                                  # what left stays out
+        s_b = sc[b, :n]
+        assert np.isfinite(s_b).all() and (s_b >= 0).all()
+        # every step hands out H_q of probability; the folded scores of the survivors cannot exceed it
+        assert 0.2 * Hq * (T - 1) < s_b.sum() <= Hq * (T - 1) * (1 + 1e-4)
+    # the last eviction took C distinct tokens, none of them among the then most recent ones
+    vic = layer.victims()
+    t_ev = W + 2 * C                      # 0-based step of the third eviction: positions < t_ev existed
+    for b in range(0, wl.batch, 9):
+        assert len(set(vic[b].tolist())) == C and vic[b].max() < t_ev - n_recent
+
+
 def test_scored_policy_argument_checks():
     wl = small()
     enc = I.encoder_params(wl)
