@@ -190,6 +190,34 @@ def test_scored_compact_id_lists():
     H.assert_close(layer.get_state(), orc.state(), H.S_ABS, H.S_REL, "state S")
 
 
+def test_scored_steps_replayed_from_a_graph_equal_eager_steps():
+    wl = small(batch=3, window=96, chunk=32, steps=230)
+    _, eager = make_both(wl, 24)
+    _, layer = make_both(wl, 24)
+    layer.set_option(ptenc.OPT_COUNTERS_IN_PLACE, 1)
+    q, k, v = I.qkv_steps(wl, 0, wl.steps)
+    q = (q.float() * 48.0).to(q.dtype)
+    q, k, v = q.cuda(), k.cuda(), v.cuda()
+    ref = eager.run(q, k, v)
+    qs, ks, vs, outs = torch.empty_like(q[0]), torch.empty_like(k[0]), torch.empty_like(v[0]), torch.empty_like(q[0])
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        layer.step(qs, ks, vs, outs)
+    for t in range(wl.steps):
+        qs.copy_(q[t]); ks.copy_(k[t]); vs.copy_(v[t])
+        g.replay()
+        if t % 11 == 0:
+            torch.cuda.synchronize()
+            _ = (q[t].float() * 2).sum().item()              # unrelated eager work between replays
+        assert torch.equal(outs, ref[t]), "replay %d" % t
+    assert all(np.array_equal(a, b) for a, b in zip(layer.counters(), eager.counters()))
+    assert np.array_equal(layer.victims(), eager.victims()) and (layer.victims() >= 0).all()
+    assert np.array_equal(layer.get_state(), eager.get_state())
+    sg, pg = layer.scores()
+    se, pe = eager.scores()
+    assert np.array_equal(pg, pe) and np.array_equal(sg, se)
+
+
 def test_scored_full_size_properties():
     # the benchmark's shape (B 128, 28 / 4 heads, window 4096, chunk 128) through three evictions, in the
     # launch configuration the benchmark times.  Which tokens leave is a floating-point decision the CPU
