@@ -31,6 +31,13 @@
 //
 // Counters are double-buffered: a step reads (len, base) from one pair of arrays and writes the
 // other, so no workgroup has to wait for the rest of its rollout before the step can end.
+//
+// Importance scores (template argument MASS, the scored eviction policy; the paper's ablation on
+// token dropping strategies).  The attention probability every cached token received in the rollout's
+// previous step is recomputed here, from that step's saved queries and softmax statistics riding in
+// the idle columns 8..15 of the score MFMA, parked in LDS during the walk and added to the per-slot
+// accumulators after it; the step whose append fills the ring also chooses the next victims
+// (pt_scored_select.h) and leaves them in the ring's oldest chunk, so the eviction above needs no change.
 #include "pt_encode_tail.h"
 #include "pt_scored_select.h"
 
@@ -784,7 +791,6 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bo
   a.knew = (const uint16_t*)k; a.vnew = (const uint16_t*)v;
   a.active = active; a.dbg_chunk = (uint16_t*)dbg_chunk;
   a.do_evict = do_evict; a.do_append = do_append; a.do_attend = do_attend;
-  // without attention there is nothing to split
   // without attention there is nothing to split
   PtDev cc = c;
   if (!do_attend) cc.n_splits = 1;
