@@ -97,3 +97,55 @@ def test_stack_equals_separate_layers_bitwise():
         ln, base = singles[l].counters()
         n = int(ln[0] - base[0])
         assert torch.equal(K0[:, :, :n], K1[:, :, :n]) and torch.equal(V0[:, :, :n], V1[:, :, :n])
+
+
+def test_stack_layers_under_the_scored_policy():
+    # every layer of a stack is an ordinary context: the importance-based policy is set per layer, and
+    # the recorded graph replays its steps (selection included) like eager launches
+    from oracle import scored_oracle as so
+    L, n_recent = 2, 24
+    wl = I.WORKLOADS["qwen7b"].replace(batch=3, n_q_heads=14, n_kv_heads=2, window=96, chunk=32, steps=200)
+    wls = _layer_workloads(wl, L)
+    encs = [I.encoder_params(w) for w in wls]
+    orcs = []
+    for w, enc in zip(wls, encs):
+        e = {k: H.f64(v) for k, v in enc.items()}
+        orcs.append(so.ScoredOracleLayer(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.window, w.chunk, n_recent,
+                                         e["q_g"], e["WaQ"], e["WaK"], e["WaV"], e["k_g"], e["v_g"]))
+    st = ptenc.Stack(L, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
+                     dtype=wl.torch_dtype, poison_cache=True)
+    for l, enc in enumerate(encs):
+        st.layers[l].set_option(ptenc.OPT_RECENT, n_recent)
+        st.layers[l].set_option(ptenc.OPT_EVICT_POLICY, ptenc.POLICY_SCORED)
+        dev = {k: v.cuda() for k, v in enc.items()}
+        st.layers[l].set_encoder(dev["q_g"], dev["WaQ"], dev["WaK"], dev["WaV"], dev["k_g"], dev["v_g"])
+    st.reset()
+    qkv = []
+    for w in wls:
+        q, k, v = I.qkv_steps(w, 0, wl.steps)
+        qkv.append(((q.float() * 48.0).to(q.dtype), k, v))
+    dev = [tuple(x.cuda() for x in t) for t in qkv]
+    host = [tuple(H.f64(x) for x in t) for t in qkv]
+    qs = [torch.empty_like(d[0][0]) for d in dev]
+    ks = [torch.empty_like(d[1][0]) for d in dev]
+    vs = [torch.empty_like(d[2][0]) for d in dev]
+    outs = [torch.empty_like(d[0][0]) for d in dev]
+    st.graph_capture(qs, ks, vs, outs)
+    for t in range(wl.steps):
+        refs = [orcs[l].step(host[l][0][t], host[l][1][t], host[l][2][t]) for l in range(L)]
+        if t % 2 == 0:
+            got = st.step([d[0][t] for d in dev], [d[1][t] for d in dev], [d[2][t] for d in dev])
+        else:
+            for l in range(L):
+                qs[l].copy_(dev[l][0][t]); ks[l].copy_(dev[l][1][t]); vs[l].copy_(dev[l][2][t])
+            st.graph_launch()
+            got = outs
+        for l in range(L):
+            H.assert_close(H.f64(got[l]), refs[l], H.BF16_ABS, H.BF16_REL, "layer %d out at step %d" % (l, t))
+    for l in range(L):
+        assert orcs[l].min_margin >= 1e-2, "inputs leave a selection too close to call: pick others"
+        assert all(np.array_equal(a, b) for a, b in zip(st.layers[l].counters(), orcs[l].counters()))
+        vic = st.layers[l].victims()
+        for b in range(wl.batch):
+            assert vic[b].tolist() == orcs[l].last_victims[b]
+        H.assert_close(st.layers[l].get_state(), orcs[l].state(), H.S_ABS, H.S_REL, "layer %d state" % l)
