@@ -195,7 +195,8 @@ ptenc_status ptenc_decode_step(ptenc_ctx* ctx, const void* d_q, const void* d_k,
 
 /* n_steps decode steps from step-major buffers: q and out [n_steps, B, H_q, d], k and v
  * [n_steps, B, H_kv, d], d_active NULL or uint8 [n_steps, B].  Same result as n_steps calls of
- * ptenc_decode_step; the loop runs on the host without synchronising. */
+ * ptenc_decode_step; the loop runs on the host without synchronising.  n_steps = 0 does nothing and
+ * accepts NULL buffers. */
 ptenc_status ptenc_decode_run(ptenc_ctx* ctx, const void* d_q, const void* d_k, const void* d_v,
                               void* d_out, const uint8_t* d_active, int64_t n_steps, void* stream);
 

@@ -429,7 +429,9 @@ ptenc_status ptenc_apply_delta(ptenc_ctx* ctx, const void* d_x, const void* d_At
 
 ptenc_status ptenc_decode_run(ptenc_ctx* ctx, const void* d_q, const void* d_k, const void* d_v, void* d_out,
                               const uint8_t* d_active, int64_t n_steps, void* stream) {
-  if (!ctx || !d_q || !d_k || !d_v || !d_out || n_steps < 0) return PTENC_ERR_INVALID_ARG;
+  if (!ctx || n_steps < 0) return PTENC_ERR_INVALID_ARG;
+  if (n_steps == 0) return PTENC_OK;          // nothing to do: the buffers may be empty (NULL)
+  if (!d_q || !d_k || !d_v || !d_out) return PTENC_ERR_INVALID_ARG;
   const ptenc_config& c = ctx->cfg;
   const size_t es = elem_bytes(c.dtype);
   const size_t qb = (size_t)c.batch * c.n_q_heads * c.head_dim * es;

@@ -71,6 +71,41 @@ def test_degenerate_window_and_chunk_sizes(W, C):
     H.run_both(wl, wl.steps, splits=2 if W >= 64 else 1)
 
 
+@pytest.mark.parametrize("name,d", [("tiny_f32", 256), ("tiny_f32", 8), ("tiny_f32", 37), ("qwen3b", 80), ("qwen3b", 256)])
+def test_head_dims_other_than_128_take_the_plain_path(name, d):
+    # the largest head_dim the library takes, the smallest, odd ones; bf16 and fp32
+    wl = I.WORKLOADS[name].replace(batch=2, n_q_heads=4, n_kv_heads=2, head_dim=d, window=40, chunk=12, steps=70)
+    layer, _ = H.run_both(wl, wl.steps, check_every=3)
+    assert layer.plan()[0] == 0
+
+
+def test_empty_lists_zero_steps_and_all_inactive_steps_change_nothing():
+    from paper_2602_16839_amd import ptenc
+    for name in ("qwen7b", "tiny_f32"):
+        wl = small(name, batch=3, window=64, chunk=16, steps=20) if name == "qwen7b" else small(name, batch=3, window=24, chunk=8, steps=20)
+        enc = I.encoder_params(wl)
+        layer = H.make_layer(wl, enc)
+        q, k, v = (x.cuda() for x in I.qkv_steps(wl, 0, 6))
+        layer.run(q[:5], k[:5], v[:5])
+        before = (layer.counters(), layer.get_state().copy(), [t.clone() for t in layer.gather_window()])
+        # a run of zero steps
+        ptenc.ptenc_decode_run(layer.ctx, q[:0], k[:0], v[:0], q[:0].clone(), None, 0)
+        # an empty rollout list: nothing is launched, pointers may be anything
+        ids = torch.zeros(0, dtype=torch.int32, device="cuda")
+        layer.step_ids(q[5][:0].contiguous(), k[5][:0].contiguous(), v[5][:0].contiguous(), ids)
+        layer.run_ids(q[5][:0].contiguous(), k[5][:0].contiguous(), v[5][:0].contiguous(), ids, np.array([0, 0, 0]))
+        # a step in which no rollout is active: zeros out, nothing moves
+        off = torch.zeros(wl.batch, dtype=torch.uint8, device="cuda")
+        out = layer.step(q[5], k[5], v[5], active=off)
+        assert (out == 0).all()
+        ln, base = layer.counters()
+        assert np.array_equal(ln, before[0][0]) and np.array_equal(base, before[0][1])
+        assert np.array_equal(layer.get_state(), before[1])
+        Kw, Vw = layer.gather_window()
+        assert torch.equal(Kw, before[2][0]) and torch.equal(Vw, before[2][1])
+        assert layer.poll_error() == 0
+
+
 @pytest.mark.parametrize("hq,hkv", [(16, 1), (4, 4), (32, 8)])
 def test_group_sizes_1_4_16(hq, hkv):
     wl = small("llama8b", batch=2, n_q_heads=hq, n_kv_heads=hkv, window=64, chunk=16, steps=100)
