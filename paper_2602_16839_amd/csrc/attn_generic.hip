@@ -5,7 +5,14 @@
 // (rollout, query head, window split): a thread scores one token, the block reduces max and sum,
 // then one thread per output column accumulates the values.  With several splits the partial
 // results (m, l, unnormalised out; base-2 domain) are merged by combine_kernel.
-#include "ptenc_internal.h"
+//
+// FUSED: the whole decode step of small problems in one launch.  The attention workgroups work out
+// for themselves what the step's eviction and append leave (the same counter arithmetic), take the
+// new token straight from the step's inputs instead of the cache, and one extra workgroup per rollout
+// at the end of the grid runs the prologue (evict-and-encode, append, counters).  Nobody reads what
+// that workgroup writes: the evicted slots are outside every attention range, the new token's slot
+// is never read from the cache in this launch, and the counters go to the other buffer pair.
+#include "pt_prologue.h"
 
 namespace {
 
@@ -25,15 +32,36 @@ __device__ inline float block_reduce(float v, float* red, bool is_max) {
   return r;
 }
 
-template <typename T>
+struct AttnSmem {
+  float qs[256];
+  float ps[kThreads];
+  int slots[kThreads];
+  float red[kThreads / 64];
+};
+
+template <bool FUSED> union StepSmem { AttnSmem a; };
+template <> union StepSmem<true> { AttnSmem a; EncSmem e; };
+
+template <typename T, bool FUSED>
 __global__ __launch_bounds__(kThreads) void attn_generic_kernel(PtDev c, const T* __restrict__ q,
                                                                T* __restrict__ out,
                                                                const uint8_t* __restrict__ active,
-                                                               const int* __restrict__ ids) {
-  __shared__ float qs[256];
-  __shared__ float ps[kThreads];
-  __shared__ int slots[kThreads];
-  __shared__ float red[kThreads / 64];
+                                                               const int* __restrict__ ids, int n_rows,
+                                                               const T* __restrict__ knew,
+                                                               const T* __restrict__ vnew) {
+  // the two roles of a fused launch never meet in one workgroup: one block of LDS serves both
+  __shared__ StepSmem<FUSED> smu;
+  float* qs = smu.a.qs;
+  float* ps = smu.a.ps;
+  int* slots = smu.a.slots;
+  float* red = smu.a.red;
+  if constexpr (FUSED) {
+    if ((int)blockIdx.x >= n_rows * c.Hq) {      // the prologue of rollout row blockIdx.x - n_rows * H_q
+      if (blockIdx.y == 0)
+        pt_step_prologue<T>(smu.e, c, blockIdx.x - n_rows * c.Hq, 1, 1, knew, vnew, active, (T*)nullptr, ids, 0);
+      return;
+    }
+  }
   // bh = (row of q and out, query head); the row's rollout is b = row, or ids[row]
   const int bh = blockIdx.x, j_row = bh / c.Hq, h = bh - j_row * c.Hq, split = blockIdx.y, t = threadIdx.x;
   float* po = c.partial + ((size_t)bh * c.n_splits + split) * (c.d + 2);
@@ -41,7 +69,14 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(PtDev c, const T
   bool bad = false;
   if (ids) { b = ids[j_row]; bad = (unsigned)b >= (unsigned)c.B; if (bad) b = 0; }
   const bool act = !bad && (!active || active[b]);
-  const long long len = c.len[b], base = c.base[b];
+  long long len = c.len[b], base = c.base[b];
+  bool newest = false;          // FUSED: the last live position is this step's token, still only in knew / vnew
+  if constexpr (FUSED) {
+    if (act) {
+      if (len - base == c.Wr) base += c.C;                 // this step's eviction
+      if (len - base < c.Wr) { newest = true; len += 1; }  // this step's append
+    }
+  }
   // logical order: the P question tokens (slots 0 .. P-1), then the live ring positions
   const int P = act ? c.n_prompt[b] : 0;
   const int n_live = act ? P + (int)(len - base) : 0;
@@ -53,6 +88,12 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(PtDev c, const T
   for (int i = t; i < c.d; i += kThreads) qs[i] = pt_ld<T>(q + (size_t)bh * c.d + i);
   __syncthreads();
 
+  // values: all threads take part, thread t = (token part, column): part p adds tokens p, p + parts, ...
+  const int parts = kThreads / c.d > 0 ? kThreads / c.d : 1;
+  const int vcol = t % c.d, vpart = t / c.d;
+  const bool vwork = vpart < parts && t < parts * c.d;
+  const size_t new_off = FUSED ? ((size_t)j_row * c.Hkv + h / c.group) * c.d : 0;
+
   float m_run = -INFINITY, l_run = 0.f, acc = 0.f;
   for (int jb = j0; jb < j1; jb += kThreads) {
     const int j = jb + t;
@@ -61,9 +102,24 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(PtDev c, const T
     if (j < j1) {
       slot = j;
       if (j >= P) { slot = s0 + (j - P); if (slot >= c.Wr) slot -= c.Wr; slot += c.n_sink; }
-      float dot = 0.f;
-      for (int i = 0; i < c.d; ++i) dot = fmaf(qs[i], pt_ld<T>(slab + pt_k_off(c.tiled, c.W, c.d, slot, i)), dot);
-      s = dot * c.scale_log2;
+      const bool from_input = FUSED && newest && j == n_live - 1;
+      if (from_input) slot = -1;
+      float d0 = 0.f, d1 = 0.f, d2 = 0.f, d3 = 0.f;
+      if (from_input || !c.tiled) {
+        // a contiguous row: four independent chains, loads free to run ahead
+        const T* kr = from_input ? knew + new_off : slab + (size_t)slot * c.d;
+        int i = 0;
+        for (; i + 4 <= c.d; i += 4) {
+          d0 = fmaf(qs[i], pt_ld<T>(kr + i), d0);
+          d1 = fmaf(qs[i + 1], pt_ld<T>(kr + i + 1), d1);
+          d2 = fmaf(qs[i + 2], pt_ld<T>(kr + i + 2), d2);
+          d3 = fmaf(qs[i + 3], pt_ld<T>(kr + i + 3), d3);
+        }
+        for (; i < c.d; ++i) d0 = fmaf(qs[i], pt_ld<T>(kr + i), d0);
+      } else {
+        for (int i = 0; i < c.d; ++i) d0 = fmaf(qs[i], pt_ld<T>(slab + pt_k_off(1, c.W, c.d, slot, i)), d0);
+      }
+      s = ((d0 + d1) + (d2 + d3)) * c.scale_log2;
     }
     slots[t] = slot;
     const float mx = block_reduce(s, red, true);
@@ -73,14 +129,25 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(PtDev c, const T
     const float sm = block_reduce(p, red, false);   // has barriers: ps/slots visible afterwards
     const float alpha = exp2f(m_run - m_new);
     l_run = l_run * alpha + sm;
-    if (t < c.d) {
+    if (vwork) {
       acc *= alpha;
       const int n = min(kThreads, j1 - jb);
-      for (int x = 0; x < n; ++x)
-        acc = fmaf(ps[x], pt_ld<T>(slab + pt_v_off(c.tiled, c.W, c.d, slots[x], t)), acc);
+      for (int x = vpart; x < n; x += parts) {
+        const int sl = slots[x];
+        const float vv = (FUSED && sl < 0) ? pt_ld<T>(vnew + new_off + vcol)
+                                           : pt_ld<T>(slab + pt_v_off(c.tiled, c.W, c.d, sl, vcol));
+        acc = fmaf(ps[x], vv, acc);
+      }
     }
     m_run = m_new;
     __syncthreads();
+  }
+  // the token parts of a column, added in part order by the column's first thread
+  ps[t] = vwork ? acc : 0.f;
+  __syncthreads();
+  if (t < c.d) {
+    acc = 0.f;
+    for (int pp = 0; pp < parts; ++pp) acc += ps[pp * c.d + t];
   }
   if (c.n_splits == 1) {
     // nothing to merge: normalise and write the output row here
@@ -132,18 +199,42 @@ __global__ void combine_kernel(PtDev c, T* __restrict__ out, const uint8_t* __re
 
 hipError_t pt_launch_attn_generic(const PtDev& c, const void* q, void* out, const uint8_t* active,
                                   const int* ids, int n_rows, hipStream_t s) {
-  const int rows = (ids ? n_rows : c.B) * c.Hq;
+  const int nr = ids ? n_rows : c.B, rows = nr * c.Hq;
   dim3 grid(rows, c.n_splits);
   const int cthreads = c.d <= 64 ? 64 : 128;
   if (c.dtype == PTENC_F32) {
-    hipLaunchKernelGGL(attn_generic_kernel<float>, grid, dim3(kThreads), 0, s, c, (const float*)q, (float*)out, active, ids);
+    hipLaunchKernelGGL((attn_generic_kernel<float, false>), grid, dim3(kThreads), 0, s, c, (const float*)q, (float*)out, active,
+                       ids, nr, (const float*)nullptr, (const float*)nullptr);
     if (c.n_splits > 1)
       hipLaunchKernelGGL(combine_kernel<float>, dim3(rows), dim3(cthreads), 0, s, c, (float*)out, active, ids);
   } else {
-    hipLaunchKernelGGL(attn_generic_kernel<uint16_t>, grid, dim3(kThreads), 0, s, c, (const uint16_t*)q, (uint16_t*)out,
-                       active, ids);
+    hipLaunchKernelGGL((attn_generic_kernel<uint16_t, false>), grid, dim3(kThreads), 0, s, c, (const uint16_t*)q,
+                       (uint16_t*)out, active, ids, nr, (const uint16_t*)nullptr, (const uint16_t*)nullptr);
     if (c.n_splits > 1)
       hipLaunchKernelGGL(combine_kernel<uint16_t>, dim3(rows), dim3(cthreads), 0, s, c, (uint16_t*)out, active, ids);
   }
+  return hipGetLastError();
+}
+
+// The whole plain-ALU decode step (evict-and-encode, append, attention) in one launch; counters go to
+// the other buffer pair (the caller rotates).  Full batch only.  With several splits the combine
+// follows as a second launch (pt_launch_combine).
+hipError_t pt_launch_step_generic(const PtDev& c, const void* q, const void* k, const void* v, void* out,
+                                  const uint8_t* active, hipStream_t s) {
+  const int rows = c.B * c.Hq;
+  dim3 grid(rows + c.B, c.n_splits);
+  if (c.dtype == PTENC_F32)
+    hipLaunchKernelGGL((attn_generic_kernel<float, true>), grid, dim3(kThreads), 0, s, c, (const float*)q, (float*)out, active,
+                       (const int*)nullptr, c.B, (const float*)k, (const float*)v);
+  else
+    hipLaunchKernelGGL((attn_generic_kernel<uint16_t, true>), grid, dim3(kThreads), 0, s, c, (const uint16_t*)q,
+                       (uint16_t*)out, active, (const int*)nullptr, c.B, (const uint16_t*)k, (const uint16_t*)v);
+  return hipGetLastError();
+}
+
+hipError_t pt_launch_combine(const PtDev& c, void* out, const uint8_t* active, hipStream_t s) {
+  const int rows = c.B * c.Hq, cthreads = c.d <= 64 ? 64 : 128;
+  if (c.dtype == PTENC_F32) hipLaunchKernelGGL(combine_kernel<float>, dim3(rows), dim3(cthreads), 0, s, c, (float*)out, active, (const int*)nullptr);
+  else hipLaunchKernelGGL(combine_kernel<uint16_t>, dim3(rows), dim3(cthreads), 0, s, c, (uint16_t*)out, active, (const int*)nullptr);
   return hipGetLastError();
 }

@@ -8,25 +8,11 @@
 // The encoder here is the general one (any dtype, layout, G and r up to 64).  It evaluates
 // S' = (Q_a (K_e W^a_K)^T)(V_e W^a_V) (Our Approach, the Delta-W equation) in the paper's
 // association, 32 tokens at a time, with fp32 accumulation.
-#include "pt_encode_alu.h"
+#include "pt_prologue.h"
 
 namespace {
 
 constexpr int kThreads = kEncThreads;
-
-// ---- token sources ---------------------------------------------------------------------------
-template <typename T>
-struct CacheChunk {   // the C oldest live thinking tokens of rollout b, logical order
-  const T* cache; int b, Hkv, d, W, tiled, s0, n_sink, Wr;
-  __device__ float get(int which, int tok, int kk) const {
-    int slot = s0 + tok; if (slot >= Wr) slot -= Wr;
-    slot += n_sink;
-    const int h = kk / d, i = kk - h * d;
-    const T* slab = cache + (size_t)(b * Hkv + h) * pt_slab_elems(W, d);
-    const size_t off = which == 0 ? pt_k_off(tiled, W, d, slot, i) : pt_v_off(tiled, W, d, slot, i);
-    return pt_ld<T>(slab + off);
-  }
-};
 
 template <typename T>
 struct GlobalTokens { // k_g, v_g: row-major [G, d_kv]
@@ -45,55 +31,7 @@ __global__ __launch_bounds__(kThreads) void step_prologue_kernel(PtDev c, int do
                                                                 T* dbg_chunk, const int* __restrict__ ids,
                                                                 int in_place) {
   __shared__ EncSmem sm;
-  const int j_row = blockIdx.x, t = threadIdx.x;   // row of k / v; rollout b = j_row, or ids[j_row]
-  int b = j_row;
-  if (ids) {
-    b = ids[j_row];
-    if ((unsigned)b >= (unsigned)c.B) {
-      if (t == 0) atomicOr(c.err, PTENC_DEVERR_BAD_ID);
-      return;
-    }
-  }
-  const long long len = c.len[b];
-  long long base = c.base[b];
-  long long len1 = len;
-  const int dkv = c.Hkv * c.d;
-  T* cache = (T*)c.cache;
-  const bool act = !active || active[b];
-
-  if (act && do_evict && len - base == c.Wr) {
-    CacheChunk<T> src{cache, b, c.Hkv, c.d, c.W, c.tiled, (int)(base % c.Wr), c.n_sink, c.Wr};
-    float sacc[16];
-    T* dbg = dbg_chunk ? dbg_chunk + (size_t)b * 2 * c.C * dkv : nullptr;
-    encode_chunk<T>(sm, src, c.C, dkv, c.G, c.r, c.Qa, (const T*)c.WaK, (const T*)c.WaV, dbg, sacc);
-    // S <- Normalize(S + S')   (Our Approach, the update rule)
-    pt_state_update<kThreads>(c, b, sacc, &sm.Ws[0][0], sm.tail.red);
-    base += c.C;
-    __syncthreads();   // every read of the evicted slots is done before the append below
-  }
-
-  if (act && do_append) {
-    if (len - base >= c.Wr) {
-      if (t == 0) atomicOr(c.err, PTENC_DEVERR_APPEND_FULL);
-    } else {
-      const int slot = c.n_sink + (int)(len % c.Wr);
-      for (int idx = t; idx < dkv; idx += kThreads) {
-        const int h = idx / c.d, i = idx - h * c.d;
-        T* slab = cache + (size_t)(b * c.Hkv + h) * pt_slab_elems(c.W, c.d);
-        const size_t src = (size_t)j_row * dkv + idx;
-        slab[pt_k_off(c.tiled, c.W, c.d, slot, i)] = knew[src];
-        slab[pt_v_off(c.tiled, c.W, c.d, slot, i)] = vnew[src];
-      }
-      len1 = len + 1;
-    }
-  }
-  // counters go to the other buffer, for every rollout, changed or not; with a compact list (which
-  // would leave the unlisted rollouts out) they are written in place: this workgroup is the only
-  // one that touches rollout b in this kernel
-  if (t == 0) {
-    if (in_place) { c.len[b] = len1; c.base[b] = base; }
-    else { c.len_nx[b] = len1; c.base_nx[b] = base; }
-  }
+  pt_step_prologue<T>(sm, c, blockIdx.x, do_evict, do_append, knew, vnew, active, dbg_chunk, ids, in_place);
 }
 
 // ---- reset / gather -----------------------------------------------------------------------------

@@ -368,6 +368,13 @@ ptenc_status ptenc_decode_step(ptenc_ctx* ctx, const void* d_q, const void* d_k,
     return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, true, true, true, d_q, d_k,
                                                d_v, d_out, d_active, nullptr, nullptr, 0, ctx->opt_in_place != 0, S(stream)));
   }
+  // small problems are bound by launches: the whole plain step as one (needs the two counter buffers:
+  // its attention workgroups read the pair the prologue workgroup does not write)
+  if (!ctx->opt_in_place && (long)ctx->cfg.batch * ctx->cfg.n_q_heads * ctx->dev.n_splits <= 2048) {
+    if (advanced(ctx, pt_launch_step_generic(ctx->dev, d_q, d_k, d_v, d_out, d_active, S(stream))) != PTENC_OK)
+      return PTENC_ERR_HIP;
+    return ctx->dev.n_splits > 1 ? hip_status(pt_launch_combine(ctx->dev, d_out, d_active, S(stream))) : PTENC_OK;
+  }
   if (advanced(ctx, pt_launch_step_prologue(ctx->dev, true, true, d_k, d_v, d_active, nullptr, nullptr, 0,
                                             ctx->opt_in_place != 0, S(stream))) != PTENC_OK)
     return PTENC_ERR_HIP;

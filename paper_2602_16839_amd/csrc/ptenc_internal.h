@@ -158,6 +158,9 @@ hipError_t pt_launch_encoder_init(const PtDev& c, const void* qg, const void* Wa
                                   const void* vg, hipStream_t s);
 hipError_t pt_launch_attn_generic(const PtDev& c, const void* q, void* out, const uint8_t* active,
                                   const int* ids, int n_rows, hipStream_t s);
+hipError_t pt_launch_step_generic(const PtDev& c, const void* q, const void* k, const void* v, void* out,
+                                  const uint8_t* active, hipStream_t s);
+hipError_t pt_launch_combine(const PtDev& c, void* out, const uint8_t* active, hipStream_t s);
 hipError_t pt_launch_apply_delta(const PtDev& c, const void* x, const void* At, const void* Bt, void* y, int d_in,
                                  int d_out, const uint8_t* active, const int* ids, int n_rows, hipStream_t s);
 hipError_t pt_launch_pack_weights(const PtDev& c, hipStream_t s);
