@@ -630,10 +630,11 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
       if (M != -INFINITY) {
 #pragma unroll
         for (int w = 0; w < kWaves; ++w) {
-          const float fw = exp2f(sm.merge.m[w][qn] - M);
+          const float fw = __builtin_amdgcn_exp2f(sm.merge.m[w][qn] - M);
           L = fmaf(fw, sm.merge.l[w][qn], L);
+          const f32x4 lo = *(const f32x4*)&sm.merge.o[w][qn][part * 8], hi = *(const f32x4*)&sm.merge.o[w][qn][part * 8 + 4];
 #pragma unroll
-          for (int x = 0; x < 8; ++x) o[x] = fmaf(fw, sm.merge.o[w][qn][part * 8 + x], o[x]);
+          for (int x = 0; x < 4; ++x) { o[x] = fmaf(fw, lo[x], o[x]); o[4 + x] = fmaf(fw, hi[x], o[4 + x]); }
         }
       }
     }
