@@ -396,8 +396,19 @@ def main() -> int:
             ptenc.ptenc_util_copy(dst, src, nbytes, 2048)
             ptenc.ptenc_util_stream_read(src, nbytes, sink, 2048)
         torch.cuda.synchronize()
+        def gbs(fn, iters=20):
+            torch.cuda.synchronize()
+            c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            c0.record()
+            for _ in range(iters):
+                fn()
+            c1.record()
+            torch.cuda.synchronize()
+            return nbytes * iters / (c0.elapsed_time(c1) * 1e-3) / 1e9
         res["calibration"] = {"copy_kernel_bytes_read": nbytes, "copy_kernel_bytes_written": nbytes,
-                              "read_kernel_bytes_read": nbytes, "launches_each": 5}
+                              "read_kernel_bytes_read": nbytes, "launches_each": 5,
+                              "stream_read_GB_per_s": gbs(lambda: ptenc.ptenc_util_stream_read(src, nbytes, sink, 2048)),
+                              "stream_read_nontemporal_GB_per_s": gbs(lambda: ptenc.ptenc_util_stream_read_nt(src, nbytes, sink, 2048))}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(res), flush=True)

@@ -319,6 +319,8 @@ ptenc_status ptenc_stack_graph_launch(ptenc_stack* stack, void* stream);
  * measure the HBM rate a kernel with no arithmetic reaches, and scale the profiler's byte
  * counters.  Pointers are device pointers, 16-byte aligned. */
 ptenc_status ptenc_util_stream_read(const void* d_src, size_t bytes, void* d_sink, int32_t n_blocks, void* stream);
+/* The same read with non-temporal loads, as the decode kernel streams K and V. */
+ptenc_status ptenc_util_stream_read_nt(const void* d_src, size_t bytes, void* d_sink, int32_t n_blocks, void* stream);
 ptenc_status ptenc_util_copy(void* d_dst, const void* d_src, size_t bytes, int32_t n_blocks, void* stream);
 
 const char* ptenc_status_string(ptenc_status s);

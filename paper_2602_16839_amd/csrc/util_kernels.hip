@@ -9,6 +9,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 // Every wavefront reads whole 16 KiB units (16 loads of 16 bytes per lane), units dealt round-robin
 // to the wavefronts of the grid: the same access shape as the attention kernel's group walk.
+template <bool NT>
 __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restrict__ src, size_t n_units,
                                                           uint32_t* __restrict__ sink) {
   const int lane = threadIdx.x & 63;
@@ -19,7 +20,7 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restric
     const u32x4* p = src + u * 1024 + lane;
     u32x4 r[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) r[i] = p[i * 64];
+    for (int i = 0; i < 16; ++i) r[i] = NT ? __builtin_nontemporal_load(p + i * 64) : p[i * 64];
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc ^= r[i];
   }
@@ -39,7 +40,14 @@ extern "C" {
 
 ptenc_status ptenc_util_stream_read(const void* d_src, size_t bytes, void* d_sink, int32_t n_blocks, void* stream) {
   if (!d_src || !d_sink || n_blocks < 1 || bytes < 16384 || ((uintptr_t)d_src & 15)) return PTENC_ERR_INVALID_ARG;
-  hipLaunchKernelGGL(stream_read_kernel, dim3(n_blocks), dim3(256), 0, (hipStream_t)stream, (const u32x4*)d_src,
+  hipLaunchKernelGGL(stream_read_kernel<false>, dim3(n_blocks), dim3(256), 0, (hipStream_t)stream, (const u32x4*)d_src,
+                     bytes / 16384, (uint32_t*)d_sink);
+  return hipGetLastError() == hipSuccess ? PTENC_OK : PTENC_ERR_HIP;
+}
+
+ptenc_status ptenc_util_stream_read_nt(const void* d_src, size_t bytes, void* d_sink, int32_t n_blocks, void* stream) {
+  if (!d_src || !d_sink || n_blocks < 1 || bytes < 16384 || ((uintptr_t)d_src & 15)) return PTENC_ERR_INVALID_ARG;
+  hipLaunchKernelGGL(stream_read_kernel<true>, dim3(n_blocks), dim3(256), 0, (hipStream_t)stream, (const u32x4*)d_src,
                      bytes / 16384, (uint32_t*)d_sink);
   return hipGetLastError() == hipSuccess ? PTENC_OK : PTENC_ERR_HIP;
 }

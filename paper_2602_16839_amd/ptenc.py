@@ -30,7 +30,7 @@ EXPORTS = [
     "ptenc_reset", "ptenc_cache_append", "ptenc_decode_attn", "ptenc_evict_encode", "ptenc_decode_step",
     "ptenc_decode_run", "ptenc_get_counters", "ptenc_set_counters", "ptenc_get_state", "ptenc_set_state",
     "ptenc_get_encoder_state", "ptenc_gather_window", "ptenc_cache_offset", "ptenc_poll_error",
-    "ptenc_get_plan", "ptenc_status_string", "ptenc_util_stream_read", "ptenc_util_copy",
+    "ptenc_get_plan", "ptenc_status_string", "ptenc_util_stream_read", "ptenc_util_stream_read_nt", "ptenc_util_copy",
     "ptenc_prefill", "ptenc_get_prompt_len", "ptenc_decode_step_ids", "ptenc_decode_run_ids",
     "ptenc_apply_delta",
     "ptenc_get_scores", "ptenc_set_scores", "ptenc_get_victims",
@@ -89,6 +89,7 @@ def lib() -> C.CDLL:
             "ptenc_poll_error": [vp, P(i32), vp],
             "ptenc_get_plan": [vp, P(i32), P(i32), P(i32)],
             "ptenc_util_stream_read": [vp, sz, vp, i32, vp],
+            "ptenc_util_stream_read_nt": [vp, sz, vp, i32, vp],
             "ptenc_util_copy": [vp, vp, sz, i32, vp],
             "ptenc_prefill": [vp, vp, vp, vp, i32, vp],
             "ptenc_get_prompt_len": [vp, vp, vp],
@@ -283,6 +284,10 @@ def ptenc_get_plan(ctx):
 
 def ptenc_util_stream_read(src, nbytes: int, sink, n_blocks: int):
     _check(lib().ptenc_util_stream_read(_ptr(src), nbytes, _ptr(sink), n_blocks, _stream()), "ptenc_util_stream_read")
+
+
+def ptenc_util_stream_read_nt(src, nbytes: int, sink, n_blocks: int):
+    _check(lib().ptenc_util_stream_read_nt(_ptr(src), nbytes, _ptr(sink), n_blocks, _stream()), "ptenc_util_stream_read_nt")
 
 
 def ptenc_util_copy(dst, src, nbytes: int, n_blocks: int):
