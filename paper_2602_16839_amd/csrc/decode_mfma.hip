@@ -249,6 +249,14 @@ __device__ inline void ld_agent2(const float* p, float& a, float& b) {
   b = __uint_as_float((unsigned)(u >> 32));
 }
 
+// A workgroup-uniform value that no workgroup of this launch writes (counters as the step finds them,
+// masks, id lists): read through the constant address space, i.e. with a scalar load, which comes back
+// sooner than a vector load and costs no vector register.  (Loads only: nothing is ever written that way.)
+template <typename T>
+__device__ inline T ld_uniform(const T* p) {
+  return *(const __attribute__((address_space(4))) T*)(uintptr_t)p;
+}
+
 struct StepArgs {
   const uint16_t* q;       // [B, H_q, 128]
   uint16_t* out;           // [B, H_q, 128]
@@ -397,7 +405,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
   const int j_row = blockIdx.x / c.Hkv, hkv = blockIdx.x - j_row * c.Hkv, split = blockIdx.y;
   int b = j_row;
   if (a.ids) {
-    b = a.ids[j_row];
+    b = ld_uniform(a.ids + j_row);
     if ((unsigned)b >= (unsigned)c.B) {            // never index with a bad id: flag it and leave
       if (threadIdx.x == 0 && hkv == 0 && split == 0) atomicOr(c.err, PTENC_DEVERR_BAD_ID);
       return;
@@ -409,10 +417,10 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
   const int ns = c.n_splits;   // window splits
   const int n = lane & 15, kgrp = lane >> 4;
   const int g = c.group;
-  const bool act = !a.active || a.active[b];
+  const bool act = !a.active || ld_uniform(a.active + b);
 
   // counters as the step finds them, and as it leaves them
-  const long long len0 = c.len[b], base0 = c.base[b];
+  const long long len0 = ld_uniform(c.len + b), base0 = ld_uniform(c.base + b);
   const bool evicting = act && a.do_evict && (len0 - base0 == c.Wr);
   const long long base1 = base0 + (evicting ? c.C : 0);
   const bool append_full = act && a.do_append && (len0 - base1 >= c.Wr);
@@ -421,7 +429,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
 
   // what this step attends over, as a walk over 32-slot groups: first the groups of the question
   // tokens (slots 0 .. P-1), then the ring of thinking tokens from its oldest live slot
-  const int P = act ? c.n_prompt[b] : 0;
+  const int P = act ? ld_uniform(c.n_prompt + b) : 0;
   const int n_live = act ? (int)(len1 - base1) : 0;
   const int s0 = (int)(base1 % c.Wr);            // ring-relative slot of the oldest live position
   const int g0 = s0 >> 5, off0 = s0 & 31;
@@ -521,7 +529,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
         // (saved by the step that left len == len0, in the buffer of that parity; the addresses are valid
         // whether or not anything waits to be folded)
         mass_slab = c.mass + (size_t)slab * c.W;
-        const long long tag = c.mtag[slab];
+        const long long tag = ld_uniform(c.mtag + slab);
         const int par = (int)(len0 & 1), hl = (n >= 8 && n - 8 < g) ? n - 8 : 0;
         const uint16_t* qb = c.qprev + (((size_t)par * c.B + b) * c.Hq + hkv * g + hl) * 128;
         const float* mlb = c.mlprev + (((size_t)par * c.B + b) * c.Hq + hkv * g + hl) * 2;
