@@ -431,7 +431,14 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
   // tokens (slots 0 .. P-1), then the ring of thinking tokens from its oldest live slot
   const int P = act ? ld_uniform(c.n_prompt + b) : 0;
   const int n_live = act ? (int)(len1 - base1) : 0;
-  const int s0 = (int)(base1 % c.Wr);            // ring-relative slot of the oldest live position
+  // ring-relative slots from ONE division (64-bit only when a counter has outgrown 32 bits; the walk
+  // cannot start before these are known): the oldest position before this step's eviction, the oldest
+  // live one after it, and the one the new token takes
+  const int s0e = ((unsigned long long)base0 >> 32) == 0 ? (int)((uint32_t)base0 % (uint32_t)c.Wr) : (int)(base0 % c.Wr);
+  int s0 = s0e + (evicting ? c.C : 0);
+  if (s0 >= c.Wr) s0 -= c.Wr;
+  int s_new = s0 + (int)(len0 - base1);
+  if (s_new >= c.Wr) s_new -= c.Wr;
   const int g0 = s0 >> 5, off0 = s0 & 31;
   const int NG = c.Wr >> 5, gs = c.n_sink >> 5;
   const int n_sink_vis = (P + PT_GROUP_TOKENS - 1) >> 5;
@@ -445,7 +452,6 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
 
   if (owner && (evicting || appending)) {
     if (evicting) {
-      const int s0e = (int)(base0 % c.Wr);  // ring-relative slot of the oldest token of the chunk
       encode_head_share(c, sm, slab_p, slab, hkv, s0e, lane, wave);
       if (a.dbg_chunk) {
         const int dkv = c.Hkv * 128;
@@ -468,9 +474,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
       Op kp[4];
       uint16_t vp[8];
       load_newest(kp, vp, a.knew, a.vnew, ((size_t)j_row * c.Hkv + hkv) * 128, n, kgrp);
-      store_newest((uint16_t*)slab_p, c.W, c.n_sink + (int)(len0 % c.Wr), kp, vp, n, kgrp);
+      store_newest((uint16_t*)slab_p, c.W, c.n_sink + s_new, kp, vp, n, kgrp);
       if (c.scored && lane == 0) {            // a new token starts with no score
-        const int slot = c.n_sink + (int)(len0 % c.Wr);
+        const int slot = c.n_sink + s_new;
         c.mass[(size_t)slab * c.W + slot] = 0.f;
         if (hkv == 0) c.pos[(size_t)b * c.W + slot] = len0;
       }
@@ -487,7 +493,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
 
     if (v0 < v1) {
       const bool patch = appending && owner;       // this workgroup's range ends with the new token
-      const int p_visit = n_visits - 1, p_tl = (int)(len0 % c.Wr) & 31;
+      const int p_visit = n_visits - 1, p_tl = s_new & 31;
       Op kp[4];
       uint16_t vp[8];
       if (patch) load_newest(kp, vp, a.knew, a.vnew, ((size_t)j_row * c.Hkv + hkv) * 128, n, kgrp);
@@ -601,7 +607,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
       // the store of the new token rides behind the walk: its inputs arrived long ago, and the
       // chunk of an evicting step was read before anything could overwrite its oldest slot
       if (patch && wave == 0)
-        store_newest((uint16_t*)slab_p, c.W, c.n_sink + (int)(len0 % c.Wr), kp, vp, n, kgrp);
+        store_newest((uint16_t*)slab_p, c.W, c.n_sink + s_new, kp, vp, n, kgrp);
       if constexpr (MASS) {
         if (patch && wave == 0) {
           // this step's queries wait for the next step, in the buffer of the parity of the length it leaves
@@ -610,7 +616,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
 #pragma unroll
             for (int cc = 0; cc < 4; ++cc) qs[cc * 4 + kgrp] = qf[cc].u;
           }
-          if (hkv == 0 && lane == 0) c.pos[(size_t)b * c.W + c.n_sink + (int)(len0 % c.Wr)] = len0;
+          if (hkv == 0 && lane == 0) c.pos[(size_t)b * c.W + c.n_sink + s_new] = len0;
         }
       }
     }
@@ -751,7 +757,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
     if (tid == 0) sm_ticket = atomicAdd(c.tick_rollout + b, 1);
     __syncthreads();
     if (sm_ticket == c.Hkv * ns - 1) {
-      if (evicting) encode_finish(c, sm, b, (int)(base0 % c.Wr) & 31);
+      if (evicting) encode_finish(c, sm, b, s0e & 31);
       if constexpr (MASS) {
         if (will_select) {
           __threadfence();
