@@ -95,7 +95,7 @@ typedef enum {
 
 /* Which tokens leave when the sliding part of the cache is full.
  * SLIDING: the C oldest thinking tokens (Our Approach, "The selection of D during training").
- * SCORED:  importance-based token dropping (Ablation studies, "Integration with inference-time token
+ * SCORED:  importance-based token dropping (Ablation Study and Discussion, "Integration with inference-time token
  *          dropping strategy": the paper finds it more accurate but 37 % slower in rollouts and leaves an
  *          efficient integration open).  Here the score is the heavy-hitter one -- the attention
  *          probability a token has received, summed over decode steps and over all query heads -- and
@@ -271,7 +271,7 @@ ptenc_status ptenc_get_plan(ptenc_ctx* ctx, int32_t* attn_kernel, int32_t* n_spl
 
 /* ---- Multi-layer driver -------------------------------------------------------------------------
  * A stack is L contexts with one configuration -- the L attention layers of one model decoding the
- * same B rollouts (Experiment setup: the evaluated models are stacks of identical attention layers,
+ * same B rollouts (Experimental Setup, Models: the evaluated models are stacks of identical attention layers,
  * each with its own KV cache; the rollout stage pays the bounded-cache step once per layer and
  * token).  d_cache and d_state hold L consecutive per-layer slices of the sizes ptenc_query_sizes
  * reports (layer l starts at l times that size); d_scratch is ONE layer's scratch, shared, which is

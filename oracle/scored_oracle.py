@@ -5,7 +5,7 @@ the benchmark's CPU leg; shares nothing with the HIP path and imports nothing fr
 
 The paper keeps the sliding window for training and reports, as an ablation, that dropping
 tokens by importance instead of by age (H2O, PyramidKV, HeadKV) helps accuracy at a 37 % cost in
-rollout time, leaving an efficient integration as future work (Ablation studies, "Integration with
+rollout time, leaving an efficient integration as future work (Ablation Study and Discussion, "Integration with
 inference-time token dropping strategy").  It gives no algorithm of its own, so this file follows
 the published heavy-hitter rule (H2O: keep the tokens with the largest accumulated attention
 probability plus the most recent ones, drop the rest) with the readings below.  It is an

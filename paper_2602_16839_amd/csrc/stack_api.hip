@@ -3,7 +3,7 @@
 // either as L launches or as a replay of a HIP graph that holds them.
 //
 // Every layer keeps its own bounded cache, counters and context state (the paper's models have
-// one KV cache and one adapted projection per layer: Experiment setup, model descriptions); the
+// one KV cache and one adapted projection per layer: Experimental Setup, Models); the
 // layers of a step run one after another on one stream, so they share a single scratch buffer.
 #include <hip/hip_runtime.h>
 
