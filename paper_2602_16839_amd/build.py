@@ -37,7 +37,28 @@ def build(verbose: bool = True) -> str:
     if verbose and out.strip():
         print(out)
     os.replace(LIB_PATH + ".tmp", LIB_PATH)
+    build_c_smoke(verbose)
     return LIB_PATH
+
+
+C_SMOKE_SRC = os.path.join(ROOT, "tests", "c_abi", "abi_smoke.c")
+C_SMOKE_BIN = os.path.join(ROOT, "tests", "c_abi", "abi_smoke")
+
+
+def build_c_smoke(verbose: bool = True) -> str:
+    """A plain C program (gcc, no HIP compiler) that drives the library through include/ptenc.h."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c11", "-O2", "-Wall", "-D__HIP_PLATFORM_AMD__", "-I" + os.path.join(ROOT, "include"),
+           "-I" + os.path.join(rocm, "include"), C_SMOKE_SRC, "-o", C_SMOKE_BIN + ".tmp",
+           "-L" + PKG_DIR, "-lptenc", "-Wl,-rpath,$ORIGIN/../../paper_2602_16839_amd",
+           "-L" + os.path.join(rocm, "lib"), "-lamdhip64", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-lm"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("gcc failed:\n" + res.stdout)
+    os.replace(C_SMOKE_BIN + ".tmp", C_SMOKE_BIN)
+    return C_SMOKE_BIN
 
 
 if __name__ == "__main__":
