@@ -127,7 +127,20 @@ def test_with_only_the_oldest_chunk_eligible_outputs_equal_the_sliding_window_bi
     assert torch.equal(Ks[:, :, :n], Kp[:, :, :n]) and torch.equal(Vs[:, :, :n], Vp[:, :, :n])
 
 
-@pytest.mark.parametrize("W,C,n_recent,n_sink", [(96, 32, 24, 0), (160, 40, 0, 32), (128, 7, 100, 0), (64, 64, 0, 0)])
+def _random_selection_cases(n):
+    rng = np.random.default_rng(424242)
+    cases = []
+    for _ in range(n):
+        n_sink = int(rng.choice([0, 32, 64]))
+        ring = 32 * int(rng.integers(1, 7))
+        C = int(rng.integers(1, ring + 1))
+        n_recent = int(rng.integers(0, ring - C + 1))
+        cases.append((n_sink + ring, C, n_recent, n_sink))
+    return cases
+
+
+@pytest.mark.parametrize("W,C,n_recent,n_sink", [(96, 32, 24, 0), (160, 40, 0, 32), (128, 7, 100, 0), (64, 64, 0, 0)]
+                         + _random_selection_cases(12))
 def test_selection_on_injected_scores_is_bit_exact(W, C, n_recent, n_sink):
     # scores with few distinct values (plenty of ties), the same float32 numbers on both sides
     wl = small(batch=3, window=W, chunk=C, n_sink=n_sink, steps=W - n_sink + 6 * C - 1)    # ends one short of a full ring
@@ -158,7 +171,7 @@ def test_selection_on_injected_scores_is_bit_exact(W, C, n_recent, n_sink):
                 n = len(orc.win[b])
                 assert np.array_equal(ps[b, :n], orc.positions(b)), "ring order of rollout %d after step %d" % (b, t)
             n_checked += 1
-    assert n_checked >= 5
+    assert n_checked >= 4
     H.assert_close(layer.get_state(), orc.state(), H.S_ABS, H.S_REL, "state S")
     # what the cache holds is what the oracle's ring holds, token for token
     Kw, Vw = layer.gather_window()
