@@ -83,14 +83,42 @@ struct Acc {
   float m, l;      // running max (base-2 domain) and this lane's share of the running sum
 };
 
+// Importance scores (the ablation on token dropping strategies; accumulated attention probability is
+// the heavy-hitter score).  The probability every token received in the rollout's PREVIOUS step is
+// recomputed while this step streams the same keys, at no extra matrix work: with at most 8 query heads
+// per KV head, columns 8..15 of the score MFMA are free, and carry the previous step's queries (saved
+// by that step, with its softmax maximum and 1 / sum).  Lane (kgrp, n >= 8) then holds, in p[], head
+// n - 8's unnormalised probabilities of its 8 tokens; il = 1 / sum (0 in lanes that carry nothing).
+// The sum over heads is a sum over the 16 lanes of a row (four rotate-and-add steps); afterwards lane
+// (kgrp, n < 8) keeps the total of token tl = (n / 4) * 16 + 4 kgrp + n % 4.
+template <int CTRL>
+__device__ inline float row_ror_add(float v) {
+  return v + __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+__device__ inline void lagged_mass_park(const float p[8], float il, float* park_grp, int n, int kgrp) {
+  float mine = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    float v = p[e] * il;                 // 0 in the lanes of this step's own heads
+    v = row_ror_add<0x128>(v);           // row_ror:8
+    v = row_ror_add<0x124>(v);           // row_ror:4
+    v = row_ror_add<0x122>(v);           // row_ror:2
+    v = row_ror_add<0x121>(v);           // row_ror:1
+    mine = n == e ? v : mine;
+  }
+  if (n < 8) park_grp[(n >> 2) * 16 + 4 * kgrp + (n & 3)] = mine;
+}
+
 // jg = logical index of the group's first slot within its region (question tokens or ring walk),
 // n_live = number of live logical indices of that region.
 // MASS: lanes with `lag` set carry a query head of the rollout's PREVIOUS step in their column (see
 // the kernel): their running maximum is frozen at that step's final one, so p[] comes out as that
-// step's unnormalised probabilities, returned in p_out for the importance scores.
+// step's unnormalised probabilities, returned in p[], from which the importance scores are parked (park_grp: 32 floats of LDS, or null).
 template <bool MASS = false>
 __device__ inline void process_group(Frag& f, const Op q[4], Acc& a, int jg, int n_live,
-                                     float scale_log2, int kgrp, bool lag = false, float* p_out = nullptr) {
+                                     float scale_log2, int kgrp, bool lag = false, float il = 0.f,
+                                     float* park_grp = nullptr, int n = 0) {
   f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int c = 0; c < 4; ++c) {
@@ -136,8 +164,7 @@ __device__ inline void process_group(Frag& f, const Op q[4], Acc& a, int jg, int
 #pragma unroll
   for (int e = 0; e < 8; ++e) { p[e] = __builtin_amdgcn_exp2f(s[e] - m_use); psum += p[e]; }
   if constexpr (MASS) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) p_out[e] = p[e];
+    if (park_grp) lagged_mass_park(p, il, park_grp, n, kgrp);   // wave-uniform
   }
   a.l = a.l * alpha + psum;
   a.m = m_new;
@@ -152,44 +179,19 @@ __device__ inline void process_group(Frag& f, const Op q[4], Acc& a, int jg, int
   for (int i = 0; i < 8; ++i) a.o[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.v[i].h, pf.h, a.o[i], 0, 0, 0);
 }
 
-// Importance scores (the ablation on token dropping strategies; accumulated attention probability is
-// the heavy-hitter score).  The probability every token received in the rollout's PREVIOUS step is
-// recomputed while this step streams the same keys, at no extra matrix work: with at most 8 query heads
-// per KV head, columns 8..15 of the score MFMA are free, and carry the previous step's queries (saved
-// by that step, with its softmax maximum and 1 / sum).  Lane (kgrp, n >= 8) then holds, in p[], head
-// n - 8's unnormalised probabilities of its 8 tokens; il = 1 / sum (0 in lanes that carry nothing).
-// The sum over heads is a sum over the 16 lanes of a row (four rotate-and-add steps); afterwards lane
-// (kgrp, n < 8) keeps the total of token tl = (n / 4) * 16 + 4 kgrp + n % 4.
-template <int CTRL>
-__device__ inline float row_ror_add(float v) {
-  return v + __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xf, 0xf, true));
-}
-
-__device__ inline void lagged_mass_park(const float p[8], float il, float* park_grp, int n, int kgrp) {
-  float mine = 0.f;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    float v = p[e] * il;                 // 0 in the lanes of this step's own heads
-    v = row_ror_add<0x128>(v);           // row_ror:8
-    v = row_ror_add<0x124>(v);           // row_ror:4
-    v = row_ror_add<0x122>(v);           // row_ror:2
-    v = row_ror_add<0x121>(v);           // row_ror:1
-    mine = n == e ? v : mine;
-  }
-  if (n < 8) park_grp[(n >> 2) * 16 + 4 * kgrp + (n & 3)] = mine;
-}
-
-// kp[c] = this lane's 16 bytes of the new key (k-chunk c), vp[i] = new value column 16 i + (lane % 16).
-__device__ inline void load_newest(Op kp[4], uint16_t vp[8], const uint16_t* __restrict__ knew,
+// kp[c] = this lane's 16 bytes of the new key (k-chunk c); new value column 16 i + (lane % 16) is the
+// low (i even) or high (i odd) half of vp[i / 2]: four registers instead of eight.
+__device__ inline void load_newest(Op kp[4], uint32_t vp[4], const uint16_t* __restrict__ knew,
                                    const uint16_t* __restrict__ vnew, size_t src, int n, int kgrp) {
 #pragma unroll
   for (int cc = 0; cc < 4; ++cc) kp[cc].u = *(const u32x4*)(knew + src + (cc * 4 + kgrp) * 8);
 #pragma unroll
-  for (int i = 0; i < 8; ++i) vp[i] = vnew[src + 16 * i + n];
+  for (int i = 0; i < 4; ++i)
+    vp[i] = (uint32_t)vnew[src + 32 * i + n] | ((uint32_t)vnew[src + 32 * i + 16 + n] << 16);
 }
 
 // One wavefront writes the new token into its ring slot: 16 key pieces of 16 bytes, 128 value elements.
-__device__ inline void store_newest(uint16_t* __restrict__ dst, int W, int slot, const Op kp[4], const uint16_t vp[8],
+__device__ inline void store_newest(uint16_t* __restrict__ dst, int W, int slot, const Op kp[4], const uint32_t vp[4],
                                     int n, int kgrp) {
   if (n == 0) {
 #pragma unroll
@@ -197,13 +199,13 @@ __device__ inline void store_newest(uint16_t* __restrict__ dst, int W, int slot,
   }
   if (kgrp == 0) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i) dst[pt_v_off(1, W, 128, slot, 16 * i + n)] = vp[i];
+    for (int i = 0; i < 8; ++i) dst[pt_v_off(1, W, 128, slot, 16 * i + n)] = (uint16_t)(vp[i >> 1] >> (16 * (i & 1)));
   }
 }
 
 // The newest token is stored to the cache and, for this step's attention, written straight into
 // the registers of the wavefront that walks the last group: no wait for the store to land.
-__device__ inline void patch_newest(Frag& f, const Op kp[4], const uint16_t vp[8], int tl, int n, int kgrp) {
+__device__ inline void patch_newest(Frag& f, const Op kp[4], const uint32_t vp[4], int tl, int n, int kgrp) {
   const int t = tl >> 4, m = tl & 15;
   if (n == m) {
     if (t == 0) {
@@ -220,7 +222,7 @@ __device__ inline void patch_newest(Frag& f, const Op kp[4], const uint16_t vp[8
     const uint32_t sh = (uint32_t)(ve & 1) * 16u, keep = ~(0xffffu << sh);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const uint32_t val = (uint32_t)vp[i] << sh;
+      const uint32_t val = ((vp[i >> 1] >> (16 * (i & 1))) & 0xffffu) << sh;
 #pragma unroll
       for (int ww = 0; ww < 4; ++ww)
         if (ww == w) f.v[i].u[ww] = (f.v[i].u[ww] & keep) | val;
@@ -472,7 +474,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
       // append without attention: straight from the inputs (with attention the store happens after
       // the walk, from the registers that also patch the last group)
       Op kp[4];
-      uint16_t vp[8];
+      uint32_t vp[4];
       load_newest(kp, vp, a.knew, a.vnew, ((size_t)j_row * c.Hkv + hkv) * 128, n, kgrp);
       store_newest((uint16_t*)slab_p, c.W, c.n_sink + s_new, kp, vp, n, kgrp);
       if (c.scored && lane == 0) {            // a new token starts with no score
@@ -495,7 +497,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
       const bool patch = appending && owner;       // this workgroup's range ends with the new token
       const int p_visit = n_visits - 1, p_tl = s_new & 31;
       Op kp[4];
-      uint16_t vp[8];
+      uint32_t vp[4];
       if (patch) load_newest(kp, vp, a.knew, a.vnew, ((size_t)j_row * c.Hkv + hkv) * 128, n, kgrp);
       Op qf[4];
       if (n < g) {
@@ -557,9 +559,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
         if (nx < v1) load_group<NT>(fb, grp_ptr(nx), lane);
         if (patch && i == p_visit) patch_newest(fa, kp, vp, p_tl, n, kgrp);
         if constexpr (MASS) {
-          float pp[8];
-          process_group<true>(fa, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp, lag, pp);
-          if (fold && i >= n_sink_vis) lagged_mass_park(pp, il, park + (i - v0) * 32, n, kgrp);
+          process_group<true>(fa, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp, lag, il,
+                              (fold && i >= n_sink_vis) ? park + (i - v0) * 32 : nullptr, n);
         } else {
           process_group(fa, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp);
         }
@@ -569,9 +570,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
         if (nx < v1) load_group<NT>(fa, grp_ptr(nx), lane);
         if (patch && i == p_visit) patch_newest(fb, kp, vp, p_tl, n, kgrp);
         if constexpr (MASS) {
-          float pp[8];
-          process_group<true>(fb, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp, lag, pp);
-          if (fold && i >= n_sink_vis) lagged_mass_park(pp, il, park + (i - v0) * 32, n, kgrp);
+          process_group<true>(fb, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp, lag, il,
+                              (fold && i >= n_sink_vis) ? park + (i - v0) * 32 : nullptr, n);
         } else {
           process_group(fb, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp);
         }
