@@ -761,7 +761,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
       if constexpr (MASS) {
         if (will_select) {
           __threadfence();
-          pt_scored_select(c, b, base1, dyn_lds, sm.sel);
+          pt_scored_select<WAVES * 64>(c, b, base1, dyn_lds, sm.sel);
         }
       }
       if (tid == 0) {
@@ -815,8 +815,13 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bo
   if (mass) {
     // parked masses of every group a workgroup may walk
     const size_t park = (size_t)(cc.W / PT_GROUP_TOKENS + 2) * PT_GROUP_TOKENS * sizeof(float);
-    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 4, true>), grid, dim3(256), park, s, cc, a);
-    else hipLaunchKernelGGL((decode_mfma_kernel<false, 4, true>), grid, dim3(256), park, s, cc, a);
+    if (waves == 8) {
+      if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 8, true>), grid, dim3(512), park, s, cc, a);
+      else hipLaunchKernelGGL((decode_mfma_kernel<false, 8, true>), grid, dim3(512), park, s, cc, a);
+    } else {
+      if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 4, true>), grid, dim3(256), park, s, cc, a);
+      else hipLaunchKernelGGL((decode_mfma_kernel<false, 4, true>), grid, dim3(256), park, s, cc, a);
+    }
   } else if (waves == 8) {
     if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 8, false>), grid, dim3(512), 0, s, cc, a);
     else hipLaunchKernelGGL((decode_mfma_kernel<false, 8, false>), grid, dim3(512), 0, s, cc, a);

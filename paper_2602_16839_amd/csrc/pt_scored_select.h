@@ -4,7 +4,7 @@
 // dropping the oldest C ring places and folding them into S (Our Approach, the Delta-W equation and
 // the update rule) -- is then the sliding window's, unchanged.
 //
-// One workgroup of 256 threads per rollout:
+// One workgroup (THREADS = 256 or 512 threads) per rollout:
 //   1. score of every eligible ring entry (all but the n_recent newest) = sum over KV heads of the
 //      per-head accumulators the decode step maintains, in head order;
 //   2. the C lowest, ties towards the older entry: a radix select on the float bit patterns
@@ -17,17 +17,18 @@
 
 #include "ptenc_internal.h"
 
-constexpr int kSelThreads = 256;
+constexpr int kSelThreads = 256;   // the stand-alone launch
 
 struct SelSmall {
   uint32_t vmask[PT_SCORED_MAX_ELIGIBLE / 32];   // bit i: ring entry i is a victim
   int wpre[PT_SCORED_MAX_ELIGIBLE / 32];         // victims before word w
   int hist[256];
   int sh[4];
-  int wsum[kSelThreads / 64];
+  int wsum[8];
 };
 
 // exclusive count, over the workgroup's threads in thread order, of a flag; total in *total
+template <int THREADS>
 __device__ inline int pt_sel_excl_count(bool flag, SelSmall& sm, int* total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const unsigned long long bal = __ballot(flag);
@@ -36,7 +37,7 @@ __device__ inline int pt_sel_excl_count(bool flag, SelSmall& sm, int* total) {
   if (lane == 0) sm.wsum[wave] = __popcll(bal);
   __syncthreads();
   int before = 0, tot = 0;
-  for (int w = 0; w < kSelThreads / 64; ++w) {
+  for (int w = 0; w < THREADS / 64; ++w) {
     if (w < wave) before += sm.wsum[w];
     tot += sm.wsum[w];
   }
@@ -46,7 +47,8 @@ __device__ inline int pt_sel_excl_count(bool flag, SelSmall& sm, int* total) {
 
 // Rollout b's ring is full and starts at position `base`.  `work` = LDS for max(n_el floats, n_el ints),
 // n_el = Wr - n_recent: first the scores by ring index, then the two index lists of the exchanges.
-// Called by all 256 threads of a workgroup; starts and ends with a barrier.
+// Called by all THREADS threads of a workgroup; starts and ends with a barrier.
+template <int THREADS>
 __device__ inline void pt_scored_select(const PtDev& c, int b, long long base, float* work, SelSmall& sm) {
   const int t = threadIdx.x;
   const int n_el = c.Wr - c.n_recent, C = c.C;
@@ -55,22 +57,22 @@ __device__ inline void pt_scored_select(const PtDev& c, int b, long long base, f
   __syncthreads();
 
   // ---- 1. scores ----
-  for (int i = t; i < n_el; i += kSelThreads) {
+  for (int i = t; i < n_el; i += THREADS) {
     const int slot = slot_of(i);
     float s = 0.f;
     for (int h = 0; h < c.Hkv; ++h) s += c.mass[(size_t)(b * c.Hkv + h) * c.W + slot];
     work[i] = s;
   }
-  for (int w = t; w < PT_SCORED_MAX_ELIGIBLE / 32; w += kSelThreads) sm.vmask[w] = 0u;
+  for (int w = t; w < PT_SCORED_MAX_ELIGIBLE / 32; w += THREADS) sm.vmask[w] = 0u;
   __syncthreads();
 
   // ---- 2. the C-th smallest bit pattern, one byte at a time from the top ----
   uint32_t prefix = 0u, pmask = 0u;
   int k = C;                                            // still to take among the entries matching prefix
   for (int shift = 24; shift >= 0; shift -= 8) {
-    sm.hist[t] = 0;
+    if (t < 256) sm.hist[t] = 0;
     __syncthreads();
-    for (int i = t; i < n_el; i += kSelThreads) {
+    for (int i = t; i < n_el; i += THREADS) {
       const uint32_t bits = __float_as_uint(work[i]);
       if ((bits & pmask) == prefix) atomicAdd(&sm.hist[(bits >> shift) & 255u], 1);
     }
@@ -92,12 +94,12 @@ __device__ inline void pt_scored_select(const PtDev& c, int b, long long base, f
   }
   // prefix = the threshold pattern; k >= 1 of the entries equal to it are taken, oldest first
   int eq_seen = 0;
-  for (int i0 = 0; i0 < n_el; i0 += kSelThreads) {
+  for (int i0 = 0; i0 < n_el; i0 += THREADS) {
     const int i = i0 + t;
     const uint32_t bits = i < n_el ? __float_as_uint(work[i]) : 0xffffffffu;
     const bool eq = i < n_el && bits == prefix;
     int tot;
-    const int rank = eq_seen + pt_sel_excl_count(eq, sm, &tot);
+    const int rank = eq_seen + pt_sel_excl_count<THREADS>(eq, sm, &tot);
     if (i < n_el && (bits < prefix || (eq && rank < k))) atomicOr(&sm.vmask[i >> 5], 1u << (i & 31));
     eq_seen += tot;
   }
@@ -114,7 +116,7 @@ __device__ inline void pt_scored_select(const PtDev& c, int b, long long base, f
                                  : sm.wpre[w - 1] + __popc(sm.vmask[w - 1]));
   };
   // what leaves, by position, in ring order (before anything trades places)
-  for (int i = t; i < n_el; i += kSelThreads)
+  for (int i = t; i < n_el; i += THREADS)
     if (is_victim(i)) c.victims[(size_t)b * C + victims_before(i)] = c.pos[(size_t)b * c.W + slot_of(i)];
   const int v_head = victims_before(min(C, n_el));      // victims inside the oldest chunk
   __syncthreads();                                      // scores are dead from here on: `work` holds the pairs
@@ -123,7 +125,7 @@ __device__ inline void pt_scored_select(const PtDev& c, int b, long long base, f
   const int n_mv = C - v_head;
   int* mv_a = (int*)work;                               // k-th survivor of the oldest chunk
   int* mv_b = mv_a + n_el / 2 + 1;                      // k-th victim beyond it (n_mv <= n_el / 2)
-  for (int i = t; i < n_el; i += kSelThreads) {
+  for (int i = t; i < n_el; i += THREADS) {
     if (i < C && !is_victim(i)) mv_a[i - victims_before(i)] = i;
     if (i >= C && is_victim(i)) mv_b[victims_before(i) - v_head] = i;
   }
@@ -133,14 +135,14 @@ __device__ inline void pt_scored_select(const PtDev& c, int b, long long base, f
   uint16_t* cache = (uint16_t*)c.cache;
   typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
   const int n_items = n_mv * c.Hkv * 144;
-  for (int i0 = 0; i0 < n_items; i0 += kSelThreads * 4) {
+  for (int i0 = 0; i0 < n_items; i0 += THREADS * 4) {
     u32x4 ka[4], kb[4];
     uint16_t va[4], vb[4];
     size_t oa[4], ob[4];
     int kind[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int idx = i0 + u * kSelThreads + t;
+      const int idx = i0 + u * THREADS + t;
       kind[u] = -1;
       if (idx < n_items) {
         const int mv = idx / (c.Hkv * 144), rem = idx - mv * (c.Hkv * 144);
@@ -168,7 +170,7 @@ __device__ inline void pt_scored_select(const PtDev& c, int b, long long base, f
       else if (kind[u] == 1) { cache[oa[u]] = vb[u]; cache[ob[u]] = va[u]; }
     }
   }
-  for (int idx = t; idx < n_mv * (c.Hkv + 1); idx += kSelThreads) {
+  for (int idx = t; idx < n_mv * (c.Hkv + 1); idx += THREADS) {
     const int mv = idx / (c.Hkv + 1), h = idx - mv * (c.Hkv + 1);
     const int sa = slot_of(mv_a[mv]), sb = slot_of(mv_b[mv]);
     if (h < c.Hkv) {

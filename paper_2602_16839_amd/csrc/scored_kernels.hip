@@ -23,7 +23,7 @@ __global__ __launch_bounds__(kSelThreads) void scored_select_kernel(PtDev c, con
   if (active && !active[b]) return;
   const long long len = c.len[b], base = c.base[b];
   if (len - base != c.Wr || c.selected[b]) return;      // not full, or already chosen: nothing to do
-  pt_scored_select(c, b, base, work, sm);
+  pt_scored_select<kSelThreads>(c, b, base, work, sm);
 }
 
 // Scores and position tags of the live ring entries in ring order (oldest ring entry first);

@@ -26,7 +26,7 @@ def small(**kw):
     return I.WORKLOADS["qwen7b"].replace(**base)
 
 
-def make_both(wl, n_recent, splits=0):
+def make_both(wl, n_recent, splits=0, waves=0):
     enc = I.encoder_params(wl)
     e = {k: H.f64(v) for k, v in enc.items()}
     orc = so.ScoredOracleLayer(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk, n_recent,
@@ -37,6 +37,8 @@ def make_both(wl, n_recent, splits=0):
     layer.set_option(ptenc.OPT_EVICT_POLICY, ptenc.POLICY_SCORED)
     if splits:
         layer.set_option(ptenc.OPT_SPLITS, splits)
+    if waves:
+        layer.set_option(ptenc.OPT_WAVES, waves)
     dev = {k: v.cuda() for k, v in enc.items()}
     layer.set_encoder(dev["q_g"], dev["WaQ"], dev["WaK"], dev["WaV"], dev["k_g"], dev["v_g"])
     layer.reset()
@@ -59,8 +61,8 @@ def check_scores(wl, orc, layer, what):
         assert (err <= SCORE_ABS + SCORE_REL * np.abs(ref)).all(), "%s: scores of rollout %d off by %.3e" % (what, b, err.max())
 
 
-def run_both(wl, T, n_recent, q_gain, splits=0, lengths=None, prompt_len=None, score_every=17):
-    orc, layer = make_both(wl, n_recent, splits)
+def run_both(wl, T, n_recent, q_gain, splits=0, lengths=None, prompt_len=None, score_every=17, waves=0):
+    orc, layer = make_both(wl, n_recent, splits, waves)
     if wl.n_sink:
         pl = np.asarray(prompt_len, dtype=np.int32)
         pk, pv = I.prompt_kv(wl)
@@ -96,10 +98,10 @@ def run_both(wl, T, n_recent, q_gain, splits=0, lengths=None, prompt_len=None, s
     return orc, layer
 
 
-@pytest.mark.parametrize("splits", [1, 3])
-def test_scored_run_matches_oracle(splits):
+@pytest.mark.parametrize("splits,waves", [(1, 4), (3, 4), (1, 8), (2, 8)])
+def test_scored_run_matches_oracle(splits, waves):
     wl = small()
-    orc, layer = run_both(wl, wl.steps, n_recent=24, q_gain=48.0, splits=splits)
+    orc, layer = run_both(wl, wl.steps, n_recent=24, q_gain=48.0, splits=splits, waves=waves)
     # the policy did something other than slide: some evicted chunk was not the oldest one
     assert any(list(orc.positions(b)) != list(range(orc.evicted[b], orc.appended[b])) for b in range(wl.batch))
 
