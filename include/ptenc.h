@@ -169,6 +169,14 @@ ptenc_status ptenc_reset(ptenc_ctx* ctx, const uint8_t* d_mask, void* stream);
  * Synchronises the stream (the host array is consumed before return). */
 ptenc_status ptenc_prefill(ptenc_ctx* ctx, const void* d_k, const void* d_v, const int32_t* h_prompt_len,
                            int32_t p_max, void* stream);
+
+/* The same for a list of rollouts only (a rollout engine that recycles finished rollouts: ptenc_reset
+ * with a mask, then this): d_k, d_v are [n, p_max, H_kv, d], row j belongs to rollout d_ids[j] (DEVICE
+ * int32[n], distinct) and has h_prompt_len[j] tokens (HOST array of n lengths).  Rollouts not listed
+ * keep their question tokens.  An id outside 0 .. B-1 sets PTENC_DEVERR_BAD_ID and is skipped.
+ * n = 0 does nothing.  Synchronises the stream. */
+ptenc_status ptenc_prefill_ids(ptenc_ctx* ctx, const void* d_k, const void* d_v, const int32_t* d_ids,
+                               const int32_t* h_prompt_len, int32_t n, int32_t p_max, void* stream);
 ptenc_status ptenc_get_prompt_len(ptenc_ctx* ctx, int32_t* h_prompt_len, void* stream);
 
 /* Writes k, v [B, H_kv, d] of every active rollout to the ring slot of position len, then len += 1

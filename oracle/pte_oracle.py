@@ -212,6 +212,10 @@ class OracleLayer:
             r.sink_k.append(np.array(kk, dtype=np.float64))
             r.sink_v.append(np.array(vv, dtype=np.float64))
 
+    def reset_rollout(self, b: int) -> None:
+        """Rollout b starts over: empty cache (question tokens included), S = S_0, counters at zero."""
+        self.rollouts[b] = OracleRollout(self.S0)
+
     # -- one batched decode step ------------------------------------------------------------
     def step(self, q: np.ndarray, k: np.ndarray, v: np.ndarray,
              active: Optional[np.ndarray] = None) -> np.ndarray:

@@ -74,12 +74,25 @@ __global__ void gather_kernel(PtDev c, T* __restrict__ Kout, T* __restrict__ Vou
 
 // Question tokens [B, p_max, H_kv, d] into the reserved slots: one workgroup per (slab, 32 tokens).
 // The 32 x d tile is staged in LDS so that the tiled layout is written in whole 16-byte vectors.
+// With a rollout list (ids, lens: row j of kin / vin belongs to rollout ids[j] and has lens[j] tokens)
+// only the listed rollouts are touched, and their question-token counts are set here.
 template <typename T>
 __global__ __launch_bounds__(256) void prefill_kernel(PtDev c, const T* __restrict__ kin, const T* __restrict__ vin,
-                                                      int p_max) {
+                                                      int p_max, const int* __restrict__ ids,
+                                                      const int* __restrict__ lens) {
   __shared__ T tile[32][256 + 8];
-  const int slab = blockIdx.x, b = slab / c.Hkv, h = slab - b * c.Hkv, j0 = blockIdx.y * 32;
-  const int P = c.n_prompt[b];
+  const int row = blockIdx.x / c.Hkv, h = blockIdx.x - row * c.Hkv, j0 = blockIdx.y * 32;
+  int b = row;
+  if (ids) {
+    b = ids[row];
+    if ((unsigned)b >= (unsigned)c.B) {            // never index with a bad id: flag it and leave
+      if (threadIdx.x == 0 && h == 0 && j0 == 0) atomicOr(c.err, PTENC_DEVERR_BAD_ID);
+      return;
+    }
+  }
+  const int slab = b * c.Hkv + h;
+  const int P = ids ? lens[row] : c.n_prompt[b];
+  if (ids && h == 0 && j0 == 0 && threadIdx.x == 0) c.n_prompt[b] = P;   // read by later launches only
   if (j0 >= P) return;
   const int n = min(32, P - j0);
   T* dst = (T*)c.cache + (size_t)slab * pt_slab_elems(c.W, c.d);
@@ -87,7 +100,7 @@ __global__ __launch_bounds__(256) void prefill_kernel(PtDev c, const T* __restri
     const T* in = which == 0 ? kin : vin;
     for (int idx = threadIdx.x; idx < 32 * c.d; idx += blockDim.x) {
       const int tk = idx / c.d, i = idx - tk * c.d;
-      tile[tk][i] = tk < n ? in[(((size_t)b * p_max + j0 + tk) * c.Hkv + h) * c.d + i] : (T)0;
+      tile[tk][i] = tk < n ? in[(((size_t)row * p_max + j0 + tk) * c.Hkv + h) * c.d + i] : (T)0;
     }
     __syncthreads();
     if (c.tiled) {
@@ -178,12 +191,14 @@ hipError_t pt_launch_gather(const PtDev& c, void* K, void* V, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t pt_launch_prefill(const PtDev& c, const void* k, const void* v, int p_max, hipStream_t s) {
-  dim3 grid(c.B * c.Hkv, (c.n_sink + 31) / 32);
+hipError_t pt_launch_prefill(const PtDev& c, const void* k, const void* v, int p_max, const int* ids, const int* lens,
+                             int n_rows, hipStream_t s) {
+  dim3 grid((ids ? n_rows : c.B) * c.Hkv, (c.n_sink + 31) / 32);
   if (c.dtype == PTENC_F32)
-    hipLaunchKernelGGL(prefill_kernel<float>, grid, dim3(256), 0, s, c, (const float*)k, (const float*)v, p_max);
+    hipLaunchKernelGGL(prefill_kernel<float>, grid, dim3(256), 0, s, c, (const float*)k, (const float*)v, p_max, ids, lens);
   else
-    hipLaunchKernelGGL(prefill_kernel<uint16_t>, grid, dim3(256), 0, s, c, (const uint16_t*)k, (const uint16_t*)v, p_max);
+    hipLaunchKernelGGL(prefill_kernel<uint16_t>, grid, dim3(256), 0, s, c, (const uint16_t*)k, (const uint16_t*)v, p_max, ids,
+                       lens);
   return hipGetLastError();
 }
 

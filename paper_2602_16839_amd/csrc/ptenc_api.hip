@@ -306,9 +306,27 @@ ptenc_status ptenc_prefill(ptenc_ctx* ctx, const void* d_k, const void* d_v, con
       hipSuccess)
     return PTENC_ERR_HIP;
   if (ctx->cfg.n_sink > 0) {
-    hipError_t e = pt_launch_prefill(ctx->dev, d_k, d_v, p_max, S(stream));
+    hipError_t e = pt_launch_prefill(ctx->dev, d_k, d_v, p_max, nullptr, nullptr, 0, S(stream));
     if (e != hipSuccess) return PTENC_ERR_HIP;
   }
+  // the host array may be pageable and reused by the caller right after return
+  return hip_status(hipStreamSynchronize(S(stream)));
+}
+
+ptenc_status ptenc_prefill_ids(ptenc_ctx* ctx, const void* d_k, const void* d_v, const int32_t* d_ids,
+                               const int32_t* h_prompt_len, int32_t n, int32_t p_max, void* stream) {
+  if (!ctx || n < 0 || n > ctx->cfg.batch) return PTENC_ERR_INVALID_ARG;
+  if (!ctx->encoder_set) return PTENC_ERR_STATE;
+  if (n == 0) return PTENC_OK;
+  if (!d_k || !d_v || !d_ids || !h_prompt_len || p_max < 1) return PTENC_ERR_INVALID_ARG;
+  for (int j = 0; j < n; ++j)
+    if (h_prompt_len[j] < 0 || h_prompt_len[j] > ctx->cfg.n_sink || h_prompt_len[j] > p_max) return PTENC_ERR_INVALID_ARG;
+  if (ctx->cfg.n_sink == 0) return PTENC_OK;            // no reserved slots: every length is 0
+  // the lengths travel through the head of the scratch buffer (idle between launches)
+  int* d_lens = (int*)ctx->dev.partial;
+  if (hipMemcpyAsync(d_lens, h_prompt_len, sizeof(int) * n, hipMemcpyHostToDevice, S(stream)) != hipSuccess)
+    return PTENC_ERR_HIP;
+  if (pt_launch_prefill(ctx->dev, d_k, d_v, p_max, d_ids, d_lens, n, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
   // the host array may be pageable and reused by the caller right after return
   return hip_status(hipStreamSynchronize(S(stream)));
 }

@@ -153,7 +153,8 @@ hipError_t pt_launch_step_prologue(const PtDev& c, bool do_evict, bool do_append
                                    const void* k, const void* v, const uint8_t* active, void* dbg_chunk,
                                    const int* ids, int n_rows, bool in_place, hipStream_t s);
 hipError_t pt_launch_gather(const PtDev& c, void* K, void* V, hipStream_t s);
-hipError_t pt_launch_prefill(const PtDev& c, const void* k, const void* v, int p_max, hipStream_t s);
+hipError_t pt_launch_prefill(const PtDev& c, const void* k, const void* v, int p_max, const int* ids, const int* lens,
+                             int n_rows, hipStream_t s);
 hipError_t pt_launch_encoder_init(const PtDev& c, const void* qg, const void* WaQ, const void* kg,
                                   const void* vg, hipStream_t s);
 hipError_t pt_launch_attn_generic(const PtDev& c, const void* q, void* out, const uint8_t* active,

@@ -33,7 +33,7 @@ EXPORTS = [
     "ptenc_get_plan", "ptenc_status_string", "ptenc_util_stream_read", "ptenc_util_stream_read_nt", "ptenc_util_copy",
     "ptenc_prefill", "ptenc_get_prompt_len", "ptenc_decode_step_ids", "ptenc_decode_run_ids",
     "ptenc_apply_delta",
-    "ptenc_get_scores", "ptenc_set_scores", "ptenc_get_victims",
+    "ptenc_get_scores", "ptenc_set_scores", "ptenc_get_victims", "ptenc_prefill_ids",
     "ptenc_stack_query_sizes", "ptenc_stack_create", "ptenc_stack_destroy", "ptenc_stack_layer",
     "ptenc_stack_reset", "ptenc_stack_decode_step", "ptenc_stack_graph_capture", "ptenc_stack_graph_launch",
 ]
@@ -93,6 +93,7 @@ def lib() -> C.CDLL:
             "ptenc_util_copy": [vp, vp, sz, i32, vp],
             "ptenc_prefill": [vp, vp, vp, vp, i32, vp],
             "ptenc_get_prompt_len": [vp, vp, vp],
+            "ptenc_prefill_ids": [vp, vp, vp, vp, vp, i32, i32, vp],
             "ptenc_decode_step_ids": [vp, vp, vp, vp, vp, vp, i32, vp],
             "ptenc_decode_run_ids": [vp, vp, vp, vp, vp, vp, vp, i64, vp],
             "ptenc_apply_delta": [vp, vp, vp, vp, vp, i32, i32, vp, vp, i32, vp],
@@ -174,6 +175,15 @@ def ptenc_prefill(ctx, k, v, prompt_len):
     pl = np.ascontiguousarray(prompt_len, dtype=np.int32)
     _check(lib().ptenc_prefill(ctx, _ptr(k), _ptr(v), pl.ctypes.data_as(C.c_void_p), int(k.shape[1]), _stream()),
            "ptenc_prefill")
+
+
+def ptenc_prefill_ids(ctx, k, v, ids, prompt_len):
+    """k, v: [n, p_max, H_kv, d] device tensors; ids: int32 [n] device tensor; prompt_len: n host integers."""
+    assert ids.dtype == torch.int32
+    pl = np.ascontiguousarray(prompt_len, dtype=np.int32)
+    assert len(pl) == ids.numel()
+    _check(lib().ptenc_prefill_ids(ctx, _ptr(k), _ptr(v), _ptr(ids), pl.ctypes.data_as(C.c_void_p), int(ids.numel()),
+                                   int(k.shape[1]) if k is not None and k.dim() > 1 else 1, _stream()), "ptenc_prefill_ids")
 
 
 def ptenc_get_prompt_len(ctx, batch: int):
@@ -415,6 +425,9 @@ class Layer:
 
     def prefill(self, k, v, prompt_len):
         ptenc_prefill(self.ctx, k, v, prompt_len)
+
+    def prefill_ids(self, k, v, ids, prompt_len):
+        ptenc_prefill_ids(self.ctx, k, v, ids, prompt_len)
 
     def prompt_len(self):
         return ptenc_get_prompt_len(self.ctx, self.B)

@@ -308,6 +308,59 @@ def test_question_tokens_generic_paths():
     assert layer.plan()[0] == 0
 
 
+@pytest.mark.parametrize("kind", ["mfma", "f32"])
+def test_finished_rollouts_are_recycled_one_at_a_time(kind):
+    # a rollout engine's loop: a rollout that has finished is reset and given a new question (its own
+    # reserved slots only) while the others keep decoding; twice, different rollouts, different lengths
+    from paper_2602_16839_amd import ptenc
+    if kind == "mfma":
+        wl = small("qwen7b", batch=4, n_q_heads=14, n_kv_heads=2, window=160, n_sink=64, chunk=40, steps=230)
+    else:
+        wl = small("tiny_f32", batch=4, window=40, n_sink=12, chunk=9, steps=120)
+    enc = I.encoder_params(wl)
+    orc = H.make_oracle(wl, enc)
+    layer = H.make_layer(wl, enc)
+    pl = H.prefill_both(wl, orc, layer, [wl.n_sink, 1, wl.n_sink // 2, 0])
+    q, k, v = I.qkv_steps(wl, 0, wl.steps)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    qn, kn, vn = H.f64(q), H.f64(k), H.f64(v)
+    abs_tol, rel_tol = H.tolerances(wl)
+    # the new questions come from another seed of the same recipe
+    pk2, pv2 = I.prompt_kv(wl.replace(seed=wl.seed + 1))
+    recycle = {wl.steps // 3: ([2], [wl.n_sink // 3]), 2 * wl.steps // 3: ([3, 0], [wl.n_sink, 2])}
+    for t in range(wl.steps):
+        if t in recycle:
+            ids, lens = recycle[t]
+            mask = np.zeros(wl.batch, dtype=np.uint8)
+            mask[ids] = 1
+            layer.reset(torch.from_numpy(mask).cuda())
+            layer.prefill_ids(pk2[ids].cuda().contiguous(), pv2[ids].cuda().contiguous(),
+                              torch.tensor(ids, dtype=torch.int32, device="cuda"), lens)
+            for b, n in zip(ids, lens):
+                orc.reset_rollout(b)
+                orc.prefill(b, H.f64(pk2[b, :n]), H.f64(pv2[b, :n]))
+                pl[b] = n
+            assert np.array_equal(layer.prompt_len(), pl)
+        ref = orc.step(qn[t], kn[t], vn[t])
+        out = layer.step(qd[t], kd[t], vd[t])
+        H.assert_close(H.f64(out), ref, abs_tol, rel_tol, "out at step %d" % t)
+        ln, base = layer.counters()
+        oln, obase = orc.counters()
+        assert np.array_equal(ln, oln) and np.array_equal(base, obase), "counters at step %d" % t
+    H.assert_close(layer.get_state(), orc.state(), H.S_ABS, H.S_REL, "state S")
+    Kw, Vw = layer.gather_window()
+    for b in range(wl.batch):
+        ko, vo = orc.window_kv(b)
+        assert torch.equal(Kw[b, :, :len(ko)].cpu().to(torch.float64), torch.from_numpy(ko).transpose(0, 1))
+        assert torch.equal(Vw[b, :, :len(vo)].cpu().to(torch.float64), torch.from_numpy(vo).transpose(0, 1))
+    assert layer.poll_error() == 0
+    # an id outside the batch is flagged and skipped; an empty list does nothing
+    layer.prefill_ids(pk2[:1].cuda().contiguous(), pv2[:1].cuda().contiguous(), torch.tensor([wl.batch], dtype=torch.int32, device="cuda"), [1])
+    assert layer.poll_error() == ptenc.DEVERR_BAD_ID
+    layer.prefill_ids(pk2[:0].cuda().contiguous(), pv2[:0].cuda().contiguous(), torch.zeros(0, dtype=torch.int32, device="cuda"), [])
+    assert np.array_equal(layer.prompt_len(), pl)
+
+
 def test_question_tokens_only_no_thinking_tokens_yet():
     # attention right after prefill, before any append: softmax over the question tokens alone
     wl = small("qwen3b", batch=2, n_q_heads=8, n_kv_heads=2, window=96, n_sink=32, chunk=16, steps=4)

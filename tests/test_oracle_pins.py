@@ -421,6 +421,26 @@ def test_question_tokens_stay_and_only_thinking_tokens_slide(W, n_sink, C, P):
         layer.prefill(0, rand(n_sink + 1, H_kv, d), rand(n_sink + 1, H_kv, d))
 
 
+def test_a_reset_rollout_behaves_like_a_fresh_one_and_leaves_the_others_alone():
+    B, H_q, H_kv, d, W, C = 2, 2, 1, 3, 7, 2
+    layer, enc = _layer(B, H_q, H_kv, d, W, C)
+    fresh, _ = _layer(1, H_q, H_kv, d, W, C)
+    fresh.__init__(1, H_q, H_kv, d, W, C, enc["q_g"], enc["WaQ"], enc["WaK"], enc["WaV"], enc["k_g"], enc["v_g"])
+    Q, K, V = rand(20, B, H_q, d), rand(20, B, H_kv, d), rand(20, B, H_kv, d)
+    for t in range(11):
+        layer.step(Q[t], K[t], V[t])
+    S_other = layer.state()[0].copy()
+    n_other = layer.counters()[0][0]
+    layer.reset_rollout(1)
+    assert layer.counters()[0][1] == 0 and layer.counters()[1][1] == 0 and np.array_equal(layer.state()[1], layer.S0)
+    assert layer.counters()[0][0] == n_other and np.array_equal(layer.state()[0], S_other)
+    for t in range(11, 20):
+        out = layer.step(Q[t], K[t], V[t])
+        ref = fresh.step(Q[t][1:], K[t][1:], V[t][1:])
+        assert np.allclose(out[1], ref[0], atol=1e-14)
+    assert np.allclose(layer.state()[1], fresh.state()[0], atol=1e-14)
+
+
 def test_ring_model_with_reserved_question_slots():
     ring = RingModel(1, 12, 3, n_sink=4)
     slots = [int(ring.step()[0]) for _ in range(20)]
