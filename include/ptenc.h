@@ -115,7 +115,9 @@ typedef enum {
  *          eligible entries; else PTENC_ERR_UNSUPPORTED.  Scores advance only through
  *          ptenc_decode_step / ptenc_decode_run / ptenc_decode_step_ids / ptenc_decode_run_ids (a
  *          separate ptenc_decode_attn leaves them alone); ptenc_set_counters accepts only empty
- *          windows.  Per step it costs one extra small launch that returns at once unless a ring is full. */
+ *          windows.  The step whose append fills a ring chooses the next victims at its own end, so a run of
+ *          decode steps needs no extra launch; a ring filled by a bare ptenc_cache_append, or re-scored by
+ *          ptenc_set_scores, gets a stand-alone selection launch from the next call that may evict. */
 typedef enum { PTENC_POLICY_SLIDING = 0, PTENC_POLICY_SCORED = 1 } ptenc_policy;
 
 #define PTENC_MAX_SPLITS 32

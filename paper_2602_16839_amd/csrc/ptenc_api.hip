@@ -488,6 +488,9 @@ ptenc_status ptenc_set_counters(ptenc_ctx* ctx, const int64_t* h_len, const int6
       if (h_len[b] != h_base[b]) return PTENC_ERR_UNSUPPORTED;
     if (hipMemsetAsync(ctx->dev.mtag, 0xff, sizeof(long long) * ctx->cfg.batch * ctx->cfg.n_kv_heads, S(stream)) != hipSuccess)
       return PTENC_ERR_HIP;
+    // a choice of victims made for the old contents does not hold for what fills the ring next
+    if (hipMemsetAsync(ctx->dev.selected, 0, sizeof(int) * ctx->cfg.batch, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
+    ctx->select_stale = 1;
   }
   const size_t n = sizeof(long long) * ctx->cfg.batch;
   if (hipMemcpyAsync(ctx->dev.len, h_len, n, hipMemcpyHostToDevice, S(stream)) != hipSuccess) return PTENC_ERR_HIP;

@@ -434,14 +434,17 @@ def test_ring_contents_and_eviction_order_are_bit_exact(name, W, C, n_sink):
     assert layer.poll_error() == 0
 
 
-def test_rotation_invariance_of_the_ring():
-    # starting the counters at x shifts every slot by x mod W; outputs, windows and S are bit-identical
-    wl = small("qwen3b", batch=2, n_q_heads=8, n_kv_heads=2, window=96, chunk=32, steps=230)
+@pytest.mark.parametrize("name,generic", [("qwen3b", False), ("qwen3b", True), ("tiny_f32", False)])
+def test_rotation_invariance_of_the_ring(name, generic):
+    # starting the counters at x shifts every slot by x mod W; outputs, windows and S are bit-identical.
+    # The offsets include counters that cross 2^31 and 2^32 during the run and ones far beyond
+    # (the ring index is taken in 32 bits only while the counters fit).
+    wl = small(name, batch=2, n_q_heads=8, n_kv_heads=2, window=96, chunk=32, steps=230)
     enc = I.encoder_params(wl)
     q, k, v = (t.cuda() for t in I.qkv_steps(wl, 0, wl.steps))
     results = []
-    for x in (0, 37, 96 * 1000003 + 95):
-        layer = H.make_layer(wl, enc)
+    for x in (0, 37, 96 * 1000003 + 95, 2**31 - 100, 2**32 - 50, 2**33 + 77, 2**62 + 12345):
+        layer = H.make_layer(wl, enc, force_generic=generic)
         layer.set_counters(np.full(2, x), np.full(2, x))
         out = layer.run(q, k, v)
         Kw, Vw = layer.gather_window()

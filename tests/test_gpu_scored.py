@@ -295,3 +295,66 @@ def test_scored_policy_argument_checks():
     with pytest.raises(ptenc.PtencError) as ei:
         layer.set_counters(np.full(wl.batch, 5), np.full(wl.batch, 2))    # live tokens without scores
     assert ei.value.status == ptenc.ERR_UNSUPPORTED
+
+
+def test_scored_run_is_invariant_to_where_the_counters_start():
+    # counters that start far beyond 2^32, and ones that cross 2^32 during the run, shift positions and
+    # victims by the start value and nothing else (margins are wide, so rounding order cannot change a choice)
+    wl = small()
+    q, k, v = I.qkv_steps(wl, 0, wl.steps)
+    q = (q.float() * 48.0).to(q.dtype)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    runs = []
+    for x in (0, 2**32 - 70, 2**40 + 5):
+        _, layer = make_both(wl, 24)
+        layer.set_counters(np.full(wl.batch, x), np.full(wl.batch, x))
+        outs, vics = [], []
+        for t in range(wl.steps):
+            base_before = layer.counters()[1] if t >= wl.window else None
+            outs.append(layer.step(qd[t], kd[t], vd[t]).cpu())
+            if base_before is not None and (layer.counters()[1] != base_before).any():
+                vics.append(layer.victims() - x)
+        sc, ps = layer.scores()
+        ln, base = layer.counters()
+        n = int(ln[0] - base[0])
+        order = np.argsort(ps[:, :n], axis=1)
+        runs.append((torch.stack(outs), vics, np.take_along_axis(ps[:, :n], order, 1) - x,
+                     np.take_along_axis(sc[:, :n], order, 1), ln - x, base - x, layer.get_state()))
+        assert layer.poll_error() == 0
+    assert len(runs[0][1]) >= 3
+    for r in runs[1:]:
+        assert len(r[1]) == len(runs[0][1]) and all(np.array_equal(a, b) for a, b in zip(r[1], runs[0][1]))
+        assert np.array_equal(r[2], runs[0][2]) and np.array_equal(r[4], runs[0][4]) and np.array_equal(r[5], runs[0][5])
+        assert np.allclose(r[3], runs[0][3], rtol=1e-4, atol=1e-5)
+        H.assert_close(H.f64(r[0]), H.f64(runs[0][0]), 2e-3, 2e-2, "outputs from shifted counters")
+        H.assert_close(r[6], runs[0][6], 1e-5, 1e-4, "state from shifted counters")
+
+
+def test_rebasing_an_emptied_ring_forgets_the_old_choice_of_victims():
+    # fill a ring by whole steps (its victims get chosen), empty it through ptenc_set_counters, fill it
+    # again by bare appends: nothing has been attended, all scores are zero, so the tie rule decides
+    # and the oldest chunk leaves; a choice kept from the first filling would name other places
+    wl = small(batch=2, window=64, chunk=16, steps=64)
+    _, layer = make_both(wl, n_recent=8)
+    q, k, v = I.qkv_steps(wl, 0, 2 * wl.window)
+    q = (q.float() * 48.0).to(q.dtype)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    for t in range(wl.window):
+        layer.step(qd[t], kd[t], vd[t])
+    first = layer.victims()
+    assert any(first[b].tolist() != list(range(wl.chunk)) for b in range(wl.batch))   # the scores did decide
+    x = 1000
+    layer.set_counters(np.full(wl.batch, x), np.full(wl.batch, x))
+    for t in range(wl.window, 2 * wl.window):
+        layer.append(kd[t], vd[t])
+    dkv = wl.n_kv_heads * wl.head_dim
+    dbg = torch.zeros((wl.batch, 2, wl.chunk, dkv), dtype=torch.bfloat16, device="cuda")
+    layer.evict_encode(dbg_chunk=dbg)
+    vic = layer.victims()
+    for b in range(wl.batch):
+        assert vic[b].tolist() == list(range(x, x + wl.chunk))
+        assert torch.equal(dbg[b, 0].cpu(), k[wl.window:wl.window + wl.chunk, b].reshape(wl.chunk, dkv))
+        assert torch.equal(dbg[b, 1].cpu(), v[wl.window:wl.window + wl.chunk, b].reshape(wl.chunk, dkv))
+    ln, base = layer.counters()
+    assert (ln == x + wl.window).all() and (base == x + wl.chunk).all()
+    assert layer.poll_error() == 0
