@@ -12,9 +12,10 @@ LIB_PATH = os.path.join(PKG_DIR, "libptenc.so")
 SOURCES = ["ptenc_api.hip", "cache_kernels.hip", "attn_generic.hip", "decode_mfma.hip", "util_kernels.hip", "adapter_kernels.hip",
            "stack_api.hip", "scored_kernels.hip"]
 # packed-fp32 instruction selection is switched off for all device code
-HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+OBJ_DIR = os.path.join(PKG_DIR, "_build")
 
 
 def hipcc_path() -> str:
@@ -24,18 +25,28 @@ def hipcc_path() -> str:
     return "hipcc"
 
 
-def build(verbose: bool = True) -> str:
-    """Compiles every HIP source for gfx950 into one shared library; returns its path."""
-    cmd = [hipcc_path()] + HIPCC_FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB_PATH + ".tmp"]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     # the host pass does not know the device-only feature flag and says so once per source
     out = "\n".join(l for l in res.stdout.splitlines() if "not a recognized feature" not in l)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + out)
+        raise RuntimeError("%s failed:\n%s" % (os.path.basename(cmd[0]), out))
     if verbose and out.strip():
         print(out)
+
+
+def build(verbose: bool = True) -> str:
+    """Compiles every HIP source for gfx950 (one object each, in parallel) and links one shared library; returns its path."""
+    from concurrent.futures import ThreadPoolExecutor
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    objs = [os.path.join(OBJ_DIR, s.replace(".hip", ".o")) for s in SOURCES]
+    cmds = [[hipcc_path()] + HIPCC_FLAGS + ["-c", os.path.join(CSRC, s), "-o", o]
+            for s, o in zip(SOURCES, objs)]
+    with ThreadPoolExecutor(max_workers=min(8, len(cmds))) as pool:
+        list(pool.map(lambda c: _run(c, verbose), cmds))
+    _run([hipcc_path(), "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB_PATH + ".tmp"], verbose)
     os.replace(LIB_PATH + ".tmp", LIB_PATH)
     build_c_smoke(verbose)
     return LIB_PATH
