@@ -15,6 +15,11 @@ SOURCES = ["ptenc_api.hip", "cache_kernels.hip", "attn_generic.hip", "decode_mfm
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+# The step kernel's leading scalar arguments (list and mask pointers, counter pointers, two sizes:
+# 12 dwords) are preloaded into SGPRs at wavefront launch, so its first loads need not wait for
+# the argument block; the compiler keeps a prologue that loads them the ordinary way where the
+# firmware does not preload.
+EXTRA_FLAGS = {"decode_mfma.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=12"]}
 OBJ_DIR = os.path.join(PKG_DIR, "_build")
 
 
@@ -42,7 +47,7 @@ def build(verbose: bool = True) -> str:
     from concurrent.futures import ThreadPoolExecutor
     os.makedirs(OBJ_DIR, exist_ok=True)
     objs = [os.path.join(OBJ_DIR, s.replace(".hip", ".o")) for s in SOURCES]
-    cmds = [[hipcc_path()] + HIPCC_FLAGS + ["-c", os.path.join(CSRC, s), "-o", o]
+    cmds = [[hipcc_path()] + HIPCC_FLAGS + EXTRA_FLAGS.get(s, []) + ["-c", os.path.join(CSRC, s), "-o", o]
             for s, o in zip(SOURCES, objs)]
     with ThreadPoolExecutor(max_workers=min(8, len(cmds))) as pool:
         list(pool.map(lambda c: _run(c, verbose), cmds))

@@ -5,7 +5,7 @@
 //   [attend over the live window]                                  decode-stage / attention equations)
 // Each part can be switched off, so the same kernel also serves the three separate entry points.
 //
-// Work decomposition: one workgroup of 4 wavefronts per (rollout, KV head, window split).
+// Work decomposition: one workgroup of 4 or 8 wavefronts per (rollout, KV head, window split).
 //
 // Attention.  A wavefront walks 32-slot groups of the ring (16 KiB each, contiguous in HBM).
 // Softmax does not care about the order of the keys, so the walk is in physical slot order
@@ -30,7 +30,9 @@
 // already runs on the window without the evicted chunk.
 //
 // Counters are double-buffered: a step reads (len, base) from one pair of arrays and writes the
-// other, so no workgroup has to wait for the rest of its rollout before the step can end.
+// other, so no workgroup has to wait for the rest of its rollout before the step can end.  (Compact
+// lists and graph replays update them in place instead: the rollout's last workgroup to arrive
+// writes them, after every other one has read them.)
 //
 // Importance scores (template argument MASS, the scored eviction policy; the paper's ablation on
 // token dropping strategies).  The attention probability every cached token received in the rollout's
@@ -251,12 +253,108 @@ __device__ inline void ld_agent2(const float* p, float& a, float& b) {
   b = __uint_as_float((unsigned)(u >> 32));
 }
 
-// A workgroup-uniform value that no workgroup of this launch writes (counters as the step finds them,
-// masks, id lists): read through the constant address space, i.e. with a scalar load, which comes back
-// sooner than a vector load and costs no vector register.  (Loads only: nothing is ever written that way.)
+// A workgroup-uniform value that no workgroup of this launch writes (id lists and the like): read
+// through the constant address space, i.e. with a scalar load, which comes back sooner than a vector
+// load and costs no vector register.  (Loads only: nothing is ever written that way.)
 template <typename T>
 __device__ inline T ld_uniform(const T* p) {
   return *(const __attribute__((address_space(4))) T*)(uintptr_t)p;
+}
+
+// A workgroup-uniform value that a workgroup of this launch MAY overwrite once every reader has taken
+// it (the tag of the saved queries; the counters below, when they are updated in place): a scalar load
+// as well, but issued by hand, because memory behind the constant address space is taken never to
+// change and a load from it may legally be repeated later.
+__device__ inline long long ld_scalar(const long long* p) {
+  long long v;
+  asm volatile(
+      "s_load_dwordx2 %0, %1, 0x0\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&s"(v)
+      : "s"(p)
+      : "memory");
+  return v;
+}
+
+// What a step must know before its first K/V load: the rollout's counters, its number of question
+// tokens and its mask byte.  All four are fetched together (scalar loads, one wait), so the step
+// pays one round trip to memory for them instead of one per dependent load; the mask byte comes
+// as the aligned dword that holds it (an aligned dword shares its page with every byte in it).
+// Issued by hand like ld_scalar above: the counters may be rewritten in place later in the launch.
+//
+// The same wait also covers one dword of every 64-byte line of the kernel's argument block
+// (TOUCH): the arguments the compiler fetches later, in several dependent batches, then come from
+// the scalar cache instead of costing a round trip each.  The touched values are discarded.
+struct StepHead { long long len, base; int n_prompt; uint32_t mask_word; };
+typedef const void* KernargPtr;   // generic pointer to the argument block
+
+// offset of the k-th touched dword inside an argument block of ARG_BYTES bytes
+#define PT_TOUCH_OFF(k) ((k) * 64 < ARG_BYTES - 4 ? (k) * 64 : ARG_BYTES - 4)
+#define PT_TOUCH_OFFSETS \
+  "i"(PT_TOUCH_OFF(0)), "i"(PT_TOUCH_OFF(1)), "i"(PT_TOUCH_OFF(2)), "i"(PT_TOUCH_OFF(3)), "i"(PT_TOUCH_OFF(4)), \
+  "i"(PT_TOUCH_OFF(5)), "i"(PT_TOUCH_OFF(6)), "i"(PT_TOUCH_OFF(7))
+
+// TOUCH: with the argument-block lines (a launch over all rollouts); else the four values only
+template <int ARG_BYTES, bool TOUCH>
+__device__ inline StepHead load_step_head(const long long* len_p, const long long* base_p, const int* n_prompt_p,
+                                          const uint32_t* mask_word_p, KernargPtr ka) {
+  static_assert(ARG_BYTES >= 4 && ARG_BYTES <= 8 * 64, "argument block larger than the lines touched");
+  StepHead h;
+  if (TOUCH) {
+    int t0, t1, t2, t3, t4, t5, t6, t7;
+    asm volatile(
+        "s_load_dwordx2 %0, %12, 0x0\n\t"
+        "s_load_dwordx2 %1, %13, 0x0\n\t"
+        "s_load_dword %2, %14, 0x0\n\t"
+        "s_load_dword %3, %15, 0x0\n\t"
+        "s_load_dword %4, %16, %17\n\t"
+        "s_load_dword %5, %16, %18\n\t"
+        "s_load_dword %6, %16, %19\n\t"
+        "s_load_dword %7, %16, %20\n\t"
+        "s_load_dword %8, %16, %21\n\t"
+        "s_load_dword %9, %16, %22\n\t"
+        "s_load_dword %10, %16, %23\n\t"
+        "s_load_dword %11, %16, %24\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&s"(h.len), "=&s"(h.base), "=&s"(h.n_prompt), "=&s"(h.mask_word), "=&s"(t0), "=&s"(t1), "=&s"(t2),
+          "=&s"(t3), "=&s"(t4), "=&s"(t5), "=&s"(t6), "=&s"(t7)
+        : "s"(len_p), "s"(base_p), "s"(n_prompt_p), "s"(mask_word_p), "s"(ka), PT_TOUCH_OFFSETS
+        : "memory");
+  } else {
+    asm volatile(
+        "s_load_dwordx2 %0, %4, 0x0\n\t"
+        "s_load_dwordx2 %1, %5, 0x0\n\t"
+        "s_load_dword %2, %6, 0x0\n\t"
+        "s_load_dword %3, %7, 0x0\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&s"(h.len), "=&s"(h.base), "=&s"(h.n_prompt), "=&s"(h.mask_word)
+        : "s"(len_p), "s"(base_p), "s"(n_prompt_p), "s"(mask_word_p)
+        : "memory");
+  }
+  return h;
+}
+
+// a compact list's entry for this row, with the argument-block lines (the counters depend on it,
+// so they follow in a second round trip)
+template <int ARG_BYTES>
+__device__ inline int load_row_id(const int* id_p, KernargPtr ka) {
+  static_assert(ARG_BYTES >= 4 && ARG_BYTES <= 8 * 64, "argument block larger than the lines touched");
+  int id, t0, t1, t2, t3, t4, t5, t6, t7;
+  asm volatile(
+      "s_load_dword %0, %9, 0x0\n\t"
+      "s_load_dword %1, %10, %11\n\t"
+      "s_load_dword %2, %10, %12\n\t"
+      "s_load_dword %3, %10, %13\n\t"
+      "s_load_dword %4, %10, %14\n\t"
+      "s_load_dword %5, %10, %15\n\t"
+      "s_load_dword %6, %10, %16\n\t"
+      "s_load_dword %7, %10, %17\n\t"
+      "s_load_dword %8, %10, %18\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&s"(id), "=&s"(t0), "=&s"(t1), "=&s"(t2), "=&s"(t3), "=&s"(t4), "=&s"(t5), "=&s"(t6), "=&s"(t7)
+      : "s"(id_p), "s"(ka), PT_TOUCH_OFFSETS
+      : "memory");
+  return id;
 }
 
 struct StepArgs {
@@ -397,18 +495,27 @@ __device__ inline void encode_finish(const PtDev& c, StepSmem<WAVES>& sm, int b,
 }
 
 template <bool NT, int WAVES, bool MASS>
-__global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, StepArgs a) {
+__global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
+    // what the walk cannot start without comes first, as plain scalars: the build asks for these
+    // leading arguments to be preloaded into registers at wavefront launch, so the counters are
+    // fetched without first waiting for the argument block (one round trip to memory less per step)
+    const int* ids, const uint8_t* active, const long long* len_cur, const long long* base_cur,
+    const int* n_prompt, int n_rollouts, int n_kv_heads, PtDev c, StepArgs a) {
   constexpr int kWaves = WAVES;
   __shared__ StepSmem<WAVES> sm;
   __shared__ int sm_ticket;
   extern __shared__ __align__(16) float dyn_lds[];   // MASS only: parked masses
 
   // row j of the launch (and of q / k / v / out) is rollout b: j itself, or ids[j] for a compact list
-  const int j_row = blockIdx.x / c.Hkv, hkv = blockIdx.x - j_row * c.Hkv, split = blockIdx.y;
+  const int j_row = blockIdx.x / n_kv_heads, hkv = blockIdx.x - j_row * n_kv_heads, split = blockIdx.y;
+  // explicit arguments: 12 preloaded dwords, then the two blocks
+  constexpr int kArgBytes = 48 + (int)sizeof(PtDev) + (int)sizeof(StepArgs);
+  static_assert(sizeof(PtDev) % 8 == 0 && sizeof(StepArgs) % 8 == 0, "argument blocks are laid out back to back");
+  const KernargPtr ka = (const void*)__builtin_amdgcn_kernarg_segment_ptr();
   int b = j_row;
-  if (a.ids) {
-    b = ld_uniform(a.ids + j_row);
-    if ((unsigned)b >= (unsigned)c.B) {            // never index with a bad id: flag it and leave
+  if (ids) {
+    b = load_row_id<kArgBytes>(ids + j_row, ka);
+    if ((unsigned)b >= (unsigned)n_rollouts) {            // never index with a bad id: flag it and leave
       if (threadIdx.x == 0 && hkv == 0 && split == 0) atomicOr(c.err, PTENC_DEVERR_BAD_ID);
       return;
     }
@@ -419,10 +526,15 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
   const int ns = c.n_splits;   // window splits
   const int n = lane & 15, kgrp = lane >> 4;
   const int g = c.group;
-  const bool act = !a.active || ld_uniform(a.active + b);
+  const uintptr_t mask_addr = (uintptr_t)(active + b);
+  const uint32_t* mask_word_p = active ? (const uint32_t*)(mask_addr & ~(uintptr_t)3) : (const uint32_t*)(n_prompt + b);
+  const StepHead head = ids ? load_step_head<kArgBytes, false>(len_cur + b, base_cur + b, n_prompt + b, mask_word_p, ka)
+                            : load_step_head<kArgBytes, true>(len_cur + b, base_cur + b, n_prompt + b, mask_word_p, ka);
+  if (head.len < head.base) return;      // counters that no sequence of calls produces: leave everything alone
+  const bool act = !active || ((head.mask_word >> (8 * (int)(mask_addr & 3))) & 0xffu) != 0;
 
   // counters as the step finds them, and as it leaves them
-  const long long len0 = ld_uniform(c.len + b), base0 = ld_uniform(c.base + b);
+  const long long len0 = head.len, base0 = head.base;
   const bool evicting = act && a.do_evict && (len0 - base0 == c.Wr);
   const long long base1 = base0 + (evicting ? c.C : 0);
   const bool append_full = act && a.do_append && (len0 - base1 >= c.Wr);
@@ -431,7 +543,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
 
   // what this step attends over, as a walk over 32-slot groups: first the groups of the question
   // tokens (slots 0 .. P-1), then the ring of thinking tokens from its oldest live slot
-  const int P = act ? ld_uniform(c.n_prompt + b) : 0;
+  const int P = act ? head.n_prompt : 0;
   const int n_live = act ? (int)(len1 - base1) : 0;
   // ring-relative slots from ONE division (64-bit only when a counter has outgrown 32 bits; the walk
   // cannot start before these are known): the oldest position before this step's eviction, the oldest
@@ -537,7 +649,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(PtDev c, Ste
         // (saved by the step that left len == len0, in the buffer of that parity; the addresses are valid
         // whether or not anything waits to be folded)
         mass_slab = c.mass + (size_t)slab * c.W;
-        const long long tag = ld_uniform(c.mtag + slab);
+        const long long tag = ld_scalar(c.mtag + slab);
         const int par = (int)(len0 & 1), hl = (n >= 8 && n - 8 < g) ? n - 8 : 0;
         const uint16_t* qb = c.qprev + (((size_t)par * c.B + b) * c.Hq + hkv * g + hl) * 128;
         const float* mlb = c.mlprev + (((size_t)par * c.B + b) * c.Hq + hkv * g + hl) * 2;
@@ -816,18 +928,18 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bo
     // parked masses of every group a workgroup may walk
     const size_t park = (size_t)(cc.W / PT_GROUP_TOKENS + 2) * PT_GROUP_TOKENS * sizeof(float);
     if (waves == 8) {
-      if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 8, true>), grid, dim3(512), park, s, cc, a);
-      else hipLaunchKernelGGL((decode_mfma_kernel<false, 8, true>), grid, dim3(512), park, s, cc, a);
+      if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 8, true>), grid, dim3(512), park, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, cc, a);
+      else hipLaunchKernelGGL((decode_mfma_kernel<false, 8, true>), grid, dim3(512), park, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, cc, a);
     } else {
-      if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 4, true>), grid, dim3(256), park, s, cc, a);
-      else hipLaunchKernelGGL((decode_mfma_kernel<false, 4, true>), grid, dim3(256), park, s, cc, a);
+      if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 4, true>), grid, dim3(256), park, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, cc, a);
+      else hipLaunchKernelGGL((decode_mfma_kernel<false, 4, true>), grid, dim3(256), park, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, cc, a);
     }
   } else if (waves == 8) {
-    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 8, false>), grid, dim3(512), 0, s, cc, a);
-    else hipLaunchKernelGGL((decode_mfma_kernel<false, 8, false>), grid, dim3(512), 0, s, cc, a);
+    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 8, false>), grid, dim3(512), 0, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, cc, a);
+    else hipLaunchKernelGGL((decode_mfma_kernel<false, 8, false>), grid, dim3(512), 0, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, cc, a);
   } else {
-    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 4, false>), grid, dim3(256), 0, s, cc, a);
-    else hipLaunchKernelGGL((decode_mfma_kernel<false, 4, false>), grid, dim3(256), 0, s, cc, a);
+    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 4, false>), grid, dim3(256), 0, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, cc, a);
+    else hipLaunchKernelGGL((decode_mfma_kernel<false, 4, false>), grid, dim3(256), 0, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, cc, a);
   }
   return hipGetLastError();
 }
