@@ -366,7 +366,9 @@ struct StepArgs {
   uint16_t* dbg_chunk;     // [B, 2, C, H_kv*128] or null
   const int* ids;          // null, or the rollouts this launch works on: row j of q/k/v/out is rollout ids[j]
   int do_evict, do_append, do_attend;
-  int in_place;            // counters written in place by the rollout's last workgroup (compact lists; graph replay)
+  int in_place;            // counters written in place by the rollout's last workgroup (graph replay)
+  int carry;               // compact list with two counter buffers: one extra workgroup carries every
+                           // rollout's counters over to the buffer this step writes (see the kernel)
 };
 
 // WAVES wavefronts per workgroup: 4 (up to 16 query heads per KV head) or 8 (up to 8), the same LDS.
@@ -500,7 +502,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
     // leading arguments to be preloaded into registers at wavefront launch, so the counters are
     // fetched without first waiting for the argument block (one round trip to memory less per step)
     const int* ids, const uint8_t* active, const long long* len_cur, const long long* base_cur,
-    const int* n_prompt, int n_rollouts, int n_kv_heads, PtDev c, StepArgs a) {
+    const int* n_prompt, int n_rollouts, int n_kv_heads, int n_rows, PtDev c, StepArgs a) {
   constexpr int kWaves = WAVES;
   __shared__ StepSmem<WAVES> sm;
   __shared__ int sm_ticket;
@@ -508,8 +510,22 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
 
   // row j of the launch (and of q / k / v / out) is rollout b: j itself, or ids[j] for a compact list
   const int j_row = blockIdx.x / n_kv_heads, hkv = blockIdx.x - j_row * n_kv_heads, split = blockIdx.y;
-  // explicit arguments: 12 preloaded dwords, then the two blocks
-  constexpr int kArgBytes = 48 + (int)sizeof(PtDev) + (int)sizeof(StepArgs);
+  if (j_row >= n_rows) {
+    // The one workgroup beyond the listed rows (compact list, two counter buffers).  A listed rollout's
+    // workgroup puts its new counters into the buffer this step writes; the unlisted rollouts' counters
+    // must arrive there too, unchanged.  Counters only grow between resets (which clear both buffers), so
+    // "the larger of what is there and the current value" is right for listed and unlisted rollouts in
+    // either order of arrival: no workgroup waits for another one.
+    if (split == 0) {
+      for (int r = threadIdx.x; r < n_rollouts; r += WAVES * 64) {
+        atomicMax(c.len_nx + r, len_cur[r]);
+        atomicMax(c.base_nx + r, base_cur[r]);
+      }
+    }
+    return;
+  }
+  // explicit arguments: 13 preloaded dwords (padded to 56 bytes), then the two blocks
+  constexpr int kArgBytes = 56 + (int)sizeof(PtDev) + (int)sizeof(StepArgs);
   static_assert(sizeof(PtDev) % 8 == 0 && sizeof(StepArgs) % 8 == 0, "argument blocks are laid out back to back");
   const KernargPtr ka = (const void*)__builtin_amdgcn_kernarg_segment_ptr();
   int b = j_row;
@@ -852,8 +868,13 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
   const bool advancing = a.do_evict || a.do_append;
   const bool in_place = a.in_place != 0;
   if (advancing && !in_place && hkv == 0 && split == 0 && tid == 0) {
-    c.len_nx[b] = len1;
-    c.base_nx[b] = base1;
+    if (a.carry) {             // commutes with the carrying workgroup's update of the same entry
+      atomicMax(c.len_nx + b, len1);
+      atomicMax(c.base_nx + b, base1);
+    } else {
+      c.len_nx[b] = len1;
+      c.base_nx[b] = base1;
+    }
   }
 
   // ---- whoever finishes last for this rollout completes the encoding, and, under the scored policy,
@@ -913,7 +934,8 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bo
                                  void* dbg_chunk, const int* ids, int n_rows, bool in_place, hipStream_t s) {
   StepArgs a;
   a.ids = ids;
-  a.in_place = (ids != nullptr || in_place) ? 1 : 0;
+  a.in_place = in_place ? 1 : 0;
+  a.carry = (ids != nullptr && !in_place) ? 1 : 0;
   a.q = (const uint16_t*)q; a.out = (uint16_t*)out;
   a.knew = (const uint16_t*)k; a.vnew = (const uint16_t*)v;
   a.active = active; a.dbg_chunk = (uint16_t*)dbg_chunk;
@@ -921,25 +943,26 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bo
   // without attention there is nothing to split
   PtDev cc = c;
   if (!do_attend) cc.n_splits = 1;
-  dim3 grid((ids ? n_rows : cc.B) * cc.Hkv, cc.n_splits);
+  const int rows = ids ? n_rows : cc.B;
+  dim3 grid(rows * cc.Hkv + (a.carry ? 1 : 0), cc.n_splits);
   // scores are maintained by whole steps only (append + attention) under the scored policy
   const bool mass = cc.scored && do_append && do_attend;
   if (mass) {
     // parked masses of every group a workgroup may walk
     const size_t park = (size_t)(cc.W / PT_GROUP_TOKENS + 2) * PT_GROUP_TOKENS * sizeof(float);
     if (waves == 8) {
-      if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 8, true>), grid, dim3(512), park, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, cc, a);
-      else hipLaunchKernelGGL((decode_mfma_kernel<false, 8, true>), grid, dim3(512), park, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, cc, a);
+      if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 8, true>), grid, dim3(512), park, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, rows, cc, a);
+      else hipLaunchKernelGGL((decode_mfma_kernel<false, 8, true>), grid, dim3(512), park, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, rows, cc, a);
     } else {
-      if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 4, true>), grid, dim3(256), park, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, cc, a);
-      else hipLaunchKernelGGL((decode_mfma_kernel<false, 4, true>), grid, dim3(256), park, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, cc, a);
+      if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 4, true>), grid, dim3(256), park, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, rows, cc, a);
+      else hipLaunchKernelGGL((decode_mfma_kernel<false, 4, true>), grid, dim3(256), park, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, rows, cc, a);
     }
   } else if (waves == 8) {
-    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 8, false>), grid, dim3(512), 0, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, cc, a);
-    else hipLaunchKernelGGL((decode_mfma_kernel<false, 8, false>), grid, dim3(512), 0, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, cc, a);
+    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 8, false>), grid, dim3(512), 0, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, rows, cc, a);
+    else hipLaunchKernelGGL((decode_mfma_kernel<false, 8, false>), grid, dim3(512), 0, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, rows, cc, a);
   } else {
-    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 4, false>), grid, dim3(256), 0, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, cc, a);
-    else hipLaunchKernelGGL((decode_mfma_kernel<false, 4, false>), grid, dim3(256), 0, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, cc, a);
+    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 4, false>), grid, dim3(256), 0, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, rows, cc, a);
+    else hipLaunchKernelGGL((decode_mfma_kernel<false, 4, false>), grid, dim3(256), 0, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, rows, cc, a);
   }
   return hipGetLastError();
 }

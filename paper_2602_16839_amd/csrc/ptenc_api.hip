@@ -77,14 +77,14 @@ bool mfma_attn_applies(const ptenc_config& c) {
 }
 
 // Window splits.  Splitting a (rollout, KV head) row over several workgroups costs a round trip
-// through memory for the partial results, and measured on MI355X one workgroup per row wins as
-// soon as there are about a hundred rows (even with half the CUs idle).  Below that, split until
-// about 128 workgroups exist, but never below 256 tokens per split.
+// through memory for the partial results; it pays while the launch has fewer workgroups than the
+// chip has CUs.  Measured on MI355X (2 KV heads, windows of 1024 and 2048, both interfaces): from
+// 60 rows up the best count is the largest one that keeps rows x splits within about 240 workgroups
+// (one split from 121 rows), below that about 128 workgroups; never fewer than 256 tokens per split.
 int heuristic_splits(const ptenc_ctx* x, long n_rollouts) {
   const ptenc_config& c = x->cfg;
   const long rows = n_rollouts * (x->attn_kernel ? c.n_kv_heads : c.n_q_heads);
-  if (rows >= 96) return 1;
-  long want = (128 + rows - 1) / rows;
+  long want = rows >= 60 ? 240 / rows : (128 + rows - 1) / rows;
   long cap = (c.window - c.n_sink) / 256;
   if (cap < 1) cap = 1;
   if (want > cap) want = cap;
@@ -411,9 +411,15 @@ ptenc_status ptenc_decode_step_ids(ptenc_ctx* ctx, const void* d_q, const void* 
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_q | (uintptr_t)d_out | (uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
     if (refresh_selection(ctx, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
-    // counters are written in place by this launch: no buffer rotation
-    return hip_status(pt_launch_decode_mfma(d, ctx->nontemporal != 0, pick_waves(ctx, n, d.n_splits), true, true, true,
-                                            d_q, d_k, d_v, d_out, nullptr, nullptr, d_ids, n, true, S(stream)));
+    // listed rollouts advance into the other counter buffer, the rest are carried over to it (or, with
+    // counters in place, the rollout's last workgroup writes them where they are)
+    // what this launch streams is the listed rollouts' share of the cache: once that fits the memory-side
+    // cache, ordinary loads (which allocate there) serve the next step better than non-temporal ones
+    bool nt = ctx->nontemporal != 0;
+    if (ctx->opt_nontemporal < 0) nt = ctx->cache_bytes / (size_t)ctx->cfg.batch * (size_t)n > ((size_t)192 << 20);
+    return advanced(ctx, pt_launch_decode_mfma(d, nt, pick_waves(ctx, n, d.n_splits), true, true, true,
+                                               d_q, d_k, d_v, d_out, nullptr, nullptr, d_ids, n, ctx->opt_in_place != 0,
+                                               S(stream)));
   }
   hipError_t e = pt_launch_step_prologue(d, true, true, d_k, d_v, nullptr, nullptr, d_ids, n, true, S(stream));
   if (e != hipSuccess) return PTENC_ERR_HIP;
@@ -495,6 +501,9 @@ ptenc_status ptenc_set_counters(ptenc_ctx* ctx, const int64_t* h_len, const int6
   const size_t n = sizeof(long long) * ctx->cfg.batch;
   if (hipMemcpyAsync(ctx->dev.len, h_len, n, hipMemcpyHostToDevice, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
   if (hipMemcpyAsync(ctx->dev.base, h_base, n, hipMemcpyHostToDevice, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
+  // the other buffer too: a compact-list step merges into it by maximum, and the new values may be lower
+  if (hipMemcpyAsync(ctx->dev.len_nx, h_len, n, hipMemcpyHostToDevice, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
+  if (hipMemcpyAsync(ctx->dev.base_nx, h_base, n, hipMemcpyHostToDevice, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
   // the host arrays may be pageable and reused by the caller right after return
   return hip_status(hipStreamSynchronize(S(stream)));
 }
