@@ -236,13 +236,7 @@ __device__ inline void patch_newest(Frag& f, const Op kp[4], const uint32_t vp[4
 // shares) is written and read with device-scope relaxed atomics: such stores write through and
 // such loads bypass the per-CU and per-XCD caches, so the hand-over needs no cache write-back or
 // invalidation.  Order is given by: stores, wait for them (workgroup fence), barrier, ticket.
-__device__ inline float ld_agent(const float* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ inline void st_agent(float* p, float v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-// two adjacent floats (8-byte aligned) as one 64-bit access
+// (two adjacent floats, 8-byte aligned, as one 64-bit access)
 __device__ inline void st_agent2(float* p, float a, float b) {
   const unsigned long long u = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
   __hip_atomic_store((unsigned long long*)p, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -104,6 +104,7 @@ __host__ __device__ inline size_t pt_slab_elems(int W, int d) { return (size_t)2
 __host__ __device__ inline int pt_share_rows(int C) { return ((C + 31) / 32 + 1) * 32; }
 
 __host__ __device__ inline size_t pt_k_off(int tiled, int W, int d, int slot, int i) {
+  (void)W;   // same signature as pt_v_off, whose row-major form needs it
   if (!tiled) return (size_t)slot * d + i;
   const int grp = slot >> 5, tl = slot & 31;
   const int t = tl >> 4, m = tl & 15;
