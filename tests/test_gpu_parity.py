@@ -190,6 +190,48 @@ def test_compact_rollout_lists_equal_masked_decoding(kind):
     assert torch.equal(torch.cat(outs), out) and np.array_equal(layer2.get_state(), layer.get_state())
 
 
+@pytest.mark.parametrize("kind,in_place", [("mfma", 0), ("mfma", 1), ("generic_bf16", 0), ("f32", 0)])
+def test_rollouts_pause_and_resume_in_compact_lists(kind, in_place):
+    # every step lists a random subset in random order (some steps nobody, some everybody), and every
+    # tenth step is a masked full-batch step: a rollout's counters must survive any number of steps it
+    # sits out, whichever interface the steps in between went through
+    from paper_2602_16839_amd import ptenc
+    if kind == "f32":
+        wl = small("tiny_f32", batch=7, window=32, chunk=8, steps=140)
+        kw = {}
+    else:
+        wl = small("ragged", batch=7, n_q_heads=8, n_kv_heads=2, window=32, chunk=8, steps=140)
+        kw = dict(force_generic=(kind == "generic_bf16"))
+    enc = I.encoder_params(wl)
+    orc = H.make_oracle(wl, enc)
+    layer = H.make_layer(wl, enc, **kw)
+    if in_place:
+        layer.set_option(ptenc.OPT_COUNTERS_IN_PLACE, 1)
+    q, k, v = I.qkv_steps(wl, 0, wl.steps)
+    rng = np.random.default_rng(77)
+    abs_tol, rel_tol = H.tolerances(wl)
+    for t in range(wl.steps):
+        p = rng.choice([0.0, 0.15, 0.5, 0.9, 1.0])
+        act = rng.random(wl.batch) < p
+        ref = orc.step(H.f64(q[t]), H.f64(k[t]), H.f64(v[t]), act)
+        if t % 10 == 9:
+            out = layer.step(q[t].cuda(), k[t].cuda(), v[t].cuda(), active=torch.from_numpy(act.astype(np.uint8)).cuda())
+            got, want = H.f64(out), ref
+        else:
+            idx = rng.permutation(np.nonzero(act)[0])
+            it = torch.from_numpy(idx)
+            out = layer.step_ids(q[t][it].cuda(), k[t][it].cuda(), v[t][it].cuda(), it.to(torch.int32).cuda())
+            got, want = H.f64(out), ref[idx]
+        if got.size:
+            H.assert_close(got, want, abs_tol, rel_tol, "outputs at step %d" % t)
+        ln, base = layer.counters()
+        oln, obase = orc.counters()
+        assert np.array_equal(ln, oln) and np.array_equal(base, obase), "counters at step %d" % t
+    assert (orc.counters()[1] > 0).any()          # some rollout did evict
+    H.assert_close(layer.get_state(), orc.state(), H.S_ABS, H.S_REL, "state S")
+    assert layer.poll_error() == 0
+
+
 def test_bad_rollout_id_is_flagged_and_skipped():
     from paper_2602_16839_amd import ptenc
     wl = small("ragged", batch=4, n_q_heads=8, n_kv_heads=2, window=32, chunk=8, steps=4)
