@@ -22,12 +22,14 @@
 // Window splits are merged by whichever workgroup of the (rollout, KV head) finishes last
 // (a counter, no waiting), in split order, so the result does not depend on the arrival order.
 //
-// Eviction.  The encoder sums over the concatenated KV heads, so the workgroup of KV head h
-// (last split) computes only its head's share of K_a = K_e W^a_K and V_a = V_e W^a_V with MFMA
-// and parks it in scratch; whichever workgroup of the rollout finishes last adds the shares in
-// head order, forms S' = (Q_a K_a^T) V_a and updates S.  The head's share is read before the same
-// workgroup overwrites the oldest slot with the new token, and the attention of this step
-// already runs on the window without the evicted chunk.
+// Eviction.  The encoder sums over the concatenated KV heads, so a rollout's chunk is folded into S by
+// ONE workgroup that reads all heads (encode_rollout: K_a = K_e W^a_K and V_a = V_e W^a_V with MFMA,
+// then S' = (Q_a K_a^T) V_a and the update of S in fp32).  Launches that may evict carry one such
+// workgroup per row behind the attention workgroups in the grid; where nothing is full it leaves at
+// once.  It shares nothing with the rollout's attention workgroups, which already walk the window
+// without the chunk and take the new token from the step's inputs, so an eviction lengthens nobody's
+// walk (rollouts of a running batch do not evict in the same step).  The new token goes into the
+// chunk's oldest slot, so the encoding workgroup stores it itself, after its last read of the chunk.
 //
 // Counters are double-buffered: a step reads (len, base) from one pair of arrays and writes the
 // other, so no workgroup has to wait for the rest of its rollout before the step can end.  (Compact
@@ -59,7 +61,6 @@ struct Frag {   // one 32-token group in registers: 64 VGPRs
   Op k0[4], k1[4], v[8];
 };
 
-constexpr int kEncWaves = 4;   // wavefronts of a workgroup that take part in the encoder's MFMA share
 constexpr int kORow = 132;   // padded fp32 row of the cross-wave merge buffer
 
 // NT = non-temporal loads: the stream is read once per step, so it should not displace anything
@@ -372,122 +373,237 @@ union StepSmem {
     float o[WAVES][64 / WAVES][kORow];
     float m[WAVES][64 / WAVES], l[WAVES][64 / WAVES];
   } merge;
-  uint16_t vstage[kEncWaves][4096];   // one group's V part per wavefront (encoder operand transposition)
-  EncTailSmem enc;   // Ka and Va (contiguous, >= G*r floats) double as the row-norm staging area
+  struct {           // the encoding workgroup of a rollout
+    uint16_t vstage[2][4096];   // one group's V part of one KV head, per V wavefront (operand transposition)
+    EncTailSmem tail;           // Ka and Va (contiguous, >= G*r floats) double as the row-norm staging area
+    float Qa[kEncMaxGR][kEncMaxGR + 1];   // Q_a, staged once
+  } enc;
   SelSmall sel;      // scored policy: the choice of the next victims, by the rollout's last workgroup
 };
 
-// This head's share of K_a and V_a for the chunk [base, base + C): rows j = logical token, RP columns.
-template <int WAVES>
-__device__ inline void encode_head_share(const PtDev& c, StepSmem<WAVES>& sm, const u32x4* __restrict__ slab_p,
-                                         int slab, int hkv, int s0, int lane, int wave) {
-  if (wave >= kEncWaves) return;
+// The evicted chunk of one rollout, by ONE workgroup that does nothing else in this launch, so that a
+// rollout's eviction is not on the path of its own or anybody's attention: K_a = K_e W^a_K and
+// V_a = V_e W^a_V over the concatenated KV heads (MFMA, accumulated over the heads in head order),
+// S' = (Q_a K_a^T) V_a, S <- Normalize(S + S')  (Our Approach, the Delta-W equation and the update rule).
+// The chunk is the ring-relative slots [s0, s0 + C) (wrapping), walked as 32-slot groups; rows of a group
+// outside the chunk count as zero.  Wavefronts 0..3 each own one 16-token tile of K_a or of V_a of the
+// group in hand; all wavefronts share the fp32 tail.
+//
+// ROLE 0: a K_a tile, 1: a V_a tile, 2: the tail only.  One instance per role, so that each keeps its own
+// operand buffer in registers; every instance passes the same barriers.
+template <int WAVES, int ROLE>
+__device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b, int s0, float sacc[16]) {
+  constexpr int THREADS = WAVES * 64;
+  constexpr int NP = ROLE == 0 ? 4 : 8;          // 16-byte pieces per lane, KV head and group
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 15, kgrp = lane >> 4;
-  const int g0 = s0 >> 5, off0 = s0 & 31, NG = c.Wr >> 5, gs = c.n_sink >> 5;   // s0: ring-relative slot
+  const int g0 = s0 >> 5, off0 = s0 & 31, NG = c.Wr >> 5, gs = c.n_sink >> 5;
   const int n_vis = (off0 + c.C + PT_GROUP_TOKENS - 1) >> 5;
-  // The share is indexed by p = 32 * visit + slot-in-group (logical token j = p - off0) and stored as
-  // [p / 4][column][p % 4], so that the 4 accumulator rows a lane holds for its column are 16
-  // contiguous bytes and a wavefront's store covers whole cache lines.
-  const int RP = c.n_rt * 16, PR = pt_share_rows(c.C);
-  float* partK = c.enc_part + (size_t)slab * 2 * PR * RP;
-  float* partV = partK + (size_t)PR * RP;
-  const u32x4* WKp = (const u32x4*)c.WKp + (size_t)hkv * 4 * 4 * 64;
-  const u32x4* WVp = (const u32x4*)c.WVp + (size_t)hkv * 4 * 4 * 64;
-  uint16_t* vs = sm.vstage[wave];
-  for (int vis = wave; vis < n_vis; vis += kEncWaves) {
+  const int t = wave & 1;
+  const size_t slab_u = pt_slab_elems(c.W, 128) / 8;                 // a slab in 16-byte units
+  const u32x4* cache0 = (const u32x4*)c.cache + (size_t)b * c.Hkv * slab_u;
+  const u32x4* Wp = (const u32x4*)(ROLE == 1 ? c.WVp : c.WKp);
+  // this lane's token within the group as the A-operand row, and where the V part keeps it
+  const int tl = t * 16 + n, vkg = (tl & 15) >> 2, ve = ((tl >> 4) << 2) | (tl & 3);
+  // Operands of a batch of HB KV heads of one group, all loads in flight together; the next batch (of
+  // this group or the next) is requested as soon as this one has been consumed, so its latency hides
+  // behind the arithmetic and the tail.
+  constexpr int HB = ROLE == 0 ? 4 : 2;
+  const int n_batches = (c.Hkv + HB - 1) / HB;
+  u32x4 buf[HB][NP];
+  auto load_batch = [&](int vis, int h0) {
     int pg = g0 + vis;
     if (pg >= NG) pg -= NG;
     if (pg >= NG) pg -= NG;
-    const u32x4* grp = slab_p + (size_t)(gs + pg) * (PT_GROUP_ELEMS / 8);
-    // V part -> LDS as stored (the operand needs 8 consecutive columns of one token, which the
-    // token-minor layout scatters)
 #pragma unroll
-    for (int i = 0; i < 8; ++i) ((u32x4*)vs)[i * 64 + lane] = grp[512 + i * 64 + lane];
-    __builtin_amdgcn_wave_barrier();
+    for (int hh = 0; hh < HB; ++hh) {
+      const int h = h0 + hh < c.Hkv ? h0 + hh : c.Hkv - 1;        // clamped: loaded, not used
+      const u32x4* grp = cache0 + (size_t)h * slab_u + (size_t)(gs + pg) * (PT_GROUP_ELEMS / 8);
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      Op ka[4], va[4];
-      const int tl = t * 16 + n;                       // this lane's token within the group (A-operand row)
-      const int vkg = (tl & 15) >> 2, ve = ((tl >> 4) << 2) | (tl & 3);
-#pragma unroll
-      for (int cc = 0; cc < 4; ++cc) {
-        ka[cc].u = grp[t * 256 + cc * 64 + lane];
-#pragma unroll
-        for (int x = 0; x < 8; ++x) {
-          const int i = cc * 32 + 8 * kgrp + x;        // value column
-          va[cc].s[x] = vs[(((i >> 4) * 4 + vkg) * 16 + (i & 15)) * 8 + ve];
-        }
-      }
-      for (int rt = 0; rt < c.n_rt; ++rt) {
-        f32x4 dk = {0.f, 0.f, 0.f, 0.f}, dv = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int cc = 0; cc < 4; ++cc) {
-          Op wk, wv;
-          wk.u = WKp[(cc * 4 + rt) * 64 + lane];
-          wv.u = WVp[(cc * 4 + rt) * 64 + lane];
-          dk = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[cc].h, wk.h, dk, 0, 0, 0);
-          dv = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va[cc].h, wv.h, dv, 0, 0, 0);
-        }
-        // D[token 4 kgrp + e][column n]: rows p = 32 vis + 16 t + 4 kgrp + e (rows outside the chunk are
-        // written too and never read)
-        const size_t o = ((size_t)(vis * 8 + t * 4 + kgrp) * RP + rt * 16 + n) * 4;
-        st_agent2(partK + o, dk[0], dk[1]);
-        st_agent2(partK + o + 2, dk[2], dk[3]);
-        st_agent2(partV + o, dv[0], dv[1]);
-        st_agent2(partV + o + 2, dv[2], dv[3]);
-      }
+      for (int i = 0; i < NP; ++i) buf[hh][i] = ROLE == 0 ? grp[t * 256 + i * 64 + lane] : grp[512 + i * 64 + lane];
     }
-    __builtin_amdgcn_wave_barrier();
-  }
-}
-
-// Last workgroup of a rollout: K_a, V_a = sum of the heads' shares (head order), S' = (Q_a K_a^T) V_a,
-// S <- Normalize(S + S').
-template <int WAVES>
-__device__ inline void encode_finish(const PtDev& c, StepSmem<WAVES>& sm, int b, int off0) {
-  constexpr int THREADS = WAVES * 64;
-  const int t = threadIdx.x;
-  const int RP = c.n_rt * 16, PR = pt_share_rows(c.C);
-  float sacc[16];
+  };
+  if (ROLE != 2) load_batch(0, 0);
+  for (int vis = 0; vis < n_vis; ++vis) {
+    if (ROLE != 2) {
+      f32x4 acc[4];
 #pragma unroll
-  for (int x = 0; x < 16; ++x) sacc[x] = 0.f;
-  const float* part0 = c.enc_part + (size_t)b * c.Hkv * 2 * PR * RP;
-  // 32 rows of p at a time, from a multiple of 4; rows outside the chunk [off0, off0 + C) count as zero
-  for (int ps = off0 & ~3; ps < off0 + c.C; ps += kEncSub) {
-    // one item = (K_a or V_a, block of 4 rows, column): 16 bytes per head, all heads' loads in flight together
-    for (int idx = t; idx < 2 * 8 * RP; idx += THREADS) {
-      const int which = idx / (8 * RP), rem = idx - which * (8 * RP);
-      const int blk = rem / RP, col = rem - blk * RP;
-      float v[4] = {0.f, 0.f, 0.f, 0.f};
-      if (ps + 4 * blk < off0 + c.C) {
-        const size_t o = ((size_t)((ps >> 2) + blk) * RP + col) * 4;
-        for (int h0 = 0; h0 < c.Hkv; h0 += 4) {
-          float x[4][4];
+      for (int rt = 0; rt < 4; ++rt) acc[rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int bi = 0; bi < n_batches; ++bi) {
+        const int h0 = bi * HB;
 #pragma unroll
-          for (int hh = 0; hh < 4; ++hh) {
-            const int h = h0 + hh < c.Hkv ? h0 + hh : c.Hkv - 1;       // clamp: loaded, not added
-            const float* sp = part0 + (size_t)(h * 2 + which) * PR * RP + o;
-            ld_agent2(sp, x[hh][0], x[hh][1]);
-            ld_agent2(sp + 2, x[hh][2], x[hh][3]);
-          }
+        for (int hh = 0; hh < HB; ++hh) {
+          const int h = h0 + hh;
+          if (h < c.Hkv) {
+            Op op[4];
+            if (ROLE == 0) {
 #pragma unroll
-          for (int hh = 0; hh < 4; ++hh)
-            if (h0 + hh < c.Hkv) {
+              for (int cc = 0; cc < 4; ++cc) op[cc].u = buf[hh][cc];
+            } else {
+              // V part -> LDS as stored (the operand needs 8 consecutive columns of one token, which the
+              // token-minor layout scatters)
+              uint16_t* vs = sm.enc.vstage[t];
 #pragma unroll
-              for (int e = 0; e < 4; ++e) v[e] += x[hh][e];
+              for (int i = 0; i < NP; ++i) ((u32x4*)vs)[i * 64 + lane] = buf[hh][i];
+              __builtin_amdgcn_wave_barrier();
+#pragma unroll
+              for (int cc = 0; cc < 4; ++cc) {
+#pragma unroll
+                for (int x = 0; x < 8; ++x) {
+                  const int i = cc * 32 + 8 * kgrp + x;        // value column
+                  op[cc].s[x] = vs[(((i >> 4) * 4 + vkg) * 16 + (i & 15)) * 8 + ve];
+                }
+              }
+              __builtin_amdgcn_wave_barrier();                 // the next head overwrites the staging area
             }
-        }
-      }
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int p = ps + 4 * blk + e;
-        (which == 0 ? sm.enc.Ka : sm.enc.Va)[4 * blk + e][col] = (p >= off0 && p < off0 + c.C) ? v[e] : 0.f;
+            for (int rt = 0; rt < 4; ++rt) {
+              if (rt < c.n_rt) {
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) {
+                  Op w;
+                  w.u = Wp[(((size_t)h * 4 + cc) * 4 + rt) * 64 + lane];
+                  acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(op[cc].h, w.h, acc[rt], 0, 0, 0);
+                }
+              }
+            }
+          }
+        }
+        if (bi + 1 < n_batches) load_batch(vis, h0 + HB);
+        else if (vis + 1 < n_vis) load_batch(vis + 1, 0);
+      }
+      // D[token 4 kgrp + e of the tile][column 16 rt + n]
+      float (*dst)[kEncMaxGR + 1] = ROLE == 1 ? sm.enc.tail.Va : sm.enc.tail.Ka;
+#pragma unroll
+      for (int rt = 0; rt < 4; ++rt) {
+        if (rt < c.n_rt) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int row = 16 * t + 4 * kgrp + e, pl = 32 * vis + row;      // place counted from the first group
+            dst[row][rt * 16 + n] = (pl >= off0 && pl < off0 + c.C) ? acc[rt][e] : 0.f;
+          }
+        }
       }
     }
     __syncthreads();
-    pt_encode_accumulate<THREADS>(sm.enc, c.Qa, c.G, c.r, kEncSub, sacc);
+    pt_encode_accumulate<THREADS>(sm.enc.tail, &sm.enc.Qa[0][0], kEncMaxGR + 1, c.G, c.r, sacc);   // ends with a barrier
   }
-  pt_state_update<THREADS>(c, b, sacc, &sm.enc.Ka[0][0], sm.enc.red);
+}
+
+template <int WAVES>
+__device__ inline void encode_rollout(const PtDev& c, StepSmem<WAVES>& sm, int b, int s0) {
+  const int wave = threadIdx.x >> 6;
+  float sacc[16];
+#pragma unroll
+  for (int x = 0; x < 16; ++x) sacc[x] = 0.f;
+  pt_encode_stage_qa<WAVES * 64>(sm.enc.Qa, c.Qa, c.G, c.r);
+  if (wave >= 4) encode_groups<WAVES, 2>(c, sm, b, s0, sacc);
+  else if (wave & 2) encode_groups<WAVES, 1>(c, sm, b, s0, sacc);
+  else encode_groups<WAVES, 0>(c, sm, b, s0, sacc);
+  pt_state_update<WAVES * 64>(c, b, sacc, &sm.enc.tail.Ka[0][0], sm.enc.tail.red);
+}
+
+// What a step does to one rollout, from the counters it finds.  Both kinds of workgroup of a rollout
+// (the attention ones and the encoding one) derive it from the same values, so they agree on who
+// takes part in the arrival count below.
+struct StepPlan {
+  bool evicting, append_full, appending, will_select, need_ticket;
+  long long base1, len1;      // the counters as the step leaves them
+};
+template <bool MASS>
+__device__ inline StepPlan plan_step(const PtDev& c, const StepArgs& a, bool act, long long len0, long long base0) {
+  StepPlan p;
+  p.evicting = act && a.do_evict && (len0 - base0 == c.Wr);
+  p.base1 = base0 + (p.evicting ? c.C : 0);
+  p.append_full = act && a.do_append && (len0 - p.base1 >= c.Wr);
+  p.appending = act && a.do_append && !p.append_full;
+  p.len1 = len0 + (p.appending ? 1 : 0);
+  // scored policy: the step whose append fills the ring chooses the next victims at its end
+  p.will_select = MASS && p.appending && (p.len1 - p.base1 == c.Wr);
+  // something must happen after every workgroup of the rollout is through: counters written in place,
+  // or the choice of victims
+  p.need_ticket = (a.in_place != 0 && (p.appending || p.evicting)) || p.will_select;
+  return p;
+}
+
+// Arrival of one workgroup of rollout b (of `expected` in all); the last one to arrive chooses the next
+// victims (scored policy, ring just filled) and writes the counters where they are (in-place mode).
+template <int WAVES, bool MASS>
+__device__ inline void arrive_rollout(const PtDev& c, const StepArgs& a, StepSmem<WAVES>& sm, int& sm_ticket,
+                                      float* dyn_lds, int b, const StepPlan& pl, int expected) {
+  if (!pl.need_ticket) return;
+  // rare (once per C steps): the other workgroups' new token and score updates must be visible to the
+  // one that selects, whichever XCD each ran on: device-wide release here, acquire there
+  if (pl.will_select) __threadfence();
+  __threadfence_block();
+  __syncthreads();
+  if (threadIdx.x == 0) sm_ticket = atomicAdd(c.tick_rollout + b, 1);
+  __syncthreads();
+  if (sm_ticket != expected - 1) return;
+  if constexpr (MASS) {
+    if (pl.will_select) {
+      __threadfence();
+      pt_scored_select<WAVES * 64>(c, b, pl.base1, dyn_lds, sm.sel);
+    }
+  }
+  if (threadIdx.x == 0) {
+    if (a.in_place) { c.len[b] = pl.len1; c.base[b] = pl.base1; }
+    c.tick_rollout[b] = 0;
+  }
+}
+
+// The encoding workgroup of row j_row (launches that may evict have one per row, after the attention
+// workgroups in the grid): if the rollout's ring is full it folds the oldest chunk into S and then, the
+// chunk's oldest slot being free at last, stores the step's new token there.  The rollout's attention
+// workgroups meanwhile walk the window without the chunk and take the new token from the step's
+// inputs; nobody waits for anybody.
+template <int WAVES, bool MASS>
+__device__ inline void encoder_role(const PtDev& c, const StepArgs& a, StepSmem<WAVES>& sm, int& sm_ticket,
+                                    float* dyn_lds, int j_row, const int* ids, const uint8_t* active,
+                                    const long long* len_cur, const long long* base_cur) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, kgrp = lane >> 4;
+  int b = j_row;
+  if (ids) {
+    b = ld_uniform(ids + j_row);
+    if ((unsigned)b >= (unsigned)c.B) return;            // flagged by the row's attention workgroups
+  }
+  const bool act = !active || active[b] != 0;
+  const long long len0 = ld_scalar(len_cur + b), base0 = ld_scalar(base_cur + b);
+  if (len0 < base0) return;
+  const StepPlan pl = plan_step<MASS>(c, a, act, len0, base0);
+  if (pl.evicting) {
+    const int s0e = (int)(base0 % c.Wr);
+    encode_rollout<WAVES>(c, sm, b, s0e);
+    if (a.dbg_chunk) {
+      const int dkv = c.Hkv * 128;
+      uint16_t* dK = a.dbg_chunk + (size_t)b * 2 * c.C * dkv;
+      uint16_t* dV = dK + (size_t)c.C * dkv;
+      for (int idx = tid; idx < c.C * dkv; idx += WAVES * 64) {
+        const int j = idx / dkv, hi = idx - j * dkv, h = hi >> 7, i = hi & 127;
+        const uint16_t* src = (const uint16_t*)c.cache + (size_t)(b * c.Hkv + h) * pt_slab_elems(c.W, 128);
+        int slot = s0e + j; if (slot >= c.Wr) slot -= c.Wr;
+        slot += c.n_sink;
+        dK[idx] = src[pt_k_off(1, c.W, 128, slot, i)];
+        dV[idx] = src[pt_v_off(1, c.W, 128, slot, i)];
+      }
+    }
+    __syncthreads();   // every read of the chunk is done: its oldest slot may take the new token
+    if (pl.appending) {
+      int s0 = s0e + c.C;
+      if (s0 >= c.Wr) s0 -= c.Wr;
+      int s_new = s0 + (int)(len0 - pl.base1);
+      if (s_new >= c.Wr) s_new -= c.Wr;
+      for (int h = wave; h < c.Hkv; h += WAVES) {
+        Op kp[4];
+        uint32_t vp[4];
+        load_newest(kp, vp, a.knew, a.vnew, ((size_t)j_row * c.Hkv + h) * 128, n, kgrp);
+        store_newest((uint16_t*)c.cache + (size_t)(b * c.Hkv + h) * pt_slab_elems(c.W, 128), c.W, c.n_sink + s_new, kp, vp,
+                     n, kgrp);
+      }
+    }
+    if (tid == 0 && !pl.will_select) c.selected[b] = 0;   // the chosen chunk has left
+  }
+  arrive_rollout<WAVES, MASS>(c, a, sm, sm_ticket, dyn_lds, b, pl, c.Hkv * c.n_splits + 1);
 }
 
 template <bool NT, int WAVES, bool MASS>
@@ -505,16 +621,21 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
   // row j of the launch (and of q / k / v / out) is rollout b: j itself, or ids[j] for a compact list
   const int j_row = blockIdx.x / n_kv_heads, hkv = blockIdx.x - j_row * n_kv_heads, split = blockIdx.y;
   if (j_row >= n_rows) {
-    // The one workgroup beyond the listed rows (compact list, two counter buffers).  A listed rollout's
-    // workgroup puts its new counters into the buffer this step writes; the unlisted rollouts' counters
-    // must arrive there too, unchanged.  Counters only grow between resets (which clear both buffers), so
-    // "the larger of what is there and the current value" is right for listed and unlisted rollouts in
-    // either order of arrival: no workgroup waits for another one.
-    if (split == 0) {
-      for (int r = threadIdx.x; r < n_rollouts; r += WAVES * 64) {
-        atomicMax(c.len_nx + r, len_cur[r]);
-        atomicMax(c.base_nx + r, base_cur[r]);
-      }
+    // beyond the attention workgroups: one encoding workgroup per row if the launch may evict, then ...
+    if (split != 0) return;
+    const int extra = blockIdx.x - n_rows * n_kv_heads;
+    if (a.do_evict && extra < n_rows) {
+      encoder_role<WAVES, MASS>(c, a, sm, sm_ticket, dyn_lds, extra, ids, active, len_cur, base_cur);
+      return;
+    }
+    // ... the one workgroup that carries counters over (compact list, two counter buffers).  A listed
+    // rollout's workgroup puts its new counters into the buffer this step writes; the unlisted rollouts'
+    // counters must arrive there too, unchanged.  Counters only grow between resets (which clear both
+    // buffers), so "the larger of what is there and the current value" is right for listed and unlisted
+    // rollouts in either order of arrival: no workgroup waits for another one.
+    for (int r = threadIdx.x; r < n_rollouts; r += WAVES * 64) {
+      atomicMax(c.len_nx + r, len_cur[r]);
+      atomicMax(c.base_nx + r, base_cur[r]);
     }
     return;
   }
@@ -545,11 +666,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
 
   // counters as the step finds them, and as it leaves them
   const long long len0 = head.len, base0 = head.base;
-  const bool evicting = act && a.do_evict && (len0 - base0 == c.Wr);
-  const long long base1 = base0 + (evicting ? c.C : 0);
-  const bool append_full = act && a.do_append && (len0 - base1 >= c.Wr);
-  const bool appending = act && a.do_append && !append_full;
-  const long long len1 = len0 + (appending ? 1 : 0);
+  const StepPlan pl = plan_step<MASS>(c, a, act, len0, base0);
+  const bool evicting = pl.evicting, append_full = pl.append_full, appending = pl.appending;
+  const long long base1 = pl.base1, len1 = pl.len1;
 
   // what this step attends over, as a walk over 32-slot groups: first the groups of the question
   // tokens (slots 0 .. P-1), then the ring of thinking tokens from its oldest live slot
@@ -569,41 +688,24 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
   const int n_visits = n_sink_vis + (n_live > 0 ? (off0 + n_live + PT_GROUP_TOKENS - 1) >> 5 : 0);
   const int per = (n_visits + ns - 1) / ns;
   const int v0 = split * per, v1 = min(n_visits, v0 + per);
-  // the split whose range ends with the newest position evicts / appends for this KV head
+  // the split whose range ends with the newest position appends for this KV head
   const bool owner = split == (n_visits > 0 ? (n_visits - 1) / per : 0);
 
   u32x4* slab_p = (u32x4*)((uint16_t*)c.cache + (size_t)slab * pt_slab_elems(c.W, 128));
 
-  if (owner && (evicting || appending)) {
-    if (evicting) {
-      encode_head_share(c, sm, slab_p, slab, hkv, s0e, lane, wave);
-      if (a.dbg_chunk) {
-        const int dkv = c.Hkv * 128;
-        const uint16_t* src = (const uint16_t*)slab_p;
-        uint16_t* dK = a.dbg_chunk + (size_t)b * 2 * c.C * dkv + hkv * 128;
-        uint16_t* dV = dK + (size_t)c.C * dkv;
-        for (int idx = tid; idx < c.C * 128; idx += kWaves * 64) {
-          const int j = idx >> 7, i = idx & 127;
-          int slot = s0e + j; if (slot >= c.Wr) slot -= c.Wr;
-          slot += c.n_sink;
-          dK[(size_t)j * dkv + i] = src[pt_k_off(1, c.W, 128, slot, i)];
-          dV[(size_t)j * dkv + i] = src[pt_v_off(1, c.W, 128, slot, i)];
-        }
-      }
-      __syncthreads();   // the chunk's oldest slot is about to be overwritten
-    }
-    if (appending && !a.do_attend && wave == 0) {
-      // append without attention: straight from the inputs (with attention the store happens after
-      // the walk, from the registers that also patch the last group)
-      Op kp[4];
-      uint32_t vp[4];
-      load_newest(kp, vp, a.knew, a.vnew, ((size_t)j_row * c.Hkv + hkv) * 128, n, kgrp);
-      store_newest((uint16_t*)slab_p, c.W, c.n_sink + s_new, kp, vp, n, kgrp);
-      if (c.scored && lane == 0) {            // a new token starts with no score
-        const int slot = c.n_sink + s_new;
-        c.mass[(size_t)slab * c.W + slot] = 0.f;
-        if (hkv == 0) c.pos[(size_t)b * c.W + slot] = len0;
-      }
+  // (an evicting rollout's chunk is folded into S, and its new token stored, by the row's encoding
+  // workgroup: see encoder_role)
+  if (owner && appending && !evicting && !a.do_attend && wave == 0) {
+    // append without attention: straight from the inputs (with attention the store happens after
+    // the walk, from the registers that also patch the last group)
+    Op kp[4];
+    uint32_t vp[4];
+    load_newest(kp, vp, a.knew, a.vnew, ((size_t)j_row * c.Hkv + hkv) * 128, n, kgrp);
+    store_newest((uint16_t*)slab_p, c.W, c.n_sink + s_new, kp, vp, n, kgrp);
+    if (c.scored && lane == 0) {            // a new token starts with no score
+      const int slot = c.n_sink + s_new;
+      c.mass[(size_t)slab * c.W + slot] = 0.f;
+      if (hkv == 0) c.pos[(size_t)b * c.W + slot] = len0;
     }
   }
   if (append_full && owner && hkv == 0 && tid == 0) atomicOr(c.err, PTENC_DEVERR_APPEND_FULL);
@@ -728,7 +830,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
       }
       // the store of the new token rides behind the walk: its inputs arrived long ago, and the
       // chunk of an evicting step was read before anything could overwrite its oldest slot
-      if (patch && wave == 0)
+      if (patch && wave == 0 && !evicting)
         store_newest((uint16_t*)slab_p, c.W, c.n_sink + s_new, kp, vp, n, kgrp);
       if constexpr (MASS) {
         if (patch && wave == 0) {
@@ -871,33 +973,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
     }
   }
 
-  // ---- whoever finishes last for this rollout completes the encoding, and, under the scored policy,
-  //      chooses the next victims as soon as this step's append has filled the ring (the scores a
-  //      selection may use are complete then; the step that evicts finds its victims in front) ----
-  const bool will_select = MASS && appending && (len1 - base1 == c.Wr);
-  if (evicting || (in_place && appending) || will_select) {
-    // rare (once per C steps): the other workgroups' new token and score updates must be visible to the
-    // one that selects, whichever XCD each ran on: device-wide release here, acquire there
-    if (will_select) __threadfence();
-    __threadfence_block();
-    __syncthreads();
-    if (tid == 0) sm_ticket = atomicAdd(c.tick_rollout + b, 1);
-    __syncthreads();
-    if (sm_ticket == c.Hkv * ns - 1) {
-      if (evicting) encode_finish(c, sm, b, s0e & 31);
-      if constexpr (MASS) {
-        if (will_select) {
-          __threadfence();
-          pt_scored_select<WAVES * 64>(c, b, base1, dyn_lds, sm.sel);
-        }
-      }
-      if (tid == 0) {
-        if (evicting && !will_select) c.selected[b] = 0;   // the chosen chunk has left
-        if (in_place) { c.len[b] = len1; c.base[b] = base1; }
-        c.tick_rollout[b] = 0;
-      }
-    }
-  }
+  // ---- arrival count of the rollout's workgroups, where the step needs one ----
+  arrive_rollout<WAVES, MASS>(c, a, sm, sm_ticket, dyn_lds, b, pl, c.Hkv * ns + (a.do_evict ? 1 : 0));
 }
 
 // W^a (row-major [H_kv*128, r]) -> MFMA B operands: [head][k-chunk c][column tile rt][lane][8],
@@ -938,7 +1015,8 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bo
   PtDev cc = c;
   if (!do_attend) cc.n_splits = 1;
   const int rows = ids ? n_rows : cc.B;
-  dim3 grid(rows * cc.Hkv + (a.carry ? 1 : 0), cc.n_splits);
+  // attention workgroups, then one encoding workgroup per row if the launch may evict, then the carrier
+  dim3 grid(rows * cc.Hkv + (do_evict ? rows : 0) + (a.carry ? 1 : 0), cc.n_splits);
   // scores are maintained by whole steps only (append + attention) under the scored policy
   const bool mass = cc.scored && do_append && do_attend;
   if (mass) {

@@ -71,7 +71,7 @@ __device__ void encode_chunk(EncSmem& sm, const Src& src, int n_tok, int dkv, in
       }
     }
     __syncthreads();
-    pt_encode_accumulate<kEncThreads>(sm.tail, Qa, G, r, ntok, sacc);
+    pt_encode_accumulate<kEncThreads>(sm.tail, Qa, r, G, r, sacc);      // rows of tokens beyond ntok are zero
   }
 }
 

@@ -16,28 +16,65 @@ struct EncTailSmem {
   float red[16];
 };
 
-// Thread t owns entries t, t+THREADS, ... of the row-major G x r accumulator sacc[16].
-// Ka / Va rows at and beyond ntok must be zero or are ignored.  Ends with a barrier.
+// Q_a (G x r, row-major in global memory) into an LDS array of rows of kEncMaxGR + 1 floats.  No
+// barrier: callers pass one before the first pt_encode_accumulate anyway.
 template <int THREADS>
-__device__ inline void pt_encode_accumulate(EncTailSmem& sm, const float* __restrict__ Qa, int G, int r,
-                                            int ntok, float sacc[16]) {
+__device__ inline void pt_encode_stage_qa(float (*dst)[kEncMaxGR + 1], const float* __restrict__ Qa, int G, int r) {
+  int g = threadIdx.x / r, a = threadIdx.x - g * r;
+  const int dg = THREADS / r, da = THREADS - dg * r;
+  for (int idx = threadIdx.x; idx < G * r; idx += THREADS) {
+    dst[g][a] = Qa[idx];
+    g += dg; a += da;
+    if (a >= r) { a -= r; ++g; }
+  }
+}
+
+// S' += (Q_a K_a^T) V_a for the 32 tokens whose K_a and V_a rows are in LDS (rows that hold no token
+// must be zero).  Qa: G rows of qa_stride floats, in LDS (staged) or in global memory.  Thread t owns
+// entries t, t+THREADS, ... of the row-major G x r accumulator sacc[16].  Ends with a barrier.  All loops have fixed trip counts or independent accumulators, so the LDS reads
+// of many terms are in flight together (the straightforward dot-product loops were latency-bound:
+// ~12 us per 32 tokens).
+template <int THREADS>
+__device__ inline void pt_encode_accumulate(EncTailSmem& sm, const float* Qa, int qa_stride, int G, int r,
+                                            float sacc[16]) {
   const int t = threadIdx.x;
-  for (int idx = t; idx < G * kEncSub; idx += THREADS) {   // P = Q_a K_a^T  (G x 32)
-    const int g = idx / kEncSub, tk = idx - g * kEncSub;
-    float p = 0.f;
-    if (tk < ntok)
-      for (int a = 0; a < r; ++a) p = fmaf(Qa[g * r + a], sm.Ka[tk][a], p);
-    sm.P[g][tk] = p;
+  {
+    // P = Q_a K_a^T (G x 32): entry t + THREADS x is (g = its index / 32, token = t % 32)
+    constexpr int NX = kEncMaxGR * kEncSub / THREADS, DG = THREADS / kEncSub;
+    const int tk = t & (kEncSub - 1), gq = t >> 5;
+    float p[NX];
+    int grow[NX];
+#pragma unroll
+    for (int x = 0; x < NX; ++x) { p[x] = 0.f; grow[x] = gq + DG * x < G ? gq + DG * x : 0; }   // clamped: computed, not stored
+#pragma unroll 4
+    for (int a = 0; a < r; ++a) {
+      const float ka = sm.Ka[tk][a];
+#pragma unroll
+      for (int x = 0; x < NX; ++x) p[x] = fmaf(Qa[grow[x] * qa_stride + a], ka, p[x]);
+    }
+#pragma unroll
+    for (int x = 0; x < NX; ++x)
+      if (gq + DG * x < G) sm.P[gq + DG * x][tk] = p[x];
   }
   __syncthreads();
+  {
+    // S' += P V_a (G x r)
+    int g = t / r, col = t - g * r;
+    const int dg = THREADS / r, dc = THREADS - dg * r;
 #pragma unroll
-  for (int x = 0; x < 4096 / THREADS; ++x) {                               // S' += P V_a  (G x r)
-    const int idx = t + THREADS * x;
-    if (idx < G * r) {
-      const int g = idx / r, col = idx - g * r;
-      float s = sacc[x];
-      for (int tk = 0; tk < ntok; ++tk) s = fmaf(sm.P[g][tk], sm.Va[tk][col], s);
-      sacc[x] = s;
+    for (int x = 0; x < 4096 / THREADS; ++x) {
+      if (THREADS * x < G * r) {                       // uniform
+        const bool mine = t + THREADS * x < G * r;
+        const int gg = mine ? g : 0, cc = mine ? col : 0;
+        // one chain over all tokens of the chunk, in order (rows of zeros leave it as it is), so S does
+        // not depend on how the chunk falls into groups of 32
+        float s = sacc[x];
+#pragma unroll
+        for (int tk = 0; tk < kEncSub; ++tk) s = fmaf(sm.P[gg][tk], sm.Va[tk][cc], s);
+        if (mine) sacc[x] = s;
+      }
+      g += dg; col += dc;
+      if (col >= r) { col -= r; ++g; }
     }
   }
   __syncthreads();

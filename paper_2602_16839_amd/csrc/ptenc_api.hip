@@ -66,11 +66,6 @@ size_t partial_bytes(const ptenc_config& c) {
   return align256((size_t)c.batch * c.n_q_heads * PTENC_MAX_SPLITS * (c.head_dim + 2) * sizeof(float));
 }
 
-size_t enc_part_bytes(const ptenc_config& c) {
-  const size_t n_rt = (c.rank + 15) / 16;
-  return align256((size_t)c.batch * c.n_kv_heads * 2 * pt_share_rows(c.chunk) * 16 * n_rt * sizeof(float));
-}
-
 bool mfma_attn_applies(const ptenc_config& c) {
   return c.dtype == PTENC_BF16 && c.head_dim == 128 && c.window % 32 == 0 && c.n_sink % 32 == 0 &&
          c.n_q_heads / c.n_kv_heads <= 16;
@@ -156,7 +151,7 @@ ptenc_status ptenc_query_sizes(const ptenc_config* cfg, size_t* cache_bytes, siz
                             elem_bytes(cfg->dtype));
   if (state_bytes) *state_bytes = state_layout(*cfg).total;
   if (scratch_bytes)
-    *scratch_bytes = partial_bytes(*cfg) + enc_part_bytes(*cfg);
+    *scratch_bytes = partial_bytes(*cfg);
   return PTENC_OK;
 }
 
@@ -194,7 +189,6 @@ ptenc_status ptenc_create(const ptenc_config* cfg, void* d_cache, void* d_state,
   d.len_nx = (long long*)(sp + L.len2); d.base_nx = (long long*)(sp + L.base2);
   d.n_prompt = (int*)(sp + L.n_prompt);
   d.partial = (float*)d_scratch;
-  d.enc_part = (float*)((char*)d_scratch + partial_bytes(*cfg));
   d.WaK = nullptr; d.WaV = nullptr;
   d.n_rt = (cfg->rank + 15) / 16;
   d.tick_rollout = (int*)(sp + L.tick_rollout); d.tick_slab = (int*)(sp + L.tick_slab);

@@ -39,7 +39,6 @@ struct PtDev {
   int* tick_slab;     // [B*H_kv]
   void* WKp;          // W^a_K, W^a_V repacked as MFMA B operands: [H_kv][4][4][64 lanes][8] bf16
   void* WVp;
-  float* enc_part;    // [B*H_kv][2][pt_share_rows(C)][16 n_rt]: each KV head's share of K_a and V_a
   // importance-based eviction (MFMA path only)
   int scored;         // 1: an eviction takes the lowest-scored tokens instead of the oldest
   int n_recent;       // most recent ring entries an eviction never takes
@@ -98,10 +97,6 @@ struct ptenc_ctx {
 #define PT_GROUP_ELEMS 8192      // 32 tokens * 128 * 2 (K and V)
 
 __host__ __device__ inline size_t pt_slab_elems(int W, int d) { return (size_t)2 * W * d; }
-
-// rows of a KV head's encoder share: the chunk's C tokens as whole 32-slot groups (one extra when the
-// chunk does not start on a group boundary)
-__host__ __device__ inline int pt_share_rows(int C) { return ((C + 31) / 32 + 1) * 32; }
 
 __host__ __device__ inline size_t pt_k_off(int tiled, int W, int d, int slot, int i) {
   (void)W;   // same signature as pt_v_off, whose row-major form needs it
