@@ -375,8 +375,7 @@ union StepSmem {
   } merge;
   struct {           // the encoding workgroup of a rollout
     uint16_t vstage[2][4096];   // one group's V part of one KV head, per V wavefront (operand transposition)
-    EncTailSmem tail;           // Ka and Va (contiguous, >= G*r floats) double as the row-norm staging area
-    float Qa[kEncMaxGR][kEncMaxGR + 1];   // Q_a, staged once
+    EncTailSmem tail;           // Ka and Va (contiguous, >= G*r floats) double as the staging area of S'
   } enc;
   SelSmall sel;      // scored policy: the choice of the next victims, by the rollout's last workgroup
 };
@@ -392,8 +391,7 @@ union StepSmem {
 // ROLE 0: a K_a tile, 1: a V_a tile, 2: the tail only.  One instance per role, so that each keeps its own
 // operand buffer in registers; every instance passes the same barriers.
 template <int WAVES, int ROLE>
-__device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b, int s0, float sacc[16]) {
-  constexpr int THREADS = WAVES * 64;
+__device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b, int s0) {
   constexpr int NP = ROLE == 0 ? 4 : 8;          // 16-byte pieces per lane, KV head and group
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 15, kgrp = lane >> 4;
@@ -424,6 +422,20 @@ __device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b,
     }
   };
   if (ROLE != 2) load_batch(0, 0);
+  // The fp32 tail on the matrix units as well (16x16x4 fp32 MFMA): wavefront w < ceil(G / 16) owns rows
+  // 16 w .. 16 w + 15 of S'.  Its slice of Q_a stays in registers: the B operand of k-step s is
+  // Q_a[16 w + lane % 16][4 s + lane / 16] (zero outside G x r).
+  const bool tail_wave = wave * 16 < c.G;
+  const int kq = lane >> 4;
+  float qreg[16];
+  f32x4 sp[4];                                       // S'[16 w + 4 (lane / 16) + e][16 ct + lane % 16]
+#pragma unroll
+  for (int x = 0; x < 16; ++x) {
+    const int g = wave * 16 + n, a = 4 * x + kq;
+    qreg[x] = (tail_wave && g < c.G && a < c.r) ? c.Qa[g * c.r + a] : 0.f;
+  }
+#pragma unroll
+  for (int ct = 0; ct < 4; ++ct) sp[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
   for (int vis = 0; vis < n_vis; ++vis) {
     if (ROLE != 2) {
       f32x4 acc[4];
@@ -486,21 +498,66 @@ __device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b,
       }
     }
     __syncthreads();
-    pt_encode_accumulate<THREADS>(sm.enc.tail, &sm.enc.Qa[0][0], kEncMaxGR + 1, c.G, c.r, sacc);   // ends with a barrier
+    if (tail_wave) {
+      // P^T = K_a Q_a^T for the two 16-token tiles: pt[t][e] = P[g = 16 w + lane % 16][token 16 t + 4 (lane / 16) + e]
+      f32x4 pt[2];
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        pt[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int x = 0; x < 16; ++x) {
+          if (x < 4 * c.n_rt)
+            pt[tt] = __builtin_amdgcn_mfma_f32_16x16x4f32(sm.enc.tail.Ka[16 * tt + n][4 * x + kq], qreg[x], pt[tt], 0, 0, 0);
+        }
+      }
+      // S' += P V_a: k-step (t, e) contracts the tokens 16 t + 4 k + e, k = 0..3, which is what lane group
+      // k holds of P in pt[t][e]: the result of the first product is the operand of the second as it is
+#pragma unroll
+      for (int ct = 0; ct < 4; ++ct) {
+        if (ct < c.n_rt) {
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              sp[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(pt[tt][e], sm.enc.tail.Va[16 * tt + 4 * kq + e][16 * ct + n], sp[ct],
+                                                            0, 0, 0);
+          }
+        }
+      }
+    }
+    __syncthreads();
+  }
+  // S' into LDS, row-major G x r, for the update of S
+  float* stage = &sm.enc.tail.Ka[0][0];
+  if (tail_wave) {
+#pragma unroll
+    for (int ct = 0; ct < 4; ++ct) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int g = wave * 16 + 4 * kq + e, col = 16 * ct + n;
+        if (ct < c.n_rt && g < c.G && col < c.r) stage[g * c.r + col] = sp[ct][e];
+      }
+    }
   }
 }
 
 template <int WAVES>
 __device__ inline void encode_rollout(const PtDev& c, StepSmem<WAVES>& sm, int b, int s0) {
+  constexpr int THREADS = WAVES * 64;
   const int wave = threadIdx.x >> 6;
+  if (wave >= 4) encode_groups<WAVES, 2>(c, sm, b, s0);
+  else if (wave & 2) encode_groups<WAVES, 1>(c, sm, b, s0);
+  else encode_groups<WAVES, 0>(c, sm, b, s0);
+  __syncthreads();
+  float* stage = &sm.enc.tail.Ka[0][0];
   float sacc[16];
 #pragma unroll
-  for (int x = 0; x < 16; ++x) sacc[x] = 0.f;
-  pt_encode_stage_qa<WAVES * 64>(sm.enc.Qa, c.Qa, c.G, c.r);
-  if (wave >= 4) encode_groups<WAVES, 2>(c, sm, b, s0, sacc);
-  else if (wave & 2) encode_groups<WAVES, 1>(c, sm, b, s0, sacc);
-  else encode_groups<WAVES, 0>(c, sm, b, s0, sacc);
-  pt_state_update<WAVES * 64>(c, b, sacc, &sm.enc.tail.Ka[0][0], sm.enc.tail.red);
+  for (int x = 0; x < 4096 / THREADS; ++x) {
+    const int idx = threadIdx.x + THREADS * x;
+    sacc[x] = idx < c.G * c.r ? stage[idx] : 0.f;
+  }
+  __syncthreads();
+  pt_state_update<THREADS>(c, b, sacc, stage, sm.enc.tail.red);
 }
 
 // What a step does to one rollout, from the counters it finds.  Both kinds of workgroup of a rollout

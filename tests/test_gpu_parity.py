@@ -495,7 +495,12 @@ def test_rotation_invariance_of_the_ring(name, generic):
     for r in results[1:]:
         assert torch.equal(r[1], results[0][1]) and torch.equal(r[2], results[0][2])
         assert np.array_equal(r[4], results[0][4]) and np.array_equal(r[5], results[0][5])
-        assert np.array_equal(r[3], results[0][3])
+        if name == "qwen3b" and not generic:
+            # the MFMA encoder contracts a chunk's tokens four at a time by their place in a 32-slot group,
+            # so which tokens share a partial sum rotates with the ring: S agrees to rounding
+            H.assert_close(r[3], results[0][3], 1e-6, 1e-5, "rotated state S")
+        else:
+            assert np.array_equal(r[3], results[0][3])
         # attention walks physical groups, so the summation order (not the set of keys) rotates too
         # (fp32 rounding order, hence now and then another bf16 rounding of the output's last bit)
         H.assert_close(H.f64(r[0]), H.f64(results[0][0]), 2e-3, 2e-2, "rotated outputs")
