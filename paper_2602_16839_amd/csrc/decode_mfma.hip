@@ -375,7 +375,11 @@ union StepSmem {
   } merge;
   struct {           // the encoding workgroup of a rollout
     uint16_t vstage[2][4096];   // one group's V part of one KV head, per V wavefront (operand transposition)
-    EncTailSmem tail;           // Ka and Va (contiguous, >= G*r floats) double as the staging area of S'
+    struct {                    // K_a and V_a of the group in hand; together (contiguous, >= G*r floats)
+      float Ka[kEncSub][kEncMaxGR + 1];   //   they double as the staging area of S'
+      float Va[kEncSub][kEncMaxGR + 1];
+      float red[16];
+    } tail;
   } enc;
   SelSmall sel;      // scored policy: the choice of the next victims, by the rollout's last workgroup
 };
@@ -624,8 +628,12 @@ __device__ inline void encoder_role(const PtDev& c, const StepArgs& a, StepSmem<
     b = ld_uniform(ids + j_row);
     if ((unsigned)b >= (unsigned)c.B) return;            // flagged by the row's attention workgroups
   }
-  const bool act = !active || active[b] != 0;
-  const long long len0 = ld_scalar(len_cur + b), base0 = ld_scalar(base_cur + b);
+  // counters and mask in one round trip (where nothing is full this workgroup should be gone at once)
+  const uintptr_t mask_addr = (uintptr_t)(active + b);
+  const uint32_t* mask_word_p = active ? (const uint32_t*)(mask_addr & ~(uintptr_t)3) : (const uint32_t*)(c.n_prompt + b);
+  const StepHead head = load_step_head<8, false>(len_cur + b, base_cur + b, c.n_prompt + b, mask_word_p, nullptr);
+  const bool act = !active || ((head.mask_word >> (8 * (int)(mask_addr & 3))) & 0xffu) != 0;
+  const long long len0 = head.len, base0 = head.base;
   if (len0 < base0) return;
   const StepPlan pl = plan_step<MASS>(c, a, act, len0, base0);
   if (pl.evicting) {
@@ -663,7 +671,9 @@ __device__ inline void encoder_role(const PtDev& c, const StepArgs& a, StepSmem<
   arrive_rollout<WAVES, MASS>(c, a, sm, sm_ticket, dyn_lds, b, pl, c.Hkv * c.n_splits + 1);
 }
 
-template <bool NT, int WAVES, bool MASS>
+// ENC: launches that may evict (they carry the encoding workgroups); the variant without them is
+// leaner and is what the steps run while no ring can be full yet.
+template <bool NT, int WAVES, bool MASS, bool ENC>
 __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
     // what the walk cannot start without comes first, as plain scalars: the build asks for these
     // leading arguments to be preloaded into registers at wavefront launch, so the counters are
@@ -677,13 +687,15 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
 
   // row j of the launch (and of q / k / v / out) is rollout b: j itself, or ids[j] for a compact list
   const int j_row = blockIdx.x / n_kv_heads, hkv = blockIdx.x - j_row * n_kv_heads, split = blockIdx.y;
-  if (j_row >= n_rows) {
+  if (__builtin_expect(j_row >= n_rows, 0)) {
     // beyond the attention workgroups: one encoding workgroup per row if the launch may evict, then ...
     if (split != 0) return;
     const int extra = blockIdx.x - n_rows * n_kv_heads;
-    if (a.do_evict && extra < n_rows) {
-      encoder_role<WAVES, MASS>(c, a, sm, sm_ticket, dyn_lds, extra, ids, active, len_cur, base_cur);
-      return;
+    if constexpr (ENC) {
+      if (extra < n_rows) {
+        encoder_role<WAVES, MASS>(c, a, sm, sm_ticket, dyn_lds, extra, ids, active, len_cur, base_cur);
+        return;
+      }
     }
     // ... the one workgroup that carries counters over (compact list, two counter buffers).  A listed
     // rollout's workgroup puts its new counters into the buffer this step writes; the unlisted rollouts'
@@ -1076,22 +1088,22 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bo
   dim3 grid(rows * cc.Hkv + (do_evict ? rows : 0) + (a.carry ? 1 : 0), cc.n_splits);
   // scores are maintained by whole steps only (append + attention) under the scored policy
   const bool mass = cc.scored && do_append && do_attend;
-  if (mass) {
-    // parked masses of every group a workgroup may walk
-    const size_t park = (size_t)(cc.W / PT_GROUP_TOKENS + 2) * PT_GROUP_TOKENS * sizeof(float);
-    if (waves == 8) {
-      if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 8, true>), grid, dim3(512), park, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, rows, cc, a);
-      else hipLaunchKernelGGL((decode_mfma_kernel<false, 8, true>), grid, dim3(512), park, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, rows, cc, a);
-    } else {
-      if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 4, true>), grid, dim3(256), park, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, rows, cc, a);
-      else hipLaunchKernelGGL((decode_mfma_kernel<false, 4, true>), grid, dim3(256), park, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, rows, cc, a);
-    }
-  } else if (waves == 8) {
-    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 8, false>), grid, dim3(512), 0, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, rows, cc, a);
-    else hipLaunchKernelGGL((decode_mfma_kernel<false, 8, false>), grid, dim3(512), 0, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, rows, cc, a);
+  // parked masses of every group a workgroup may walk
+  const size_t park = mass ? (size_t)(cc.W / PT_GROUP_TOKENS + 2) * PT_GROUP_TOKENS * sizeof(float) : 0;
+#define PT_STEP_LAUNCH(NT_, WAVES_, MASS_, ENC_)                                                                      \
+  hipLaunchKernelGGL((decode_mfma_kernel<NT_, WAVES_, MASS_, ENC_>), grid, dim3(WAVES_ * 64), park, s, ids, active, \
+                     cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, rows, cc, a)
+#define PT_STEP_PICK_ENC(NT_, WAVES_, MASS_) \
+  do { if (do_evict) PT_STEP_LAUNCH(NT_, WAVES_, MASS_, true); else PT_STEP_LAUNCH(NT_, WAVES_, MASS_, false); } while (0)
+#define PT_STEP_PICK_MASS(NT_, WAVES_) \
+  do { if (mass) PT_STEP_PICK_ENC(NT_, WAVES_, true); else PT_STEP_PICK_ENC(NT_, WAVES_, false); } while (0)
+  if (waves == 8) {
+    if (nontemporal) PT_STEP_PICK_MASS(true, 8); else PT_STEP_PICK_MASS(false, 8);
   } else {
-    if (nontemporal) hipLaunchKernelGGL((decode_mfma_kernel<true, 4, false>), grid, dim3(256), 0, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, rows, cc, a);
-    else hipLaunchKernelGGL((decode_mfma_kernel<false, 4, false>), grid, dim3(256), 0, s, ids, active, cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, rows, cc, a);
+    if (nontemporal) PT_STEP_PICK_MASS(true, 4); else PT_STEP_PICK_MASS(false, 4);
   }
+#undef PT_STEP_PICK_MASS
+#undef PT_STEP_PICK_ENC
+#undef PT_STEP_LAUNCH
   return hipGetLastError();
 }

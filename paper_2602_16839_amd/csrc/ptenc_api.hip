@@ -128,6 +128,14 @@ ptenc_status advanced(ptenc_ctx* x, hipError_t e) {
 }
 inline ptenc_status hip_status(hipError_t e) { return e == hipSuccess ? PTENC_OK : PTENC_ERR_HIP; }
 
+// Launches that may evict carry one encoding workgroup per row.  While no ring can be full yet (the host
+// keeps an upper bound on the fullest one: appends since the last full reset or ptenc_set_counters),
+// steps are launched without them and without the eviction logic; should the bound ever be wrong, the
+// append on the full ring sets PTENC_DEVERR_APPEND_FULL instead of going unnoticed.  Steps that may be
+// replayed from a graph (counters in place) always carry them.
+bool may_evict(const ptenc_ctx* x) { return x->opt_in_place != 0 || x->live_ub >= x->dev.Wr; }
+void appended_one(ptenc_ctx* x) { if (x->live_ub < x->dev.Wr) ++x->live_ub; }
+
 // Scored policy: a decode step chooses the next victims itself when its append fills a ring.  A ring
 // can also fill up, or lose its selection, in ways that step does not see (a bare ptenc_cache_append,
 // ptenc_set_scores, a change of policy); the next call that may evict then runs the stand-alone
@@ -200,6 +208,7 @@ ptenc_status ptenc_create(const ptenc_config* cfg, void* d_cache, void* d_state,
   d.selected = (int*)(sp + L.selected);
   x->select_stale = 1;
   x->opt_recent = -1;
+  x->live_ub = d.Wr;       // nothing is known about the counters the state block holds
   replan(x);
   *out = x;
   return PTENC_OK;
@@ -287,6 +296,7 @@ ptenc_status ptenc_set_encoder(ptenc_ctx* ctx, const void* d_qg, const void* d_W
 ptenc_status ptenc_reset(ptenc_ctx* ctx, const uint8_t* d_mask, void* stream) {
   if (!ctx) return PTENC_ERR_INVALID_ARG;
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
+  if (!d_mask) ctx->live_ub = 0;        // every ring is empty (a masked reset leaves the other rings as they are)
   return hip_status(pt_launch_reset(ctx->dev, d_mask, d_mask == nullptr, S(stream)));
 }
 
@@ -338,6 +348,7 @@ ptenc_status ptenc_cache_append(ptenc_ctx* ctx, const void* d_k, const void* d_v
   if (!ctx || !d_k || !d_v) return PTENC_ERR_INVALID_ARG;
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
   ctx->select_stale = 1;   // a bare append may fill a ring without choosing its victims
+  appended_one(ctx);
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
     return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, false, true, false, nullptr, d_k, d_v,
@@ -377,9 +388,12 @@ ptenc_status ptenc_decode_step(ptenc_ctx* ctx, const void* d_q, const void* d_k,
   if (ctx->attn_kernel == 1) {
     if (((uintptr_t)d_q | (uintptr_t)d_out | (uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
     if (refresh_selection(ctx, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
-    return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, true, true, true, d_q, d_k,
+    const bool ev = may_evict(ctx);
+    appended_one(ctx);
+    return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, ev, true, true, d_q, d_k,
                                                d_v, d_out, d_active, nullptr, nullptr, 0, ctx->opt_in_place != 0, S(stream)));
   }
+  appended_one(ctx);
   // small problems are bound by launches: the whole plain step as one (needs the two counter buffers:
   // its attention workgroups read the pair the prologue workgroup does not write)
   if (!ctx->opt_in_place && (long)ctx->cfg.batch * ctx->cfg.n_q_heads * ctx->dev.n_splits <= 2048) {
@@ -411,10 +425,13 @@ ptenc_status ptenc_decode_step_ids(ptenc_ctx* ctx, const void* d_q, const void* 
     // cache, ordinary loads (which allocate there) serve the next step better than non-temporal ones
     bool nt = ctx->nontemporal != 0;
     if (ctx->opt_nontemporal < 0) nt = ctx->cache_bytes / (size_t)ctx->cfg.batch * (size_t)n > ((size_t)192 << 20);
-    return advanced(ctx, pt_launch_decode_mfma(d, nt, pick_waves(ctx, n, d.n_splits), true, true, true,
+    const bool ev = may_evict(ctx);
+    appended_one(ctx);
+    return advanced(ctx, pt_launch_decode_mfma(d, nt, pick_waves(ctx, n, d.n_splits), ev, true, true,
                                                d_q, d_k, d_v, d_out, nullptr, nullptr, d_ids, n, ctx->opt_in_place != 0,
                                                S(stream)));
   }
+  appended_one(ctx);
   hipError_t e = pt_launch_step_prologue(d, true, true, d_k, d_v, nullptr, nullptr, d_ids, n, true, S(stream));
   if (e != hipSuccess) return PTENC_ERR_HIP;
   return hip_status(pt_launch_attn_generic(d, d_q, d_out, nullptr, d_ids, n, S(stream)));
@@ -492,6 +509,9 @@ ptenc_status ptenc_set_counters(ptenc_ctx* ctx, const int64_t* h_len, const int6
     if (hipMemsetAsync(ctx->dev.selected, 0, sizeof(int) * ctx->cfg.batch, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
     ctx->select_stale = 1;
   }
+  ctx->live_ub = 0;
+  for (int b = 0; b < ctx->cfg.batch; ++b)
+    if (h_len[b] - h_base[b] > ctx->live_ub) ctx->live_ub = h_len[b] - h_base[b];
   const size_t n = sizeof(long long) * ctx->cfg.batch;
   if (hipMemcpyAsync(ctx->dev.len, h_len, n, hipMemcpyHostToDevice, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
   if (hipMemcpyAsync(ctx->dev.base, h_base, n, hipMemcpyHostToDevice, S(stream)) != hipSuccess) return PTENC_ERR_HIP;

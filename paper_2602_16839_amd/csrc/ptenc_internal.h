@@ -66,6 +66,7 @@ struct ptenc_ctx {
   int opt_policy;        // 0 sliding window, 1 scored
   int opt_recent;        // -1 = default
   int select_stale;      // scored policy: a ring may be full without a valid selection (see ptenc_api.hip)
+  long long live_ub;     // upper bound on the live thinking tokens of the fullest ring (see may_evict)
   int waves;             // resolved: wavefronts per workgroup of the MFMA kernel
   int attn_kernel;       // 0 generic, 1 mfma
   int encode_kernel;     // 0 generic, 1 mfma
