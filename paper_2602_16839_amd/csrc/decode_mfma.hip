@@ -374,7 +374,10 @@ union StepSmem {
     float m[WAVES][64 / WAVES], l[WAVES][64 / WAVES];
   } merge;
   struct {           // the encoding workgroup of a rollout
-    uint16_t vstage[2][4096];   // one group's V part of one KV head, per V wavefront (operand transposition)
+    // one group's V part of one KV head, per V wavefront (operand transposition): the 16-byte piece of
+    // (value-column tile it, lane group k, row m) sits at 16-byte index (4 it + k) * 18 + m + m / 8, a pitch
+    // that spreads the pieces one gather touches over all banks (2-way conflicts instead of 16-way)
+    uint16_t vstage[2][32 * 18 * 8];
     struct {                    // K_a and V_a of the group in hand; together (contiguous, >= G*r floats)
       float Ka[kEncSub][kEncMaxGR + 1];   //   they double as the staging area of S'
       float Va[kEncSub][kEncMaxGR + 1];
@@ -451,23 +454,32 @@ __device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b,
         for (int hh = 0; hh < HB; ++hh) {
           const int h = h0 + hh;
           if (h < c.Hkv) {
+            // this head's slices of W^a first: their latency runs under the transposition below
+            Op w[4][4];
+#pragma unroll
+            for (int rt = 0; rt < 4; ++rt) {
+              if (rt < c.n_rt) {
+#pragma unroll
+                for (int cc = 0; cc < 4; ++cc) w[cc][rt].u = Wp[(((size_t)h * 4 + cc) * 4 + rt) * 64 + lane];
+              }
+            }
             Op op[4];
             if (ROLE == 0) {
 #pragma unroll
               for (int cc = 0; cc < 4; ++cc) op[cc].u = buf[hh][cc];
             } else {
-              // V part -> LDS as stored (the operand needs 8 consecutive columns of one token, which the
-              // token-minor layout scatters)
+              // V part -> LDS (the operand needs 8 consecutive columns of one token, which the token-minor
+              // layout scatters)
               uint16_t* vs = sm.enc.vstage[t];
 #pragma unroll
-              for (int i = 0; i < NP; ++i) ((u32x4*)vs)[i * 64 + lane] = buf[hh][i];
+              for (int i = 0; i < NP; ++i) ((u32x4*)vs)[(i * 4 + kgrp) * 18 + n + (n >> 3)] = buf[hh][i];
               __builtin_amdgcn_wave_barrier();
 #pragma unroll
               for (int cc = 0; cc < 4; ++cc) {
 #pragma unroll
                 for (int x = 0; x < 8; ++x) {
-                  const int i = cc * 32 + 8 * kgrp + x;        // value column
-                  op[cc].s[x] = vs[(((i >> 4) * 4 + vkg) * 16 + (i & 15)) * 8 + ve];
+                  const int i = cc * 32 + 8 * kgrp + x, mm = i & 15;        // value column; its row in the tile
+                  op[cc].s[x] = vs[(((i >> 4) * 4 + vkg) * 18 + mm + (mm >> 3)) * 8 + ve];
                 }
               }
               __builtin_amdgcn_wave_barrier();                 // the next head overwrites the staging area
@@ -476,11 +488,8 @@ __device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b,
             for (int rt = 0; rt < 4; ++rt) {
               if (rt < c.n_rt) {
 #pragma unroll
-                for (int cc = 0; cc < 4; ++cc) {
-                  Op w;
-                  w.u = Wp[(((size_t)h * 4 + cc) * 4 + rt) * 64 + lane];
-                  acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(op[cc].h, w.h, acc[rt], 0, 0, 0);
-                }
+                for (int cc = 0; cc < 4; ++cc)
+                  acc[rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(op[cc].h, w[cc][rt].h, acc[rt], 0, 0, 0);
               }
             }
           }
