@@ -132,6 +132,9 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=0,
                     help="also time a stack of this many layers (each with its own cache) over the same steps: "
                          "eager launches, then replays of the recorded one-step HIP graph")
+    ap.add_argument("--stagger", action="store_true",
+                    help="also time steady-state steps with the rollouts' evictions spread evenly over the steps "
+                         "(a running batch whose rollouts started at different times) next to all evicting together")
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch the plain copy / read kernels on 1 GiB (scale for the profiler's byte counters)")
     args = ap.parse_args()
@@ -301,6 +304,31 @@ def main() -> int:
         "algorithmic_gbytes": all_bytes / 1e9,
         "roofline": roofline,
     }
+    if args.stagger and not wl.ragged and not wl.n_sink and args.policy == "sliding":
+        # steady state, rings nearly full: the cache keeps what the run left (the counters are re-based, so
+        # positions and contents no longer correspond: timing only)
+        Wr, C, B = wl.window, wl.chunk, wl.batch
+        ns = min(2 * C, K)
+        zeros = np.zeros(B, dtype=np.int64)
+
+        def timed_from(ln):
+            best = None
+            for _ in range(3):
+                layer.set_counters(ln, zeros)
+                torch.cuda.synchronize()
+                a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a0.record()
+                layer.run(q[:ns], k[:ns], v[:ns], out[:ns])
+                a1.record()
+                torch.cuda.synchronize()
+                us = a0.elapsed_time(a1) * 1e3 / ns
+                best = us if best is None else min(best, us)
+            return best
+
+        together = timed_from(np.full(B, Wr - C // 2, dtype=np.int64))
+        spread = timed_from((Wr - (np.arange(B) * C // B) % C).astype(np.int64))
+        res["staggered_evictions"] = {"steps": ns, "us_per_step_all_evicting_together": together,
+                                      "us_per_step_evictions_spread_over_steps": spread}
     if args.extras:
         # y += ((x A) S) B at the model's hidden size (the query projection width stands in for it)
         ex = {}
