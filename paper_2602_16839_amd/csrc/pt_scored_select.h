@@ -57,11 +57,22 @@ __device__ inline void pt_scored_select(const PtDev& c, int b, long long base, f
   __syncthreads();
 
   // ---- 1. scores ----
-  for (int i = t; i < n_el; i += THREADS) {
-    const int slot = slot_of(i);
-    float s = 0.f;
-    for (int h = 0; h < c.Hkv; ++h) s += c.mass[(size_t)(b * c.Hkv + h) * c.W + slot];
-    work[i] = s;
+  for (int i0 = 0; i0 < n_el; i0 += 8 * THREADS) {       // 8 entries per thread at a time, loads in flight together
+    float sc[8];
+    int sl[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { sc[u] = 0.f; sl[u] = slot_of(min(i0 + u * THREADS + t, n_el - 1)); }
+    for (int h = 0; h < c.Hkv; ++h) {                     // head order: the score is reproducible
+      const float* m = c.mass + (size_t)(b * c.Hkv + h) * c.W;
+      float x[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) x[u] = m[sl[u]];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) sc[u] += x[u];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (i0 + u * THREADS + t < n_el) work[i0 + u * THREADS + t] = sc[u];
   }
   for (int w = t; w < PT_SCORED_MAX_ELIGIBLE / 32; w += THREADS) sm.vmask[w] = 0u;
   __syncthreads();
@@ -77,14 +88,23 @@ __device__ inline void pt_scored_select(const PtDev& c, int b, long long base, f
       if ((bits & pmask) == prefix) atomicAdd(&sm.hist[(bits >> shift) & 255u], 1);
     }
     __syncthreads();
-    if (t == 0) {
-      int cum = 0, dgt = 255;
-      for (int x = 0; x < 256; ++x) {
-        if (cum + sm.hist[x] >= k) { dgt = x; break; }
-        cum += sm.hist[x];
+    if (t < 64) {
+      // the first digit whose cumulative count reaches k: lane l holds digits 4 l .. 4 l + 3
+      const int h0 = sm.hist[4 * t], h1 = sm.hist[4 * t + 1], h2 = sm.hist[4 * t + 2], h3 = sm.hist[4 * t + 3];
+      const int mine = h0 + h1 + h2 + h3;
+      int incl = mine;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int v = __shfl_up(incl, o, 64);
+        if (t >= o) incl += v;
       }
-      sm.sh[0] = dgt;
-      sm.sh[1] = k - cum;
+      const int before = incl - mine;
+      if (before < k && incl >= k) {                      // exactly one lane (k >= 1, the total is >= k)
+        int cum = before, dgt = 4 * t;
+        if (cum + h0 < k) { cum += h0; ++dgt; if (cum + h1 < k) { cum += h1; ++dgt; if (cum + h2 < k) { cum += h2; ++dgt; } } }
+        sm.sh[0] = dgt;
+        sm.sh[1] = k - cum;
+      }
     }
     __syncthreads();
     prefix |= (uint32_t)sm.sh[0] << shift;
@@ -104,9 +124,21 @@ __device__ inline void pt_scored_select(const PtDev& c, int b, long long base, f
     eq_seen += tot;
   }
   __syncthreads();
-  if (t == 0) {
-    int cum = 0;
-    for (int w = 0; w < (n_el + 31) / 32; ++w) { sm.wpre[w] = cum; cum += __popc(sm.vmask[w]); }
+  if (t < 64) {
+    // victims before each 32-entry word: lane l takes words l, l + 64, ... in turn, carrying the running total
+    int carry = 0;
+    for (int w0 = 0; w0 < (n_el + 31) / 32; w0 += 64) {
+      const int w = w0 + t;
+      const int cnt = w < (n_el + 31) / 32 ? __popc(sm.vmask[w]) : 0;
+      int incl = cnt;
+#pragma unroll
+      for (int o = 1; o < 64; o <<= 1) {
+        const int v = __shfl_up(incl, o, 64);
+        if (t >= o) incl += v;
+      }
+      if (w < (n_el + 31) / 32) sm.wpre[w] = carry + incl - cnt;
+      carry += __shfl(incl, 63, 64);
+    }
   }
   __syncthreads();
   auto is_victim = [&](int i) { return i < n_el && ((sm.vmask[i >> 5] >> (i & 31)) & 1u); };
@@ -130,44 +162,72 @@ __device__ inline void pt_scored_select(const PtDev& c, int b, long long base, f
     if (i >= C && is_victim(i)) mv_b[victims_before(i) - v_head] = i;
   }
   __syncthreads();
-  // a token of one KV head = 16 key pieces of 16 bytes + 128 value elements (token-minor): 144 items,
-  // exchanged in batches of loads followed by stores so that the round trips overlap
+  // a token of one KV head = 16 key pieces of 16 bytes + 128 value elements (token-minor, one per
+  // 16-byte piece of the group's V part).  Exchanged in batches: all loads of a batch, then its stores,
+  // with enough of them in flight per thread that the exchange of a whole chunk takes a few round trips
+  // to memory (keys: 8 pieces per thread and batch; values: 32 elements).
   uint16_t* cache = (uint16_t*)c.cache;
   typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-  const int n_items = n_mv * c.Hkv * 144;
-  for (int i0 = 0; i0 < n_items; i0 += THREADS * 4) {
-    u32x4 ka[4], kb[4];
-    uint16_t va[4], vb[4];
-    size_t oa[4], ob[4];
-    int kind[4];
+  auto pair_slabs = [&](int mv, int h, int& sa, int& sb) {
+    sa = slot_of(mv_a[mv]); sb = slot_of(mv_b[mv]);
+    return (size_t)(b * c.Hkv + h) * pt_slab_elems(c.W, 128);
+  };
+  {
+    constexpr int NB = 8;
+    const int n_items = n_mv * c.Hkv * 16;
+    for (int i0 = 0; i0 < n_items; i0 += THREADS * NB) {
+      u32x4 ka[NB], kb[NB];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int idx = i0 + u * THREADS + t;
-      kind[u] = -1;
-      if (idx < n_items) {
-        const int mv = idx / (c.Hkv * 144), rem = idx - mv * (c.Hkv * 144);
-        const int h = rem / 144, it = rem - h * 144;
-        const int sa = slot_of(mv_a[mv]), sb = slot_of(mv_b[mv]);
-        const size_t so = (size_t)(b * c.Hkv + h) * pt_slab_elems(c.W, 128);
-        if (it < 16) {
-          kind[u] = 0;
-          oa[u] = so + pt_k_off(1, c.W, 128, sa, it * 8);
-          ob[u] = so + pt_k_off(1, c.W, 128, sb, it * 8);
-          ka[u] = *(const u32x4*)(cache + oa[u]);
-          kb[u] = *(const u32x4*)(cache + ob[u]);
-        } else {
-          kind[u] = 1;
-          oa[u] = so + pt_v_off(1, c.W, 128, sa, it - 16);
-          ob[u] = so + pt_v_off(1, c.W, 128, sb, it - 16);
-          va[u] = cache[oa[u]];
-          vb[u] = cache[ob[u]];
+      for (int u = 0; u < NB; ++u) {
+        const int idx = i0 + u * THREADS + t;
+        if (idx < n_items) {
+          const int it = idx & 15, mh = idx >> 4, mv = mh / c.Hkv, h = mh - mv * c.Hkv;
+          int sa, sb;
+          const size_t so = pair_slabs(mv, h, sa, sb);
+          ka[u] = *(const u32x4*)(cache + so + pt_k_off(1, c.W, 128, sa, it * 8));
+          kb[u] = *(const u32x4*)(cache + so + pt_k_off(1, c.W, 128, sb, it * 8));
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < NB; ++u) {
+        const int idx = i0 + u * THREADS + t;
+        if (idx < n_items) {
+          const int it = idx & 15, mh = idx >> 4, mv = mh / c.Hkv, h = mh - mv * c.Hkv;
+          int sa, sb;
+          const size_t so = pair_slabs(mv, h, sa, sb);
+          *(u32x4*)(cache + so + pt_k_off(1, c.W, 128, sa, it * 8)) = kb[u];
+          *(u32x4*)(cache + so + pt_k_off(1, c.W, 128, sb, it * 8)) = ka[u];
         }
       }
     }
+  }
+  {
+    constexpr int NB = 32;
+    const int n_items = n_mv * c.Hkv * 128;
+    for (int i0 = 0; i0 < n_items; i0 += THREADS * NB) {
+      uint16_t va[NB], vb[NB];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (kind[u] == 0) { *(u32x4*)(cache + oa[u]) = kb[u]; *(u32x4*)(cache + ob[u]) = ka[u]; }
-      else if (kind[u] == 1) { cache[oa[u]] = vb[u]; cache[ob[u]] = va[u]; }
+      for (int u = 0; u < NB; ++u) {
+        const int idx = i0 + u * THREADS + t;
+        if (idx < n_items) {
+          const int i = idx & 127, mh = idx >> 7, mv = mh / c.Hkv, h = mh - mv * c.Hkv;
+          int sa, sb;
+          const size_t so = pair_slabs(mv, h, sa, sb);
+          va[u] = cache[so + pt_v_off(1, c.W, 128, sa, i)];
+          vb[u] = cache[so + pt_v_off(1, c.W, 128, sb, i)];
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < NB; ++u) {
+        const int idx = i0 + u * THREADS + t;
+        if (idx < n_items) {
+          const int i = idx & 127, mh = idx >> 7, mv = mh / c.Hkv, h = mh - mv * c.Hkv;
+          int sa, sb;
+          const size_t so = pair_slabs(mv, h, sa, sb);
+          cache[so + pt_v_off(1, c.W, 128, sa, i)] = vb[u];
+          cache[so + pt_v_off(1, c.W, 128, sb, i)] = va[u];
+        }
+      }
     }
   }
   for (int idx = t; idx < n_mv * (c.Hkv + 1); idx += THREADS) {
