@@ -233,8 +233,8 @@ __device__ inline void patch_newest(Frag& f, const Op kp[4], const uint32_t vp[4
   }
 }
 
-// Data handed from one workgroup to another inside this kernel (split partials, the heads' encoder
-// shares) is written and read with device-scope relaxed atomics: such stores write through and
+// Data handed from one workgroup to another inside this kernel (the window splits' partial results)
+// is written and read with device-scope relaxed atomics: such stores write through and
 // such loads bypass the per-CU and per-XCD caches, so the hand-over needs no cache write-back or
 // invalidation.  Order is given by: stores, wait for them (workgroup fence), barrier, ticket.
 // (two adjacent floats, 8-byte aligned, as one 64-bit access)

@@ -1,5 +1,6 @@
-// Shared tail of the thought encoder: given K_a and V_a of up to 32 tokens in LDS, accumulate
-// S' += (Q_a K_a^T) V_a, and the state update S <- Normalize(S + S')
+// Tail of the thought encoder: given K_a and V_a of up to 32 tokens in LDS, accumulate
+// S' += (Q_a K_a^T) V_a (plain ALU: the encoder of the plain path; the MFMA kernel does this part on
+// the matrix units), and the state update S <- Normalize(S + S') that both share
 // (Our Approach, the Delta-W equation and the update rule).  THREADS = workgroup size (256 or 512).
 #pragma once
 
@@ -15,19 +16,6 @@ struct EncTailSmem {
   float P[kEncMaxGR][kEncSub + 1];
   float red[16];
 };
-
-// Q_a (G x r, row-major in global memory) into an LDS array of rows of kEncMaxGR + 1 floats.  No
-// barrier: callers pass one before the first pt_encode_accumulate anyway.
-template <int THREADS>
-__device__ inline void pt_encode_stage_qa(float (*dst)[kEncMaxGR + 1], const float* __restrict__ Qa, int G, int r) {
-  int g = threadIdx.x / r, a = threadIdx.x - g * r;
-  const int dg = THREADS / r, da = THREADS - dg * r;
-  for (int idx = threadIdx.x; idx < G * r; idx += THREADS) {
-    dst[g][a] = Qa[idx];
-    g += dg; a += da;
-    if (a >= r) { a -= r; ++g; }
-  }
-}
 
 // S' += (Q_a K_a^T) V_a for the 32 tokens whose K_a and V_a rows are in LDS (rows that hold no token
 // must be zero).  Qa: G rows of qa_stride floats, in LDS (staged) or in global memory.  Thread t owns
