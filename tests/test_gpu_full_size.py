@@ -149,3 +149,62 @@ def test_ragged_full_run_sampled():
     Lm = int(lengths[b_med])
     sample_t = sorted(set([1, int(lengths[b_short]), wl.window + 1, Lm, Lm + 1, int(lengths[b_long])]))
     _check(wl, sample_b, sample_t, seg_steps=1024)
+
+
+def test_qwen7b_rollouts_that_start_at_different_steps_full_size():
+    # a running batch: rollout b joins at step start_b, so the rollouts' evictions fall in different steps
+    # (every step of the steady state has an evicting rollout whose chunk is encoded beside everybody's
+    # attention).  Masked full-batch steps at the benchmark's shape; sampled outputs, rings, states.
+    wl = I.WORKLOADS["qwen7b"]
+    B, W, C = wl.batch, wl.window, wl.chunk
+    T = W + 3 * C + 57
+    starts = (np.arange(B) * C) // B + (np.arange(B) % 3)             # 0 .. C + 1, spread
+    dev = torch.device("cuda:0")
+    enc = I.encoder_params(wl, device=dev)
+    layer = ptenc.Layer(B, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, W, C, dtype=wl.torch_dtype,
+                        n_global=wl.n_global, rank=wl.rank, poison_cache=True)
+    layer.set_encoder(enc["q_g"], enc["WaQ"], enc["WaK"], enc["WaV"], enc["k_g"], enc["v_g"])
+    layer.reset()
+    sample_t = [1, 60, W, W + 1, W + C, W + 2 * C + 31, T]
+    start_dev = torch.from_numpy(starts).to(dev).view(1, -1)
+    kept = {}
+    for t0 in range(0, T, 1024):
+        t1 = min(T, t0 + 1024)
+        q, k, v = I.qkv_steps(wl, t0, t1, device=dev)
+        tt = torch.arange(t0, t1, device=dev).view(-1, 1)
+        active = (tt >= start_dev).to(torch.uint8).contiguous()
+        out = layer.run(q, k, v, active=active)
+        for t in sample_t:
+            if t0 < t <= t1:
+                kept[t] = out[t - 1 - t0].cpu()
+        del q, k, v, out
+    assert layer.poll_error() == 0
+    ln, base = layer.counters()
+    Wr = W
+    assert np.array_equal(ln, T - starts)
+    assert np.array_equal(base, np.array([evicted_closed_form(int(T - s), Wr, C) for s in starts]))
+    assert len(set(base.tolist())) > 1                                 # they did not evict in step
+    e64 = {kk: H.f64(vv) for kk, vv in I.encoder_params(wl).items()}
+    Kw, Vw = layer.gather_window()
+    S = layer.get_state()
+    for b in (0, 41, 127):
+        s = int(starts[b])
+        for t in sample_t:
+            tl = t - s                                                # the rollout's own step count
+            if tl <= 0:
+                assert not kept[t][b].any()
+                continue
+            E = evicted_closed_form(tl, Wr, C)
+            q, k, v = I.qkv_steps(wl, s + E, t, b0=b, b1=b + 1)
+            ref = po.attend(H.f64(q[-1, 0]), list(H.f64(k[:, 0])), list(H.f64(v[:, 0])))
+            H.assert_close(H.f64(kept[t][b]), ref, H.BF16_ABS, H.BF16_REL, "out b=%d t=%d" % (b, t))
+        E, n = int(base[b]), int(ln[b] - base[b])
+        _, k, v = I.qkv_steps(wl, s + E, T, b0=b, b1=b + 1)
+        assert torch.equal(Kw[b, :, :n].cpu(), k[:, 0].transpose(0, 1)) and torch.equal(Vw[b, :, :n].cpu(), v[:, 0].transpose(0, 1))
+        Q_a, Sr = po.init_state(e64["q_g"], e64["WaQ"], e64["WaK"], e64["WaV"], e64["k_g"], e64["v_g"])
+        if E:
+            _, k, v = I.qkv_steps(wl, s, s + E, b0=b, b1=b + 1)
+            k, v = H.f64(k[:, 0]).reshape(E, -1), H.f64(v[:, 0]).reshape(E, -1)
+            for c0 in range(0, E, C):
+                Sr = po.normalize(Sr + po.encode_chunk(Q_a, k[c0:c0 + C], v[c0:c0 + C], e64["WaK"], e64["WaV"]))
+        H.assert_close(S[b], Sr, H.S_ABS, H.S_REL, "S b=%d" % b)
