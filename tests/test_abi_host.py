@@ -195,3 +195,23 @@ def test_oracle_and_product_do_not_import_each_other():
         if f.endswith(".py"):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2602_16839_amd" not in text and "ptenc" not in text and "import torch" not in text
+
+
+@pytest.mark.parametrize("batch,hq,hkv,window,splits", [
+    (128, 28, 4, 4096, 1),      # qwen7b: 512 (rollout, KV head) rows
+    (64, 16, 2, 2048, 1),       # qwen3b: 128 rows, one split from 121 rows up
+    (256, 32, 8, 8192, 1),      # llama8b
+    (60, 16, 2, 2048, 2),       # 120 rows: the largest count within about 240 workgroups
+    (40, 16, 2, 2048, 3),       # 80 rows
+    (30, 16, 2, 2048, 4),       # 60 rows
+    (16, 16, 2, 2048, 4),       # 32 rows: about 128 workgroups
+    (4, 16, 2, 2048, 8),        # 8 rows: capped by 256 tokens per split
+    (4, 16, 2, 512, 2),         # a short window allows two splits only
+    (1, 8, 1, 8192, 32),        # one row: the maximum
+])
+def test_window_split_plan_for_known_shapes(batch, hq, hkv, window, splits):
+    # the measured rule of the host's plan (documented with the heuristic): a change shows up here
+    st, h = _host_ctx(cfg(batch=batch, n_q_heads=hq, n_kv_heads=hkv, window=window, chunk=64))
+    assert st == ptenc.OK
+    assert ptenc.ptenc_get_plan(h) == (1, splits, 1)
+    ptenc.ptenc_destroy(h)
