@@ -119,7 +119,7 @@ def test_norm_modes_and_zero_initialised_state(norm):
     H.run_both(wl, wl.steps, norm_mode=norm, with_global_kv=(norm != po.NORM_NONE), check_every=7)
 
 
-@pytest.mark.parametrize("G,r", [(48, 64), (64, 16), (1, 1)])
+@pytest.mark.parametrize("G,r", [(48, 64), (64, 16), (1, 1), (64, 64), (33, 17), (17, 50)])
 def test_global_token_counts_and_latent_widths(G, r):
     # the global-token ablation sizes (16 / 32 / 48 / 64) and latent widths up to 64, on the MFMA encoder
     wl = small("qwen7b", batch=2, n_q_heads=14, n_kv_heads=2, window=64, chunk=40, steps=150, n_global=G, rank=r)
