@@ -106,6 +106,16 @@ def test_scored_run_matches_oracle(splits, waves):
     assert any(list(orc.positions(b)) != list(range(orc.evicted[b], orc.appended[b])) for b in range(wl.batch))
 
 
+def test_scored_run_with_a_long_window():
+    # 66 groups walked by one workgroup of 4 wavefronts (17 groups' scores folded per wavefront and
+    # step), one rollout so that the oracle stays cheap
+    # (80 eligible entries and a seed whose margins are wide: with thousands eligible the chunk's
+    # boundary would fall between scores too close to call)
+    wl = small(batch=1, n_q_heads=2, n_kv_heads=1, window=2112, chunk=64, steps=2112 + 3 * 64 + 5, seed=5)
+    orc, layer = run_both(wl, wl.steps, n_recent=2032, q_gain=48.0, splits=1, waves=4, score_every=257)
+    assert layer.plan()[1] == 1
+
+
 def test_scored_run_with_question_tokens_and_ragged_lengths():
     wl = small(batch=4, window=160, n_sink=64, chunk=40, steps=260, seed=2006)    # a seed with wide margins
     lengths = np.array([260, 90, 200, 131])
