@@ -590,3 +590,31 @@ def test_nan_poisoned_dead_slots_never_reach_outputs():
                 raw[layer.cache_offset(0, 1, s, 5, which)] = float("nan")
         out = layer.attend(qd[t])
         H.assert_close(H.f64(out), ref, H.BF16_ABS, H.BF16_REL, "step %d" % t)
+
+
+def test_two_contexts_on_two_streams_do_not_disturb_each_other():
+    # every context owns its cache, state and scratch, and every call takes its stream: two layers decoding
+    # at the same time on different streams give the bits they give alone
+    wls = [small("qwen7b", batch=3, n_q_heads=14, n_kv_heads=2, window=160, chunk=48, steps=260),
+           small("qwen3b", batch=5, n_q_heads=8, n_kv_heads=2, window=96, chunk=32, steps=260, seed=9)]
+    encs = [I.encoder_params(w) for w in wls]
+    ins = [tuple(t.cuda() for t in I.qkv_steps(w, 0, w.steps)) for w in wls]
+    alone = []
+    for w, e, (q, k, v) in zip(wls, encs, ins):
+        layer = H.make_layer(w, e, splits=2)
+        alone.append((layer.run(q, k, v).clone(), layer.get_state()))
+    torch.cuda.synchronize()
+    layers = [H.make_layer(w, e, splits=2) for w, e in zip(wls, encs)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [torch.empty_like(ins[0][0]), torch.empty_like(ins[1][0])]
+    torch.cuda.synchronize()
+    for t0 in range(0, 260, 20):                       # interleave the two runs in slices of 20 steps
+        for i in (0, 1):
+            q, k, v = ins[i]
+            with torch.cuda.stream(streams[i]):
+                layers[i].run(q[t0:t0 + 20], k[t0:t0 + 20], v[t0:t0 + 20], out=outs[i][t0:t0 + 20])
+    torch.cuda.synchronize()
+    for i in (0, 1):
+        assert torch.equal(outs[i], alone[i][0])
+        assert np.array_equal(layers[i].get_state(), alone[i][1])
+        assert layers[i].poll_error() == 0
