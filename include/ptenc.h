@@ -41,6 +41,10 @@
  *     untouched by append / evict and its rows of `out` are written as zeros.
  *   - Element type: q, k, v, out, the cache and the encoder parameters all have cfg.dtype.
  *     Scores, softmax statistics, accumulators and S are fp32.
+ *   - The state block is the library's: change counters and S only through ptenc_reset,
+ *     ptenc_set_counters and ptenc_set_state (the host side keeps a bound on how full the fullest
+ *     ring can be and launches steps without the eviction machinery while none can be full; a
+ *     ring filled behind its back shows up as PTENC_DEVERR_APPEND_FULL).
  *   - Overlapping calls on one context from different streams race; serialise them.
  *   - HIP graphs: every decode entry point only launches kernels (no allocation, copy or memset),
  *     so it can be captured; set PTENC_OPT_COUNTERS_IN_PLACE first, and give the graph fixed
