@@ -393,10 +393,11 @@ union StepSmem {
 // S' = (Q_a K_a^T) V_a, S <- Normalize(S + S')  (Our Approach, the Delta-W equation and the update rule).
 // The chunk is the ring-relative slots [s0, s0 + C) (wrapping), walked as 32-slot groups; rows of a group
 // outside the chunk count as zero.  Wavefronts 0..3 each own one 16-token tile of K_a or of V_a of the
-// group in hand; all wavefronts share the fp32 tail.
+// group in hand; wavefront w < ceil(G / 16) then adds the group to rows 16 w .. 16 w + 15 of S'.
 //
-// ROLE 0: a K_a tile, 1: a V_a tile, 2: the tail only.  One instance per role, so that each keeps its own
-// operand buffer in registers; every instance passes the same barriers.
+// ROLE 0: a K_a tile, 1: a V_a tile, 2: neither (wavefronts 4..7 of an 8-wavefront workgroup only pass
+// the barriers).  One instance per role, so that each keeps its own operand buffer in registers; every
+// instance passes the same barriers.
 template <int WAVES, int ROLE>
 __device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b, int s0) {
   constexpr int NP = ROLE == 0 ? 4 : 8;          // 16-byte pieces per lane, KV head and group
