@@ -414,7 +414,7 @@ __device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b,
   // Operands of a batch of HB KV heads of one group, all loads in flight together; the next batch (of
   // this group or the next) is requested as soon as this one has been consumed, so its latency hides
   // behind the arithmetic and the tail.
-  constexpr int HB = ROLE == 0 ? 4 : 2;
+  constexpr int HB = 2;      // (4 for the K tiles gained nothing and made the code larger)
   const int n_batches = (c.Hkv + HB - 1) / HB;
   u32x4 buf[HB][NP];
   auto load_batch = [&](int vis, int h0) {
