@@ -60,3 +60,22 @@ def test_encoder_params_shapes():
     assert p["q_g"].shape == (32, 2048) and p["WaQ"].shape == (2048, 32)
     assert p["WaK"].shape == (256, 32) and p["k_g"].shape == (32, 256) and p["WaV"].dtype == torch.bfloat16
     assert "k_g" not in I.encoder_params(wl, with_global_kv=False)
+
+
+def test_bench_byte_model_gives_the_workloads_published_totals():
+    # the algorithmic bytes bench.py prices a run at (K and V stream over the live window, q in / out out,
+    # append, chunk re-read and S update per eviction) summed over the three model-shaped runs: the
+    # totals the workload table of the survey quotes (GB, 4 significant digits there)
+    import bench
+    for name, total_gb in (("qwen3b", 410.7), ("qwen7b", 6547.7), ("llama8b", 104557.0)):
+        wl = I.WORKLOADS[name]
+        lengths = I.rollout_lengths(wl)
+        ab, act = bench.attention_bytes_per_step(wl, lengths, wl.steps)
+        tot = float(ab.sum()) + bench.prologue_bytes_total(wl, lengths, wl.steps)
+        assert abs(tot / 1e9 - total_gb) / total_gb < 2e-4, (name, tot / 1e9)
+        assert int(act.sum()) == wl.batch * wl.steps
+        # closed form of the live-token count behind it: t for t <= W, then cycling W - C + 1 .. W
+        W, C = wl.window, wl.chunk
+        for t in (1, W, W + 1, W + C, W + C + 1, wl.steps):
+            expect = t if t <= W else W - C + ((t - W - 1) % C) + 1
+            assert bench.n_live_at(t, W, C) == expect
