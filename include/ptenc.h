@@ -291,8 +291,7 @@ ptenc_status ptenc_get_plan(ptenc_ctx* ctx, int32_t* attn_kernel, int32_t* n_spl
  * reports (layer l starts at l times that size); d_scratch is ONE layer's scratch, shared, which is
  * safe because the layers of a stack run in stream order -- all calls on a stack and on its
  * layers must be issued to one stream, or be serialised by the caller.  Layers are created with
- * PTENC_OPT_COUNTERS_IN_PLACE = 1, and with non-temporal K/V loads when the L caches together
- * exceed the memory-side cache.  Everything per layer (ptenc_set_encoder, ptenc_prefill,
+ * non-temporal K/V loads when the L caches together exceed the memory-side cache.  Everything per layer (ptenc_set_encoder, ptenc_prefill,
  * ptenc_get_state, ...) goes through the borrowed context ptenc_stack_layer returns; it dies with
  * the stack. */
 typedef struct ptenc_stack ptenc_stack; /* opaque, host side */
@@ -315,9 +314,12 @@ ptenc_status ptenc_stack_decode_step(ptenc_stack* stack, const void* const* h_q,
                                      const void* const* h_v, void* const* h_out, const uint8_t* d_active,
                                      void* stream);
 
-/* Records one ptenc_stack_decode_step over the given buffers into a HIP graph kept by the stack
- * (replacing an earlier one); nothing is executed.  The pointers are frozen into the graph: refill
- * the same buffers between replays.  Every layer's encoder must be set (else PTENC_ERR_STATE).
+/* Records one ptenc_stack_decode_step over the given buffers into HIP graphs kept by the stack
+ * (replacing earlier ones); nothing is executed.  (Two recordings, one for either role assignment of
+ * the layers' two counter buffers: replays and eager steps can be mixed freely.  Stepping a single
+ * layer of the stack on its own in between leaves the layers in disagreement: PTENC_ERR_STATE from
+ * the next recording or replay until the others have been stepped too.)  The pointers are frozen
+ * into the graphs: refill the same buffers between replays.  Every layer's encoder must be set (else PTENC_ERR_STATE).
  * The recording uses a stream of the library's own, so the caller's stream can be the default one.
  * A graph holds whatever kernel plan the layers had when it was recorded: record again after
  * ptenc_set_option. */

@@ -124,6 +124,7 @@ ptenc_status advanced(ptenc_ctx* x, hipError_t e) {
   if (x->opt_in_place) return PTENC_OK;
   long long* t = x->dev.len; x->dev.len = x->dev.len_nx; x->dev.len_nx = t;
   t = x->dev.base; x->dev.base = x->dev.base_nx; x->dev.base_nx = t;
+  ++x->swaps;
   return PTENC_OK;
 }
 inline ptenc_status hip_status(hipError_t e) { return e == hipSuccess ? PTENC_OK : PTENC_ERR_HIP; }
@@ -147,6 +148,15 @@ hipError_t refresh_selection(ptenc_ctx* x, hipStream_t s) {
 }
 
 }  // namespace
+
+void pt_ctx_stepped_by_replay(ptenc_ctx* ctx) {
+  appended_one(ctx);
+  (void)advanced(ctx, hipSuccess);
+}
+
+void pt_ctx_assume_full(ptenc_ctx* ctx) { ctx->live_ub = ctx->dev.Wr; }
+
+hipError_t pt_ctx_refresh_selection(ptenc_ctx* ctx, hipStream_t s) { return refresh_selection(ctx, s); }
 
 extern "C" {
 

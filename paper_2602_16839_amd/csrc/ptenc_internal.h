@@ -67,6 +67,7 @@ struct ptenc_ctx {
   int opt_recent;        // -1 = default
   int select_stale;      // scored policy: a ring may be full without a valid selection (see ptenc_api.hip)
   long long live_ub;     // upper bound on the live thinking tokens of the fullest ring (see may_evict)
+  int swaps;             // how often the two counter buffers have changed roles (parity = which is current)
   int waves;             // resolved: wavefronts per workgroup of the MFMA kernel
   int attn_kernel;       // 0 generic, 1 mfma
   int encode_kernel;     // 0 generic, 1 mfma
@@ -141,6 +142,15 @@ template <> __device__ inline float pt_ld<uint16_t>(const uint16_t* p) { return 
 template <typename T> __device__ inline void pt_st(T* p, float v);
 template <> __device__ inline void pt_st<float>(float* p, float v) { *p = v; }
 template <> __device__ inline void pt_st<uint16_t>(uint16_t* p, float v) { *p = pt_f32_to_bf16(v); }
+
+// Host bookkeeping of a decode step whose launch the context did not issue itself (the replay of
+// a recorded graph): the counter buffers change roles, the fill bound grows (ptenc_api.hip).
+void pt_ctx_stepped_by_replay(ptenc_ctx* ctx);
+// Before a step is recorded for replay: it may run at any later time, so it must carry the eviction machinery.
+void pt_ctx_assume_full(ptenc_ctx* ctx);
+// Scored policy: the stand-alone choice of victims, if the context's state asks for one (a launch, no
+// allocation); a replay does this first, because a recorded step cannot.
+hipError_t pt_ctx_refresh_selection(ptenc_ctx* ctx, hipStream_t s);
 
 // ------------------------------------------------------------------------------------------
 // Launchers implemented in the kernel files (host side, return hipError_t).

@@ -13,18 +13,32 @@
 #include "ptenc.h"
 #include "ptenc_internal.h"
 
+// A step reads one pair of counter buffers and writes the other, and the host swaps their roles after
+// every step; a recorded step has its pair frozen in.  So the stack records the step twice, once for
+// either assignment, and a replay takes the recording that matches the layers' current one: replays and
+// eager steps can then be mixed freely and no step needs its counters updated in place.
 struct ptenc_stack {
   std::vector<ptenc_ctx*> layers;
   hipStream_t capture_stream = nullptr;
-  hipGraph_t graph = nullptr;
-  hipGraphExec_t exec = nullptr;
+  hipGraph_t graph[2] = {nullptr, nullptr};          // by parity of the layers' swap count when the step starts
+  hipGraphExec_t exec[2] = {nullptr, nullptr};
 };
 
 namespace {
 
 void drop_graph(ptenc_stack* s) {
-  if (s->exec) { (void)hipGraphExecDestroy(s->exec); s->exec = nullptr; }
-  if (s->graph) { (void)hipGraphDestroy(s->graph); s->graph = nullptr; }
+  for (int p = 0; p < 2; ++p) {
+    if (s->exec[p]) { (void)hipGraphExecDestroy(s->exec[p]); s->exec[p] = nullptr; }
+    if (s->graph[p]) { (void)hipGraphDestroy(s->graph[p]); s->graph[p] = nullptr; }
+  }
+}
+
+// the layers' common swap parity, or -1 if a layer was stepped on its own and they disagree
+int common_parity(const ptenc_stack* s) {
+  const int p = s->layers[0]->swaps & 1;
+  for (const ptenc_ctx* x : s->layers)
+    if ((x->swaps & 1) != p) return -1;
+  return p;
 }
 
 ptenc_status launch_layers(ptenc_stack* s, const void* const* h_q, const void* const* h_k, const void* const* h_v,
@@ -66,8 +80,6 @@ ptenc_status ptenc_stack_create(const ptenc_config* cfg, int32_t n_layers, void*
   for (int l = 0; l < n_layers; ++l) {
     ptenc_ctx* x = nullptr;
     st = ptenc_create(cfg, (char*)d_cache + cb * l, (char*)d_state + sb * l, d_scratch, &x);
-    // counters in place: a step of the stack may be replayed from a graph at any time
-    if (st == PTENC_OK) st = ptenc_set_option(x, PTENC_OPT_COUNTERS_IN_PLACE, 1);
     // the layers' caches together decide whether the memory-side cache can hold the stream
     if (st == PTENC_OK && cb * (size_t)n_layers > ((size_t)192 << 20)) st = ptenc_set_option(x, PTENC_OPT_NONTEMPORAL, 1);
     if (x) s->layers.push_back(x);
@@ -119,30 +131,66 @@ ptenc_status ptenc_stack_graph_capture(ptenc_stack* s, const void* const* h_q, c
     if (!s->layers[l]->encoder_set) return PTENC_ERR_STATE;
   }
   drop_graph(s);
+  const int p0 = common_parity(s);
+  if (p0 < 0) return PTENC_ERR_STATE;
   // a stream of the library's own (default priority) records the launches; nothing runs on it
   if (!s->capture_stream && hipStreamCreateWithFlags(&s->capture_stream, hipStreamNonBlocking) != hipSuccess)
     return PTENC_ERR_HIP;
-  if (hipStreamBeginCapture(s->capture_stream, hipStreamCaptureModeThreadLocal) != hipSuccess) return PTENC_ERR_HIP;
-  ptenc_status st = launch_layers(s, h_q, h_k, h_v, h_out, d_active, s->capture_stream);
-  hipGraph_t g = nullptr;
-  hipError_t e = hipStreamEndCapture(s->capture_stream, &g);   // always ends the capture
-  if (st != PTENC_OK || e != hipSuccess || !g) {
-    if (g) (void)hipGraphDestroy(g);
-    return st != PTENC_OK ? st : PTENC_ERR_HIP;
+  // (a pending stand-alone choice of victims stays pending: a recording runs nothing, so it must not
+  // take the request away, and a replay sees to it before the recorded step)
+  std::vector<int> stale(s->layers.size());
+  for (size_t l = 0; l < s->layers.size(); ++l) {
+    pt_ctx_assume_full(s->layers[l]);
+    stale[l] = s->layers[l]->select_stale;
+    s->layers[l]->select_stale = 0;
   }
-  s->graph = g;
-  if (hipGraphInstantiate(&s->exec, g, nullptr, nullptr, 0) != hipSuccess) {
-    s->exec = nullptr;
-    drop_graph(s);
-    return PTENC_ERR_HIP;
+  auto restore_stale = [&]() {
+    for (size_t l = 0; l < s->layers.size(); ++l) s->layers[l]->select_stale = stale[l];
+  };
+  // two recordings: the step as it would run now, and as it would run after it (each recording swaps the
+  // host's buffer roles like a real step does, so after both the layers are as they were)
+  for (int rec = 0; rec < 2; ++rec) {
+    const int p = p0 ^ rec;
+    if (hipStreamBeginCapture(s->capture_stream, hipStreamCaptureModeThreadLocal) != hipSuccess) {
+      drop_graph(s);
+      restore_stale();
+      return PTENC_ERR_HIP;
+    }
+    ptenc_status st = launch_layers(s, h_q, h_k, h_v, h_out, d_active, s->capture_stream);
+    hipGraph_t g = nullptr;
+    hipError_t e = hipStreamEndCapture(s->capture_stream, &g);   // always ends the capture
+    if (st != PTENC_OK || e != hipSuccess || !g) {
+      if (g) (void)hipGraphDestroy(g);
+      // layers that were launched have swapped: bring everybody back to the starting assignment
+      for (ptenc_ctx* x : s->layers)
+        if ((x->swaps & 1) != p0) pt_ctx_stepped_by_replay(x);
+      drop_graph(s);
+      restore_stale();
+      return st != PTENC_OK ? st : PTENC_ERR_HIP;
+    }
+    s->graph[p] = g;
+    if (hipGraphInstantiate(&s->exec[p], g, nullptr, nullptr, 0) != hipSuccess) {
+      s->exec[p] = nullptr;
+      for (ptenc_ctx* x : s->layers)
+        if ((x->swaps & 1) != p0) pt_ctx_stepped_by_replay(x);
+      drop_graph(s);
+      restore_stale();
+      return PTENC_ERR_HIP;
+    }
   }
+  restore_stale();
   return PTENC_OK;
 }
 
 ptenc_status ptenc_stack_graph_launch(ptenc_stack* s, void* stream) {
   if (!s) return PTENC_ERR_INVALID_ARG;
-  if (!s->exec) return PTENC_ERR_STATE;
-  return hipGraphLaunch(s->exec, (hipStream_t)stream) == hipSuccess ? PTENC_OK : PTENC_ERR_HIP;
+  const int p = common_parity(s);
+  if (p < 0 || !s->exec[p]) return PTENC_ERR_STATE;
+  for (ptenc_ctx* x : s->layers)
+    if (pt_ctx_refresh_selection(x, (hipStream_t)stream) != hipSuccess) return PTENC_ERR_HIP;
+  if (hipGraphLaunch(s->exec[p], (hipStream_t)stream) != hipSuccess) return PTENC_ERR_HIP;
+  for (ptenc_ctx* x : s->layers) pt_ctx_stepped_by_replay(x);
+  return PTENC_OK;
 }
 
 }  // extern "C"

@@ -149,3 +149,31 @@ def test_stack_layers_under_the_scored_policy():
         for b in range(wl.batch):
             assert vic[b].tolist() == orcs[l].last_victims[b]
         H.assert_close(st.layers[l].get_state(), orcs[l].state(), H.S_ABS, H.S_REL, "layer %d state" % l)
+
+
+def test_a_layer_stepped_on_its_own_is_noticed_by_the_recorded_step():
+    # the recorded step exists once for either role assignment of the layers' two counter buffers; a
+    # layer that is stepped alone leaves the assignment the others have, and the stack says so
+    L = 2
+    wl = I.WORKLOADS["qwen7b"].replace(batch=2, n_q_heads=14, n_kv_heads=2, window=64, chunk=16, steps=8)
+    wls = _layer_workloads(wl, L)
+    st = _make_stack(wl, L, [I.encoder_params(w) for w in wls])
+    dev = [tuple(x.cuda() for x in I.qkv_steps(w, 0, 4)) for w in wls]
+    qs, ks, vs = ([d[i][0].clone() for d in dev] for i in range(3))
+    outs = [torch.empty_like(x) for x in qs]
+    st.graph_capture(qs, ks, vs, outs)
+    st.graph_launch()
+    st.graph_launch()
+    st.step([d[0][1] for d in dev], [d[1][1] for d in dev], [d[2][1] for d in dev])
+    st.graph_launch()                                        # any mix of replays and eager steps is fine
+    st.layers[1].step(dev[1][0][2], dev[1][1][2], dev[1][2][2])
+    with pytest.raises(ptenc.PtencError) as ei:
+        st.graph_launch()
+    assert ei.value.status == ptenc.ERR_STATE
+    st.layers[0].step(dev[0][0][2], dev[0][1][2], dev[0][2][2])   # the other layer catches up
+    st.graph_launch()
+    torch.cuda.synchronize()
+    for layer in st.layers:
+        ln, base = layer.counters()
+        assert (ln == 6).all() and (base == 0).all()
+        assert layer.poll_error() == 0
