@@ -118,6 +118,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--workload", default="qwen7b")
     ap.add_argument("--splits", type=int, default=0)
+    ap.add_argument("--encode-parts", type=int, default=0,
+                    help="workgroups that share one evicted chunk's encoding (0 = the library's heuristic)")
     ap.add_argument("--chunk", type=int, default=0,
                     help="override the workload's eviction chunk C (eviction-ratio sweeps; 0 = the workload's own)")
     ap.add_argument("--ragged-mode", choices=["compact", "masked"], default="compact",
@@ -201,6 +203,8 @@ def main() -> int:
 
     if args.splits:
         layer.set_option(ptenc.OPT_SPLITS, args.splits)
+    if args.encode_parts:
+        layer.set_option(ptenc.OPT_ENCODE_PARTS, args.encode_parts)
     if args.policy == "scored":
         layer.set_option(ptenc.OPT_RECENT, args.recent)
         layer.set_option(ptenc.OPT_EVICT_POLICY, ptenc.POLICY_SCORED)

@@ -93,8 +93,12 @@ typedef enum {
                                  arrival counter per rollout and step.  Default 0. */
   PTENC_OPT_EVICT_POLICY = 5, /* ptenc_policy: which tokens an eviction takes.  Set it before the first step after
                                  a reset (scores are kept only while it is PTENC_POLICY_SCORED). */
-  PTENC_OPT_RECENT = 6        /* scored policy: the n most recent ring entries are never taken; 0 .. W - n_sink - C;
+  PTENC_OPT_RECENT = 6,       /* scored policy: the n most recent ring entries are never taken; 0 .. W - n_sink - C;
                                  -1 = default (half the ring, at most W - n_sink - C) */
+  PTENC_OPT_ENCODE_PARTS = 7  /* MFMA path: workgroups that share the encoding of one rollout's evicted chunk, each
+                                 a contiguous range of its 32-token groups, their shares of S' added in range
+                                 order; 1..8; 0 = heuristic (one per 64 tokens of the chunk, at most 8).  S
+                                 depends on it in the last bits only (fp32 summation order). */
 } ptenc_option;
 
 /* Which tokens leave when the sliding part of the cache is full.

@@ -39,7 +39,7 @@ __global__ void reset_kernel(PtDev c, const uint8_t* __restrict__ mask, int clea
   const int b = blockIdx.x;
   if (clear_err && b == 0 && threadIdx.x == 0) *c.err = 0;
   // arrival counters are zero between kernels anyway; a fresh context gets them zeroed here
-  if (threadIdx.x == 0) c.tick_rollout[b] = 0;
+  if (threadIdx.x == 0) { c.tick_rollout[b] = 0; c.tick_enc[b] = 0; }
   for (int h = threadIdx.x; h < c.Hkv; h += blockDim.x) c.tick_slab[b * c.Hkv + h] = 0;
   if (mask && !mask[b]) return;
   const int n = c.G * c.r;

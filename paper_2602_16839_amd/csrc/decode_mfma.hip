@@ -23,13 +23,15 @@
 // (a counter, no waiting), in split order, so the result does not depend on the arrival order.
 //
 // Eviction.  The encoder sums over the concatenated KV heads, so a rollout's chunk is folded into S by
-// ONE workgroup that reads all heads (encode_rollout: K_a = K_e W^a_K and V_a = V_e W^a_V with MFMA,
-// then S' = (Q_a K_a^T) V_a and the update of S in fp32).  Launches that may evict carry one such
-// workgroup per row behind the attention workgroups in the grid; where nothing is full it leaves at
-// once.  It shares nothing with the rollout's attention workgroups, which already walk the window
-// without the chunk and take the new token from the step's inputs, so an eviction lengthens nobody's
-// walk (rollouts of a running batch do not evict in the same step).  The new token goes into the
-// chunk's oldest slot, so the encoding workgroup stores it itself, after its last read of the chunk.
+// workgroups that read all heads (encode_rollout: K_a = K_e W^a_K and V_a = V_e W^a_V with MFMA,
+// then S' = (Q_a K_a^T) V_a and the update of S in fp32).  Launches that may evict carry such
+// workgroups behind the attention workgroups in the grid: c.enc_parts per row, each with a contiguous
+// range of the chunk's 32-token groups; where nothing is full they leave at once.  They share
+// nothing with the rollout's attention workgroups, which already walk the window without the chunk
+// and take the new token from the step's inputs, so an eviction lengthens nobody's walk (rollouts
+// of a running batch do not evict in the same step).  The parts' shares of S' meet in memory; the
+// last part to arrive adds them in part order, updates S and, the chunk's oldest slot being free
+// now that every part has read its range, stores the new token there.
 //
 // Counters are double-buffered: a step reads (len, base) from one pair of arrays and writes the
 // other, so no workgroup has to wait for the rest of its rollout before the step can end.  (Compact
@@ -242,6 +244,12 @@ __device__ inline void st_agent2(float* p, float a, float b) {
   const unsigned long long u = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
   __hip_atomic_store((unsigned long long*)p, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+__device__ inline void st_agent1(float* p, float a) {
+  __hip_atomic_store(p, a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline float ld_agent1(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 __device__ inline void ld_agent2(const float* p, float& a, float& b) {
   const unsigned long long u = __hip_atomic_load((const unsigned long long*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   a = __uint_as_float((unsigned)u);
@@ -398,13 +406,17 @@ union StepSmem {
 // ROLE 0: a K_a tile, 1: a V_a tile, 2: neither (wavefronts 4..7 of an 8-wavefront workgroup only pass
 // the barriers).  One instance per role, so that each keeps its own operand buffer in registers; every
 // instance passes the same barriers.
+//
+// A long chunk is shared by c.enc_parts workgroups: this one (`part`) takes a contiguous range of the
+// groups and leaves its share of S'.
 template <int WAVES, int ROLE>
-__device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b, int s0) {
+__device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b, int s0, int part) {
   constexpr int NP = ROLE == 0 ? 4 : 8;          // 16-byte pieces per lane, KV head and group
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 15, kgrp = lane >> 4;
   const int g0 = s0 >> 5, off0 = s0 & 31, NG = c.Wr >> 5, gs = c.n_sink >> 5;
   const int n_vis = (off0 + c.C + PT_GROUP_TOKENS - 1) >> 5;
+  const int v_lo = part * n_vis / c.enc_parts, v_hi = (part + 1) * n_vis / c.enc_parts;
   const int t = wave & 1;
   const size_t slab_u = pt_slab_elems(c.W, 128) / 8;                 // a slab in 16-byte units
   const u32x4* cache0 = (const u32x4*)c.cache + (size_t)b * c.Hkv * slab_u;
@@ -429,7 +441,7 @@ __device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b,
       for (int i = 0; i < NP; ++i) buf[hh][i] = ROLE == 0 ? grp[t * 256 + i * 64 + lane] : grp[512 + i * 64 + lane];
     }
   };
-  if (ROLE != 2) load_batch(0, 0);
+  if (ROLE != 2 && v_lo < v_hi) load_batch(v_lo, 0);
   // The fp32 tail on the matrix units as well (16x16x4 fp32 MFMA): wavefront w < ceil(G / 16) owns rows
   // 16 w .. 16 w + 15 of S'.  Its slice of Q_a stays in registers: the B operand of k-step s is
   // Q_a[16 w + lane % 16][4 s + lane / 16] (zero outside G x r).
@@ -444,7 +456,7 @@ __device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b,
   }
 #pragma unroll
   for (int ct = 0; ct < 4; ++ct) sp[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
-  for (int vis = 0; vis < n_vis; ++vis) {
+  for (int vis = v_lo; vis < v_hi; ++vis) {
     if (ROLE != 2) {
       f32x4 acc[4];
 #pragma unroll
@@ -496,7 +508,7 @@ __device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b,
           }
         }
         if (bi + 1 < n_batches) load_batch(vis, h0 + HB);
-        else if (vis + 1 < n_vis) load_batch(vis + 1, 0);
+        else if (vis + 1 < v_hi) load_batch(vis + 1, 0);
       }
       // D[token 4 kgrp + e of the tile][column 16 rt + n]
       float (*dst)[kEncMaxGR + 1] = ROLE == 1 ? sm.enc.tail.Va : sm.enc.tail.Ka;
@@ -555,23 +567,50 @@ __device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b,
   }
 }
 
+// Returns whether this workgroup is the one that went on to update S (with one part per chunk: always;
+// otherwise the last part to arrive, which adds the parts' shares in part order, so that the sum does
+// not depend on who arrived when).
 template <int WAVES>
-__device__ inline void encode_rollout(const PtDev& c, StepSmem<WAVES>& sm, int b, int s0) {
+__device__ inline bool encode_rollout(const PtDev& c, StepSmem<WAVES>& sm, int& sm_ticket, int b, int s0, int part) {
   constexpr int THREADS = WAVES * 64;
   const int wave = threadIdx.x >> 6;
-  if (wave >= 4) encode_groups<WAVES, 2>(c, sm, b, s0);
-  else if (wave & 2) encode_groups<WAVES, 1>(c, sm, b, s0);
-  else encode_groups<WAVES, 0>(c, sm, b, s0);
+  if (wave >= 4) encode_groups<WAVES, 2>(c, sm, b, s0, part);
+  else if (wave & 2) encode_groups<WAVES, 1>(c, sm, b, s0, part);
+  else encode_groups<WAVES, 0>(c, sm, b, s0, part);
   __syncthreads();
   float* stage = &sm.enc.tail.Ka[0][0];
+  const int gr = c.G * c.r;
   float sacc[16];
+  if (c.enc_parts == 1) {
 #pragma unroll
-  for (int x = 0; x < 4096 / THREADS; ++x) {
-    const int idx = threadIdx.x + THREADS * x;
-    sacc[x] = idx < c.G * c.r ? stage[idx] : 0.f;
+    for (int x = 0; x < 4096 / THREADS; ++x) {
+      const int idx = threadIdx.x + THREADS * x;
+      sacc[x] = idx < gr ? stage[idx] : 0.f;
+    }
+  } else {
+    // park this part's share (device-scope stores, as for the window splits); the last part to arrive
+    // adds all of them
+    float* mine = c.enc_part + ((size_t)b * c.enc_parts + part) * gr;
+    for (int idx = threadIdx.x; idx < gr; idx += THREADS) st_agent1(mine + idx, stage[idx]);
+    __threadfence_block();
+    __syncthreads();
+    if (threadIdx.x == 0) sm_ticket = atomicAdd(c.tick_enc + b, 1);
+    __syncthreads();
+    if (sm_ticket != c.enc_parts - 1) return false;
+    if (threadIdx.x == 0) c.tick_enc[b] = 0;
+    const float* all = c.enc_part + (size_t)b * c.enc_parts * gr;
+#pragma unroll
+    for (int x = 0; x < 4096 / THREADS; ++x) {
+      const int idx = threadIdx.x + THREADS * x;
+      float v = 0.f;
+      if (idx < gr)
+        for (int p = 0; p < c.enc_parts; ++p) v += ld_agent1(all + (size_t)p * gr + idx);
+      sacc[x] = v;
+    }
   }
   __syncthreads();
   pt_state_update<THREADS>(c, b, sacc, stage, sm.enc.tail.red);
+  return true;
 }
 
 // What a step does to one rollout, from the counters it finds.  Both kinds of workgroup of a rollout
@@ -630,9 +669,12 @@ __device__ inline void arrive_rollout(const PtDev& c, const StepArgs& a, StepSme
 // inputs; nobody waits for anybody.
 template <int WAVES, bool MASS>
 __device__ inline void encoder_role(const PtDev& c, const StepArgs& a, StepSmem<WAVES>& sm, int& sm_ticket,
-                                    float* dyn_lds, int j_row, const int* ids, const uint8_t* active,
+                                    float* dyn_lds, int enc_idx, const int* ids, const uint8_t* active,
                                     const long long* len_cur, const long long* base_cur) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, kgrp = lane >> 4;
+  // a long chunk has several encoding workgroups per row: part 0 stands for the row where nothing is
+  // evicted; of an evicting row's parts, the last one to finish its share does everything after it
+  const int j_row = enc_idx / c.enc_parts, part = enc_idx - j_row * c.enc_parts;
   int b = j_row;
   if (ids) {
     b = ld_uniform(ids + j_row);
@@ -646,9 +688,10 @@ __device__ inline void encoder_role(const PtDev& c, const StepArgs& a, StepSmem<
   const long long len0 = head.len, base0 = head.base;
   if (len0 < base0) return;
   const StepPlan pl = plan_step<MASS>(c, a, act, len0, base0);
+  if (!pl.evicting && part != 0) return;
   if (pl.evicting) {
     const int s0e = (int)(base0 % c.Wr);
-    encode_rollout<WAVES>(c, sm, b, s0e);
+    if (!encode_rollout<WAVES>(c, sm, sm_ticket, b, s0e, part)) return;
     if (a.dbg_chunk) {
       const int dkv = c.Hkv * 128;
       uint16_t* dK = a.dbg_chunk + (size_t)b * 2 * c.C * dkv;
@@ -702,7 +745,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
     if (split != 0) return;
     const int extra = blockIdx.x - n_rows * n_kv_heads;
     if constexpr (ENC) {
-      if (extra < n_rows) {
+      if (extra < n_rows * c.enc_parts) {
         encoder_role<WAVES, MASS>(c, a, sm, sm_ticket, dyn_lds, extra, ids, active, len_cur, base_cur);
         return;
       }
@@ -1094,8 +1137,8 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bo
   PtDev cc = c;
   if (!do_attend) cc.n_splits = 1;
   const int rows = ids ? n_rows : cc.B;
-  // attention workgroups, then one encoding workgroup per row if the launch may evict, then the carrier
-  dim3 grid(rows * cc.Hkv + (do_evict ? rows : 0) + (a.carry ? 1 : 0), cc.n_splits);
+  // attention workgroups, then the encoding workgroups of every row if the launch may evict, then the carrier
+  dim3 grid(rows * cc.Hkv + (do_evict ? rows * cc.enc_parts : 0) + (a.carry ? 1 : 0), cc.n_splits);
   // scores are maintained by whole steps only (append + attention) under the scored policy
   const bool mass = cc.scored && do_append && do_attend;
   // parked masses of every group a workgroup may walk

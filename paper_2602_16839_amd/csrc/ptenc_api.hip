@@ -11,7 +11,7 @@ namespace {
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct StateLayout {
-  size_t S, Qa, S0, len, base, len2, base2, n_prompt, err, tick_rollout, tick_slab, WKp, WVp;
+  size_t S, Qa, S0, len, base, len2, base2, n_prompt, err, tick_rollout, tick_slab, tick_enc, WKp, WVp;
   size_t mass, pos, victims, qprev, mlprev, mtag, selected, total;   // importance-based eviction
 };
 
@@ -30,6 +30,7 @@ StateLayout state_layout(const ptenc_config& c) {
   L.err = off;  off = align256(off + sizeof(int));
   L.tick_rollout = off; off = align256(off + sizeof(int) * c.batch);
   L.tick_slab = off;    off = align256(off + sizeof(int) * c.batch * c.n_kv_heads);
+  L.tick_enc = off;     off = align256(off + sizeof(int) * c.batch);
   const size_t packed = (size_t)c.n_kv_heads * 4 * 4 * 64 * 8 * 2;   // MFMA operand form of W^a_K / W^a_V
   L.WKp = off;  off = align256(off + packed);
   L.WVp = off;  off = align256(off + packed);
@@ -64,6 +65,18 @@ size_t elem_bytes(int dtype) { return dtype == PTENC_F32 ? 4 : 2; }
 
 size_t partial_bytes(const ptenc_config& c) {
   return align256((size_t)c.batch * c.n_q_heads * PTENC_MAX_SPLITS * (c.head_dim + 2) * sizeof(float));
+}
+
+// A chunk is encoded by several workgroups, each a contiguous range of its 32-token groups: about two
+// groups each is where the step time stopped improving when the rollouts' evictions fall on different
+// steps (one workgroup takes about 4.5 us per group, and while it runs it holds a place an attention
+// workgroup would have had)
+int enc_parts_for(const ptenc_config& c) {
+  const int e = c.chunk / 64;
+  return e < 1 ? 1 : (e > PT_MAX_ENC_PARTS ? PT_MAX_ENC_PARTS : e);
+}
+size_t enc_part_bytes(const ptenc_config& c) {
+  return align256((size_t)c.batch * PT_MAX_ENC_PARTS * c.n_global * c.rank * sizeof(float));
 }
 
 bool mfma_attn_applies(const ptenc_config& c) {
@@ -110,6 +123,7 @@ void replan(ptenc_ctx* x) {
   x->dev.scored = (x->opt_policy == PTENC_POLICY_SCORED && x->attn_kernel == 1) ? 1 : 0;
   x->dev.n_recent = resolved_recent(x);
   x->encode_kernel = x->attn_kernel;
+  x->dev.enc_parts = x->opt_enc_parts > 0 ? x->opt_enc_parts : enc_parts_for(x->cfg);
   x->dev.n_splits = x->opt_splits > 0 ? x->opt_splits : heuristic_splits(x, x->cfg.batch);
   x->waves = pick_waves(x, x->cfg.batch, x->dev.n_splits);
   // a cache that fits the 256 MiB memory-side cache is better served by ordinary loads
@@ -169,7 +183,7 @@ ptenc_status ptenc_query_sizes(const ptenc_config* cfg, size_t* cache_bytes, siz
                             elem_bytes(cfg->dtype));
   if (state_bytes) *state_bytes = state_layout(*cfg).total;
   if (scratch_bytes)
-    *scratch_bytes = partial_bytes(*cfg);
+    *scratch_bytes = partial_bytes(*cfg) + enc_part_bytes(*cfg);
   return PTENC_OK;
 }
 
@@ -210,6 +224,8 @@ ptenc_status ptenc_create(const ptenc_config* cfg, void* d_cache, void* d_state,
   d.WaK = nullptr; d.WaV = nullptr;
   d.n_rt = (cfg->rank + 15) / 16;
   d.tick_rollout = (int*)(sp + L.tick_rollout); d.tick_slab = (int*)(sp + L.tick_slab);
+  d.tick_enc = (int*)(sp + L.tick_enc);
+  d.enc_part = (float*)((char*)d_scratch + partial_bytes(*cfg));
   d.WKp = sp + L.WKp; d.WVp = sp + L.WVp;
   d.scored = 0; d.n_recent = 0;
   d.mass = (float*)(sp + L.mass); d.pos = (long long*)(sp + L.pos); d.victims = (long long*)(sp + L.victims);
@@ -240,6 +256,10 @@ ptenc_status ptenc_set_option(ptenc_ctx* ctx, int32_t option, int32_t value) {
     case PTENC_OPT_NONTEMPORAL:
       if (value < -1 || value > 1) return PTENC_ERR_INVALID_ARG;
       ctx->opt_nontemporal = value;
+      break;
+    case PTENC_OPT_ENCODE_PARTS:
+      if (value < 0 || value > PT_MAX_ENC_PARTS) return PTENC_ERR_INVALID_ARG;
+      ctx->opt_enc_parts = value;
       break;
     case PTENC_OPT_WAVES:
       if (value != 0 && value != 4 && value != 8) return PTENC_ERR_INVALID_ARG;

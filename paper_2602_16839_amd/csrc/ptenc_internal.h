@@ -37,6 +37,9 @@ struct PtDev {
   int n_rt;           // ceil(r / 16): 16-column tiles of the latent space
   int* tick_rollout;  // [B]      arrival counters, zero between kernels
   int* tick_slab;     // [B*H_kv]
+  int* tick_enc;      // [B]      (the parts of a long chunk's encoding)
+  int enc_parts;      // workgroups that share one rollout's chunk (1 unless the chunk is long)
+  float* enc_part;    // [B][enc_parts][G*r] their partial S', in the scratch buffer after `partial`
   void* WKp;          // W^a_K, W^a_V repacked as MFMA B operands: [H_kv][4][4][64 lanes][8] bf16
   void* WVp;
   // importance-based eviction (MFMA path only)
@@ -62,6 +65,7 @@ struct ptenc_ctx {
   int opt_nontemporal;   // -1 = heuristic, 0, 1
   int nontemporal;       // resolved
   int opt_waves;         // 0 = heuristic, 4, 8
+  int opt_enc_parts;     // 0 = heuristic, 1..PT_MAX_ENC_PARTS
   int opt_in_place;      // 1 = counters are updated in place (no buffer rotation on the host)
   int opt_policy;        // 0 sliding window, 1 scored
   int opt_recent;        // -1 = default
@@ -96,6 +100,7 @@ struct ptenc_ctx {
 //    group in each lane, so the probabilities feed the second MFMA without any lane exchange).
 // ------------------------------------------------------------------------------------------
 #define PT_GROUP_TOKENS 32
+#define PT_MAX_ENC_PARTS 8  /* workgroups that may share the encoding of one evicted chunk */
 #define PT_GROUP_ELEMS 8192      // 32 tokens * 128 * 2 (K and V)
 
 __host__ __device__ inline size_t pt_slab_elems(int W, int d) { return (size_t)2 * W * d; }

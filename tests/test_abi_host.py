@@ -77,6 +77,8 @@ def test_create_checks_pointers_and_order_of_calls():
     assert L.ptenc_decode_attn(h, None, C.c_void_p(256), None, None) == ptenc.ERR_INVALID_ARG
     assert L.ptenc_set_option(h, ptenc.OPT_SPLITS, ptenc.MAX_SPLITS + 1) == ptenc.ERR_INVALID_ARG
     assert L.ptenc_set_option(h, 99, 0) == ptenc.ERR_INVALID_ARG
+    for v, st in ((-1, ptenc.ERR_INVALID_ARG), (9, ptenc.ERR_INVALID_ARG), (8, ptenc.OK), (0, ptenc.OK)):
+        assert L.ptenc_set_option(h, ptenc.OPT_ENCODE_PARTS, v) == st
     assert L.ptenc_set_option(h, ptenc.OPT_SPLITS, 3) == ptenc.OK
     assert ptenc.ptenc_get_plan(h) == (1, 3, 1)
     assert L.ptenc_destroy(h) == ptenc.OK

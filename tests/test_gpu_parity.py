@@ -53,6 +53,25 @@ def test_eight_wavefront_workgroups(splits):
     H.run_both(wl, wl.steps, waves=8, check_every=11)
 
 
+@pytest.mark.parametrize("W,C,n_sink,waves,splits,parts", [(1056, 520, 0, 4, 1, 0), (1120, 800, 32, 8, 2, 3),
+                                                          (2112, 2070, 0, 4, 3, 0), (1024, 1024, 0, 8, 1, 5),
+                                                          (160, 48, 0, 4, 1, 8), (96, 33, 0, 4, 1, 2)])
+def test_chunks_are_encoded_by_several_workgroups(W, C, n_sink, waves, splits, parts):
+    # the encoding of a chunk is shared by up to 8 workgroups per rollout (by default one per 64 tokens),
+    # each a contiguous range of the chunk's 32-token groups; here with chunks that are not whole groups
+    # (so later evictions start inside a group), that wrap around the ring's end, that are the whole ring,
+    # and with more workgroups than the chunk has groups (some get nothing)
+    wl = small("qwen3b", batch=2, n_q_heads=4, n_kv_heads=2, window=W, n_sink=n_sink, chunk=C,
+               steps=(W - n_sink) + 2 * C + 40)
+    lengths = np.array([wl.steps, (W - n_sink) + C + 17])        # the second rollout stops before its third eviction
+    layer, _ = H.run_both(wl, wl.steps, splits=splits, waves=waves, check_every=61, lengths=lengths,
+                          prompt_len=[n_sink, 5] if n_sink else None, enc_parts=parts)
+    assert layer.plan()[:2] == (1, splits)
+    ln, base = layer.counters()
+    Wr = W - n_sink
+    assert [int(x) for x in base] == [-(-(int(T) - Wr) // C) * C for T in lengths]      # an eviction at steps Wr, Wr + C, ...
+
+
 def test_bf16_generic_path_small_window():
     wl = small("qwen3b", batch=2, n_q_heads=8, n_kv_heads=2, window=96, chunk=40, steps=250)
     layer, _ = H.run_both(wl, wl.steps, force_generic=True, splits=2)

@@ -151,7 +151,8 @@ def _random_selection_cases(n):
     return cases
 
 
-@pytest.mark.parametrize("W,C,n_recent,n_sink", [(96, 32, 24, 0), (160, 40, 0, 32), (128, 7, 100, 0), (64, 64, 0, 0)]
+@pytest.mark.parametrize("W,C,n_recent,n_sink", [(96, 32, 24, 0), (160, 40, 0, 32), (128, 7, 100, 0), (64, 64, 0, 0),
+                                                   (608, 520, 50, 0)]     # (a chunk long enough for two encoding workgroups)
                          + _random_selection_cases(12))
 def test_selection_on_injected_scores_is_bit_exact(W, C, n_recent, n_sink):
     # scores with few distinct values (plenty of ties), the same float32 numbers on both sides
