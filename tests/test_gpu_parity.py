@@ -220,7 +220,7 @@ def test_rollouts_pause_and_resume_in_compact_lists(kind, in_place):
         kw = {}
     else:
         wl = small("ragged", batch=7, n_q_heads=8, n_kv_heads=2, window=32, chunk=8, steps=140)
-        kw = dict(force_generic=(kind == "generic_bf16"))
+        kw = dict(force_generic=(kind == "generic_bf16"), enc_parts=2 if in_place else 0)
     enc = I.encoder_params(wl)
     orc = H.make_oracle(wl, enc)
     layer = H.make_layer(wl, enc, **kw)
@@ -305,9 +305,10 @@ def test_a_captured_step_replays_like_eager_steps(kind):
         wl = small("tiny_f32", batch=3, window=24, chunk=8, steps=60)
     enc = I.encoder_params(wl)
     q, k, v = (x.cuda() for x in I.qkv_steps(wl, 0, wl.steps))
-    eager = H.make_layer(wl, enc)
+    parts = 3 if kind == "mfma" else 0       # (three encoding workgroups per rollout for chunks of one or two groups)
+    eager = H.make_layer(wl, enc, enc_parts=parts)
     ref = eager.run(q, k, v)
-    layer = H.make_layer(wl, enc)
+    layer = H.make_layer(wl, enc, enc_parts=parts)
     layer.set_option(ptenc.OPT_COUNTERS_IN_PLACE, 1)
     qs, ks, vs = torch.empty_like(q[0]), torch.empty_like(k[0]), torch.empty_like(v[0])
     outs = torch.empty_like(q[0])

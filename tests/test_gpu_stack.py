@@ -38,6 +38,10 @@ def test_stack_steps_and_graph_replays_match_per_layer_oracles(kind):
     orcs = [H.make_oracle(w, e) for w, e in zip(wls, encs)]
     st = _make_stack(wl, L, encs)
     assert [layer.plan()[0] for layer in st.layers] == [1 if kind == "mfma" else 0] * L
+    if kind == "mfma":
+        # two encoding workgroups per rollout: their shares of S' meet in the scratch buffer the layers share
+        for layer in st.layers:
+            layer.set_option(ptenc.OPT_ENCODE_PARTS, 2)
     T = wl.steps
     qkv = [I.qkv_steps(w, 0, T) for w in wls]
     dev = [tuple(x.cuda() for x in t) for t in qkv]
