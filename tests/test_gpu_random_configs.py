@@ -1,6 +1,7 @@
 """Seeded random small configurations through the whole decode path against the oracle: shapes, window
-/ chunk / reserved-slot sizes, window splits, workgroup sizes, masks and compact id lists are drawn
-together, so that combinations nobody wrote a dedicated test for get exercised too."""
+/ chunk / reserved-slot sizes, window splits, workgroup sizes, encoding workgroups per chunk, masks and
+compact id lists are drawn together, so that combinations nobody wrote a dedicated test for get
+exercised too."""
 import numpy as np
 import pytest
 import torch
@@ -47,7 +48,9 @@ def test_random_configuration(kind, seed):
     wl, splits, waves, mode = _draw(rng, kind)
     enc = I.encoder_params(wl)
     orc = H.make_oracle(wl, enc)
-    layer = H.make_layer(wl, enc, splits=splits, waves=waves)
+    # (a generator of its own, so that the cases drawn before this option existed stay what they were)
+    parts = int(np.random.default_rng(5000 + seed).choice([0, 1, 2, 3, 5, 8])) if kind == "mfma" else 0
+    layer = H.make_layer(wl, enc, splits=splits, waves=waves, enc_parts=parts)
     assert layer.plan()[0] == (1 if kind == "mfma" else 0), (kind, wl)
     prompt_len = None
     if wl.n_sink:
@@ -62,7 +65,7 @@ def test_random_configuration(kind, seed):
     qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
     qn, kn, vn = H.f64(q), H.f64(k), H.f64(v)
     abs_tol, rel_tol = H.tolerances(wl)
-    what = "%s seed %d: %s splits %d waves %d %s" % (kind, seed, wl, splits, waves, mode)
+    what = "%s seed %d: %s splits %d waves %d parts %d %s" % (kind, seed, wl, splits, waves, parts, mode)
     for t in range(T):
         act = I.active_mask(lengths, t)
         ref = orc.step(qn[t], kn[t], vn[t], None if mode == "full" else act)
