@@ -46,6 +46,9 @@
  *     ring can be and launches steps without the eviction machinery while none can be full; a
  *     ring filled behind its back shows up as PTENC_DEVERR_APPEND_FULL).
  *   - Overlapping calls on one context from different streams race; serialise them.
+ *   - The scratch block only carries what workgroups of ONE launch hand to each other (the window
+ *     splits' partial results, the shares of a chunk's encoding); nothing in it outlives a launch,
+ *     so contexts whose launches never overlap may share one block (the layers of a ptenc_stack do).
  *   - HIP graphs: every decode entry point only launches kernels (no allocation, copy or memset),
  *     so it can be captured; set PTENC_OPT_COUNTERS_IN_PLACE first, and give the graph fixed
  *     input / output buffers that are refilled between replays.
