@@ -69,8 +69,8 @@ size_t partial_bytes(const ptenc_config& c) {
 
 // A chunk is encoded by several workgroups, each a contiguous range of its 32-token groups: about two
 // groups each is where the step time stopped improving when the rollouts' evictions fall on different
-// steps (one workgroup takes about 4.5 us per group, and while it runs it holds a place an attention
-// workgroup would have had)
+// steps (one workgroup takes about 4.5 us per group, more while the attention of the other rollouts
+// keeps the memory system busy, and it starts only when the first attention workgroups have left)
 int enc_parts_for(const ptenc_config& c) {
   const int e = c.chunk / 64;
   return e < 1 ? 1 : (e > PT_MAX_ENC_PARTS ? PT_MAX_ENC_PARTS : e);
