@@ -34,9 +34,10 @@
 // now that every part has read its range, stores the new token there.
 //
 // Counters are double-buffered: a step reads (len, base) from one pair of arrays and writes the
-// other, so no workgroup has to wait for the rest of its rollout before the step can end.  (Compact
-// lists and graph replays update them in place instead: the rollout's last workgroup to arrive
-// writes them, after every other one has read them.)
+// other, so no workgroup has to wait for the rest of its rollout before the step can end.  A compact
+// list does the same for the rollouts it names, and one extra workgroup carries everybody's counters
+// over to the other pair.  (With the in-place option, for steps a caller replays from a graph, the
+// rollout's last workgroup to arrive writes them where they are, after every other one has read them.)
 //
 // Importance scores (template argument MASS, the scored eviction policy; the paper's ablation on
 // token dropping strategies).  The attention probability every cached token received in the rollout's
@@ -235,7 +236,8 @@ __device__ inline void patch_newest(Frag& f, const Op kp[4], const uint32_t vp[4
   }
 }
 
-// Data handed from one workgroup to another inside this kernel (the window splits' partial results)
+// Data handed from one workgroup to another inside this kernel (the window splits' partial results, the
+// encoding workgroups' shares of S')
 // is written and read with device-scope relaxed atomics: such stores write through and
 // such loads bypass the per-CU and per-XCD caches, so the hand-over needs no cache write-back or
 // invalidation.  Order is given by: stores, wait for them (workgroup fence), barrier, ticket.
@@ -381,7 +383,7 @@ union StepSmem {
     float o[WAVES][64 / WAVES][kORow];
     float m[WAVES][64 / WAVES], l[WAVES][64 / WAVES];
   } merge;
-  struct {           // the encoding workgroup of a rollout
+  struct {           // an encoding workgroup
     // one group's V part of one KV head, per V wavefront (operand transposition): the 16-byte piece of
     // (value-column tile it, lane group k, row m) sits at 16-byte index (4 it + k) * 18 + m + m / 8, a pitch
     // that spreads the pieces one gather touches over all banks (2-way conflicts instead of 16-way)
@@ -395,8 +397,9 @@ union StepSmem {
   SelSmall sel;      // scored policy: the choice of the next victims, by the rollout's last workgroup
 };
 
-// The evicted chunk of one rollout, by ONE workgroup that does nothing else in this launch, so that a
-// rollout's eviction is not on the path of its own or anybody's attention: K_a = K_e W^a_K and
+// The evicted chunk of one rollout (or this workgroup's part of it: see below), by a workgroup that
+// does nothing else in this launch, so that a rollout's eviction is not on the path of its own or
+// anybody's attention: K_a = K_e W^a_K and
 // V_a = V_e W^a_V over the concatenated KV heads (MFMA, accumulated over the heads in head order),
 // S' = (Q_a K_a^T) V_a, S <- Normalize(S + S')  (Our Approach, the Delta-W equation and the update rule).
 // The chunk is the ring-relative slots [s0, s0 + C) (wrapping), walked as 32-slot groups; rows of a group
@@ -407,8 +410,8 @@ union StepSmem {
 // the barriers).  One instance per role, so that each keeps its own operand buffer in registers; every
 // instance passes the same barriers.
 //
-// A long chunk is shared by c.enc_parts workgroups: this one (`part`) takes a contiguous range of the
-// groups and leaves its share of S'.
+// A chunk is shared by c.enc_parts workgroups: this one (`part`) takes a contiguous range of the
+// groups and leaves its share of S' (in LDS, row-major G x r).
 template <int WAVES, int ROLE>
 __device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b, int s0, int part) {
   constexpr int NP = ROLE == 0 ? 4 : 8;          // 16-byte pieces per lane, KV head and group
@@ -662,11 +665,11 @@ __device__ inline void arrive_rollout(const PtDev& c, const StepArgs& a, StepSme
   }
 }
 
-// The encoding workgroup of row j_row (launches that may evict have one per row, after the attention
-// workgroups in the grid): if the rollout's ring is full it folds the oldest chunk into S and then, the
-// chunk's oldest slot being free at last, stores the step's new token there.  The rollout's attention
-// workgroups meanwhile walk the window without the chunk and take the new token from the step's
-// inputs; nobody waits for anybody.
+// An encoding workgroup (launches that may evict have c.enc_parts per row, after the attention
+// workgroups in the grid): if the rollout's ring is full, the row's encoding workgroups fold the oldest
+// chunk into S and then, the chunk's oldest slot being free at last, the one that finished the job
+// stores the step's new token there.  The rollout's attention workgroups meanwhile walk the window
+// without the chunk and take the new token from the step's inputs; nobody waits for anybody.
 template <int WAVES, bool MASS>
 __device__ inline void encoder_role(const PtDev& c, const StepArgs& a, StepSmem<WAVES>& sm, int& sm_ticket,
                                     float* dyn_lds, int enc_idx, const int* ids, const uint8_t* active,
@@ -741,7 +744,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
   // row j of the launch (and of q / k / v / out) is rollout b: j itself, or ids[j] for a compact list
   const int j_row = blockIdx.x / n_kv_heads, hkv = blockIdx.x - j_row * n_kv_heads, split = blockIdx.y;
   if (__builtin_expect(j_row >= n_rows, 0)) {
-    // beyond the attention workgroups: one encoding workgroup per row if the launch may evict, then ...
+    // beyond the attention workgroups: every row's encoding workgroups if the launch may evict, then ...
     if (split != 0) return;
     const int extra = blockIdx.x - n_rows * n_kv_heads;
     if constexpr (ENC) {
@@ -816,7 +819,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
   u32x4* slab_p = (u32x4*)((uint16_t*)c.cache + (size_t)slab * pt_slab_elems(c.W, 128));
 
   // (an evicting rollout's chunk is folded into S, and its new token stored, by the row's encoding
-  // workgroup: see encoder_role)
+  // workgroups: see encoder_role)
   if (owner && appending && !evicting && !a.do_attend && wave == 0) {
     // append without attention: straight from the inputs (with attention the store happens after
     // the walk, from the registers that also patch the last group)
