@@ -1083,13 +1083,14 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
   }
 
   // ---- counters ----
-  // Full batch: they go to the other buffer (nobody reads that one in this kernel), so no workgroup
-  // waits for the rest of its rollout.  Compact list: the other buffer would miss the unlisted
-  // rollouts, so the last workgroup of the rollout to arrive writes them in place.
+  // They go to the other buffer (nobody reads that one in this kernel), so no workgroup waits for the
+  // rest of its rollout; under a compact list as "the larger of what is there and mine", which commutes
+  // with the carrying workgroup's update of the same entry.  With the in-place option the rollout's last
+  // workgroup to arrive writes them where they are (arrive_rollout).
   const bool advancing = a.do_evict || a.do_append;
   const bool in_place = a.in_place != 0;
   if (advancing && !in_place && hkv == 0 && split == 0 && tid == 0) {
-    if (a.carry) {             // commutes with the carrying workgroup's update of the same entry
+    if (a.carry) {
       atomicMax(c.len_nx + b, len1);
       atomicMax(c.base_nx + b, base1);
     } else {
