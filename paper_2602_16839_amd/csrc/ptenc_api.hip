@@ -143,7 +143,7 @@ ptenc_status advanced(ptenc_ctx* x, hipError_t e) {
 }
 inline ptenc_status hip_status(hipError_t e) { return e == hipSuccess ? PTENC_OK : PTENC_ERR_HIP; }
 
-// Launches that may evict carry one encoding workgroup per row.  While no ring can be full yet (the host
+// Launches that may evict carry encoding workgroups for every row.  While no ring can be full yet (the host
 // keeps an upper bound on the fullest one: appends since the last full reset or ptenc_set_counters),
 // steps are launched without them and without the eviction logic; should the bound ever be wrong, the
 // append on the full ring sets PTENC_DEVERR_APPEND_FULL instead of going unnoticed.  Steps that may be
