@@ -276,9 +276,14 @@ ptenc_status ptenc_cache_offset(ptenc_ctx* ctx, int32_t b, int32_t h, int32_t sl
  *   ring entry first; entries past the live count read 0 and -1.  Either output may be NULL.  Device
  *   pointers; asynchronous.
  * ptenc_set_scores: overwrites the scores of the live ring entries (same layout) and drops the
- *   probabilities of the latest step that were still waiting to be folded.
- * ptenc_get_victims: the positions the last eviction of every rollout took (int64 [B][C], ring order;
- *   -1 where none happened since the reset).  Host pointer; synchronises. */
+ *   probabilities of the latest step that were still waiting to be folded.  A full ring has had its
+ *   victims chosen and brought to its oldest places already: ring order is what that left, and the
+ *   next call that may evict chooses again from the new scores, in that order.
+ * ptenc_get_victims: the positions of every rollout's latest choice of victims (int64 [B][C], ring
+ *   order; -1 where none was made since the reset).  The choice is made when a ring fills and carried
+ *   out by the rollout's next step, so after an evicting step this names what that step took -- unless
+ *   the step refilled the ring (C = 1), in which case it already names what leaves next.  Host
+ *   pointer; synchronises. */
 ptenc_status ptenc_get_scores(ptenc_ctx* ctx, float* d_score, int64_t* d_pos, void* stream);
 ptenc_status ptenc_set_scores(ptenc_ctx* ctx, const float* d_score, void* stream);
 ptenc_status ptenc_get_victims(ptenc_ctx* ctx, int64_t* h_pos, void* stream);
