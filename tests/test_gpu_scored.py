@@ -382,3 +382,78 @@ def test_rebasing_an_emptied_ring_forgets_the_old_choice_of_victims():
     ln, base = layer.counters()
     assert (ln == x + wl.window).all() and (base == x + wl.chunk).all()
     assert layer.poll_error() == 0
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_call_sequences_with_planted_scores(seed):
+    # full, masked and compact steps in random order, options changed in mid-run, rollouts that fill
+    # their rings at different ticks; whenever a rollout is one token short of a full ring its scores
+    # are planted (few distinct values, the same float32 numbers on both sides), so that every choice
+    # of victims is an integer decision both sides must take alike, whatever rounding did to the
+    # scores in between
+    rng = np.random.default_rng(900 + seed)
+    n_sink = int(rng.choice([0, 32]))
+    ring = 32 * int(rng.integers(1, 5))
+    C = int(rng.integers(2, ring + 1))
+    n_recent = int(rng.integers(0, ring - C + 1))
+    wl = small(batch=4, n_q_heads=8, window=n_sink + ring, n_sink=n_sink, chunk=C, steps=3 * ring + 3 * C,
+               seed=int(rng.integers(1, 1 << 20)))
+    B, T, W = wl.batch, wl.steps, wl.window
+    orc, layer = make_both(wl, n_recent)
+    q, k, v = I.qkv_steps(wl, 0, T)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    qn, kn, vn = H.f64(q), H.f64(k), H.f64(v)
+    n_evictions = 0
+    for t in range(T):
+        plant = [b for b in range(B) if len(orc.win[b]) == ring - 1]
+        if plant:
+            sc, _ = layer.scores()                       # the library's own values go back to it unchanged
+            sc = np.array(sc, dtype=np.float32)
+            levels = int(rng.integers(2, 9))
+            for b in range(B):
+                if b in plant:
+                    sc[b, :ring - 1] = (rng.integers(0, levels, ring - 1) / np.float32(levels)).astype(np.float32)
+                    orc.set_scores(b, sc[b, :ring - 1].astype(np.float64))
+                else:
+                    orc.set_scores(b, orc.scores(b))     # its own values; the waiting probabilities are dropped, as on the GPU
+            layer.set_scores(sc)
+        op = str(rng.choice(["step", "masked", "ids", "option"]))
+        before = list(orc.evicted)
+        if op == "step":
+            ref = orc.step(qn[t], kn[t], vn[t])
+            H.assert_close(H.f64(layer.step(qd[t], kd[t], vd[t])), ref, H.BF16_ABS, H.BF16_REL, "step %d" % t)
+        elif op == "masked":
+            act = rng.random(B) < 0.6
+            ref = orc.step(qn[t], kn[t], vn[t], act)
+            out = layer.step(qd[t], kd[t], vd[t], active=torch.from_numpy(act.astype(np.uint8)).cuda())
+            H.assert_close(H.f64(out), ref, H.BF16_ABS, H.BF16_REL, "masked step %d" % t)
+        elif op == "ids":
+            idx = rng.permutation(np.nonzero(rng.random(B) < 0.6)[0])
+            m = np.zeros(B, dtype=bool)
+            m[idx] = True
+            ref = orc.step(qn[t], kn[t], vn[t], m)
+            it = torch.from_numpy(idx).cuda()
+            out = layer.step_ids(qd[t][it].contiguous(), kd[t][it].contiguous(), vd[t][it].contiguous(), it.to(torch.int32))
+            if len(idx):
+                H.assert_close(H.f64(out), ref[idx], H.BF16_ABS, H.BF16_REL, "compact step %d" % t)
+        else:
+            which = str(rng.choice(["splits", "waves", "parts"]))
+            if which == "splits":
+                layer.set_option(ptenc.OPT_SPLITS, int(rng.choice([0, 1, 2, 3])))
+            elif which == "waves":
+                layer.set_option(ptenc.OPT_WAVES, int(rng.choice([0, 4, 8])))
+            else:
+                layer.set_option(ptenc.OPT_ENCODE_PARTS, int(rng.choice([0, 1, 2, 5])))
+        ln, base = layer.counters()
+        oln, obase = orc.counters()
+        assert np.array_equal(ln, oln) and np.array_equal(base, obase), "counters after tick %d" % t
+        if list(orc.evicted) != before:
+            _, ps = layer.scores()
+            for b in range(B):
+                if orc.evicted[b] != before[b]:
+                    n = len(orc.win[b])
+                    assert np.array_equal(ps[b, :n], orc.positions(b)), "ring order of rollout %d after tick %d" % (b, t)
+                    n_evictions += 1
+    assert n_evictions >= 2
+    H.assert_close(layer.get_state(), orc.state(), H.S_ABS, H.S_REL, "state S")
+    assert layer.poll_error() == 0
