@@ -15,11 +15,11 @@ SOURCES = ["ptenc_api.hip", "cache_kernels.hip", "attn_generic.hip", "decode_mfm
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
-# The step kernel's leading scalar arguments (list and mask pointers, counter pointers, two sizes:
-# 13 dwords) are preloaded into SGPRs at wavefront launch, so its first loads need not wait for
-# the argument block; the compiler keeps a prologue that loads them the ordinary way where the
-# firmware does not preload.
-EXTRA_FLAGS = {"decode_mfma.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=13"]}
+# The step kernel's leading scalar arguments (list and mask pointers, counter pointers, the cache
+# pointer, two sizes: the 14 dwords that fit) are preloaded into SGPRs at wavefront launch, so its
+# first loads need not wait for the argument block; the compiler keeps a prologue that loads them the
+# ordinary way where the firmware does not preload.
+EXTRA_FLAGS = {"decode_mfma.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=16"]}
 OBJ_DIR = os.path.join(PKG_DIR, "_build")
 
 

@@ -121,8 +121,10 @@ __device__ inline void lagged_mass_park(const float p[8], float il, float* park_
 // MASS: lanes with `lag` set carry a query head of the rollout's PREVIOUS step in their column (see
 // the kernel): their running maximum is frozen at that step's final one, so p[] comes out as that
 // step's unnormalised probabilities, returned in p[], from which the importance scores are parked (park_grp: 32 floats of LDS, or null).
+// wrap: 0, or the ring size for the one group that holds the ring's start (jg < 0 then: the slots in
+// front of the start are the ring's newest, their logical indices are jg + i + wrap).
 template <bool MASS = false>
-__device__ inline void process_group(Frag& f, const Op q[4], Acc& a, int jg, int n_live,
+__device__ inline void process_group(Frag& f, const Op q[4], Acc& a, int jg, int n_live, int wrap,
                                      float scale_log2, int kgrp, bool lag = false, float il = 0.f,
                                      float* park_grp = nullptr, int n = 0) {
   f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
@@ -143,8 +145,11 @@ __device__ inline void process_group(Frag& f, const Op q[4], Acc& a, int jg, int
     uint32_t live = 0;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const bool l0 = (unsigned)(jl + e) < (unsigned)n_live;
-      const bool l1 = (unsigned)(jl + 16 + e) < (unsigned)n_live;
+      int j0 = jl + e, j1 = jl + 16 + e;
+      j0 += j0 < 0 ? wrap : 0;
+      j1 += j1 < 0 ? wrap : 0;
+      const bool l0 = (unsigned)j0 < (unsigned)n_live;
+      const bool l1 = (unsigned)j1 < (unsigned)n_live;
       s[e] = l0 ? s0[e] * scale_log2 : -INFINITY;
       s[4 + e] = l1 ? s1[e] * scale_log2 : -INFINITY;
       live |= (l0 ? 1u : 0u) << e | (l1 ? 1u : 0u) << (4 + e);
@@ -732,10 +737,16 @@ __device__ inline void encoder_role(const PtDev& c, const StepArgs& a, StepSmem<
 template <bool NT, int WAVES, bool MASS, bool ENC>
 __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
     // what the walk cannot start without comes first, as plain scalars: the build asks for these
-    // leading arguments to be preloaded into registers at wavefront launch, so the counters are
-    // fetched without first waiting for the argument block (one round trip to memory less per step)
+    // leading arguments to be preloaded into registers at wavefront launch, so the counters and the
+    // first K/V group are requested without first waiting for the argument block (one round trip to
+    // memory less per step)
     const int* ids, const uint8_t* active, const long long* len_cur, const long long* base_cur,
-    const int* n_prompt, int n_rollouts, int n_kv_heads, int n_rows, PtDev c, StepArgs a) {
+    const int* n_prompt, const void* cache_p, int n_rows, unsigned heads_and_groups, PtDev c, StepArgs a) {
+  // (14 dwords can be preloaded; KV heads, window splits, one flag and W / 32 share one: 8, 7, 1 and 16 bits)
+  const int n_kv_heads = (int)(heads_and_groups & 0xffu), ns = (int)((heads_and_groups >> 8) & 0x7fu);
+  const bool ahead2 = WAVES == 4 && ((heads_and_groups >> 15) & 1u) != 0;   // (8 wavefronts: short walks)
+  const int NGt = (int)(heads_and_groups >> 16), w_slots = NGt << 5;
+  const int n_rollouts = c.B;
   constexpr int kWaves = WAVES;
   __shared__ StepSmem<WAVES> sm;
   __shared__ int sm_ticket;
@@ -764,7 +775,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
     }
     return;
   }
-  // explicit arguments: 13 preloaded dwords (padded to 56 bytes), then the two blocks
+  // explicit arguments: 14 preloaded dwords, then the two blocks
   constexpr int kArgBytes = 56 + (int)sizeof(PtDev) + (int)sizeof(StepArgs);
   static_assert(sizeof(PtDev) % 8 == 0 && sizeof(StepArgs) % 8 == 0, "argument blocks are laid out back to back");
   const KernargPtr ka = (const void*)__builtin_amdgcn_kernarg_segment_ptr();
@@ -776,16 +787,33 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
       return;
     }
   }
-  const int slab = b * c.Hkv + hkv;                // cache slab, scratch and arrival counters go by rollout
+  const int slab = b * n_kv_heads + hkv;           // cache slab, scratch and arrival counters go by rollout
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-  const int ns = c.n_splits;   // window splits
-  const int n = lane & 15, kgrp = lane >> 4;
-  const int g = c.group;
+  // The slab is W / 32 groups (question groups first, then the ring's); wavefront w of split s takes
+  // groups s * WAVES + w, + n_splits * WAVES, ... whatever the counters say (softmax does not care
+  // about the order of the keys), so its first group (long walks: its first two) can be requested
+  // before the counters are known: the two round trips to memory run side by side instead of one
+  // after the other.  Should a group turn out not to be live, what arrived is dropped (the addresses
+  // are inside the slab in any case).  Two groups ahead pay on long walks (-1.1 % per step at 32 groups
+  // per wavefront against -0.5 % with one); on short ones the first group's arithmetic then waits for
+  // the second group's bytes as well, because the queries are requested after both (with 8 groups per
+  // wavefront: -1.5 % instead of -3 %).
+  const int stride = ns * kWaves;
+  const int pg_first = split * kWaves + wave;
+  u32x4* slab_p = (u32x4*)((uint16_t*)const_cast<void*>(cache_p) + (size_t)slab * pt_slab_elems(w_slots, 128));
+  Frag fa, fb;
+  if (pg_first < NGt) load_group<NT>(fa, (const u32x4*)slab_p + (size_t)pg_first * (PT_GROUP_ELEMS / 8), lane);
+  if (ahead2 && pg_first + stride < NGt)
+    load_group<NT>(fb, (const u32x4*)slab_p + (size_t)(pg_first + stride) * (PT_GROUP_ELEMS / 8), lane);
   const uintptr_t mask_addr = (uintptr_t)(active + b);
   const uint32_t* mask_word_p = active ? (const uint32_t*)(mask_addr & ~(uintptr_t)3) : (const uint32_t*)(n_prompt + b);
+  // (the scalar loads of the counters wait for themselves only: the K/V requests above stay in flight)
   const StepHead head = ids ? load_step_head<kArgBytes, false>(len_cur + b, base_cur + b, n_prompt + b, mask_word_p, ka)
                             : load_step_head<kArgBytes, true>(len_cur + b, base_cur + b, n_prompt + b, mask_word_p, ka);
+
+  const int n = lane & 15, kgrp = lane >> 4;
+  const int g = c.group;
   if (head.len < head.base) return;      // counters that no sequence of calls produces: leave everything alone
   const bool act = !active || ((head.mask_word >> (8 * (int)(mask_addr & 3))) & 0xffu) != 0;
 
@@ -809,14 +837,31 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
   if (s_new >= c.Wr) s_new -= c.Wr;
   const int g0 = s0 >> 5, off0 = s0 & 31;
   const int NG = c.Wr >> 5, gs = c.n_sink >> 5;
-  const int n_sink_vis = (P + PT_GROUP_TOKENS - 1) >> 5;
-  const int n_visits = n_sink_vis + (n_live > 0 ? (off0 + n_live + PT_GROUP_TOKENS - 1) >> 5 : 0);
-  const int per = (n_visits + ns - 1) / ns;
-  const int v0 = split * per, v1 = min(n_visits, v0 + per);
-  // the split whose range ends with the newest position appends for this KV head
-  const bool owner = split == (n_visits > 0 ? (n_visits - 1) / per : 0);
-
-  u32x4* slab_p = (u32x4*)((uint16_t*)c.cache + (size_t)slab * pt_slab_elems(c.W, 128));
+  // live groups: question group pg < gs holds slots 32 pg .. of the P question tokens; ring group r is
+  // live iff it is among the nv groups from the one that holds the oldest live token on (mod NG)
+  const int nv = n_live > 0 ? min(NG, (off0 + n_live + PT_GROUP_TOKENS - 1) >> 5) : 0;
+  auto group_live = [&](int pg) {
+    if (pg < gs) return pg * PT_GROUP_TOKENS < P;
+    int d = pg - gs - g0;
+    d += d < 0 ? NG : 0;
+    return d < nv;
+  };
+  auto next_live = [&](int pg) {
+    while (pg < NGt && !group_live(pg)) pg += stride;
+    return pg;
+  };
+  // logical index of a group's first slot within its region (negative for the group that holds the
+  // ring's start: process_group wraps), and that region's live count
+  auto group_jg = [&](int pg) {
+    if (pg < gs) return pg * PT_GROUP_TOKENS;
+    const int a0 = (pg - gs) * PT_GROUP_TOKENS - s0;
+    return a0 <= -PT_GROUP_TOKENS ? a0 + c.Wr : a0;
+  };
+  auto group_lim = [&](int pg) { return pg < gs ? P : n_live; };
+  auto group_wrap = [&](int pg) { return pg < gs ? 0 : c.Wr; };
+  // the group the new token goes to; the split that walks it appends for this KV head
+  const int pg_new = gs + (s_new >> 5);
+  const bool owner = (pg_new % stride) / kWaves == split;
 
   // (an evicting rollout's chunk is folded into S, and its new token stored, by the row's encoding
   // workgroups: see encoder_role)
@@ -842,9 +887,9 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
     acc.m = -INFINITY;
     acc.l = 0.f;
 
-    if (v0 < v1) {
-      const bool patch = appending && owner;       // this workgroup's range ends with the new token
-      const int p_visit = n_visits - 1, p_tl = s_new & 31;
+    {
+      const bool patch = appending && owner;       // this workgroup walks the group the new token goes to
+      const int p_tl = s_new & 31;
       Op kp[4];
       uint32_t vp[4];
       if (patch) load_newest(kp, vp, a.knew, a.vnew, ((size_t)j_row * c.Hkv + hkv) * 128, n, kgrp);
@@ -863,24 +908,17 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
       float il = 0.f;                      // that step's 1 / sum for the lane's head
       float* mass_slab = nullptr;
       float* park = dyn_lds;               // MASS: 32 floats per group this workgroup walks
-      auto grp_ptr = [&](int visit) {
-        int pg = visit;                       // question tokens: group `visit`
-        if (visit >= n_sink_vis) {
-          pg = g0 + visit - n_sink_vis;
-          if (pg >= NG) pg -= NG;
-          if (pg >= NG) pg -= NG;             // a full ring that starts mid-group visits its first group twice
-          pg += gs;
-        }
-        return (const u32x4*)slab_p + (size_t)pg * (PT_GROUP_ELEMS / 8);
-      };
-      // logical index of a visit's first slot within its region, and that region's live count
-      auto visit_jg = [&](int visit) {
-        return visit < n_sink_vis ? visit * PT_GROUP_TOKENS : (visit - n_sink_vis) * PT_GROUP_TOKENS - off0;
-      };
-      auto visit_lim = [&](int visit) { return visit < n_sink_vis ? P : n_live; };
-      int i = v0 + wave;
-      Frag fa, fb;
-      if (i < v1) load_group<NT>(fa, grp_ptr(i), lane);
+      auto grp_ptr = [&](int pg) { return (const u32x4*)slab_p + (size_t)pg * (PT_GROUP_ELEMS / 8); };
+      // where a group's 32 masses are parked: by its place in this wavefront's sequence
+      auto park_of = [&](int pg) { return park + (((pg - pg_first) / stride) * kWaves + wave) * PT_GROUP_TOKENS; };
+      int i = pg_first;
+      // of the two groups requested ahead of the counters, the second is of use if both are part of this walk
+      bool have_next = ahead2 && i + stride < NGt && group_live(i) && group_live(i + stride);
+      if (!(i < NGt && group_live(i))) {
+        // not part of this walk: what arrives is dropped
+        i = next_live(i + stride);
+        if (i < NGt) load_group<NT>(fa, grp_ptr(i), lane);
+      }
       if constexpr (MASS) {
         // after the first group's loads are on their way: the previous step's queries into columns 8..15
         // (saved by the step that left len == len0, in the buffer of that parity; the addresses are valid
@@ -903,53 +941,55 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
           il = ill;
         }
       }
-      while (i < v1) {
-        int nx = i + kWaves;
-        if (nx < v1) load_group<NT>(fb, grp_ptr(nx), lane);
-        if (patch && i == p_visit) patch_newest(fa, kp, vp, p_tl, n, kgrp);
+      while (i < NGt) {
+        int nx = next_live(i + stride);
+        if (nx < NGt && !have_next) load_group<NT>(fb, grp_ptr(nx), lane);
+        have_next = false;
+        if (patch && i == pg_new) patch_newest(fa, kp, vp, p_tl, n, kgrp);
         if constexpr (MASS) {
-          process_group<true>(fa, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp, lag, il,
-                              (fold && i >= n_sink_vis) ? park + (i - v0) * 32 : nullptr, n);
+          process_group<true>(fa, qf, acc, group_jg(i), group_lim(i), group_wrap(i), c.scale_log2, kgrp, lag, il,
+                              (fold && i >= gs) ? park_of(i) : nullptr, n);
         } else {
-          process_group(fa, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp);
+          process_group(fa, qf, acc, group_jg(i), group_lim(i), group_wrap(i), c.scale_log2, kgrp);
         }
         i = nx;
-        if (i >= v1) break;
-        nx = i + kWaves;
-        if (nx < v1) load_group<NT>(fa, grp_ptr(nx), lane);
-        if (patch && i == p_visit) patch_newest(fb, kp, vp, p_tl, n, kgrp);
+        if (i >= NGt) break;
+        nx = next_live(i + stride);
+        if (nx < NGt) load_group<NT>(fa, grp_ptr(nx), lane);
+        if (patch && i == pg_new) patch_newest(fb, kp, vp, p_tl, n, kgrp);
         if constexpr (MASS) {
-          process_group<true>(fb, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp, lag, il,
-                              (fold && i >= n_sink_vis) ? park + (i - v0) * 32 : nullptr, n);
+          process_group<true>(fb, qf, acc, group_jg(i), group_lim(i), group_wrap(i), c.scale_log2, kgrp, lag, il,
+                              (fold && i >= gs) ? park_of(i) : nullptr, n);
         } else {
-          process_group(fb, qf, acc, visit_jg(i), visit_lim(i), c.scale_log2, kgrp);
+          process_group(fb, qf, acc, group_jg(i), group_lim(i), group_wrap(i), c.scale_log2, kgrp);
         }
         i = nx;
       }
       if constexpr (MASS) {
         // every wavefront folds the groups it walked: lanes 0..31 own a group's 32 accumulators
-        // (slot = lane).  The token this step appended starts at zero and took no part in the previous
-        // step; question tokens are not scored.
-        auto mass_ptr = [&](int visit) {
-          return mass_slab + ((const uint16_t*)grp_ptr(visit) - (const uint16_t*)slab_p) / (PT_GROUP_ELEMS / PT_GROUP_TOKENS) +
-                 (lane & 31);
-        };
+        // (slot = 32 pg + lane).  The token this step appended starts at zero and took no part in the
+        // previous step; question tokens are not scored.
         // one lane adds to one accumulator once per step, so a returnless hardware float add gives the same
         // bits as load-add-store and needs no round trip
-        for (int i0 = v0 + wave; i0 < v1; i0 += 8 * kWaves) {
+        int pgc = next_live(pg_first);
+        while (pgc < NGt) {
           float add[8];
+          int pgs[8];
 #pragma unroll
           for (int u = 0; u < 8; ++u) {          // the LDS reads of a batch together, then its adds
-            const int vi = i0 + u * kWaves;
-            add[u] = (vi < v1 && lane < 32) ? park[(vi - v0) * 32 + lane] : 0.f;
+            pgs[u] = pgc;
+            add[u] = (pgc < NGt && pgc >= gs && lane < 32) ? park_of(pgc)[lane] : 0.f;
+            if (pgc < NGt) pgc = next_live(pgc + stride);
           }
 #pragma unroll
           for (int u = 0; u < 8; ++u) {
-            const int vi = i0 + u * kWaves;
-            if (vi >= v1 || vi < n_sink_vis || lane >= 32) continue;
-            const int j = visit_jg(vi) + lane;
-            if (appending && j == n_live - 1) *mass_ptr(vi) = 0.f;
-            else if (fold && (unsigned)j < (unsigned)(n_live - 1)) unsafeAtomicAdd(mass_ptr(vi), add[u]);
+            const int pgu = pgs[u];
+            if (pgu >= NGt || pgu < gs || lane >= 32) continue;
+            int j = (pgu - gs) * PT_GROUP_TOKENS + lane - s0;          // logical index of the slot
+            j += j < 0 ? c.Wr : 0;
+            float* mp = mass_slab + (size_t)pgu * PT_GROUP_TOKENS + lane;
+            if (appending && j == n_live - 1) *mp = 0.f;
+            else if (fold && (unsigned)j < (unsigned)(n_live - 1)) unsafeAtomicAdd(mp, add[u]);
           }
         }
       }
@@ -1146,10 +1186,15 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bo
   // scores are maintained by whole steps only (append + attention) under the scored policy
   const bool mass = cc.scored && do_append && do_attend;
   // parked masses of every group a workgroup may walk
-  const size_t park = mass ? (size_t)(cc.W / PT_GROUP_TOKENS + 2) * PT_GROUP_TOKENS * sizeof(float) : 0;
+  // long walks request two groups ahead of the counters, short ones one (see the kernel)
+  const unsigned ahead2 = (waves != 8 && (cc.W / PT_GROUP_TOKENS) / (cc.n_splits * 4) >= 16) ? 1u : 0u;
+  const size_t park = mass ? (size_t)(cc.W / PT_GROUP_TOKENS + 8) * PT_GROUP_TOKENS * sizeof(float) : 0;
 #define PT_STEP_LAUNCH(NT_, WAVES_, MASS_, ENC_)                                                                      \
   hipLaunchKernelGGL((decode_mfma_kernel<NT_, WAVES_, MASS_, ENC_>), grid, dim3(WAVES_ * 64), park, s, ids, active, \
-                     cc.len, cc.base, cc.n_prompt, cc.B, cc.Hkv, rows, cc, a)
+                     cc.len, cc.base, cc.n_prompt, (const void*)cc.cache, rows,                             \
+                     (unsigned)cc.Hkv | ((unsigned)cc.n_splits << 8) | (ahead2 << 15) |                      \
+                         ((unsigned)(cc.W / PT_GROUP_TOKENS) << 16),                                                   \
+                     cc, a)
 #define PT_STEP_PICK_ENC(NT_, WAVES_, MASS_) \
   do { if (do_evict) PT_STEP_LAUNCH(NT_, WAVES_, MASS_, true); else PT_STEP_LAUNCH(NT_, WAVES_, MASS_, false); } while (0)
 #define PT_STEP_PICK_MASS(NT_, WAVES_) \

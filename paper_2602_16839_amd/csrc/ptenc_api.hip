@@ -81,7 +81,8 @@ size_t enc_part_bytes(const ptenc_config& c) {
 
 bool mfma_attn_applies(const ptenc_config& c) {
   return c.dtype == PTENC_BF16 && c.head_dim == 128 && c.window % 32 == 0 && c.n_sink % 32 == 0 &&
-         c.n_q_heads / c.n_kv_heads <= 16;
+         c.n_q_heads / c.n_kv_heads <= 16 &&
+         c.n_kv_heads <= 0xff && c.window / 32 <= 0xffff;        // (they share one kernel argument)
 }
 
 // Window splits.  Splitting a (rollout, KV head) row over several workgroups costs a round trip
