@@ -7,10 +7,13 @@
 //
 // Work decomposition: one workgroup of 4 or 8 wavefronts per (rollout, KV head, window split).
 //
-// Attention.  A wavefront walks 32-slot groups of the ring (16 KiB each, contiguous in HBM).
-// Softmax does not care about the order of the keys, so the walk is in physical slot order
-// starting at the group that holds the oldest live token; only the first and last group of the
-// live range need a mask.  All H_q/H_kv query heads of the KV head ride in the N dimension of
+// Attention.  A wavefront walks 32-slot groups of the slab (16 KiB each, contiguous in HBM).
+// Softmax does not care about the order of the keys, so the walk is in physical slot order and the
+// groups are dealt to the wavefronts (and window splits) by their index alone: which groups a
+// wavefront takes does not depend on the counters, only which of them are live does, so its first
+// loads are on their way before the counters have arrived.  Only the groups at the two ends of the
+// live range need a mask (one group when the ring's start lies inside it: its slots in front of the
+// start are the newest).  All H_q/H_kv query heads of the KV head ride in the N dimension of
 // the MFMA (padded to 16), so every K/V byte is fetched from HBM once per step and shared by
 // the whole query group in registers.  Per group and wavefront:
 //   S^T[token, query]  = K_tile (16 x 32k) * Q^T (32k x 16), 4 k-chunks, two 16-token tiles
