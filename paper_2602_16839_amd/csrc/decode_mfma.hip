@@ -745,9 +745,10 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
     // memory less per step)
     const int* ids, const uint8_t* active, const long long* len_cur, const long long* base_cur,
     const int* n_prompt, const void* cache_p, int n_rows, unsigned heads_and_groups, PtDev c, StepArgs a) {
-  // (14 dwords can be preloaded; KV heads, window splits, one flag and W / 32 share one: 8, 7, 1 and 16 bits)
-  const int n_kv_heads = (int)(heads_and_groups & 0xffu), ns = (int)((heads_and_groups >> 8) & 0x7fu);
-  const bool ahead2 = WAVES == 4 && ((heads_and_groups >> 15) & 1u) != 0;   // (8 wavefronts: short walks)
+  // (14 dwords can be preloaded; KV heads, window splits, groups requested ahead and W / 32 share one:
+  // 8, 6, 2 and 16 bits)
+  const int n_kv_heads = (int)(heads_and_groups & 0xffu), ns = (int)((heads_and_groups >> 8) & 0x3fu);
+  const bool ahead2 = WAVES == 4 && ((heads_and_groups >> 14) & 3u) == 2u;   // (8 wavefronts: short walks)
   const int NGt = (int)(heads_and_groups >> 16), w_slots = NGt << 5;
   const int n_rollouts = c.B;
   constexpr int kWaves = WAVES;
@@ -912,8 +913,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
       float* mass_slab = nullptr;
       float* park = dyn_lds;               // MASS: 32 floats per group this workgroup walks
       auto grp_ptr = [&](int pg) { return (const u32x4*)slab_p + (size_t)pg * (PT_GROUP_ELEMS / 8); };
-      // where a group's 32 masses are parked: by its place in this wavefront's sequence
-      auto park_of = [&](int pg) { return park + (((pg - pg_first) / stride) * kWaves + wave) * PT_GROUP_TOKENS; };
+      // where a group's 32 masses are parked: by its index in the slab
+      auto park_of = [&](int pg) { return park + pg * PT_GROUP_TOKENS; };
       int i = pg_first;
       // of the two groups requested ahead of the counters, the second is of use if both are part of this walk
       bool have_next = ahead2 && i + stride < NGt && group_live(i) && group_live(i + stride);
@@ -1188,14 +1189,14 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bo
   dim3 grid(rows * cc.Hkv + (do_evict ? rows * cc.enc_parts : 0) + (a.carry ? 1 : 0), cc.n_splits);
   // scores are maintained by whole steps only (append + attention) under the scored policy
   const bool mass = cc.scored && do_append && do_attend;
-  // parked masses of every group a workgroup may walk
   // long walks request two groups ahead of the counters, short ones one (see the kernel)
-  const unsigned ahead2 = (waves != 8 && (cc.W / PT_GROUP_TOKENS) / (cc.n_splits * 4) >= 16) ? 1u : 0u;
-  const size_t park = mass ? (size_t)(cc.W / PT_GROUP_TOKENS + 8) * PT_GROUP_TOKENS * sizeof(float) : 0;
+  const unsigned ahead = (waves != 8 && (cc.W / PT_GROUP_TOKENS) / (cc.n_splits * 4) >= 16) ? 2u : 1u;
+  // parked masses of every group of the slab
+  const size_t park = mass ? (size_t)(cc.W / PT_GROUP_TOKENS + 2) * PT_GROUP_TOKENS * sizeof(float) : 0;
 #define PT_STEP_LAUNCH(NT_, WAVES_, MASS_, ENC_)                                                                      \
   hipLaunchKernelGGL((decode_mfma_kernel<NT_, WAVES_, MASS_, ENC_>), grid, dim3(WAVES_ * 64), park, s, ids, active, \
                      cc.len, cc.base, cc.n_prompt, (const void*)cc.cache, rows,                             \
-                     (unsigned)cc.Hkv | ((unsigned)cc.n_splits << 8) | (ahead2 << 15) |                      \
+                     (unsigned)cc.Hkv | ((unsigned)cc.n_splits << 8) | (ahead << 14) |                       \
                          ((unsigned)(cc.W / PT_GROUP_TOKENS) << 16),                                                   \
                      cc, a)
 #define PT_STEP_PICK_ENC(NT_, WAVES_, MASS_) \
