@@ -748,7 +748,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
   // (14 dwords can be preloaded; KV heads, window splits, groups requested ahead and W / 32 share one:
   // 8, 6, 2 and 16 bits)
   const int n_kv_heads = (int)(heads_and_groups & 0xffu), ns = (int)((heads_and_groups >> 8) & 0x3fu);
-  const bool ahead2 = WAVES == 4 && ((heads_and_groups >> 14) & 3u) == 2u;   // (8 wavefronts: short walks)
+  const int ahead = (int)((heads_and_groups >> 14) & 3u);   // groups a wavefront requests before it knows the counters
+  const bool ahead2 = WAVES == 4 && ahead == 2;             // (8 wavefronts: short walks)
   const int NGt = (int)(heads_and_groups >> 16), w_slots = NGt << 5;
   const int n_rollouts = c.B;
   constexpr int kWaves = WAVES;
@@ -807,7 +808,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
   const int pg_first = split * kWaves + wave;
   u32x4* slab_p = (u32x4*)((uint16_t*)const_cast<void*>(cache_p) + (size_t)slab * pt_slab_elems(w_slots, 128));
   Frag fa, fb;
-  if (pg_first < NGt) load_group<NT>(fa, (const u32x4*)slab_p + (size_t)pg_first * (PT_GROUP_ELEMS / 8), lane);
+  if (ahead != 0 && pg_first < NGt) load_group<NT>(fa, (const u32x4*)slab_p + (size_t)pg_first * (PT_GROUP_ELEMS / 8), lane);
   if (ahead2 && pg_first + stride < NGt)
     load_group<NT>(fb, (const u32x4*)slab_p + (size_t)(pg_first + stride) * (PT_GROUP_ELEMS / 8), lane);
   const uintptr_t mask_addr = (uintptr_t)(active + b);
@@ -918,7 +919,10 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
       int i = pg_first;
       // of the two groups requested ahead of the counters, the second is of use if both are part of this walk
       bool have_next = ahead2 && i + stride < NGt && group_live(i) && group_live(i + stride);
-      if (!(i < NGt && group_live(i))) {
+      if (ahead == 0) {
+        i = next_live(i);
+        if (i < NGt) load_group<NT>(fa, grp_ptr(i), lane);
+      } else if (!(i < NGt && group_live(i))) {
         // not part of this walk: what arrives is dropped
         i = next_live(i + stride);
         if (i < NGt) load_group<NT>(fa, grp_ptr(i), lane);
@@ -1190,7 +1194,15 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bo
   // scores are maintained by whole steps only (append + attention) under the scored policy
   const bool mass = cc.scored && do_append && do_attend;
   // long walks request two groups ahead of the counters, short ones one (see the kernel)
-  const unsigned ahead = (waves != 8 && (cc.W / PT_GROUP_TOKENS) / (cc.n_splits * 4) >= 16) ? 2u : 1u;
+  const int kw = waves == 8 ? 8 : 4;
+  unsigned ahead = (kw == 4 && (cc.W / PT_GROUP_TOKENS) / (cc.n_splits * 4) >= 16) ? 2u : 1u;
+  // ... and none while every ring is known to be short (a run's first steps): most of what would be
+  // requested is not live yet.  (Not for launches that may be replayed, whose rings grow between replays;
+  // with question tokens the first groups are theirs.)
+  if (!in_place && cc.n_sink == 0) {
+    const long long per_group_ahead = (long long)PT_GROUP_TOKENS * cc.n_splits * kw;   // tokens that make one more group per wavefront live
+    while (ahead > 0 && 2 * cc.live_ub < per_group_ahead * ahead) --ahead;
+  }
   // parked masses of every group of the slab
   const size_t park = mass ? (size_t)(cc.W / PT_GROUP_TOKENS + 2) * PT_GROUP_TOKENS * sizeof(float) : 0;
 #define PT_STEP_LAUNCH(NT_, WAVES_, MASS_, ENC_)                                                                      \

@@ -149,8 +149,8 @@ inline ptenc_status hip_status(hipError_t e) { return e == hipSuccess ? PTENC_OK
 // steps are launched without them and without the eviction logic; should the bound ever be wrong, the
 // append on the full ring sets PTENC_DEVERR_APPEND_FULL instead of going unnoticed.  Steps that may be
 // replayed from a graph (counters in place) always carry them.
-bool may_evict(const ptenc_ctx* x) { return x->opt_in_place != 0 || x->live_ub >= x->dev.Wr; }
-void appended_one(ptenc_ctx* x) { if (x->live_ub < x->dev.Wr) ++x->live_ub; }
+bool may_evict(const ptenc_ctx* x) { return x->opt_in_place != 0 || x->dev.live_ub >= x->dev.Wr; }
+void appended_one(ptenc_ctx* x) { if (x->dev.live_ub < x->dev.Wr) ++x->dev.live_ub; }
 
 // Scored policy: a decode step chooses the next victims itself when its append fills a ring.  A ring
 // can also fill up, or lose its selection, in ways that step does not see (a bare ptenc_cache_append,
@@ -169,7 +169,7 @@ void pt_ctx_stepped_by_replay(ptenc_ctx* ctx) {
   (void)advanced(ctx, hipSuccess);
 }
 
-void pt_ctx_assume_full(ptenc_ctx* ctx) { ctx->live_ub = ctx->dev.Wr; }
+void pt_ctx_assume_full(ptenc_ctx* ctx) { ctx->dev.live_ub = ctx->dev.Wr; }
 
 hipError_t pt_ctx_refresh_selection(ptenc_ctx* ctx, hipStream_t s) { return refresh_selection(ctx, s); }
 
@@ -235,7 +235,7 @@ ptenc_status ptenc_create(const ptenc_config* cfg, void* d_cache, void* d_state,
   d.selected = (int*)(sp + L.selected);
   x->select_stale = 1;
   x->opt_recent = -1;
-  x->live_ub = d.Wr;       // nothing is known about the counters the state block holds
+  x->dev.live_ub = d.Wr;       // nothing is known about the counters the state block holds
   replan(x);
   *out = x;
   return PTENC_OK;
@@ -327,7 +327,7 @@ ptenc_status ptenc_set_encoder(ptenc_ctx* ctx, const void* d_qg, const void* d_W
 ptenc_status ptenc_reset(ptenc_ctx* ctx, const uint8_t* d_mask, void* stream) {
   if (!ctx) return PTENC_ERR_INVALID_ARG;
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
-  if (!d_mask) ctx->live_ub = 0;        // every ring is empty (a masked reset leaves the other rings as they are)
+  if (!d_mask) ctx->dev.live_ub = 0;        // every ring is empty (a masked reset leaves the other rings as they are)
   return hip_status(pt_launch_reset(ctx->dev, d_mask, d_mask == nullptr, S(stream)));
 }
 
@@ -540,9 +540,9 @@ ptenc_status ptenc_set_counters(ptenc_ctx* ctx, const int64_t* h_len, const int6
     if (hipMemsetAsync(ctx->dev.selected, 0, sizeof(int) * ctx->cfg.batch, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
     ctx->select_stale = 1;
   }
-  ctx->live_ub = 0;
+  ctx->dev.live_ub = 0;
   for (int b = 0; b < ctx->cfg.batch; ++b)
-    if (h_len[b] - h_base[b] > ctx->live_ub) ctx->live_ub = h_len[b] - h_base[b];
+    if (h_len[b] - h_base[b] > ctx->dev.live_ub) ctx->dev.live_ub = h_len[b] - h_base[b];
   const size_t n = sizeof(long long) * ctx->cfg.batch;
   if (hipMemcpyAsync(ctx->dev.len, h_len, n, hipMemcpyHostToDevice, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
   if (hipMemcpyAsync(ctx->dev.base, h_base, n, hipMemcpyHostToDevice, S(stream)) != hipSuccess) return PTENC_ERR_HIP;

@@ -53,6 +53,9 @@ struct PtDev {
   float* mlprev;      // [2][B][H_q][2]   that step's softmax maximum (base-2 domain) and 1 / sum
   long long* mtag;    // [B*H_kv] the length that step left (its data waits to be folded); -1: none
   int* selected;      // [B] 1: the ring is full and its next victims already sit in its oldest C places
+  // host side only (travels with the launch parameters): upper bound on the live thinking tokens of the
+  // fullest ring, this launch's append included (appends since the last full reset or ptenc_set_counters)
+  long long live_ub;
 };
 
 struct ptenc_ctx {
@@ -70,7 +73,6 @@ struct ptenc_ctx {
   int opt_policy;        // 0 sliding window, 1 scored
   int opt_recent;        // -1 = default
   int select_stale;      // scored policy: a ring may be full without a valid selection (see ptenc_api.hip)
-  long long live_ub;     // upper bound on the live thinking tokens of the fullest ring (see may_evict)
   int swaps;             // how often the two counter buffers have changed roles (parity = which is current)
   int waves;             // resolved: wavefronts per workgroup of the MFMA kernel
   int attn_kernel;       // 0 generic, 1 mfma
