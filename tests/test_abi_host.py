@@ -217,3 +217,14 @@ def test_window_split_plan_for_known_shapes(batch, hq, hkv, window, splits):
     assert st == ptenc.OK
     assert ptenc.ptenc_get_plan(h) == (1, splits, 1)
     ptenc.ptenc_destroy(h)
+
+
+def test_shapes_beyond_the_step_kernels_packed_arguments_take_the_plain_path():
+    # the MFMA step kernel receives KV heads (8 bits) and W / 32 (16 bits) in one preloaded argument
+    for c, kernel in ((cfg(n_q_heads=255, n_kv_heads=255), 1), (cfg(n_q_heads=256, n_kv_heads=256), 0),
+                      (cfg(batch=1, n_q_heads=1, n_kv_heads=1, window=32 * 0xffff, chunk=32), 1),
+                      (cfg(batch=1, n_q_heads=1, n_kv_heads=1, window=32 * 0x10000, chunk=32), 0)):
+        st, h = _host_ctx(c)
+        assert st == ptenc.OK
+        assert ptenc.ptenc_get_plan(h)[0] == kernel
+        assert ptenc.lib().ptenc_destroy(h) == ptenc.OK
