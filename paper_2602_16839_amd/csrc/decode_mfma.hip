@@ -851,9 +851,12 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
     d += d < 0 ? NG : 0;
     return d < nv;
   };
+  // (while a ring's live range does not wrap around its end, nothing at or beyond live_end is live: the
+  // search for the next live group stops there instead of running through the dead rest of the slab)
+  const int live_end = g0 + nv <= NG ? gs + g0 + nv : NGt;
   auto next_live = [&](int pg) {
-    while (pg < NGt && !group_live(pg)) pg += stride;
-    return pg;
+    while (pg < live_end && !group_live(pg)) pg += stride;
+    return pg < live_end ? pg : NGt;
   };
   // logical index of a group's first slot within its region (negative for the group that holds the
   // ring's start: process_group wraps), and that region's live count
