@@ -1,17 +1,27 @@
 #!/usr/bin/env python3
 """Benchmark of the bounded-cache rollout decode path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload qwen7b] [--splits S]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload qwen7b]
 
 A step is one pass of the whole hot path (evict-and-encode where a window is full, ring append,
-windowed GQA decode attention) over one batch of B rollouts.  The default workload is the
+windowed GQA decode attention) over one batch of B rollouts.  The headline workload is the
 Qwen2.5-7B-shaped layer (bf16, 28 query / 4 KV heads, head_dim 128, window 4096, chunk 128,
-128 rollouts) decoded for 8192 steps from an empty cache; inputs are synthetic, seeded, and
-resident in HBM before the timed region starts.
+128 rollouts, 8192 decode steps); inputs are synthetic, seeded, and resident in HBM before any
+timed region starts.
 
-Prints ONE JSON line: whole-job decode tokens/s, the HBM roofline of the step kernel
-(algorithmic bytes per launch / mean launch time measured with HIP events on the launch
-stream), and the CPU oracle timed on the host cores on a bounded sample of the same workload.
+What is timed.  The metric is quoted on the whole T-step run of the workload, most of which runs
+with full rings.  With --steps K < T the timed region is the LAST K steps of that run: steps
+1 .. T-K are decoded first, untimed, through the same entry point (the last W of them are the
+warm-up), so the K timed steps find the rings as the real run leaves them.  --steps 0 (or K >= T)
+times the whole run from an empty cache.  Beside it the same JSON line carries
+
+  full_run             the whole T-step run from an empty cache, timed in the same process
+  staggered_evictions  full-ring steps with the rollouts' evictions in the same step / spread over the steps
+  workloads            the other configurations (3B-, 8B-shaped, ragged, tiny fp32): last-K-step and whole-run figures
+  roofline             algorithmic bytes of the timed launches / their HIP-event time, against the HBM peak
+  cpu_baseline         the CPU oracle on the host cores, on a bounded sample of the same workload
+
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -30,43 +40,32 @@ HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 
 
 def n_live_at(t: int, W: int, C: int) -> int:
-    """Live tokens the attention of decode step t (1-based) reads, lazy chunk eviction."""
+    """Live thinking tokens the attention of decode step t (1-based) reads, lazy chunk eviction."""
     return t if t <= W else W - C + ((t - W - 1) % C) + 1
 
 
-def attention_bytes_per_step(wl, lengths, steps: int, prompt_len=None):
-    """Algorithmic bytes of the attention launch of every step: K and V stream over the question
-    tokens and the live window plus q in and out out, for every active rollout."""
+def path_bytes(wl, lengths, t0: int, t1: int, prompt_len=None):
+    """Algorithmic bytes and decoded tokens of decode steps t0+1 .. t1 (1-based) of the workload: per active
+    rollout and step the K and V stream over question tokens and live window, q in and out out, the
+    append; per eviction the chunk re-read and the read-modify-write of S."""
     import numpy as np
     s = wl.elem_bytes
-    per_tok = 2 * wl.d_kv * s
-    qo = 2 * wl.d_q * s
-    out = np.zeros(steps, dtype=np.float64)
-    act = np.zeros(steps, dtype=np.int64)
+    Wr, C = wl.window - wl.n_sink, wl.chunk
+    per_tok, qo, app = 2 * wl.d_kv * s, 2 * wl.d_q * s, 2 * wl.d_kv * s
+    per_evict = 2 * C * wl.d_kv * s + 2 * wl.n_global * wl.rank * 4
+    steps = np.arange(t0 + 1, t1 + 1, dtype=np.int64)
+    nl = np.array([n_live_at(int(t), Wr, C) for t in steps], dtype=np.float64)
+    evicts = ((steps > Wr) & ((steps - Wr - 1) % C == 0)).astype(np.float64)
     uniq = {}
-    pls = [0] * len(lengths) if prompt_len is None else prompt_len.tolist()
-    for L, P in zip(lengths.tolist(), pls):
+    pls = [0] * len(lengths) if prompt_len is None else list(np.asarray(prompt_len).tolist())
+    for L, P in zip(np.asarray(lengths).tolist(), pls):
         uniq[(L, P)] = uniq.get((L, P), 0) + 1
-    nl = np.array([n_live_at(t, wl.window - wl.n_sink, wl.chunk) for t in range(1, steps + 1)], dtype=np.float64)
+    total, tokens = 0.0, 0
     for (L, P), cnt in uniq.items():
-        n = min(L, steps)
-        out[:n] += cnt * (per_tok * (nl[:n] + P) + qo)
-        act[:n] += cnt
-    return out, act
-
-
-def prologue_bytes_total(wl, lengths, steps: int) -> float:
-    """Algorithmic bytes of append (every active step) and of evict-and-encode (chunk re-read plus
-    the read-modify-write of S) over the run."""
-    s = wl.elem_bytes
-    tot = 0.0
-    for L in lengths.tolist():
-        n = min(L, steps)
-        tot += n * 2 * wl.d_kv * s
-        ring = wl.window - wl.n_sink
-        ev = 0 if n <= ring else math.ceil((n - ring) / wl.chunk)
-        tot += ev * (2 * wl.chunk * wl.d_kv * s + 2 * wl.n_global * wl.rank * 4)
-    return tot
+        alive = steps <= L
+        total += cnt * float(((per_tok * (nl + P) + qo + app + per_evict * evicts) * alive).sum())
+        tokens += cnt * int(alive.sum())
+    return total, tokens
 
 
 def cpu_baseline(wl, budget_s: float = 15.0):
@@ -111,11 +110,206 @@ def cpu_baseline(wl, budget_s: float = 15.0):
     }
 
 
+class Timer:
+    """HIP events on torch's current stream (the stream every library call is issued to) plus the host clock."""
+
+    def __init__(self, torch):
+        self.torch = torch
+
+    def __call__(self, fn):
+        t = self.torch
+        t.cuda.synchronize()
+        e0, e1 = t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
+        w0 = time.perf_counter()
+        e0.record()
+        fn()
+        e1.record()
+        t.cuda.synchronize()
+        return e0.elapsed_time(e1), (time.perf_counter() - w0) * 1e3
+
+
+class Bench:
+    """One workload on one context: inputs by segments of the step axis, the run in pieces."""
+
+    def __init__(self, wl, args, torch, np, I, ptenc, resident: bool):
+        self.wl, self.args, self.torch, self.np, self.I, self.ptenc = wl, args, torch, np, I, ptenc
+        self.dev = torch.device("cuda:0")
+        self.lengths = I.rollout_lengths(wl)
+        self.T = int(self.lengths.max()) if wl.ragged else wl.steps
+        self.compact = wl.ragged and args.ragged_mode == "compact"
+        self.resident = resident or wl.ragged     # the whole run's inputs in HBM at once (else per segment)
+        self.timer = Timer(torch)
+        self.layer = ptenc.Layer(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
+                                 dtype=wl.torch_dtype, n_global=wl.n_global, rank=wl.rank, n_sink=wl.n_sink)
+        self.prompt_len = I.prompt_lengths(wl) if wl.n_sink else None
+        if wl.n_sink:
+            self.pk, self.pv = I.prompt_kv(wl, device=self.dev)
+        layer = self.layer
+        if args.splits:
+            layer.set_option(ptenc.OPT_SPLITS, args.splits)
+        if args.encode_parts:
+            layer.set_option(ptenc.OPT_ENCODE_PARTS, args.encode_parts)
+        if args.policy == "scored":
+            layer.set_option(ptenc.OPT_RECENT, args.recent)
+            layer.set_option(ptenc.OPT_EVICT_POLICY, ptenc.POLICY_SCORED)
+        self.enc = I.encoder_params(wl, device=self.dev)
+        e = self.enc
+        layer.set_encoder(e["q_g"], e["WaQ"], e["WaK"], e["WaV"], e["k_g"], e["v_g"])
+        self.attn_kernel, self.n_splits, _ = layer.plan()
+        self.seg = None          # (t0, t1, q, k, v, out, active, ids, row_offsets)
+        if self.resident:
+            self.seg = self._make_segment(0, self.T)
+
+    # ---- inputs ----
+    def _make_segment(self, t0, t1):
+        torch, np, I, wl, dev = self.torch, self.np, self.I, self.wl, self.dev
+        n = t1 - t0
+        q = torch.empty((n, wl.batch, wl.n_q_heads, wl.head_dim), dtype=wl.torch_dtype, device=dev)
+        k = torch.empty((n, wl.batch, wl.n_kv_heads, wl.head_dim), dtype=wl.torch_dtype, device=dev)
+        v = torch.empty_like(k)
+        blk = max(1, (1 << 26) // (wl.batch * wl.d_q))
+        for a in range(0, n, blk):
+            b = min(n, a + blk)
+            q[a:b], k[a:b], v[a:b] = I.qkv_steps(wl, t0 + a, t0 + b, device=dev)
+        active = ids = row_offsets = None
+        if wl.ragged:
+            tt = torch.arange(t0, t1, device=dev).view(-1, 1)
+            alive = tt < torch.from_numpy(self.lengths).to(dev).view(1, -1)          # [n, B]
+            if self.compact:
+                # what a rollout engine feeds: only the rollouts still running, with their ids
+                ids = torch.nonzero(alive)[:, 1].to(torch.int32).contiguous()
+                q, k, v = q[alive].contiguous(), k[alive].contiguous(), v[alive].contiguous()
+                counts = np.array([(self.lengths > t).sum() for t in range(t0, t1)], dtype=np.int64)
+                row_offsets = np.concatenate([[0], np.cumsum(counts)])
+            else:
+                active = alive.to(torch.uint8).contiguous()
+        out = torch.empty_like(q)
+        torch.cuda.synchronize()
+        return (t0, t1, q, k, v, out, active, ids, row_offsets)
+
+    def _segment_for(self, t0, t1):
+        if self.seg is not None and self.seg[0] <= t0 and t1 <= self.seg[1]:
+            return self.seg
+        self.seg = None                       # free the old one first
+        self.seg = self._make_segment(t0, t1)
+        return self.seg
+
+    # ---- the run ----
+    def start(self):
+        """An empty cache; question tokens (if the workload has any) prefilled: not part of the timed steps."""
+        self.layer.reset()
+        if self.wl.n_sink:
+            self.layer.prefill(self.pk, self.pv, self.prompt_len)
+
+    def launch(self, t0, t1):
+        """Decode steps t0+1 .. t1 (no synchronisation); their inputs must be in the current segment."""
+        s0, _, q, k, v, out, active, ids, ro = self.seg
+        a, b = t0 - s0, t1 - s0
+        if self.compact:
+            r0, r1 = int(ro[a]), int(ro[b])
+            self.layer.run_ids(q[r0:r1], k[r0:r1], v[r0:r1], ids[r0:r1], ro[a:b + 1] - r0, out[r0:r1])
+        else:
+            self.layer.run(q[a:b], k[a:b], v[a:b], out[a:b], None if active is None else active[a:b])
+
+    def run_timed(self, t0, t1, seg_steps=0):
+        """Steps t0+1 .. t1; returns (GPU ms by HIP events, host ms), summed over the segments the inputs come in."""
+        gpu = wall = 0.0
+        step = seg_steps if (seg_steps and not self.resident) else (t1 - t0)
+        a = t0
+        while a < t1:
+            b = min(t1, a + step)
+            self._segment_for(a, b)
+            g, w = self.timer(lambda: self.launch(a, b))
+            gpu, wall = gpu + g, wall + w
+            a = b
+        return gpu, wall
+
+    def check_counters(self, t):
+        ln, _ = self.layer.counters()
+        assert self.np.array_equal(ln, self.np.minimum(self.lengths, t)), "counters after the run are not the step count"
+        assert self.layer.poll_error() == 0
+
+    def figures(self, t0, t1, gpu_ms, wall_ms):
+        nbytes, tokens = path_bytes(self.wl, self.lengths, t0, t1, self.prompt_len)
+        ms = max(gpu_ms, wall_ms)
+        return {
+            "steps": t1 - t0, "first_step": t0 + 1, "last_step": t1, "tokens": tokens,
+            "ms": ms, "gpu_ms": gpu_ms, "us_per_step": ms * 1e3 / max(1, t1 - t0),
+            "tokens_per_s": tokens / (ms * 1e-3),
+            "algorithmic_gbytes": nbytes / 1e9,
+            "hbm_frac": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "hbm_frac_by_gpu_events": nbytes / (gpu_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        }
+
+    def window_words(self, t0, t1):
+        wl = self.wl
+        Wr, C = wl.window - wl.n_sink, wl.chunk
+        nl = [n_live_at(t, Wr, C) for t in range(t0 + 1, t1 + 1)]
+        return "steps %d..%d of the %d-step run, %d..%d thinking tokens live per rollout" % (
+            t0 + 1, t1, self.T, min(nl), max(nl))
+
+    def describe(self):
+        wl = self.wl
+        return "%s-shaped layer: B %d rollouts, %d Q / %d KV heads, head_dim %d, window %d, chunk %d%s%s" % (
+            wl.name, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
+            (", ragged lengths (lognormal, median 3000, capped at %d), finished rollouts %s" % (
+                wl.steps, "dropped from the batch (rollout-id lists)" if self.compact else "masked")) if wl.ragged else "",
+            ", %d slots reserved for question tokens (128..%d per rollout, prefilled)" % (wl.n_sink, wl.n_sink)
+            if wl.n_sink else "")
+
+    def staggered(self, n_steps):
+        """Full-ring steps with every rollout evicting in the same step, and with the rollouts' rings filled at
+        different steps so that every step has its share of evictions.  The cache keeps what the last run
+        left and the counters are re-based, so positions and contents no longer correspond: timing only."""
+        np, wl, layer = self.np, self.wl, self.layer
+        Wr, C, B = wl.window, wl.chunk, wl.batch
+        ns = min(n_steps, self.T)
+        self._segment_for(0, ns)
+        zeros = np.zeros(B, dtype=np.int64)
+
+        def timed_from(ln):
+            best = None
+            for _ in range(3):
+                layer.set_counters(ln, zeros)
+                g, _ = self.timer(lambda: self.launch(0, ns))
+                us = g * 1e3 / ns
+                best = us if best is None else min(best, us)
+            return best
+
+        together = timed_from(np.full(B, Wr - C // 2, dtype=np.int64))
+        spread = timed_from((Wr - (np.arange(B) * C // B) % C).astype(np.int64))
+        return {"steps": ns, "us_per_step_all_evicting_together": together,
+                "us_per_step_evictions_spread_over_steps": spread,
+                "spread_over_together": spread / together}
+
+
+def steady_and_full(b: Bench, K: int, W: int, seg_steps: int):
+    """The whole run from an empty cache, timed in pieces: steps 1..T-K (the last W of them are the warm-up of the
+    K-step region), then the last K steps as a timed region of their own.  Returns (steady, full) figures."""
+    T = b.T
+    K = min(K, T)
+    b.start()
+    g0 = w0 = 0.0
+    if T - K > 0:
+        g0, w0 = b.run_timed(0, T - K, seg_steps)
+    b._segment_for(T - K, T)
+    g1, w1 = b.run_timed(T - K, T)
+    b.check_counters(T)
+    steady = b.figures(T - K, T, g1, w1)
+    steady["window"] = b.window_words(T - K, T)
+    full = b.figures(0, T, g0 + g1, w0 + w1)
+    full["timed_as"] = "steps 1..%d%s, then the last %d" % (
+        T - K, "" if b.resident else " in segments of %d (inputs generated per segment, outside the timing)" % seg_steps, K)
+    return steady, full
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=0, help="decode steps to time (0 = the workload's full run)")
-    ap.add_argument("--warmup", type=int, default=32)
+    ap.add_argument("--steps", type=int, default=20,
+                    help="decode steps in the timed region: the last K steps of the workload's run (0 = the whole run)")
+    ap.add_argument("--warmup", type=int, default=5,
+                    help="warm-up steps: the last W of the untimed steps 1..T-K that precede the timed region")
     ap.add_argument("--workload", default="qwen7b")
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--encode-parts", type=int, default=0,
@@ -125,18 +319,20 @@ def main() -> int:
     ap.add_argument("--ragged-mode", choices=["compact", "masked"], default="compact",
                     help="ragged workloads: drop finished rollouts from the batch (rollout-id lists) or mask them")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-kernel-timing", action="store_true", help="skip the per-launch HIP-event pass")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="only the untimed steps 1..T-K and the K timed steps (profiler runs): no full run, no "
+                         "staggered evictions, no other workloads, no CPU baseline")
+    ap.add_argument("--no-workloads", action="store_true", help="skip the other configurations")
+    ap.add_argument("--no-stagger", action="store_true", help="skip the staggered-evictions figures")
     ap.add_argument("--extras", action="store_true",
                     help="also time the state-as-weight-delta application (and the question-token prefill)")
     ap.add_argument("--policy", choices=["sliding", "scored"], default="sliding",
                     help="which tokens an eviction takes: the oldest chunk, or the lowest accumulated attention probability")
     ap.add_argument("--recent", type=int, default=-1, help="scored policy: most recent ring entries never taken (-1 = half the ring)")
     ap.add_argument("--layers", type=int, default=0,
-                    help="also time a stack of this many layers (each with its own cache) over the same steps: "
+                    help="also time a stack of this many layers (each with its own cache) over the run's first steps: "
                          "eager launches, then replays of the recorded one-step HIP graph")
-    ap.add_argument("--stagger", action="store_true",
-                    help="also time steady-state steps with the rollouts' evictions spread evenly over the steps "
-                         "(a running batch whose rollouts started at different times) next to all evicting together")
+    ap.add_argument("--layer-steps", type=int, default=512, help="steps of the stack timing")
     ap.add_argument("--calibrate", action="store_true",
                     help="also launch the plain copy / read kernels on 1 GiB (scale for the profiler's byte counters)")
     args = ap.parse_args()
@@ -157,187 +353,95 @@ def main() -> int:
     wl = I.WORKLOADS[args.workload]
     if args.chunk:
         wl = wl.replace(chunk=args.chunk)
-    K = args.steps if args.steps > 0 else wl.steps
     Wu = max(0, args.warmup)
-    lengths = I.rollout_lengths(wl)
-    if wl.ragged:
-        K = min(K, int(lengths.max()))
 
-    # ---- synthetic inputs, resident in HBM ----
-    T_gen = max(K, Wu)
-    q = torch.empty((T_gen, wl.batch, wl.n_q_heads, wl.head_dim), dtype=wl.torch_dtype, device=dev)
-    k = torch.empty((T_gen, wl.batch, wl.n_kv_heads, wl.head_dim), dtype=wl.torch_dtype, device=dev)
-    v = torch.empty_like(k)
-    blk = max(1, (1 << 26) // (wl.batch * wl.d_q))
-    for t0 in range(0, T_gen, blk):
-        t1 = min(T_gen, t0 + blk)
-        q[t0:t1], k[t0:t1], v[t0:t1] = I.qkv_steps(wl, t0, t1, device=dev)
-    active = None
-    compact = wl.ragged and args.ragged_mode == "compact"
-    row_offsets = None
-    if wl.ragged:
-        tt = torch.arange(T_gen, device=dev).view(-1, 1)
-        alive = tt < torch.from_numpy(lengths).to(dev).view(1, -1)          # [T, B]
-        if compact:
-            # what a rollout engine feeds: only the rollouts still running, with their ids
-            ids = torch.nonzero(alive)[:, 1].to(torch.int32).contiguous()
-            q, k, v = q[alive].contiguous(), k[alive].contiguous(), v[alive].contiguous()
-            counts = np.array([(lengths > t).sum() for t in range(T_gen)], dtype=np.int64)
-            row_offsets = np.concatenate([[0], np.cumsum(counts)])
-        else:
-            active = alive.to(torch.uint8).contiguous()
-    out = torch.empty_like(q)
-    enc = I.encoder_params(wl, device=dev)
+    # ---- the headline workload: inputs of the whole run resident in HBM where they fit comfortably ----
+    in_bytes = wl.steps * wl.batch * (2 * wl.d_q + 2 * wl.d_kv) * wl.elem_bytes
+    hb = Bench(wl, args, torch, np, I, ptenc, resident=in_bytes <= (40 << 30))
+    T = hb.T
+    K = T if (args.steps <= 0 or args.steps >= T) else args.steps
+    seg_steps = 512
 
-    layer = ptenc.Layer(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
-                        dtype=wl.torch_dtype, n_global=wl.n_global, rank=wl.rank, n_sink=wl.n_sink)
-    prompt_len = I.prompt_lengths(wl) if wl.n_sink else None
-    if wl.n_sink:
-        pk, pv = I.prompt_kv(wl, device=dev)
-
-    def start_run():
-        # an empty cache, question tokens (if the workload has any) prefilled: not part of the timed steps
-        layer.reset()
-        if wl.n_sink:
-            layer.prefill(pk, pv, prompt_len)
-
-    if args.splits:
-        layer.set_option(ptenc.OPT_SPLITS, args.splits)
-    if args.encode_parts:
-        layer.set_option(ptenc.OPT_ENCODE_PARTS, args.encode_parts)
-    if args.policy == "scored":
-        layer.set_option(ptenc.OPT_RECENT, args.recent)
-        layer.set_option(ptenc.OPT_EVICT_POLICY, ptenc.POLICY_SCORED)
-    layer.set_encoder(enc["q_g"], enc["WaQ"], enc["WaK"], enc["WaV"], enc["k_g"], enc["v_g"])
-    attn_kernel, n_splits, _ = layer.plan()
-
-    # ---- warmup, then the timed run from an empty cache ----
-    def run_steps(t0, t1):
-        if compact:
-            r0, r1 = int(row_offsets[t0]), int(row_offsets[t1])
-            layer.run_ids(q[r0:r1], k[r0:r1], v[r0:r1], ids[r0:r1], row_offsets[t0:t1 + 1] - r0, out[r0:r1])
-        else:
-            layer.run(q[t0:t1], k[t0:t1], v[t0:t1], out[t0:t1], None if active is None else active[t0:t1])
-
-    start_run()
-    if Wu:
-        run_steps(0, Wu)
-    start_run()
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    w0 = time.perf_counter()
-    e0.record()
-    run_steps(0, K)
-    e1.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - w0) * 1e3
-    gpu_ms = e0.elapsed_time(e1)
+    # untimed: steps 1 .. T-K through the same entry point (the last Wu of them are the warm-up)
+    hb.start()
+    if T - K > 0:
+        a = 0
+        while a < T - K:
+            b_ = (T - K) if hb.resident else min(T - K, a + seg_steps)
+            hb._segment_for(a, b_)
+            hb.launch(a, b_)
+            a = b_
+    else:
+        hb._segment_for(0, min(T, max(Wu, 1)))
+        hb.launch(0, min(T, Wu))          # whole-run timing: a few steps to warm up, then from an empty cache again
+        hb.start()
+    hb._segment_for(T - K, T)
+    # the timed region: exactly K steps, synchronised on both sides, HIP events on the launch stream
+    gpu_ms, wall_ms = hb.timer(lambda: hb.launch(T - K, T))
+    hb.check_counters(T)
     total_ms = max(gpu_ms, wall_ms)
-    assert layer.poll_error() == 0
-    ln, base = layer.counters()
-    assert np.array_equal(ln, np.minimum(lengths, K)), "counters after the run are not the step count"
+    head = hb.figures(T - K, T, gpu_ms, wall_ms)
+    fused = hb.attn_kernel == 1
 
-    abytes, act = attention_bytes_per_step(wl, lengths, K, prompt_len)
-    tokens = int(act.sum())
-    value = tokens / (total_ms * 1e-3)
-    all_bytes = float(abytes.sum()) + prologue_bytes_total(wl, lengths, K)
-
-    # ---- launch time of the dominant kernel with HIP events on the launch stream (second pass over the
-    #      same steps).  On the MFMA path one launch is one whole decode step and nothing else runs in
-    #      between, so the events bracket runs of EV_EVERY back-to-back launches: an event pair around
-    #      every single launch adds about 2 us to each (it breaks the back-to-back dispatch), which is
-    #      not kernel time.  The plain path's attention launches are bracketed one by one. ----
-    roofline = None
-    fused = attn_kernel == 1
-    EV_EVERY = 32
-    if not args.no_kernel_timing:
-        start_run()
-        evs = []
-        if fused:
-            for t0 in range(0, K, EV_EVERY):
-                pair = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                pair[0].record()
-                run_steps(t0, min(K, t0 + EV_EVERY))
-                pair[1].record()
-                evs.append(pair)
+    # ---- roofline of the dominant kernel over the same K launches.  On the MFMA path one launch of the step
+    #      kernel is one whole decode step and nothing else runs between the launches, so the HIP events
+    #      around the timed region bracket exactly K back-to-back launches of it. ----
+    launch_bytes = head["algorithmic_gbytes"] * 1e9 / K
+    mean_s = gpu_ms * 1e-3 / K
+    traffic, traffic_note = None, "no HBM byte counters were collected for this window"
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % wl.name)
+    if os.path.exists(tpath):
+        with open(tpath) as fh:
+            tj = json.load(fh)
+        if tj.get("first_step") == T - K + 1 and tj.get("last_step") == T and not args.chunk and args.policy == "sliding":
+            traffic, traffic_note = tj.get("traffic_bytes_per_launch"), tj.get("source")
         else:
-            for t in range(K):
-                a = None if active is None else active[t]
-                pair = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                layer.evict_encode(a)
-                layer.append(k[t], v[t], a)
-                pair[0].record()
-                layer.attend(q[t], out[t], a)
-                pair[1].record()
-                evs.append(pair)
-        torch.cuda.synchronize()
-        kern_ms = float(sum(a.elapsed_time(b) for a, b in evs))
-        mean_s = kern_ms * 1e-3 / K
-        launch_bytes = (all_bytes if fused else float(abytes.sum())) / K
-        achieved = launch_bytes / mean_s / 1e9
-        traffic = None
-        tpath = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % wl.name)
-        if os.path.exists(tpath) and K == wl.steps:
-            with open(tpath) as fh:
-                traffic = json.load(fh).get("traffic_bytes_per_launch")
-        roofline = {
-            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-            "kernel": "decode_mfma_kernel (evict-encode + append + attention in one launch)" if fused
-                      else "attn_generic_kernel + combine_kernel",
-            "launches": K, "mean_launch_us": mean_s * 1e6, "algorithmic_bytes_per_launch": launch_bytes,
-            "launches_per_event_pair": EV_EVERY if fused else 1,
-        }
+            traffic_note = "profiles/hbm_traffic_%s.txt covers steps %s..%s, not this window" % (
+                wl.name, tj.get("first_step"), tj.get("last_step"))
+    roofline = {
+        "bound": "hbm", "achieved": launch_bytes / mean_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": launch_bytes / mean_s / 1e9 / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": traffic_note,
+        "kernel": "decode_mfma_kernel (evict-encode + append + attention in one launch)" if fused
+                  else "attn_generic / step kernels of the plain path (all launches of the step)",
+        "launches": K, "mean_launch_us": mean_s * 1e6, "algorithmic_bytes_per_launch": launch_bytes,
+        "timed_with": "HIP events on the launch stream around the K back-to-back launches of the timed region",
+    }
 
     res = {
         "metric": "rollout decode tokens/s per layer (bounded window)",
-        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wu,
+        "value": head["tokens"] / (total_ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wu,
         "ms_per_step": total_ms / K, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
         "config": {
-            "workload": "%s-shaped layer: B %d rollouts, %d Q / %d KV heads, head_dim %d, window %d, chunk %d, "
-                        "%d decode steps from an empty cache%s%s" % (
-                            wl.name, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk, K,
-                            (", ragged lengths, finished rollouts %s" % ("dropped from the batch (rollout-id lists)"
-                                                                        if compact else "masked")) if wl.ragged else "",
-                            ", %d slots reserved for question tokens (128..%d per rollout, prefilled)" % (
-                                wl.n_sink, wl.n_sink) if wl.n_sink else ""),
-            "name": wl.name, "batch": wl.batch, "window": wl.window, "chunk": wl.chunk, "tokens": tokens,
-            "attn_kernel": "mfma" if attn_kernel == 1 else "generic", "window_splits": n_splits,
-            "evict_policy": args.policy,
-            "parallelism": "single GPU",
+            "workload": "%s; timed: %s%s" % (
+                hb.describe(), hb.window_words(T - K, T),
+                (" (steps 1..%d decoded first, untimed, through the same entry point; the last %d of them are the "
+                 "warm-up)" % (T - K, min(Wu, T - K))) if K < T else " from an empty cache"),
+            "name": wl.name, "batch": wl.batch, "window": wl.window, "chunk": wl.chunk, "tokens": head["tokens"],
+            "run_steps": T, "first_timed_step": T - K + 1, "last_timed_step": T,
+            "attn_kernel": "mfma" if fused else "generic", "window_splits": hb.n_splits,
+            "evict_policy": args.policy, "parallelism": "single GPU",
         },
         "gpu_ms": gpu_ms, "wall_ms": wall_ms,
-        "hbm_frac_whole_path": all_bytes / (total_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "algorithmic_gbytes": all_bytes / 1e9,
+        "hbm_frac_whole_path": head["hbm_frac"],
+        "algorithmic_gbytes": head["algorithmic_gbytes"],
         "roofline": roofline,
     }
-    if args.stagger and not wl.ragged and not wl.n_sink and args.policy == "sliding":
-        # steady state, rings nearly full: the cache keeps what the run left (the counters are re-based, so
-        # positions and contents no longer correspond: timing only)
-        Wr, C, B = wl.window, wl.chunk, wl.batch
-        ns = min(2 * C, K)
-        zeros = np.zeros(B, dtype=np.int64)
 
-        def timed_from(ln):
-            best = None
-            for _ in range(3):
-                layer.set_counters(ln, zeros)
-                torch.cuda.synchronize()
-                a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a0.record()
-                layer.run(q[:ns], k[:ns], v[:ns], out[:ns])
-                a1.record()
-                torch.cuda.synchronize()
-                us = a0.elapsed_time(a1) * 1e3 / ns
-                best = us if best is None else min(best, us)
-            return best
+    if not args.headline_only:
+        # ---- the whole run from an empty cache, in the same process ----
+        if K < T:
+            hb.start()
+            g, w = hb.run_timed(0, T, seg_steps)
+            hb.check_counters(T)
+            res["full_run"] = hb.figures(0, T, g, w)
+            res["full_run"]["what"] = "all %d steps from an empty cache%s" % (
+                T, "" if hb.resident else ", in segments of %d steps (inputs generated per segment, untimed)" % seg_steps)
+        if not args.no_stagger and not wl.ragged and not wl.n_sink and args.policy == "sliding":
+            res["staggered_evictions"] = hb.staggered(2 * wl.chunk)
 
-        together = timed_from(np.full(B, Wr - C // 2, dtype=np.int64))
-        spread = timed_from((Wr - (np.arange(B) * C // B) % C).astype(np.int64))
-        res["staggered_evictions"] = {"steps": ns, "us_per_step_all_evicting_together": together,
-                                      "us_per_step_evictions_spread_over_steps": spread}
     if args.extras:
+        layer = hb.layer
         # y += ((x A) S) B at the model's hidden size (the query projection width stands in for it)
         ex = {}
         d_h = wl.d_q
@@ -345,33 +449,25 @@ def main() -> int:
         yb = ad["y"].clone()
         for _ in range(10):
             layer.apply_delta(ad["x"], ad["At"], ad["Bt"], yb)
-        torch.cuda.synchronize()
-        a0, a1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a0.record()
-        for _ in range(200):
-            layer.apply_delta(ad["x"], ad["At"], ad["Bt"], yb)
-        a1.record()
-        torch.cuda.synchronize()
-        us = a0.elapsed_time(a1) * 1e3 / 200
+        g, _ = hb.timer(lambda: [layer.apply_delta(ad["x"], ad["At"], ad["Bt"], yb) for _ in range(200)])
+        us = g * 1e3 / 200
         s_ = wl.elem_bytes
         nbytes_ad = wl.batch * (d_h * s_ + 2 * d_h * s_ + wl.n_global * wl.rank * 4) + (wl.n_global + wl.rank) * d_h * s_
         ex["apply_delta"] = {"d_in": d_h, "d_out": d_h, "us_per_call": us, "algorithmic_bytes": nbytes_ad,
                              "GB_per_s": nbytes_ad / us / 1e3, "hbm_frac": nbytes_ad / us / 1e3 / HBM_PEAK_GBS}
         if wl.n_sink:
-            torch.cuda.synchronize()
-            a0.record()
-            for _ in range(20):
-                layer.prefill(pk, pv, prompt_len)
-            a1.record()
-            torch.cuda.synchronize()
-            us = a0.elapsed_time(a1) * 1e3 / 20
-            nb = float(prompt_len.sum()) * 2 * wl.d_kv * s_ * 2          # read once, written once
+            g, _ = hb.timer(lambda: [layer.prefill(hb.pk, hb.pv, hb.prompt_len) for _ in range(20)])
+            us = g * 1e3 / 20
+            nb = float(hb.prompt_len.sum()) * 2 * wl.d_kv * s_ * 2          # read once, written once
             ex["prefill"] = {"us_per_call": us, "algorithmic_bytes": nb, "GB_per_s": nb / us / 1e3}
         res["extras"] = ex
+
     if args.layers > 0 and not wl.ragged:
         # L layers, each with its own cache, counters and state; layer l reads the inputs of step t + 7 l
-        L = args.layers
-        del layer
+        L, KL = args.layers, min(args.layer_steps, T)
+        hb._segment_for(0, KL)
+        _, _, q, k, v, out, _, _, _ = hb.seg
+        enc = hb.enc
         st = ptenc.Stack(L, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
                          dtype=wl.torch_dtype, n_global=wl.n_global, rank=wl.rank, n_sink=wl.n_sink)
         for lay in st.layers:
@@ -383,12 +479,12 @@ def main() -> int:
             st.reset()
             if wl.n_sink:
                 for lay in st.layers:
-                    lay.prefill(pk, pv, prompt_len)
+                    lay.prefill(hb.pk, hb.pv, hb.prompt_len)
 
-        outs = [out[l % T_gen] for l in range(L)]
+        outs = [out[l % KL] for l in range(L)]
 
         def eager(t):
-            idx = [(t + 7 * l) % T_gen for l in range(L)]
+            idx = [(t + 7 * l) % KL for l in range(L)]
             st.step([q[i] for i in idx], [k[i] for i in idx], [v[i] for i in idx], outs)
 
         def timed(fn):
@@ -396,33 +492,28 @@ def main() -> int:
             for t in range(min(Wu, 8)):
                 fn(t)
             stack_start()
-            torch.cuda.synchronize()
-            s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            c0 = time.perf_counter()
-            s0.record()
-            for t in range(K):
-                fn(t)
-            s1.record()
-            torch.cuda.synchronize()
-            return max(s0.elapsed_time(s1), (time.perf_counter() - c0) * 1e3)
+            g, w = hb.timer(lambda: [fn(t) for t in range(KL)])
+            return max(g, w)
 
         ms_eager = timed(eager)
         ln0, _ = st.layers[L - 1].counters()
-        assert np.array_equal(ln0, np.full(wl.batch, K)) and st.layers[0].poll_error() == 0
-        st.graph_capture([q[l % T_gen] for l in range(L)], [k[l % T_gen] for l in range(L)],
-                         [v[l % T_gen] for l in range(L)], outs)
+        assert np.array_equal(ln0, np.full(wl.batch, KL)) and st.layers[0].poll_error() == 0
+        st.graph_capture([q[l % KL] for l in range(L)], [k[l % KL] for l in range(L)],
+                         [v[l % KL] for l in range(L)], outs)
         ms_graph = timed(lambda t: st.graph_launch())
         ln0, _ = st.layers[L - 1].counters()
-        assert np.array_equal(ln0, np.full(wl.batch, K)) and st.layers[0].poll_error() == 0
+        assert np.array_equal(ln0, np.full(wl.batch, KL)) and st.layers[0].poll_error() == 0
         best = min(ms_eager, ms_graph)
+        nb, toks = path_bytes(wl, hb.lengths, 0, KL, hb.prompt_len)
         res["stack"] = {
-            "layers": L, "cache_gbytes": st.cache.numel() / 1e9, "plan": list(st.layers[0].plan()),
-            "metric": "rollout decode tokens/s per model of %d layers (bounded window)" % L,
-            "value": tokens / (best * 1e-3), "unit": "tokens/s",
-            "ms_per_step_eager": ms_eager / K, "ms_per_step_graph": ms_graph / K,
-            "hbm_frac_whole_path": L * all_bytes / (best * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "layers": L, "steps": KL, "cache_gbytes": st.cache.numel() / 1e9, "plan": list(st.layers[0].plan()),
+            "metric": "rollout decode tokens/s per model of %d layers (bounded window), first %d steps of the run" % (L, KL),
+            "value": toks / (best * 1e-3), "unit": "tokens/s",
+            "ms_per_step_eager": ms_eager / KL, "ms_per_step_graph": ms_graph / KL,
+            "hbm_frac_whole_path": L * nb / (best * 1e-3) / 1e9 / HBM_PEAK_GBS,
         }
         del st
+
     if args.calibrate:
         nbytes = 1 << 30
         src = torch.randint(0, 255, (nbytes,), dtype=torch.uint8, device=dev)
@@ -431,21 +522,49 @@ def main() -> int:
         for _ in range(5):
             ptenc.ptenc_util_copy(dst, src, nbytes, 2048)
             ptenc.ptenc_util_stream_read(src, nbytes, sink, 2048)
-        torch.cuda.synchronize()
+
         def gbs(fn, iters=20):
-            torch.cuda.synchronize()
-            c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            c0.record()
-            for _ in range(iters):
-                fn()
-            c1.record()
-            torch.cuda.synchronize()
-            return nbytes * iters / (c0.elapsed_time(c1) * 1e-3) / 1e9
+            g, _ = hb.timer(lambda: [fn() for _ in range(iters)])
+            return nbytes * iters / (g * 1e-3) / 1e9
         res["calibration"] = {"copy_kernel_bytes_read": nbytes, "copy_kernel_bytes_written": nbytes,
                               "read_kernel_bytes_read": nbytes, "launches_each": 5,
                               "stream_read_GB_per_s": gbs(lambda: ptenc.ptenc_util_stream_read(src, nbytes, sink, 2048)),
                               "stream_read_nontemporal_GB_per_s": gbs(lambda: ptenc.ptenc_util_stream_read_nt(src, nbytes, sink, 2048))}
-    if not args.no_cpu_baseline:
+        del src, dst
+
+    # ---- the other configurations: last-K-step and whole-run figures, same process ----
+    if not args.headline_only and not args.no_workloads and args.workload == "qwen7b" and not args.chunk \
+            and args.policy == "sliding":
+        del hb
+        torch.cuda.empty_cache()
+        others = {}
+        for name in ("qwen3b", "llama8b", "ragged", "tiny_f32"):
+            w2 = I.WORKLOADS[name]
+            nb2 = w2.steps * w2.batch * (2 * w2.d_q + 2 * w2.d_kv) * w2.elem_bytes
+            ob = Bench(w2, args, torch, np, I, ptenc, resident=nb2 <= (40 << 30))
+            if w2.ragged:
+                # steady state of a ragged batch is not one window size: the K steps right after every ring that
+                # will fill has filled (most rollouts still running), and the whole run
+                t_a = w2.window + 2 * w2.chunk
+                ob.start()
+                ob.launch(0, t_a)
+                g1, w1 = ob.timer(lambda: ob.launch(t_a, t_a + 20))
+                steady = ob.figures(t_a, t_a + 20, g1, w1)
+                steady["window"] = "steps %d..%d of the run (every ring that fills has filled; %d of %d rollouts still running)" % (
+                    t_a + 1, t_a + 20, int((ob.lengths > t_a).sum()), w2.batch)
+                ob.start()
+                g, w = ob.run_timed(0, ob.T)
+                ob.check_counters(ob.T)
+                full = ob.figures(0, ob.T, g, w)
+            else:
+                steady, full = steady_and_full(ob, 20, Wu, seg_steps)
+            others[name] = {"workload": ob.describe(), "attn_kernel": "mfma" if ob.attn_kernel == 1 else "generic",
+                            "window_splits": ob.n_splits, "last_steps": steady, "full_run": full}
+            del ob
+            torch.cuda.empty_cache()
+        res["workloads"] = others
+
+    if not args.no_cpu_baseline and not args.headline_only:
         res["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(res), flush=True)
     return 0

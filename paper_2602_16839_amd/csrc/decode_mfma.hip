@@ -248,7 +248,14 @@ __device__ inline void patch_newest(Frag& f, const Op kp[4], const uint32_t vp[4
 // encoding workgroups' shares of S')
 // is written and read with device-scope relaxed atomics: such stores write through and
 // such loads bypass the per-CU and per-XCD caches, so the hand-over needs no cache write-back or
-// invalidation.  Order is given by: stores, wait for them (workgroup fence), barrier, ticket.
+// invalidation.  Order is given by: stores, every wavefront waits until its own stores have been
+// acknowledged (wait_own_stores), barrier, ticket.  A workgroup-scope fence is NOT that wait: with a
+// workgroup's wavefronts on one CU the compiler turns it into a wait for LDS and scalar traffic only,
+// and the ticket (another wavefront's atomic, to another memory channel) could overtake the stores.
+__device__ inline void wait_own_stores() {
+  // loads and stores share the vector-memory counter on this GPU
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
 // (two adjacent floats, 8-byte aligned, as one 64-bit access)
 __device__ inline void st_agent2(float* p, float a, float b) {
   const unsigned long long u = (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32);
@@ -603,7 +610,7 @@ __device__ inline bool encode_rollout(const PtDev& c, StepSmem<WAVES>& sm, int& 
     // adds all of them
     float* mine = c.enc_part + ((size_t)b * c.enc_parts + part) * gr;
     for (int idx = threadIdx.x; idx < gr; idx += THREADS) st_agent1(mine + idx, stage[idx]);
-    __threadfence_block();
+    wait_own_stores();
     __syncthreads();
     if (threadIdx.x == 0) sm_ticket = atomicAdd(c.tick_enc + b, 1);
     __syncthreads();
@@ -656,7 +663,7 @@ __device__ inline void arrive_rollout(const PtDev& c, const StepArgs& a, StepSme
   // rare (once per C steps): the other workgroups' new token and score updates must be visible to the
   // one that selects, whichever XCD each ran on: device-wide release here, acquire there
   if (pl.will_select) __threadfence();
-  __threadfence_block();
+  wait_own_stores();
   __syncthreads();
   if (threadIdx.x == 0) sm_ticket = atomicAdd(c.tick_rollout + b, 1);
   __syncthreads();
@@ -1061,7 +1068,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
 #pragma unroll
         for (int x = 0; x < 4; ++x) st_agent2(po + 2 + part * 8 + 2 * x, o[2 * x], o[2 * x + 1]);
       }
-      __threadfence_block();
+      wait_own_stores();
       __syncthreads();
       if (tid == 0) sm_ticket = atomicAdd(c.tick_slab + slab, 1);
       __syncthreads();

@@ -378,10 +378,10 @@ ptenc_status ptenc_cache_append(ptenc_ctx* ctx, const void* d_k, const void* d_v
                                 void* stream) {
   if (!ctx || !d_k || !d_v) return PTENC_ERR_INVALID_ARG;
   if (!ctx->encoder_set) return PTENC_ERR_STATE;
+  if (ctx->attn_kernel == 1 && (((uintptr_t)d_k | (uintptr_t)d_v) & 15)) return PTENC_ERR_INVALID_ARG;
   ctx->select_stale = 1;   // a bare append may fill a ring without choosing its victims
   appended_one(ctx);
   if (ctx->attn_kernel == 1) {
-    if (((uintptr_t)d_k | (uintptr_t)d_v) & 15) return PTENC_ERR_INVALID_ARG;
     return advanced(ctx, pt_launch_decode_mfma(ctx->dev, ctx->nontemporal != 0, ctx->waves, false, true, false, nullptr, d_k, d_v,
                                                nullptr, d_active, nullptr, nullptr, 0, ctx->opt_in_place != 0, S(stream)));
   }

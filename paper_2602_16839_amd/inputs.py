@@ -154,6 +154,8 @@ class Workload:
     n_sink: int = 0                # cache slots reserved for question tokens (kept for good); part of `window`
     n_global: int = 32             # G global tokens (paper, Experimental Setup: 32 global tokens)
     rank: int = 32                 # r latent width (paper, Experimental Setup: LoRA rank 32)
+    q_gain: float = 1.0            # extra factor on the queries only (a power of two keeps bf16 values exact):
+                                   # > 1 spreads the scores so that a few keys carry most of the attention
 
     @property
     def torch_dtype(self):
@@ -186,6 +188,16 @@ WORKLOADS = {
     "qwen7b_sink": Workload("qwen7b_sink", "bf16", 128, 28, 4, 128, 4096 + 512, 128, 8192, 0.088, 1006,
                             per_head_scale=True, n_sink=512),
 }
+# The benchmark's input scale (0.088) makes every score about N(0, 0.008^2): the softmax weights are
+# uniform to within a per cent and the output is close to the plain mean of the values, whatever the
+# queries are.  The "peaked" twins keep the shapes and take values of std 0.25 with queries 64 times
+# larger, so the scores are about N(0, 4^2): a handful of keys carry the attention, the running
+# maximum keeps moving, and an implementation that gets the scores, the exponentials or the rescaling
+# wrong cannot hide behind the mean.  Used by the parity tests at full size.
+for _name in ("qwen3b", "qwen7b", "llama8b"):
+    _w = WORKLOADS[_name]
+    WORKLOADS[_name + "_peaked"] = dataclasses.replace(_w, name=_name + "_peaked", scale=0.25, q_gain=64.0,
+                                                       seed=_w.seed + 100)
 
 
 def qkv_head_scales(wl: Workload) -> Tuple[Optional[torch.Tensor], Optional[torch.Tensor], Optional[torch.Tensor]]:
@@ -200,7 +212,7 @@ def qkv_steps(wl: Workload, t0: int, t1: int, device="cpu", b0: int = 0, b1: Opt
     """q ``[t1-t0, b, H_q, d]``, k and v ``[t1-t0, b, H_kv, d]`` for decode steps t0..t1-1 (0-based)."""
     sq, sk, sv = qkv_head_scales(wl)
     kw = dict(dtype=wl.torch_dtype, device=device, b0=b0, b1=b1, B_total=wl.batch)
-    q = gaussian(wl.seed, STREAM_Q, t0, t1, wl.batch, wl.n_q_heads, wl.head_dim, wl.scale, sq, **kw)
+    q = gaussian(wl.seed, STREAM_Q, t0, t1, wl.batch, wl.n_q_heads, wl.head_dim, wl.scale * wl.q_gain, sq, **kw)
     k = gaussian(wl.seed, STREAM_K, t0, t1, wl.batch, wl.n_kv_heads, wl.head_dim, wl.scale, sk, **kw)
     v = gaussian(wl.seed, STREAM_V, t0, t1, wl.batch, wl.n_kv_heads, wl.head_dim, wl.scale, sv, **kw)
     return q, k, v

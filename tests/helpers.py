@@ -30,11 +30,39 @@ def row_errors(got: np.ndarray, ref: np.ndarray):
     return float(diff.max()), float((row_err / np.maximum(row_ref, 1e-30)).max())
 
 
-def assert_close(got, ref, abs_tol, rel_tol, what=""):
+# Errors observed on MI355X are far below the contract bars above (which stay the contract).  A regression
+# guard of about four times the observed maximum, where one is on record for the case, catches a kernel
+# that drifts towards the bar long before it crosses it.  Keys: the `what` prefix a full-size test uses.
+# (max abs, max row-relative); measured values are listed in the design notes.
+GUARDS = {}
+
+# every comparison made through assert_close, for the record of observed errors: {what: (abs, rel)} maxima
+OBSERVED = {}
+
+
+def _record(what, a, r):
+    key = what.split(" b=")[0].split(" at step")[0]
+    pa, pr = OBSERVED.get(key, (0.0, 0.0))
+    OBSERVED[key] = (max(pa, a), max(pr, r))
+
+
+def assert_close(got, ref, abs_tol, rel_tol, what="", guard=None):
+    """The contract bars abs_tol / rel_tol must hold; `guard` = (abs, rel), or the GUARDS entry whose key
+    starts `what`, is the tighter regression bar."""
     assert np.isfinite(np.asarray(got, dtype=np.float64)).all(), "%s: non-finite output" % what
     a, r = row_errors(got, ref)
+    _record(what, a, r)
     assert a <= abs_tol and r <= rel_tol, "%s: max abs %.3e (tol %.1e), max row-rel %.3e (tol %.1e)" % (
         what, a, abs_tol, r, rel_tol)
+    if guard is None:
+        for key, g in GUARDS.items():
+            if what.startswith(key):
+                guard = g
+                break
+    if guard is not None:
+        assert a <= guard[0] and r <= guard[1], (
+            "%s: within the contract but beyond the regression guard: max abs %.3e (guard %.1e), max row-rel %.3e "
+            "(guard %.1e)" % (what, a, guard[0], r, guard[1]))
 
 
 def tolerances(wl):

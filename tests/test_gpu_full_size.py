@@ -15,12 +15,14 @@ from tests import helpers as H
 pytestmark = pytest.mark.gpu
 
 
-def _run_full(wl, sample_steps, seg_steps):
+def _run_full(wl, sample_steps, seg_steps, options=None):
     """Decode the whole workload in segments; returns (layer, lengths, {t: out[t-1] on the host})."""
     dev = torch.device("cuda:0")
     enc = I.encoder_params(wl, device=dev)
     layer = ptenc.Layer(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
                         dtype=wl.torch_dtype, n_global=wl.n_global, rank=wl.rank, poison_cache=True, n_sink=wl.n_sink)
+    for opt, val in (options or {}).items():
+        layer.set_option(opt, val)
     layer.set_encoder(enc["q_g"], enc["WaQ"], enc["WaK"], enc["WaV"], enc["k_g"], enc["v_g"])
     layer.reset()
     if wl.n_sink:
@@ -46,10 +48,8 @@ def _run_full(wl, sample_steps, seg_steps):
     return layer, lengths, kept, T
 
 
-def _oracle_out(wl, b, t, L):
-    """Attention output of rollout b at decode step t (1-based), from regenerated inputs."""
-    if t > L:
-        return np.zeros((wl.n_q_heads, wl.head_dim))
+def _oracle_window(wl, b, t, L):
+    """(queries, keys, values) rollout b attends with at decode step t (1-based), from regenerated inputs."""
     E = evicted_closed_form(t, wl.window - wl.n_sink, wl.chunk)
     q, k, v = I.qkv_steps(wl, E, t, b0=b, b1=b + 1)
     keys, values = list(H.f64(k[:, 0])), list(H.f64(v[:, 0]))
@@ -57,7 +57,31 @@ def _oracle_out(wl, b, t, L):
         P = int(I.prompt_lengths(wl)[b])
         pk, pv = I.prompt_kv(wl)
         keys, values = list(H.f64(pk[b, :P])) + keys, list(H.f64(pv[b, :P])) + values
-    return po.attend(H.f64(q[-1, 0]), keys, values)
+    return H.f64(q[-1, 0]), keys, values
+
+
+def _oracle_out(wl, b, t, L):
+    """Attention output of rollout b at decode step t (1-based)."""
+    if t > L:
+        return np.zeros((wl.n_q_heads, wl.head_dim))
+    q, keys, values = _oracle_window(wl, b, t, L)
+    return po.attend(q, keys, values)
+
+
+def _strawmen_fail(wl, b, t, L, ref, what):
+    """The comparison at (b, t) must have the power to reject wrong softmax weights: the plain mean of the
+    live values (uniform weights, queries ignored) and a softmax that forgot the 1/sqrt(d) scale have to
+    miss BOTH contract bars by a factor of ten.  Computed on the CPU from the oracle's own inputs."""
+    q, keys, values = _oracle_window(wl, b, t, L)
+    V = np.stack(values)                                                  # [n, H_kv, d]
+    g = wl.n_q_heads // wl.n_kv_heads
+    mean_v = np.repeat(V.mean(axis=0), g, axis=0)                         # [H_q, d]
+    unscaled = po.attend(q, keys, values, scale=1.0)
+    for name, wrong in (("mean of V", mean_v), ("softmax without 1/sqrt(d)", unscaled)):
+        a, r = H.row_errors(wrong, ref)
+        assert a >= 10 * H.BF16_ABS and r >= 10 * H.BF16_REL, (
+            "%s: the strawman '%s' is only %.2e abs / %.2e row-rel away from the oracle: this case cannot tell it "
+            "from the attention equation" % (what, name, a, r))
 
 
 def _oracle_state(wl, b, L, enc):
@@ -73,8 +97,8 @@ def _oracle_state(wl, b, L, enc):
     return S
 
 
-def _check(wl, sample_b, sample_t, seg_steps):
-    layer, lengths, kept, T = _run_full(wl, sample_t, seg_steps)
+def _check(wl, sample_b, sample_t, seg_steps, peaked=False, options=None):
+    layer, lengths, kept, T = _run_full(wl, sample_t, seg_steps, options)
     assert layer.poll_error() == 0
     # counters, all rollouts, against the closed forms
     ln, base = layer.counters()
@@ -86,6 +110,8 @@ def _check(wl, sample_b, sample_t, seg_steps):
         for b in sample_b:
             ref = _oracle_out(wl, b, t, int(lengths[b]))
             H.assert_close(got[b], ref, H.BF16_ABS, H.BF16_REL, "%s out b=%d t=%d" % (wl.name, b, t))
+            if peaked and t > 64:
+                _strawmen_fail(wl, b, t, int(lengths[b]), ref, "%s b=%d t=%d" % (wl.name, b, t))
     # sampled ring contents (bit exact) and states
     Kw, Vw = layer.gather_window()
     S = layer.get_state()
@@ -137,6 +163,46 @@ def test_llama8b_full_run_sampled():
     wl = I.WORKLOADS["llama8b"]
     W, C, T = wl.window, wl.chunk, wl.steps
     _check(wl, [3, 255], [W, W + 1, T], seg_steps=512)
+
+
+# The benchmark's input scale leaves the softmax weights uniform to within a per cent, so the cases above check
+# which keys are live and the value sum, but could not tell the attention equation from a plain mean of V.
+# The peaked twins (values of std 0.25, queries 64 times larger: scores about N(0, 4^2)) run the same shapes,
+# plans and kernels -- the non-temporal instantiation, the walk that requests two groups ahead of the counters,
+# the 8-wavefront workgroups of the 3B shape -- with a few keys carrying the attention and the running maximum
+# moving throughout the walk; each sampled comparison also proves its own power (_strawmen_fail).
+def test_qwen7b_peaked_full_run_sampled():
+    wl = I.WORKLOADS["qwen7b_peaked"]
+    W, C, T = wl.window, wl.chunk, wl.steps
+    layer = _check(wl, [0, 77, 127], [W, W + 1, W + C, T], seg_steps=1024, peaked=True)
+    assert layer.plan() == (1, 1, 1)
+
+
+def test_llama8b_peaked_full_run_sampled():
+    wl = I.WORKLOADS["llama8b_peaked"]
+    W, C, T = wl.window, wl.chunk, wl.steps
+    _check(wl, [3, 255], [W, W + 1, W + C, T], seg_steps=512, peaked=True)
+
+
+def test_qwen3b_peaked_full_run_sampled():
+    # one workgroup per CU at most: the plan takes 8 wavefronts per workgroup here
+    wl = I.WORKLOADS["qwen3b_peaked"]
+    W, C, T = wl.window, wl.chunk, wl.steps
+    layer = _check(wl, [0, 37, 63], [33, W, W + 1, W + C, T], seg_steps=1024, peaked=True)
+    assert layer.plan()[0] == 1
+
+
+@pytest.mark.parametrize("waves,splits", [(4, 1), (8, 3)])
+def test_forced_nontemporal_variant_peaked(waves, splits):
+    # The kernel instantiation with non-temporal loads is otherwise chosen only for caches beyond the
+    # memory-side cache; forced here on a cache of a few MB, with peaked attention.  4 wavefronts and one
+    # split over 64 groups is also the walk that requests two groups ahead of the counters.
+    wl = I.WORKLOADS["qwen7b_peaked"].replace(name="nt_peaked", batch=3, n_q_heads=16, n_kv_heads=2, window=2048,
+                                              chunk=100, steps=2048 + 2 * 100 + 17)
+    W, C, T = wl.window, wl.chunk, wl.steps
+    layer = _check(wl, [0, 1, 2], [33, 1000, W, W + 1, W + C + 1, T], seg_steps=1024, peaked=True,
+                   options={ptenc.OPT_NONTEMPORAL: 1, ptenc.OPT_WAVES: waves, ptenc.OPT_SPLITS: splits})
+    assert layer.plan()[:2] == (1, splits)
 
 
 def test_ragged_full_run_sampled():

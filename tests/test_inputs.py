@@ -70,12 +70,20 @@ def test_bench_byte_model_gives_the_workloads_published_totals():
     for name, total_gb in (("qwen3b", 410.7), ("qwen7b", 6547.7), ("llama8b", 104557.0)):
         wl = I.WORKLOADS[name]
         lengths = I.rollout_lengths(wl)
-        ab, act = bench.attention_bytes_per_step(wl, lengths, wl.steps)
-        tot = float(ab.sum()) + bench.prologue_bytes_total(wl, lengths, wl.steps)
+        tot, tokens = bench.path_bytes(wl, lengths, 0, wl.steps)
         assert abs(tot / 1e9 - total_gb) / total_gb < 2e-4, (name, tot / 1e9)
-        assert int(act.sum()) == wl.batch * wl.steps
+        assert tokens == wl.batch * wl.steps
+        # a run priced in pieces adds up to the run priced at once (the last-K-steps window of the benchmark)
+        a, ta = bench.path_bytes(wl, lengths, 0, wl.steps - 20)
+        b, tb = bench.path_bytes(wl, lengths, wl.steps - 20, wl.steps)
+        assert abs(a + b - tot) <= 1e-9 * tot and ta + tb == tokens
         # closed form of the live-token count behind it: t for t <= W, then cycling W - C + 1 .. W
         W, C = wl.window, wl.chunk
         for t in (1, W, W + 1, W + C, W + C + 1, wl.steps):
             expect = t if t <= W else W - C + ((t - W - 1) % C) + 1
             assert bench.n_live_at(t, W, C) == expect
+    # the last 20 steps of the qwen7b run by hand: 128 rollouts, windows of 4077 .. 4096 tokens, no eviction
+    wl = I.WORKLOADS["qwen7b"]
+    got, _ = bench.path_bytes(wl, I.rollout_lengths(wl), wl.steps - 20, wl.steps)
+    per_rollout = sum(2 * 512 * 2 * n for n in range(4077, 4097)) + 20 * (2 * 3584 * 2 + 2 * 512 * 2)
+    assert got == 128 * per_rollout
