@@ -201,15 +201,18 @@ class Bench:
         if self.wl.n_sink:
             self.layer.prefill(self.pk, self.pv, self.prompt_len)
 
-    def launch(self, t0, t1):
-        """Decode steps t0+1 .. t1 (no synchronisation); their inputs must be in the current segment."""
+    def prepared(self, t0, t1):
+        """Decode steps t0+1 .. t1 as a function that only makes the library call (no synchronisation; the
+        arguments are marshalled here, outside any timed region); the inputs must be in the current segment."""
         s0, _, q, k, v, out, active, ids, ro = self.seg
         a, b = t0 - s0, t1 - s0
         if self.compact:
             r0, r1 = int(ro[a]), int(ro[b])
-            self.layer.run_ids(q[r0:r1], k[r0:r1], v[r0:r1], ids[r0:r1], ro[a:b + 1] - r0, out[r0:r1])
-        else:
-            self.layer.run(q[a:b], k[a:b], v[a:b], out[a:b], None if active is None else active[a:b])
+            return self.layer.prepared_run_ids(q[r0:r1], k[r0:r1], v[r0:r1], ids[r0:r1], ro[a:b + 1] - r0, out[r0:r1])
+        return self.layer.prepared_run(q[a:b], k[a:b], v[a:b], out[a:b], None if active is None else active[a:b])
+
+    def launch(self, t0, t1):
+        self.prepared(t0, t1)()
 
     def run_timed(self, t0, t1, seg_steps=0):
         """Steps t0+1 .. t1; returns (GPU ms by HIP events, host ms), summed over the segments the inputs come in."""
@@ -219,7 +222,7 @@ class Bench:
         while a < t1:
             b = min(t1, a + step)
             self._segment_for(a, b)
-            g, w = self.timer(lambda: self.launch(a, b))
+            g, w = self.timer(self.prepared(a, b))
             gpu, wall = gpu + g, wall + w
             a = b
         return gpu, wall
@@ -271,7 +274,7 @@ class Bench:
             best = None
             for _ in range(3):
                 layer.set_counters(ln, zeros)
-                g, _ = self.timer(lambda: self.launch(0, ns))
+                g, _ = self.timer(self.prepared(0, ns))
                 us = g * 1e3 / ns
                 best = us if best is None else min(best, us)
             return best
@@ -377,7 +380,7 @@ def main() -> int:
         hb.start()
     hb._segment_for(T - K, T)
     # the timed region: exactly K steps, synchronised on both sides, HIP events on the launch stream
-    gpu_ms, wall_ms = hb.timer(lambda: hb.launch(T - K, T))
+    gpu_ms, wall_ms = hb.timer(hb.prepared(T - K, T))
     hb.check_counters(T)
     total_ms = max(gpu_ms, wall_ms)
     head = hb.figures(T - K, T, gpu_ms, wall_ms)
@@ -542,22 +545,25 @@ def main() -> int:
             w2 = I.WORKLOADS[name]
             nb2 = w2.steps * w2.batch * (2 * w2.d_q + 2 * w2.d_kv) * w2.elem_bytes
             ob = Bench(w2, args, torch, np, I, ptenc, resident=nb2 <= (40 << 30))
+            # two eviction periods at a full ring: long enough for the shorter steps of these shapes to be timed
+            # as a region of their own, and every rollout evicts twice in it
+            K2 = max(20, 2 * w2.chunk)
             if w2.ragged:
                 # steady state of a ragged batch is not one window size: the K steps right after every ring that
                 # will fill has filled (most rollouts still running), and the whole run
                 t_a = w2.window + 2 * w2.chunk
                 ob.start()
                 ob.launch(0, t_a)
-                g1, w1 = ob.timer(lambda: ob.launch(t_a, t_a + 20))
-                steady = ob.figures(t_a, t_a + 20, g1, w1)
+                g1, w1 = ob.timer(ob.prepared(t_a, t_a + K2))
+                steady = ob.figures(t_a, t_a + K2, g1, w1)
                 steady["window"] = "steps %d..%d of the run (every ring that fills has filled; %d of %d rollouts still running)" % (
-                    t_a + 1, t_a + 20, int((ob.lengths > t_a).sum()), w2.batch)
+                    t_a + 1, t_a + K2, int((ob.lengths > t_a).sum()), w2.batch)
                 ob.start()
                 g, w = ob.run_timed(0, ob.T)
                 ob.check_counters(ob.T)
                 full = ob.figures(0, ob.T, g, w)
             else:
-                steady, full = steady_and_full(ob, 20, Wu, seg_steps)
+                steady, full = steady_and_full(ob, K2, Wu, seg_steps)
             others[name] = {"workload": ob.describe(), "attn_kernel": "mfma" if ob.attn_kernel == 1 else "generic",
                             "window_splits": ob.n_splits, "last_steps": steady, "full_run": full}
             del ob

@@ -472,6 +472,30 @@ class Layer:
         ptenc_decode_run(self.ctx, q, k, v, out, active, q.shape[0])
         return out
 
+    def prepared_run(self, q, k, v, out, active=None):
+        """The same call with its arguments marshalled now: returns a function that only makes the C call
+        (on the stream that is current now), for callers that time the call."""
+        args = (self.ctx, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(active), int(q.shape[0]), _stream())
+        fn, keep = lib().ptenc_decode_run, (q, k, v, out, active)
+
+        def go():
+            _check(fn(*args), "ptenc_decode_run")
+            return keep[3]
+        return go
+
+    def prepared_run_ids(self, q, k, v, ids, row_offsets, out):
+        """ptenc_decode_run_ids with its arguments marshalled now (see prepared_run)."""
+        assert ids.dtype == torch.int32
+        ro = np.ascontiguousarray(row_offsets, dtype=np.int64)
+        args = (self.ctx, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(ids), ro.ctypes.data_as(C.c_void_p), len(ro) - 1,
+                _stream())
+        fn, keep = lib().ptenc_decode_run_ids, (q, k, v, out, ids, ro)
+
+        def go():
+            _check(fn(*args), "ptenc_decode_run_ids")
+            return keep[3]
+        return go
+
     def counters(self):
         return ptenc_get_counters(self.ctx, self.B)
 
