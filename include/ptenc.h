@@ -69,7 +69,8 @@ typedef enum {
   PTENC_ERR_STATE = 2,        /* call order: e.g. evict_encode before set_encoder */
   PTENC_ERR_UNSUPPORTED = 3,
   PTENC_ERR_HIP = 4,
-  PTENC_ERR_NOMEM = 5
+  PTENC_ERR_NOMEM = 5,
+  PTENC_ERR_TOO_LARGE = 6     /* ptenc_decode_step_noalloc: more scratch needed than the built-in block holds */
 } ptenc_status;
 
 typedef enum { PTENC_F32 = 0, PTENC_BF16 = 1 } ptenc_dtype;
@@ -213,6 +214,28 @@ ptenc_status ptenc_evict_encode(ptenc_ctx* ctx, const uint8_t* d_active, void* d
 /* One decode step: evict_encode, cache_append, decode_attn, in this order. */
 ptenc_status ptenc_decode_step(ptenc_ctx* ctx, const void* d_q, const void* d_k, const void* d_v,
                                void* d_out, const uint8_t* d_active, void* stream);
+
+/* ptenc_decode_step for callers that cannot allocate or hand over a scratch block of their own choosing:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same result, but what the step's workgroups hand to each other (the window splits' partial results,
+ * the encoding workgroups' shares of S') goes through a block built into the library -- a fixed array of
+ * PTENC_NOALLOC_SCRATCH_BYTES in device memory, one copy per GPU, held until the process ends --
+ * instead of the d_scratch given to ptenc_create (which is not touched).  The call allocates and
+ * frees nothing and only launches kernels.
+ *   - Limit: with the context's current plan (window splits, encoding workgroups per chunk) the step needs
+ *     B * H_q * n_splits * (d + 2) * 4  +  B * enc_parts * G * r * 4  bytes (each part rounded up to 256);
+ *     beyond PTENC_NOALLOC_SCRATCH_BYTES the call returns PTENC_ERR_TOO_LARGE and does nothing.  (All of the
+ *     benchmark shapes fit: the 7B-shaped layer needs 6 MiB, the 8B-shaped one 8.5 MiB.)
+ *   - The block keeps the last call's contents; nothing in it has to start at zero (every word a launch
+ *     reads from it was written earlier in the same launch), so nothing is cleared.
+ *   - Every context on a GPU shares that GPU's block: calls whose kernels may overlap on one GPU (different
+ *     streams, no ordering between them) race on it.  Calls on one stream, or ordered by events, are safe.
+ *   - The block's address is looked up once per GPU, by the first ptenc_decode_step_noalloc issued with
+ *     that GPU current (the library has no initialisation call); the GPU that `stream` belongs to must be
+ *     the current one during every call.  A failed look-up returns PTENC_ERR_HIP. */
+#define PTENC_NOALLOC_SCRATCH_BYTES (16u << 20)
+ptenc_status ptenc_decode_step_noalloc(ptenc_ctx* ctx, const void* d_q, const void* d_k, const void* d_v,
+                                       void* d_out, const uint8_t* d_active, void* stream);
 
 /* n_steps decode steps from step-major buffers: q and out [n_steps, B, H_q, d], k and v
  * [n_steps, B, H_kv, d], d_active NULL or uint8 [n_steps, B].  Same result as n_steps calls of

@@ -1,14 +1,43 @@
 // Host side of libptenc: argument checks, context bookkeeping, kernel launches.
 #include <math.h>
+#include <mutex>
 #include <new>
 #include <stdlib.h>
 #include <string.h>
 
 #include "ptenc_internal.h"
 
+// The built-in scratch block of ptenc_decode_step_noalloc: what the caller's d_scratch is to ptenc_decode_step
+// (window splits' partial results, encoding workgroups' shares of S'), for callers that cannot provide or
+// allocate one.  Every GPU the library runs on holds its own copy until the process ends.  In host code
+// the array's name is only a handle for hipGetSymbolAddress; kernels get the resolved device address.
+static __device__ __align__(256) unsigned char scratch[PTENC_NOALLOC_SCRATCH_BYTES];
+
 namespace {
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// device address of `scratch` on each GPU, resolved once per device with that device current
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+hipError_t builtin_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
 
 struct StateLayout {
   size_t S, Qa, S0, len, base, len2, base2, n_prompt, err, tick_rollout, tick_slab, tick_enc, WKp, WVp;
@@ -438,6 +467,35 @@ ptenc_status ptenc_decode_step(ptenc_ctx* ctx, const void* d_q, const void* d_k,
   return ptenc_decode_attn(ctx, d_q, d_out, d_active, stream);
 }
 
+// What one step of this context hands between workgroups through the scratch block, with the plan in use:
+// the window splits' partial results, then the encoding workgroups' shares of S'.
+static size_t step_scratch_bytes(const ptenc_ctx* x, size_t* enc_off) {
+  const ptenc_config& c = x->cfg;
+  const size_t part = align256((size_t)c.batch * c.n_q_heads * x->dev.n_splits * (c.head_dim + 2) * sizeof(float));
+  const size_t enc = align256((size_t)c.batch * x->dev.enc_parts * c.n_global * c.rank * sizeof(float));
+  if (enc_off) *enc_off = part;
+  return part + enc;
+}
+
+ptenc_status ptenc_decode_step_noalloc(ptenc_ctx* ctx, const void* d_q, const void* d_k, const void* d_v, void* d_out,
+                                       const uint8_t* d_active, void* stream) {
+  if (!ctx || !d_q || !d_k || !d_v || !d_out) return PTENC_ERR_INVALID_ARG;
+  if (!ctx->encoder_set) return PTENC_ERR_STATE;
+  size_t enc_off = 0;
+  if (step_scratch_bytes(ctx, &enc_off) > (size_t)PTENC_NOALLOC_SCRATCH_BYTES) return PTENC_ERR_TOO_LARGE;
+  void* sp = nullptr;
+  if (builtin_scratch(&sp) != hipSuccess) return PTENC_ERR_HIP;
+  // the same step on the built-in block: the kernels take the block's address as they take the caller's
+  float* const partial0 = ctx->dev.partial;
+  float* const enc0 = ctx->dev.enc_part;
+  ctx->dev.partial = (float*)sp;
+  ctx->dev.enc_part = (float*)((char*)sp + enc_off);
+  const ptenc_status st = ptenc_decode_step(ctx, d_q, d_k, d_v, d_out, d_active, stream);
+  ctx->dev.partial = partial0;
+  ctx->dev.enc_part = enc0;
+  return st;
+}
+
 ptenc_status ptenc_decode_step_ids(ptenc_ctx* ctx, const void* d_q, const void* d_k, const void* d_v, void* d_out,
                                    const int32_t* d_ids, int32_t n, void* stream) {
   if (!ctx || n < 0 || n > ctx->cfg.batch) return PTENC_ERR_INVALID_ARG;
@@ -630,6 +688,7 @@ const char* ptenc_status_string(ptenc_status s) {
     case PTENC_ERR_UNSUPPORTED: return "unsupported configuration";
     case PTENC_ERR_HIP: return "HIP runtime error";
     case PTENC_ERR_NOMEM: return "out of host memory";
+    case PTENC_ERR_TOO_LARGE: return "the configuration needs more scratch than the built-in block holds";
   }
   return "unknown status";
 }

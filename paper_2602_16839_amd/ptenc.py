@@ -16,7 +16,8 @@ import torch
 _PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG_DIR, "libptenc.so")
 
-OK, ERR_INVALID_ARG, ERR_STATE, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM = range(6)
+OK, ERR_INVALID_ARG, ERR_STATE, ERR_UNSUPPORTED, ERR_HIP, ERR_NOMEM, ERR_TOO_LARGE = range(7)
+NOALLOC_SCRATCH_BYTES = 16 << 20
 F32, BF16 = 0, 1
 NORM_FROBENIUS, NORM_ROW_L2, NORM_NONE = 0, 1, 2
 DEVERR_APPEND_FULL, DEVERR_ATTEND_EMPTY, DEVERR_BAD_ID = 1, 2, 4
@@ -36,6 +37,7 @@ EXPORTS = [
     "ptenc_get_scores", "ptenc_set_scores", "ptenc_get_victims", "ptenc_prefill_ids",
     "ptenc_stack_query_sizes", "ptenc_stack_create", "ptenc_stack_destroy", "ptenc_stack_layer",
     "ptenc_stack_reset", "ptenc_stack_decode_step", "ptenc_stack_graph_capture", "ptenc_stack_graph_launch",
+    "ptenc_decode_step_noalloc",
 ]
 
 
@@ -78,6 +80,7 @@ def lib() -> C.CDLL:
             "ptenc_decode_attn": [vp, vp, vp, vp, vp],
             "ptenc_evict_encode": [vp, vp, vp, vp],
             "ptenc_decode_step": [vp, vp, vp, vp, vp, vp, vp],
+            "ptenc_decode_step_noalloc": [vp, vp, vp, vp, vp, vp, vp],
             "ptenc_decode_run": [vp, vp, vp, vp, vp, vp, i64, vp],
             "ptenc_get_counters": [vp, vp, vp, vp],
             "ptenc_set_counters": [vp, vp, vp, vp],
@@ -207,6 +210,11 @@ def ptenc_evict_encode(ctx, active=None, dbg_chunk=None):
 def ptenc_decode_step(ctx, q, k, v, out, active=None):
     _check(lib().ptenc_decode_step(ctx, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(active), _stream()),
            "ptenc_decode_step")
+
+
+def ptenc_decode_step_noalloc(ctx, q, k, v, out, active=None):
+    _check(lib().ptenc_decode_step_noalloc(ctx, _ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(active), _stream()),
+           "ptenc_decode_step_noalloc")
 
 
 def ptenc_decode_run(ctx, q, k, v, out, active, n_steps: int):
@@ -448,6 +456,11 @@ class Layer:
         if out is None:
             out = torch.empty_like(q)
         ptenc_decode_step(self.ctx, q, k, v, out, active)
+        return out
+
+    def step_noalloc(self, q, k, v, out, active=None):
+        """One decode step through the library's built-in scratch block; `out` is the caller's (nothing is allocated)."""
+        ptenc_decode_step_noalloc(self.ctx, q, k, v, out, active)
         return out
 
     def step_ids(self, q, k, v, ids, out=None):
