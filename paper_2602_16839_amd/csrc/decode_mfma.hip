@@ -26,15 +26,15 @@
 // (a counter, no waiting), in split order, so the result does not depend on the arrival order.
 //
 // Eviction.  The encoder sums over the concatenated KV heads, so a rollout's chunk is folded into S by
-// workgroups that read all heads (encode_rollout: K_a = K_e W^a_K and V_a = V_e W^a_V with MFMA,
-// then S' = (Q_a K_a^T) V_a and the update of S in fp32).  Launches that may evict carry such
-// workgroups behind the attention workgroups in the grid: c.enc_parts per row, each with a contiguous
-// range of the chunk's 32-token groups; where nothing is full they leave at once.  They share
-// nothing with the rollout's attention workgroups, which already walk the window without the chunk
-// and take the new token from the step's inputs, so an eviction lengthens nobody's walk (rollouts
-// of a running batch do not evict in the same step).  The parts' shares of S' meet in memory; the
-// last part to arrive adds them in part order, updates S and, the chunk's oldest slot being free
-// now that every part has read its range, stores the new token there.
+// workgroups that read all heads (encode_groups: K_a = K_e W^a_K and V_a = V_e W^a_V with MFMA, then
+// S' = (Q_a K_a^T) V_a; encode_rollout_finish: the update of S in fp32).  A chunk may be shared by c.enc_parts
+// workgroups, each with a contiguous range of its 32-token groups; their shares of S' meet in memory and the
+// last part to arrive adds them in part order, updates S and, the chunk's oldest slot being free now that
+// every part has read its range, stores the new token there.  The rollout's attention never depends on any
+// of this: it walks the window without the chunk and takes the new token from the step's inputs.  Who does
+// the encoding depends on whether the launch fills the chip (see the launcher): encoding workgroups of their
+// own behind the attention workgroups in the grid (encoder_role), which start at once where CUs are free; or
+// the row's own workgroups before they walk (encode_part), where every CU is taken.
 //
 // Counters are double-buffered: a step reads (len, base) from one pair of arrays and writes the
 // other, so no workgroup has to wait for the rest of its rollout before the step can end.  A compact
@@ -387,6 +387,8 @@ struct StepArgs {
   const int* ids;          // null, or the rollouts this launch works on: row j of q/k/v/out is rollout ids[j]
   int do_evict, do_append, do_attend;
   int in_place;            // counters written in place by the rollout's last workgroup (graph replay)
+  int enc_inline;          // who folds an evicted chunk into S: 1 the row's own workgroups before their walk, 0 encoding
+                           // workgroups of their own behind the attention workgroups in the grid (see the launcher)
   int carry;               // compact list with two counter buffers: one extra workgroup carries every
                            // rollout's counters over to the buffer this step writes (see the kernel)
 };
@@ -585,49 +587,73 @@ __device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b,
   }
 }
 
-// Returns whether this workgroup is the one that went on to update S (with one part per chunk: always;
-// otherwise the last part to arrive, which adds the parts' shares in part order, so that the sum does
-// not depend on who arrived when).
+// This workgroup's part of the chunk: its share of S' into LDS.  Ends with a barrier.
 template <int WAVES>
-__device__ inline bool encode_rollout(const PtDev& c, StepSmem<WAVES>& sm, int& sm_ticket, int b, int s0, int part) {
-  constexpr int THREADS = WAVES * 64;
+__device__ inline void encode_rollout_groups(const PtDev& c, StepSmem<WAVES>& sm, int b, int s0, int part) {
   const int wave = threadIdx.x >> 6;
   if (wave >= 4) encode_groups<WAVES, 2>(c, sm, b, s0, part);
   else if (wave & 2) encode_groups<WAVES, 1>(c, sm, b, s0, part);
   else encode_groups<WAVES, 0>(c, sm, b, s0, part);
   __syncthreads();
+}
+
+// The parts' shares meet, S is updated.  Returns whether this workgroup is the one that updated S (with
+// one part per chunk: always; otherwise the last part to arrive, which adds the parts' shares in part
+// order, so that the sum does not depend on who arrived when).
+// `on_the_way` is called once this workgroup's stores have been acknowledged, before the ticket is drawn: what
+// the caller requests there travels while the ticket does.
+template <int WAVES, typename F>
+__device__ inline bool encode_rollout_finish(const PtDev& c, StepSmem<WAVES>& sm, int& sm_ticket, int b, int part,
+                                             F on_the_way) {
+  constexpr int THREADS = WAVES * 64, NX = 4096 / THREADS;
   float* stage = &sm.enc.tail.Ka[0][0];
   const int gr = c.G * c.r;
   float sacc[16];
   if (c.enc_parts == 1) {
 #pragma unroll
-    for (int x = 0; x < 4096 / THREADS; ++x) {
+    for (int x = 0; x < NX; ++x) {
       const int idx = threadIdx.x + THREADS * x;
       sacc[x] = idx < gr ? stage[idx] : 0.f;
     }
-  } else {
-    // park this part's share (device-scope stores, as for the window splits); the last part to arrive
-    // adds all of them
-    float* mine = c.enc_part + ((size_t)b * c.enc_parts + part) * gr;
-    for (int idx = threadIdx.x; idx < gr; idx += THREADS) st_agent1(mine + idx, stage[idx]);
-    wait_own_stores();
+    on_the_way();
     __syncthreads();
-    if (threadIdx.x == 0) sm_ticket = atomicAdd(c.tick_enc + b, 1);
-    __syncthreads();
-    if (sm_ticket != c.enc_parts - 1) return false;
-    if (threadIdx.x == 0) c.tick_enc[b] = 0;
-    const float* all = c.enc_part + (size_t)b * c.enc_parts * gr;
+    pt_state_update<THREADS>(c, b, sacc, stage, sm.enc.tail.red);
+    return true;
+  }
+  // park this part's share (device-scope stores, as for the window splits); the last part to arrive
+  // adds all of them.  Nobody else touches S[b] in this launch, so its old value is fetched now, while
+  // the stores and the ticket are on their way, whoever turns out to need it.
+  float* mine = c.enc_part + ((size_t)b * c.enc_parts + part) * gr;
+  for (int idx = threadIdx.x; idx < gr; idx += THREADS) st_agent1(mine + idx, stage[idx]);
+  float sprev[NX];
 #pragma unroll
-    for (int x = 0; x < 4096 / THREADS; ++x) {
-      const int idx = threadIdx.x + THREADS * x;
-      float v = 0.f;
-      if (idx < gr)
-        for (int p = 0; p < c.enc_parts; ++p) v += ld_agent1(all + (size_t)p * gr + idx);
-      sacc[x] = v;
-    }
+  for (int x = 0; x < NX; ++x) {
+    const int idx = threadIdx.x + THREADS * x;
+    sprev[x] = idx < gr ? c.S[(size_t)b * gr + idx] : 0.f;
+  }
+  wait_own_stores();
+  on_the_way();
+  __syncthreads();
+  if (threadIdx.x == 0) sm_ticket = atomicAdd(c.tick_enc + b, 1);
+  __syncthreads();
+  if (sm_ticket != c.enc_parts - 1) return false;
+  if (threadIdx.x == 0) c.tick_enc[b] = 0;
+  const float* all = c.enc_part + (size_t)b * c.enc_parts * gr;
+#pragma unroll
+  for (int x = 0; x < NX; ++x) {
+    const int idx = threadIdx.x + THREADS * x;
+    // every part's value requested before the first is added (in part order)
+    float t[PT_MAX_ENC_PARTS];
+#pragma unroll
+    for (int p = 0; p < PT_MAX_ENC_PARTS; ++p)
+      t[p] = (idx < gr && p < c.enc_parts) ? ld_agent1(all + (size_t)p * gr + idx) : 0.f;
+    float v = 0.f;
+#pragma unroll
+    for (int p = 0; p < PT_MAX_ENC_PARTS; ++p) v += t[p];
+    sacc[x] = v + sprev[x];
   }
   __syncthreads();
-  pt_state_update<THREADS>(c, b, sacc, stage, sm.enc.tail.red);
+  pt_state_update<THREADS, false>(c, b, sacc, stage, sm.enc.tail.red);
   return true;
 }
 
@@ -680,8 +706,55 @@ __device__ inline void arrive_rollout(const PtDev& c, const StepArgs& a, StepSme
   }
 }
 
-// An encoding workgroup (launches that may evict have c.enc_parts per row, after the attention
-// workgroups in the grid): if the rollout's ring is full, the row's encoding workgroups fold the oldest
+// A rollout whose ring is full has its oldest chunk folded into S by its own workgroups BEFORE they walk the
+// window: workgroup number `part` (< c.enc_parts) of the row takes that part of the chunk's groups.  The walk
+// skips the chunk and takes the new token from the step's inputs, so it depends on nothing done here; a
+// workgroup that starts its walk a few microseconds late shares the memory system with the others all the
+// same and ends with them (while encoding workgroups of their own, queued behind the attention workgroups
+// in the grid, got a CU only when the first attention workgroups left, and ran their chain of dependent
+// memory accesses against a saturated memory system: the tail of every step of a running batch).  The last
+// part to finish updates S and, the chunk's oldest slot being free at last, stores the step's new token
+// there.  Ends with the workgroup's LDS free for the walk.
+template <int WAVES, bool MASS, typename F>
+__device__ inline void encode_part(const PtDev& c, const StepArgs& a, StepSmem<WAVES>& sm, int& sm_ticket, int b,
+                                   int j_row, int s0e, int part, const StepPlan& pl, long long len0, F on_the_way) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, kgrp = lane >> 4;
+  encode_rollout_groups<WAVES>(c, sm, b, s0e, part);
+  if (encode_rollout_finish<WAVES>(c, sm, sm_ticket, b, part, on_the_way)) {
+    if (a.dbg_chunk) {
+      const int dkv = c.Hkv * 128;
+      uint16_t* dK = a.dbg_chunk + (size_t)b * 2 * c.C * dkv;
+      uint16_t* dV = dK + (size_t)c.C * dkv;
+      for (int idx = tid; idx < c.C * dkv; idx += WAVES * 64) {
+        const int j = idx / dkv, hi = idx - j * dkv, h = hi >> 7, i = hi & 127;
+        const uint16_t* src = (const uint16_t*)c.cache + (size_t)(b * c.Hkv + h) * pt_slab_elems(c.W, 128);
+        int slot = s0e + j; if (slot >= c.Wr) slot -= c.Wr;
+        slot += c.n_sink;
+        dK[idx] = src[pt_k_off(1, c.W, 128, slot, i)];
+        dV[idx] = src[pt_v_off(1, c.W, 128, slot, i)];
+      }
+    }
+    __syncthreads();   // every read of the chunk is done: its oldest slot may take the new token
+    if (pl.appending) {
+      int s0 = s0e + c.C;
+      if (s0 >= c.Wr) s0 -= c.Wr;
+      int s_new = s0 + (int)(len0 - pl.base1);
+      if (s_new >= c.Wr) s_new -= c.Wr;
+      for (int h = wave; h < c.Hkv; h += WAVES) {
+        Op kp[4];
+        uint32_t vp[4];
+        load_newest(kp, vp, a.knew, a.vnew, ((size_t)j_row * c.Hkv + h) * 128, n, kgrp);
+        store_newest((uint16_t*)c.cache + (size_t)(b * c.Hkv + h) * pt_slab_elems(c.W, 128), c.W, c.n_sink + s_new, kp, vp,
+                     n, kgrp);
+      }
+    }
+    if (tid == 0 && !pl.will_select) c.selected[b] = 0;   // the chosen chunk has left
+  }
+  __syncthreads();     // the encoder's LDS is the walk's merge buffer
+}
+
+// An encoding workgroup of its own (launches that leave CUs free, see the kernel: c.enc_parts per row, after the
+// attention workgroups in the grid): if the rollout's ring is full, the row's encoding workgroups fold the oldest
 // chunk into S and then, the chunk's oldest slot being free at last, the one that finished the job
 // stores the step's new token there.  The rollout's attention workgroups meanwhile walk the window
 // without the chunk and take the new token from the step's inputs; nobody waits for anybody.
@@ -709,7 +782,8 @@ __device__ inline void encoder_role(const PtDev& c, const StepArgs& a, StepSmem<
   if (!pl.evicting && part != 0) return;
   if (pl.evicting) {
     const int s0e = (int)(base0 % c.Wr);
-    if (!encode_rollout<WAVES>(c, sm, sm_ticket, b, s0e, part)) return;
+    encode_rollout_groups<WAVES>(c, sm, b, s0e, part);
+    if (!encode_rollout_finish<WAVES>(c, sm, sm_ticket, b, part, []() {})) return;
     if (a.dbg_chunk) {
       const int dkv = c.Hkv * 128;
       uint16_t* dK = a.dbg_chunk + (size_t)b * 2 * c.C * dkv;
@@ -767,11 +841,11 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
   // row j of the launch (and of q / k / v / out) is rollout b: j itself, or ids[j] for a compact list
   const int j_row = blockIdx.x / n_kv_heads, hkv = blockIdx.x - j_row * n_kv_heads, split = blockIdx.y;
   if (__builtin_expect(j_row >= n_rows, 0)) {
-    // beyond the attention workgroups: every row's encoding workgroups if the launch may evict, then ...
+    // beyond the rows' workgroups: every row's encoding workgroups, if the launch carries them, then ...
     if (split != 0) return;
     const int extra = blockIdx.x - n_rows * n_kv_heads;
     if constexpr (ENC) {
-      if (extra < n_rows * c.enc_parts) {
+      if (!a.enc_inline && extra < n_rows * c.enc_parts) {
         encoder_role<WAVES, MASS>(c, a, sm, sm_ticket, dyn_lds, extra, ids, active, len_cur, base_cur);
         return;
       }
@@ -878,8 +952,21 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
   const int pg_new = gs + (s_new >> 5);
   const bool owner = (pg_new % stride) / kWaves == split;
 
-  // (an evicting rollout's chunk is folded into S, and its new token stored, by the row's encoding
-  // workgroups: see encoder_role)
+  // an evicting rollout's chunk is folded into S first, by the row's own workgroups (see encode_part).  The
+  // two groups requested ahead of the counters are requested again afterwards, whatever this launch's
+  // setting (clamped into the slab: what the walk does not want it drops): redefined on this path, their
+  // registers are free during the encoding instead of being carried across it.
+  if constexpr (ENC) {
+    const int part = hkv + n_kv_heads * split;
+    if (a.enc_inline && evicting && part < c.enc_parts) {
+      // (the first one while the parts' shares meet, once this part's own stores need no more waiting for:
+      // it travels while the ticket does; both groups would not fit the registers next to the hand-over's own)
+      encode_part<WAVES, MASS>(c, a, sm, sm_ticket, b, j_row, s0e, part, pl, len0, [&]() {
+        load_group<NT>(fa, (const u32x4*)slab_p + (size_t)min(pg_first, NGt - 1) * (PT_GROUP_ELEMS / 8), lane);
+      });
+      load_group<NT>(fb, (const u32x4*)slab_p + (size_t)min(pg_first + stride, NGt - 1) * (PT_GROUP_ELEMS / 8), lane);
+    }
+  }
   if (owner && appending && !evicting && !a.do_attend && wave == 0) {
     // append without attention: straight from the inputs (with attention the store happens after
     // the walk, from the registers that also patch the last group)
@@ -1158,7 +1245,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
   }
 
   // ---- arrival count of the rollout's workgroups, where the step needs one ----
-  arrive_rollout<WAVES, MASS>(c, a, sm, sm_ticket, dyn_lds, b, pl, c.Hkv * ns + (a.do_evict ? 1 : 0));
+  arrive_rollout<WAVES, MASS>(c, a, sm, sm_ticket, dyn_lds, b, pl, c.Hkv * ns + ((a.do_evict && !a.enc_inline) ? 1 : 0));
 }
 
 // W^a (row-major [H_kv*128, r]) -> MFMA B operands: [head][k-chunk c][column tile rt][lane][8],
@@ -1199,8 +1286,19 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bo
   PtDev cc = c;
   if (!do_attend) cc.n_splits = 1;
   const int rows = ids ? n_rows : cc.B;
-  // attention workgroups, then the encoding workgroups of every row if the launch may evict, then the carrier
-  dim3 grid(rows * cc.Hkv + (do_evict ? rows * cc.enc_parts : 0) + (a.carry ? 1 : 0), cc.n_splits);
+  // Who encodes an evicted chunk.  A launch of at most one workgroup per CU leaves CUs free: encoding workgroups
+  // of their own, behind the attention workgroups in the grid, start at once and run beside the walks (folded into
+  // the row's own workgroups the encoding would lengthen the step by its whole duration: +36 % per step
+  // at the 3B shape with evictions in every step).  A launch that fills the chip has no place for them until
+  // the first attention workgroups leave, and what they then do against a saturated memory system is the
+  // tail of the step (+5 % at the 7B shape): there the row's own workgroups fold the chunk before they walk.
+  a.enc_inline = (long)rows * cc.Hkv * cc.n_splits > 256 ? 1 : 0;
+  if (a.enc_inline) {
+    cc.enc_parts = cc.enc_parts_inline;
+    if (cc.enc_parts > cc.Hkv * cc.n_splits) cc.enc_parts = cc.Hkv * cc.n_splits;
+  }
+  // one workgroup per (row, KV head, split), then the encoding workgroups if they are on their own, then the carrier
+  dim3 grid(rows * cc.Hkv + ((do_evict && !a.enc_inline) ? rows * cc.enc_parts : 0) + (a.carry ? 1 : 0), cc.n_splits);
   // scores are maintained by whole steps only (append + attention) under the scored policy
   const bool mass = cc.scored && do_append && do_attend;
   // long walks request two groups ahead of the counters, short ones one (see the kernel)

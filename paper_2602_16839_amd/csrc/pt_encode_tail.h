@@ -81,7 +81,8 @@ __device__ inline float pt_block_sum(float v, float* red) {
 }
 
 // S[b] <- Normalize(S[b] + S'), S' in sacc.  `stage` is G*r floats of LDS (row-norm mode only).
-template <int THREADS>
+// ADD_S = false: the caller has added S[b] to sacc already (it fetched S while it waited for something else).
+template <int THREADS, bool ADD_S = true>
 __device__ inline void pt_state_update(const PtDev& c, int b, float sacc[16], float* stage, float* red) {
   const int t = threadIdx.x, n = c.G * c.r;
   float* S = c.S + (size_t)b * n;
@@ -90,7 +91,7 @@ __device__ inline void pt_state_update(const PtDev& c, int b, float sacc[16], fl
   for (int x = 0; x < 4096 / THREADS; ++x) {
     const int idx = t + THREADS * x;
     if (idx < n) {
-      sacc[x] += S[idx];
+      if (ADD_S) sacc[x] += S[idx];
       ss = fmaf(sacc[x], sacc[x], ss);
       if (c.norm_mode == PTENC_NORM_ROW_L2) stage[idx] = sacc[x];
     }

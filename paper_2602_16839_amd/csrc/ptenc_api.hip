@@ -96,12 +96,15 @@ size_t partial_bytes(const ptenc_config& c) {
   return align256((size_t)c.batch * c.n_q_heads * PTENC_MAX_SPLITS * (c.head_dim + 2) * sizeof(float));
 }
 
-// A chunk is encoded by several workgroups, each a contiguous range of its 32-token groups: about two
-// groups each is where the step time stopped improving when the rollouts' evictions fall on different
-// steps (one workgroup takes about 4.5 us per group, more while the attention of the other rollouts
-// keeps the memory system busy, and it starts only when the first attention workgroups have left)
-int enc_parts_for(const ptenc_config& c) {
-  const int e = c.chunk / 64;
+// A chunk is encoded by several workgroups, each a contiguous range of its 32-token groups (one workgroup takes
+// about 4.5 us per group; every further part costs a hand-over through memory).  Encoding workgroups of their
+// own (launches that leave CUs free) take about two groups each.  Where the row's own workgroups encode before
+// they walk, a part delays one walk by its whole duration, and what the delay costs the step depends on how
+// much earlier than the step's last workgroup that walk would have ended: measured at the 7B shape with the
+// evictions of a running batch spread over the steps, per chunk size the best count was one part per four
+// groups (C = 128: 1 part +0.4 % per step, 2 parts +2.2 %; C = 512: 1, 2, 4 parts +8.7, +4.8, +2.2 %).
+int enc_parts_for(const ptenc_config& c, bool inline_mode) {
+  const int e = c.chunk / (inline_mode ? 128 : 64);
   return e < 1 ? 1 : (e > PT_MAX_ENC_PARTS ? PT_MAX_ENC_PARTS : e);
 }
 size_t enc_part_bytes(const ptenc_config& c) {
@@ -153,7 +156,8 @@ void replan(ptenc_ctx* x) {
   x->dev.scored = (x->opt_policy == PTENC_POLICY_SCORED && x->attn_kernel == 1) ? 1 : 0;
   x->dev.n_recent = resolved_recent(x);
   x->encode_kernel = x->attn_kernel;
-  x->dev.enc_parts = x->opt_enc_parts > 0 ? x->opt_enc_parts : enc_parts_for(x->cfg);
+  x->dev.enc_parts = x->opt_enc_parts > 0 ? x->opt_enc_parts : enc_parts_for(x->cfg, false);
+  x->dev.enc_parts_inline = x->opt_enc_parts > 0 ? x->opt_enc_parts : enc_parts_for(x->cfg, true);
   x->dev.n_splits = x->opt_splits > 0 ? x->opt_splits : heuristic_splits(x, x->cfg.batch);
   x->waves = pick_waves(x, x->cfg.batch, x->dev.n_splits);
   // a cache that fits the 256 MiB memory-side cache is better served by ordinary loads

@@ -38,7 +38,9 @@ struct PtDev {
   int* tick_rollout;  // [B]      arrival counters, zero between kernels
   int* tick_slab;     // [B*H_kv]
   int* tick_enc;      // [B]      (the parts of a long chunk's encoding)
-  int enc_parts;      // workgroups that share one rollout's chunk (1 unless the chunk is long)
+  int enc_parts;      // workgroups that share one rollout's chunk (1 unless the chunk is long): encoding workgroups
+                      //   of their own
+  int enc_parts_inline; // the same where the row's own workgroups encode before they walk (capped by their number)
   float* enc_part;    // [B][enc_parts][G*r] their partial S', in the scratch buffer after `partial`
   void* WKp;          // W^a_K, W^a_V repacked as MFMA B operands: [H_kv][4][4][64 lanes][8] bf16
   void* WVp;

@@ -34,7 +34,20 @@ def row_errors(got: np.ndarray, ref: np.ndarray):
 # guard of about four times the observed maximum, where one is on record for the case, catches a kernel
 # that drifts towards the bar long before it crosses it.  Keys: the `what` prefix a full-size test uses.
 # (max abs, max row-relative); measured values are listed in the design notes.
-GUARDS = {}
+GUARDS = {
+    # full-size cases (tests/test_gpu_full_size.py): observed maxima are listed in the design notes.  Output
+    # errors are dominated by the bf16 rounding of the output itself (half an ulp = 2^-9 of the value) and of
+    # the probabilities, so the observed row-relative error sits at 4-5e-3 whatever the shape: its guard is
+    # 3 x that (4 x would be the contract bar); the absolute guards are 4 x the observed maxima.
+    "qwen3b out": (1.0e-3, 1.5e-2), "qwen7b out": (1.1e-3, 1.5e-2), "llama8b out": (4.0e-5, 1.5e-2),
+    "ragged out": (3.0e-4, 1.5e-2), "qwen7b_sink out": (3.0e-4, 1.5e-2),
+    "qwen3b_peaked out": (8.0e-3, 1.5e-2), "qwen7b_peaked out": (8.0e-3, 1.5e-2),
+    "llama8b_peaked out": (8.0e-3, 1.5e-2), "nt_peaked out": (8.0e-3, 1.5e-2),
+    # the state: fp32 accumulation of exactly representable products, observed <= 1.1e-7 abs / 1.6e-6 row-rel
+    "qwen3b S": (4e-7, 6e-6), "qwen7b S": (4e-7, 6e-6), "llama8b S": (4e-7, 6e-6), "ragged S": (4e-7, 6e-6),
+    "qwen7b_sink S": (4e-7, 6e-6), "qwen3b_peaked S": (4e-7, 6e-6), "qwen7b_peaked S": (4e-7, 6e-6),
+    "llama8b_peaked S": (4e-7, 6e-6), "nt_peaked S": (4e-7, 6e-6),
+}
 
 # every comparison made through assert_close, for the record of observed errors: {what: (abs, rel)} maxima
 OBSERVED = {}
