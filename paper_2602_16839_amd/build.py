@@ -57,6 +57,51 @@ def build(verbose: bool = True) -> str:
     return LIB_PATH
 
 
+SAN_LIB_PATH = os.path.join(OBJ_DIR, "libptenc_hostsan.so")
+SAN_SOURCES = ("ptenc_api.hip", "stack_api.hip")
+SAN_FLAGS = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+             "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+
+
+def sanitizer_runtime() -> str:
+    """The AddressSanitizer runtime of the compiler that builds the library (to be preloaded into a host
+    program that was not built with it, such as the Python interpreter)."""
+    res = subprocess.run([hipcc_path().replace("hipcc", "amdclang++"), "-print-file-name=libclang_rt.asan-x86_64.so"],
+                         stdout=subprocess.PIPE, text=True)
+    path = res.stdout.strip()
+    if not os.path.isabs(path) or not os.path.exists(path):
+        raise RuntimeError("AddressSanitizer runtime not found")
+    return os.path.realpath(path)
+
+
+def build_host_sanitized(verbose: bool = False) -> str:
+    """The same library with its HOST code (argument checks, context bookkeeping, launch glue) built with
+    AddressSanitizer and UndefinedBehaviorSanitizer; device code is built as always.  For host-only tests:
+    it is kept beside the objects, never next to the real library, and nothing loads it by default
+    (PTENC_LIB selects it)."""
+    from concurrent.futures import ThreadPoolExecutor
+    san_dir = os.path.join(OBJ_DIR, "hostsan")
+    os.makedirs(san_dir, exist_ok=True)
+    # the host glue is in these two sources; the others hold kernels and their one-line launchers, and their
+    # objects are taken from the ordinary build
+    objs, cmds = [], []
+    for s in SOURCES:
+        if s in SAN_SOURCES:
+            o = os.path.join(san_dir, s.replace(".hip", ".o"))
+            cmds.append([hipcc_path()] + HIPCC_FLAGS + SAN_FLAGS + EXTRA_FLAGS.get(s, []) + ["-c", os.path.join(CSRC, s), "-o", o])
+        else:
+            o = os.path.join(OBJ_DIR, s.replace(".hip", ".o"))
+            if not os.path.exists(o):
+                raise RuntimeError("%s is missing: run build() first" % o)
+        objs.append(o)
+    with ThreadPoolExecutor(max_workers=min(8, len(cmds))) as pool:
+        list(pool.map(lambda c: _run(c, verbose), cmds))
+    _run([hipcc_path(), "--offload-arch=gfx950", "-shared", "-fPIC", "-Xarch_host", "-fsanitize=address",
+          "-Xarch_host", "-fsanitize=undefined", "-shared-libsan"] + objs + ["-o", SAN_LIB_PATH + ".tmp"], verbose)
+    os.replace(SAN_LIB_PATH + ".tmp", SAN_LIB_PATH)
+    return SAN_LIB_PATH
+
+
 C_SMOKE_SRC = os.path.join(ROOT, "tests", "c_abi", "abi_smoke.c")
 C_SMOKE_BIN = os.path.join(ROOT, "tests", "c_abi", "abi_smoke")
 

@@ -59,14 +59,16 @@ _LIB = None
 
 
 def lib() -> C.CDLL:
-    """Loads libptenc.so (built by ``paper_2602_16839_amd.build``); raises if it is not there."""
+    """Loads libptenc.so (built by ``paper_2602_16839_amd.build``); raises if it is not there.
+    PTENC_LIB names another build of the same library (the host-sanitized one of the host-only tests)."""
     global _LIB
     if _LIB is None:
-        if not os.path.exists(LIB_PATH):
+        path = os.environ.get("PTENC_LIB") or LIB_PATH
+        if not os.path.exists(path):
             raise FileNotFoundError(
                 "%s is missing: build it with `python -m paper_2602_16839_amd.build`; there is no fallback path"
-                % LIB_PATH)
-        L = C.CDLL(LIB_PATH)
+                % path)
+        L = C.CDLL(path)
         vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
         P = C.POINTER
         sig = {

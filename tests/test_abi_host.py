@@ -178,6 +178,7 @@ def test_tiled_layout_matches_its_documented_formula():
 def test_missing_library_fails_loudly(monkeypatch):
     # no CPU fallback: without the shared library the binding raises instead of computing anything
     monkeypatch.setattr(ptenc, "_LIB", None)
+    monkeypatch.delenv("PTENC_LIB", raising=False)
     monkeypatch.setattr(ptenc, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libptenc.so"))
     with pytest.raises(FileNotFoundError):
         ptenc.lib()
