@@ -149,6 +149,8 @@ class Bench:
             layer.set_option(ptenc.OPT_SPLITS, args.splits)
         if args.encode_parts:
             layer.set_option(ptenc.OPT_ENCODE_PARTS, args.encode_parts)
+        if args.encode_inline >= 0:
+            layer.set_option(ptenc.OPT_ENCODE_INLINE, args.encode_inline)
         if args.policy == "scored":
             layer.set_option(ptenc.OPT_RECENT, args.recent)
             layer.set_option(ptenc.OPT_EVICT_POLICY, ptenc.POLICY_SCORED)
@@ -317,6 +319,9 @@ def main() -> int:
     ap.add_argument("--splits", type=int, default=0)
     ap.add_argument("--encode-parts", type=int, default=0,
                     help="workgroups that share one evicted chunk's encoding (0 = the library's heuristic)")
+    ap.add_argument("--encode-inline", type=int, default=-1, choices=[-1, 0, 1],
+                    help="who folds evicted chunks into the state: 0 encoding workgroups of their own, 1 the rollouts' own "
+                         "workgroups ahead of time, -1 the library's choice by launch size")
     ap.add_argument("--chunk", type=int, default=0,
                     help="override the workload's eviction chunk C (eviction-ratio sweeps; 0 = the workload's own)")
     ap.add_argument("--ragged-mode", choices=["compact", "masked"], default="compact",

@@ -99,10 +99,18 @@ typedef enum {
                                  a reset (scores are kept only while it is PTENC_POLICY_SCORED). */
   PTENC_OPT_RECENT = 6,       /* scored policy: the n most recent ring entries are never taken; 0 .. W - n_sink - C;
                                  -1 = default (half the ring, at most W - n_sink - C) */
-  PTENC_OPT_ENCODE_PARTS = 7  /* MFMA path: workgroups that share the encoding of one rollout's evicted chunk, each
+  PTENC_OPT_ENCODE_PARTS = 7, /* MFMA path: workgroups that share the encoding of one rollout's evicted chunk, each
                                  a contiguous range of its 32-token groups, their shares of S' added in range
                                  order; 1..8; 0 = heuristic (one per 64 tokens of the chunk, at most 8).  S
                                  depends on it in the last bits only (fp32 summation order). */
+  PTENC_OPT_ENCODE_INLINE = 8 /* MFMA path: who folds evicted chunks into S.  0: encoding workgroups of their own,
+                                 launched behind the attention workgroups, fold the whole chunk in the evicting
+                                 step (right where the launch leaves CUs free).  1: the rollout's own workgroups
+                                 do it before they walk the window -- under the sliding window one 32-token group
+                                 at a time, ahead of time, spread over the steps that refill the ring, so that the
+                                 evicting step only adds what is pending (right where the launch fills the
+                                 chip).  -1 = heuristic by launch size (default).  S depends on it in the last
+                                 bits only. */
 } ptenc_option;
 
 /* Which tokens leave when the sliding part of the cache is full.

@@ -43,7 +43,8 @@ __global__ void reset_kernel(PtDev c, const uint8_t* __restrict__ mask, int clea
   for (int h = threadIdx.x; h < c.Hkv; h += blockDim.x) c.tick_slab[b * c.Hkv + h] = 0;
   if (mask && !mask[b]) return;
   const int n = c.G * c.r;
-  for (int i = threadIdx.x; i < n; i += blockDim.x) c.S[(size_t)b * n + i] = c.S0[i];
+  for (int i = threadIdx.x; i < n; i += blockDim.x) { c.S[(size_t)b * n + i] = c.S0[i]; c.pend[(size_t)b * n + i] = 0.f; }
+  if (threadIdx.x == 0) c.enc_done[b] = 0;            // nothing of a next chunk is folded ahead of time
   // both counter buffers: a compact-list step merges into the other one by maximum
   if (threadIdx.x == 0) { c.len[b] = 0; c.base[b] = 0; c.len_nx[b] = 0; c.base_nx[b] = 0; c.n_prompt[b] = 0; }
   // importance scores: nothing waits to be folded, no eviction has happened

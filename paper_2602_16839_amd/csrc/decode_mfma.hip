@@ -297,7 +297,7 @@ __device__ inline long long ld_scalar(const long long* p) {
 }
 
 // What a step must know before its first K/V load: the rollout's counters, its number of question
-// tokens and its mask byte.  All four are fetched together (scalar loads, one wait), so the step
+// tokens, its mask byte and how much of its next chunk is folded already.  All five are fetched together (scalar loads, one wait), so the step
 // pays one round trip to memory for them instead of one per dependent load; the mask byte comes
 // as the aligned dword that holds it (an aligned dword shares its page with every byte in it).
 // Issued by hand like ld_scalar above: the counters may be rewritten in place later in the launch.
@@ -305,7 +305,7 @@ __device__ inline long long ld_scalar(const long long* p) {
 // The same wait also covers one dword of every 64-byte line of the kernel's argument block
 // (TOUCH): the arguments the compiler fetches later, in several dependent batches, then come from
 // the scalar cache instead of costing a round trip each.  The touched values are discarded.
-struct StepHead { long long len, base; int n_prompt; uint32_t mask_word; };
+struct StepHead { long long len, base; int n_prompt; uint32_t mask_word; int enc_done; };
 typedef const void* KernargPtr;   // generic pointer to the argument block
 
 // offset of the k-th touched dword inside an argument block of ARG_BYTES bytes
@@ -314,41 +314,43 @@ typedef const void* KernargPtr;   // generic pointer to the argument block
   "i"(PT_TOUCH_OFF(0)), "i"(PT_TOUCH_OFF(1)), "i"(PT_TOUCH_OFF(2)), "i"(PT_TOUCH_OFF(3)), "i"(PT_TOUCH_OFF(4)), \
   "i"(PT_TOUCH_OFF(5)), "i"(PT_TOUCH_OFF(6)), "i"(PT_TOUCH_OFF(7))
 
-// TOUCH: with the argument-block lines (a launch over all rollouts); else the four values only
+// TOUCH: with the argument-block lines (a launch over all rollouts); else the five values only
 template <int ARG_BYTES, bool TOUCH>
 __device__ inline StepHead load_step_head(const long long* len_p, const long long* base_p, const int* n_prompt_p,
-                                          const uint32_t* mask_word_p, KernargPtr ka) {
+                                          const uint32_t* mask_word_p, const int* enc_done_p, KernargPtr ka) {
   static_assert(ARG_BYTES >= 4 && ARG_BYTES <= 8 * 64, "argument block larger than the lines touched");
   StepHead h;
   if (TOUCH) {
     int t0, t1, t2, t3, t4, t5, t6, t7;
     asm volatile(
-        "s_load_dwordx2 %0, %12, 0x0\n\t"
-        "s_load_dwordx2 %1, %13, 0x0\n\t"
-        "s_load_dword %2, %14, 0x0\n\t"
-        "s_load_dword %3, %15, 0x0\n\t"
-        "s_load_dword %4, %16, %17\n\t"
-        "s_load_dword %5, %16, %18\n\t"
-        "s_load_dword %6, %16, %19\n\t"
-        "s_load_dword %7, %16, %20\n\t"
-        "s_load_dword %8, %16, %21\n\t"
-        "s_load_dword %9, %16, %22\n\t"
-        "s_load_dword %10, %16, %23\n\t"
-        "s_load_dword %11, %16, %24\n\t"
+        "s_load_dwordx2 %0, %13, 0x0\n\t"
+        "s_load_dwordx2 %1, %14, 0x0\n\t"
+        "s_load_dword %2, %15, 0x0\n\t"
+        "s_load_dword %3, %16, 0x0\n\t"
+        "s_load_dword %4, %17, 0x0\n\t"
+        "s_load_dword %5, %18, %19\n\t"
+        "s_load_dword %6, %18, %20\n\t"
+        "s_load_dword %7, %18, %21\n\t"
+        "s_load_dword %8, %18, %22\n\t"
+        "s_load_dword %9, %18, %23\n\t"
+        "s_load_dword %10, %18, %24\n\t"
+        "s_load_dword %11, %18, %25\n\t"
+        "s_load_dword %12, %18, %26\n\t"
         "s_waitcnt lgkmcnt(0)"
-        : "=&s"(h.len), "=&s"(h.base), "=&s"(h.n_prompt), "=&s"(h.mask_word), "=&s"(t0), "=&s"(t1), "=&s"(t2),
-          "=&s"(t3), "=&s"(t4), "=&s"(t5), "=&s"(t6), "=&s"(t7)
-        : "s"(len_p), "s"(base_p), "s"(n_prompt_p), "s"(mask_word_p), "s"(ka), PT_TOUCH_OFFSETS
+        : "=&s"(h.len), "=&s"(h.base), "=&s"(h.n_prompt), "=&s"(h.mask_word), "=&s"(h.enc_done), "=&s"(t0), "=&s"(t1),
+          "=&s"(t2), "=&s"(t3), "=&s"(t4), "=&s"(t5), "=&s"(t6), "=&s"(t7)
+        : "s"(len_p), "s"(base_p), "s"(n_prompt_p), "s"(mask_word_p), "s"(enc_done_p), "s"(ka), PT_TOUCH_OFFSETS
         : "memory");
   } else {
     asm volatile(
-        "s_load_dwordx2 %0, %4, 0x0\n\t"
-        "s_load_dwordx2 %1, %5, 0x0\n\t"
-        "s_load_dword %2, %6, 0x0\n\t"
-        "s_load_dword %3, %7, 0x0\n\t"
+        "s_load_dwordx2 %0, %5, 0x0\n\t"
+        "s_load_dwordx2 %1, %6, 0x0\n\t"
+        "s_load_dword %2, %7, 0x0\n\t"
+        "s_load_dword %3, %8, 0x0\n\t"
+        "s_load_dword %4, %9, 0x0\n\t"
         "s_waitcnt lgkmcnt(0)"
-        : "=&s"(h.len), "=&s"(h.base), "=&s"(h.n_prompt), "=&s"(h.mask_word)
-        : "s"(len_p), "s"(base_p), "s"(n_prompt_p), "s"(mask_word_p)
+        : "=&s"(h.len), "=&s"(h.base), "=&s"(h.n_prompt), "=&s"(h.mask_word), "=&s"(h.enc_done)
+        : "s"(len_p), "s"(base_p), "s"(n_prompt_p), "s"(mask_word_p), "s"(enc_done_p)
         : "memory");
   }
   return h;
@@ -427,16 +429,16 @@ union StepSmem {
 // the barriers).  One instance per role, so that each keeps its own operand buffer in registers; every
 // instance passes the same barriers.
 //
-// A chunk is shared by c.enc_parts workgroups: this one (`part`) takes a contiguous range of the
-// groups and leaves its share of S' (in LDS, row-major G x r).
+// The caller names a contiguous range [v_lo, v_hi) of the chunk's groups (0 = the group that holds the chunk's
+// oldest token; see pt_chunk_groups); their contribution to S' is left in LDS, row-major G x r.
+__device__ inline int pt_chunk_groups(const PtDev& c, int s0) { return ((s0 & 31) + c.C + PT_GROUP_TOKENS - 1) >> 5; }
+
 template <int WAVES, int ROLE>
-__device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b, int s0, int part) {
+__device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b, int s0, int v_lo, int v_hi) {
   constexpr int NP = ROLE == 0 ? 4 : 8;          // 16-byte pieces per lane, KV head and group
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 15, kgrp = lane >> 4;
   const int g0 = s0 >> 5, off0 = s0 & 31, NG = c.Wr >> 5, gs = c.n_sink >> 5;
-  const int n_vis = (off0 + c.C + PT_GROUP_TOKENS - 1) >> 5;
-  const int v_lo = part * n_vis / c.enc_parts, v_hi = (part + 1) * n_vis / c.enc_parts;
   const int t = wave & 1;
   const size_t slab_u = pt_slab_elems(c.W, 128) / 8;                 // a slab in 16-byte units
   const u32x4* cache0 = (const u32x4*)c.cache + (size_t)b * c.Hkv * slab_u;
@@ -587,57 +589,78 @@ __device__ inline void encode_groups(const PtDev& c, StepSmem<WAVES>& sm, int b,
   }
 }
 
-// This workgroup's part of the chunk: its share of S' into LDS.  Ends with a barrier.
+// Groups [v_lo, v_hi) of the chunk: their contribution to S' into LDS.  Ends with a barrier.
 template <int WAVES>
-__device__ inline void encode_rollout_groups(const PtDev& c, StepSmem<WAVES>& sm, int b, int s0, int part) {
+__device__ inline void encode_rollout_groups(const PtDev& c, StepSmem<WAVES>& sm, int b, int s0, int v_lo, int v_hi) {
   const int wave = threadIdx.x >> 6;
-  if (wave >= 4) encode_groups<WAVES, 2>(c, sm, b, s0, part);
-  else if (wave & 2) encode_groups<WAVES, 1>(c, sm, b, s0, part);
-  else encode_groups<WAVES, 0>(c, sm, b, s0, part);
+  if (wave >= 4) encode_groups<WAVES, 2>(c, sm, b, s0, v_lo, v_hi);
+  else if (wave & 2) encode_groups<WAVES, 1>(c, sm, b, s0, v_lo, v_hi);
+  else encode_groups<WAVES, 0>(c, sm, b, s0, v_lo, v_hi);
   __syncthreads();
 }
 
-// The parts' shares meet, S is updated.  Returns whether this workgroup is the one that updated S (with
+// Groups of the chunk a rollout will evict NEXT, folded ahead of time: their contribution is added to the
+// rollout's pending block (c.pend), which the eviction adds to S' (encode_rollout_finish).  Only one
+// workgroup per rollout does this, one group or so every few steps (see the kernel), so the sum is the same
+// whatever the launch looks like.  Ends with a barrier.
+template <int WAVES>
+__device__ inline void encode_ahead(const PtDev& c, StepSmem<WAVES>& sm, int b, int s0, int v_lo, int v_hi) {
+  constexpr int THREADS = WAVES * 64;
+  encode_rollout_groups<WAVES>(c, sm, b, s0, v_lo, v_hi);
+  const float* stage = &sm.enc.tail.Ka[0][0];
+  const int gr = c.G * c.r;
+  float* pend = c.pend + (size_t)b * gr;
+  for (int idx = threadIdx.x; idx < gr; idx += THREADS) pend[idx] += stage[idx];
+  if (threadIdx.x == 0) c.enc_done[b] = v_hi;
+  __syncthreads();
+}
+
+// The parts' shares meet, S is updated: S <- Normalize(S + (shares in part order + what was folded ahead of
+// time)).  Returns whether this workgroup is the one that updated S (with
 // one part per chunk: always; otherwise the last part to arrive, which adds the parts' shares in part
 // order, so that the sum does not depend on who arrived when).
 // `on_the_way` is called once this workgroup's stores have been acknowledged, before the ticket is drawn: what
 // the caller requests there travels while the ticket does.
 template <int WAVES, typename F>
 __device__ inline bool encode_rollout_finish(const PtDev& c, StepSmem<WAVES>& sm, int& sm_ticket, int b, int part,
-                                             F on_the_way) {
+                                             int n_parts, F on_the_way) {
   constexpr int THREADS = WAVES * 64, NX = 4096 / THREADS;
   float* stage = &sm.enc.tail.Ka[0][0];
   const int gr = c.G * c.r;
+  float* pend = c.pend + (size_t)b * gr;
   float sacc[16];
-  if (c.enc_parts == 1) {
+  if (n_parts == 1) {
 #pragma unroll
     for (int x = 0; x < NX; ++x) {
       const int idx = threadIdx.x + THREADS * x;
-      sacc[x] = idx < gr ? stage[idx] : 0.f;
+      sacc[x] = idx < gr ? stage[idx] + pend[idx] : 0.f;
+      if (idx < gr) pend[idx] = 0.f;
     }
+    if (threadIdx.x == 0) c.enc_done[b] = 0;
     on_the_way();
     __syncthreads();
     pt_state_update<THREADS>(c, b, sacc, stage, sm.enc.tail.red);
     return true;
   }
   // park this part's share (device-scope stores, as for the window splits); the last part to arrive
-  // adds all of them.  Nobody else touches S[b] in this launch, so its old value is fetched now, while
-  // the stores and the ticket are on their way, whoever turns out to need it.
+  // adds all of them.  Nobody else touches S[b] or the pending block in this launch, so their old values are
+  // fetched now, while the stores and the ticket are on their way, whoever turns out to need them.
   float* mine = c.enc_part + ((size_t)b * c.enc_parts + part) * gr;
   for (int idx = threadIdx.x; idx < gr; idx += THREADS) st_agent1(mine + idx, stage[idx]);
-  float sprev[NX];
+  float sprev[NX], spend[NX];
 #pragma unroll
   for (int x = 0; x < NX; ++x) {
     const int idx = threadIdx.x + THREADS * x;
     sprev[x] = idx < gr ? c.S[(size_t)b * gr + idx] : 0.f;
+    spend[x] = idx < gr ? pend[idx] : 0.f;
   }
   wait_own_stores();
   on_the_way();
   __syncthreads();
   if (threadIdx.x == 0) sm_ticket = atomicAdd(c.tick_enc + b, 1);
   __syncthreads();
-  if (sm_ticket != c.enc_parts - 1) return false;
-  if (threadIdx.x == 0) c.tick_enc[b] = 0;
+  if (sm_ticket != n_parts - 1) return false;
+  if (threadIdx.x == 0) { c.tick_enc[b] = 0; c.enc_done[b] = 0; }
   const float* all = c.enc_part + (size_t)b * c.enc_parts * gr;
 #pragma unroll
   for (int x = 0; x < NX; ++x) {
@@ -646,11 +669,12 @@ __device__ inline bool encode_rollout_finish(const PtDev& c, StepSmem<WAVES>& sm
     float t[PT_MAX_ENC_PARTS];
 #pragma unroll
     for (int p = 0; p < PT_MAX_ENC_PARTS; ++p)
-      t[p] = (idx < gr && p < c.enc_parts) ? ld_agent1(all + (size_t)p * gr + idx) : 0.f;
+      t[p] = (idx < gr && p < n_parts) ? ld_agent1(all + (size_t)p * gr + idx) : 0.f;
     float v = 0.f;
 #pragma unroll
     for (int p = 0; p < PT_MAX_ENC_PARTS; ++p) v += t[p];
-    sacc[x] = v + sprev[x];
+    sacc[x] = (v + spend[x]) + sprev[x];
+    if (idx < gr) pend[idx] = 0.f;
   }
   __syncthreads();
   pt_state_update<THREADS, false>(c, b, sacc, stage, sm.enc.tail.red);
@@ -717,10 +741,11 @@ __device__ inline void arrive_rollout(const PtDev& c, const StepArgs& a, StepSme
 // there.  Ends with the workgroup's LDS free for the walk.
 template <int WAVES, bool MASS, typename F>
 __device__ inline void encode_part(const PtDev& c, const StepArgs& a, StepSmem<WAVES>& sm, int& sm_ticket, int b,
-                                   int j_row, int s0e, int part, const StepPlan& pl, long long len0, F on_the_way) {
+                                   int j_row, int s0e, int part, int n_parts, int v_lo, int v_hi, const StepPlan& pl,
+                                   long long len0, F on_the_way) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, n = lane & 15, kgrp = lane >> 4;
-  encode_rollout_groups<WAVES>(c, sm, b, s0e, part);
-  if (encode_rollout_finish<WAVES>(c, sm, sm_ticket, b, part, on_the_way)) {
+  encode_rollout_groups<WAVES>(c, sm, b, s0e, v_lo, v_hi);
+  if (encode_rollout_finish<WAVES>(c, sm, sm_ticket, b, part, n_parts, on_the_way)) {
     if (a.dbg_chunk) {
       const int dkv = c.Hkv * 128;
       uint16_t* dK = a.dbg_chunk + (size_t)b * 2 * c.C * dkv;
@@ -774,7 +799,7 @@ __device__ inline void encoder_role(const PtDev& c, const StepArgs& a, StepSmem<
   // counters and mask in one round trip (where nothing is full this workgroup should be gone at once)
   const uintptr_t mask_addr = (uintptr_t)(active + b);
   const uint32_t* mask_word_p = active ? (const uint32_t*)(mask_addr & ~(uintptr_t)3) : (const uint32_t*)(c.n_prompt + b);
-  const StepHead head = load_step_head<8, false>(len_cur + b, base_cur + b, c.n_prompt + b, mask_word_p, nullptr);
+  const StepHead head = load_step_head<8, false>(len_cur + b, base_cur + b, c.n_prompt + b, mask_word_p, c.enc_done + b, nullptr);
   const bool act = !active || ((head.mask_word >> (8 * (int)(mask_addr & 3))) & 0xffu) != 0;
   const long long len0 = head.len, base0 = head.base;
   if (len0 < base0) return;
@@ -782,8 +807,11 @@ __device__ inline void encoder_role(const PtDev& c, const StepArgs& a, StepSmem<
   if (!pl.evicting && part != 0) return;
   if (pl.evicting) {
     const int s0e = (int)(base0 % c.Wr);
-    encode_rollout_groups<WAVES>(c, sm, b, s0e, part);
-    if (!encode_rollout_finish<WAVES>(c, sm, sm_ticket, b, part, []() {})) return;
+    // what has not been folded ahead of time (every part reads the same count: the one that resets it is
+    // the last to draw its ticket)
+    const int n_vis = pt_chunk_groups(c, s0e), done = MASS ? 0 : min(max(head.enc_done, 0), n_vis), rest = n_vis - done;
+    encode_rollout_groups<WAVES>(c, sm, b, s0e, done + part * rest / c.enc_parts, done + (part + 1) * rest / c.enc_parts);
+    if (!encode_rollout_finish<WAVES>(c, sm, sm_ticket, b, part, c.enc_parts, []() {})) return;
     if (a.dbg_chunk) {
       const int dkv = c.Hkv * 128;
       uint16_t* dK = a.dbg_chunk + (size_t)b * 2 * c.C * dkv;
@@ -816,9 +844,11 @@ __device__ inline void encoder_role(const PtDev& c, const StepArgs& a, StepSmem<
   arrive_rollout<WAVES, MASS>(c, a, sm, sm_ticket, dyn_lds, b, pl, c.Hkv * c.n_splits + 1);
 }
 
-// ENC: launches that may evict (they carry the encoding workgroups); the variant without them is
-// leaner and is what the steps run while no ring can be full yet.
-template <bool NT, int WAVES, bool MASS, bool ENC>
+// ENC: 0 = launches that cannot evict (what the steps run while no ring can be nearly full yet: leaner);
+// 1 = may evict, encoding workgroups of their own behind the attention workgroups; 2 = may evict, the rows'
+// own workgroups encode before they walk.  (One instantiation per way of encoding, so that neither carries
+// the other's code and registers.)
+template <bool NT, int WAVES, bool MASS, int ENC>
 __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
     // what the walk cannot start without comes first, as plain scalars: the build asks for these
     // leading arguments to be preloaded into registers at wavefront launch, so the counters and the
@@ -844,8 +874,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
     // beyond the rows' workgroups: every row's encoding workgroups, if the launch carries them, then ...
     if (split != 0) return;
     const int extra = blockIdx.x - n_rows * n_kv_heads;
-    if constexpr (ENC) {
-      if (!a.enc_inline && extra < n_rows * c.enc_parts) {
+    if constexpr (ENC == 1) {
+      if (extra < n_rows * c.enc_parts) {
         encoder_role<WAVES, MASS>(c, a, sm, sm_ticket, dyn_lds, extra, ids, active, len_cur, base_cur);
         return;
       }
@@ -895,8 +925,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
   const uintptr_t mask_addr = (uintptr_t)(active + b);
   const uint32_t* mask_word_p = active ? (const uint32_t*)(mask_addr & ~(uintptr_t)3) : (const uint32_t*)(n_prompt + b);
   // (the scalar loads of the counters wait for themselves only: the K/V requests above stay in flight)
-  const StepHead head = ids ? load_step_head<kArgBytes, false>(len_cur + b, base_cur + b, n_prompt + b, mask_word_p, ka)
-                            : load_step_head<kArgBytes, true>(len_cur + b, base_cur + b, n_prompt + b, mask_word_p, ka);
+  const StepHead head = ids ? load_step_head<kArgBytes, false>(len_cur + b, base_cur + b, n_prompt + b, mask_word_p, c.enc_done + b, ka)
+                            : load_step_head<kArgBytes, true>(len_cur + b, base_cur + b, n_prompt + b, mask_word_p, c.enc_done + b, ka);
 
   const int n = lane & 15, kgrp = lane >> 4;
   const int g = c.group;
@@ -952,19 +982,60 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
   const int pg_new = gs + (s_new >> 5);
   const bool owner = (pg_new % stride) / kWaves == split;
 
-  // an evicting rollout's chunk is folded into S first, by the row's own workgroups (see encode_part).  The
-  // two groups requested ahead of the counters are requested again afterwards, whatever this launch's
+  // Where the row's own workgroups encode (a launch that fills the chip), they do it before they walk.
+  //   Sliding window: the chunk a rollout evicts next is known as soon as the previous one has left (its oldest
+  //   C tokens), so it is folded AHEAD OF TIME, a group at a time, spread evenly over the C steps that refill
+  //   the ring, into the rollout's pending block (encode_ahead), by the workgroup of KV head 0: a walk that
+  //   starts a few microseconds late, once in a while.  The evicting step then only adds the pending block to
+  //   S; what is not folded yet (counters set by the host, steps taken through other entry points) it folds
+  //   first.  A whole chunk in the evicting step made the evicting rollout's walks late by the chunk's whole
+  //   duration: with the evictions of a running batch spread over the steps, +3.5 % per step at a quarter-window chunk.
+  //   Scored policy: the victims are known only when the ring is full, so the evicting step folds all of them,
+  //   shared by c.enc_parts of the row's workgroups.
+  // The groups requested ahead of the counters are requested again afterwards, whatever this launch's
   // setting (clamped into the slab: what the walk does not want it drops): redefined on this path, their
   // registers are free during the encoding instead of being carried across it.
-  if constexpr (ENC) {
-    const int part = hkv + n_kv_heads * split;
-    if (a.enc_inline && evicting && part < c.enc_parts) {
-      // (the first one while the parts' shares meet, once this part's own stores need no more waiting for:
-      // it travels while the ticket does; both groups would not fit the registers next to the hand-over's own)
-      encode_part<WAVES, MASS>(c, a, sm, sm_ticket, b, j_row, s0e, part, pl, len0, [&]() {
-        load_group<NT>(fa, (const u32x4*)slab_p + (size_t)min(pg_first, NGt - 1) * (PT_GROUP_ELEMS / 8), lane);
-      });
-      load_group<NT>(fb, (const u32x4*)slab_p + (size_t)min(pg_first + stride, NGt - 1) * (PT_GROUP_ELEMS / 8), lane);
+  if constexpr (ENC == 2) {
+    {
+      int part = -1, n_parts = 1, v_lo = 0, v_hi = 0;
+      bool ahead_of_time = false;
+      if constexpr (MASS) {
+        const int p = hkv + n_kv_heads * split;
+        if (evicting && p < c.enc_parts) {
+          const int n_vis = pt_chunk_groups(c, s0e);
+          part = p; n_parts = c.enc_parts;
+          v_lo = p * n_vis / n_parts; v_hi = (p + 1) * n_vis / n_parts;
+        }
+      } else if (hkv == 0 && split == 0) {
+        const int n_vis = pt_chunk_groups(c, s0e), done = min(max(head.enc_done, 0), n_vis);
+        if (evicting) {
+          part = 0; v_lo = done; v_hi = n_vis;
+        } else if (appending) {
+          // after this step's append the ring holds Wr - C + j tokens: by then j / C of the next chunk's groups
+          // are to be folded (all of them when the ring is full)
+          const int j = n_live - (c.Wr - c.C);
+          int target = j >= 1 ? (int)min((long long)n_vis, (long long)j * n_vis / c.C) : 0;
+          // ... but only groups whose tokens are all in the cache already: this step's own token is not yet
+          // (a chunk as long as the ring reaches up to the newest token)
+          const long long have = len0 - base0;             // tokens of the ring before this step
+          const int present = have >= c.C ? n_vis : (int)((have + (s0e & 31)) >> 5);
+          target = min(target, present);
+          if (done < target) { part = 0; v_lo = done; v_hi = target; ahead_of_time = true; }
+        }
+      }
+      if (part >= 0) {
+        if (ahead_of_time) {
+          encode_ahead<WAVES>(c, sm, b, s0e, v_lo, v_hi);
+          load_group<NT>(fa, (const u32x4*)slab_p + (size_t)min(pg_first, NGt - 1) * (PT_GROUP_ELEMS / 8), lane);
+        } else {
+          // (the first group while the parts' shares meet, once this part's own stores need no more waiting
+          // for: it travels while the ticket does; both groups would not fit the registers next to the hand-over's own)
+          encode_part<WAVES, MASS>(c, a, sm, sm_ticket, b, j_row, s0e, part, n_parts, v_lo, v_hi, pl, len0, [&]() {
+            load_group<NT>(fa, (const u32x4*)slab_p + (size_t)min(pg_first, NGt - 1) * (PT_GROUP_ELEMS / 8), lane);
+          });
+        }
+        load_group<NT>(fb, (const u32x4*)slab_p + (size_t)min(pg_first + stride, NGt - 1) * (PT_GROUP_ELEMS / 8), lane);
+      }
     }
   }
   if (owner && appending && !evicting && !a.do_attend && wave == 0) {
@@ -1292,8 +1363,12 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bo
   // at the 3B shape with evictions in every step).  A launch that fills the chip has no place for them until
   // the first attention workgroups leave, and what they then do against a saturated memory system is the
   // tail of the step (+5 % at the 7B shape): there the row's own workgroups fold the chunk before they walk.
-  a.enc_inline = (long)rows * cc.Hkv * cc.n_splits > 256 ? 1 : 0;
+  // (8-wavefront workgroups sit one per CU, 4-wavefront ones two: 256 or 512 places; a launch within a few dozen
+  // of all of them still leaves encoding workgroups nowhere to start at once)
+  const long places = waves == 8 ? 256 : 448;
+  a.enc_inline = cc.enc_inline_opt >= 0 ? cc.enc_inline_opt : ((long)rows * cc.Hkv * cc.n_splits > places ? 1 : 0);
   if (a.enc_inline) {
+    // (scored policy only: the sliding window folds its chunks ahead of time, one workgroup per rollout)
     cc.enc_parts = cc.enc_parts_inline;
     if (cc.enc_parts > cc.Hkv * cc.n_splits) cc.enc_parts = cc.Hkv * cc.n_splits;
   }
@@ -1319,8 +1394,12 @@ hipError_t pt_launch_decode_mfma(const PtDev& c, bool nontemporal, int waves, bo
                      (unsigned)cc.Hkv | ((unsigned)cc.n_splits << 8) | (ahead << 14) |                       \
                          ((unsigned)(cc.W / PT_GROUP_TOKENS) << 16),                                                   \
                      cc, a)
-#define PT_STEP_PICK_ENC(NT_, WAVES_, MASS_) \
-  do { if (do_evict) PT_STEP_LAUNCH(NT_, WAVES_, MASS_, true); else PT_STEP_LAUNCH(NT_, WAVES_, MASS_, false); } while (0)
+#define PT_STEP_PICK_ENC(NT_, WAVES_, MASS_)                                  \
+  do {                                                                       \
+    if (!do_evict) PT_STEP_LAUNCH(NT_, WAVES_, MASS_, 0);                    \
+    else if (a.enc_inline) PT_STEP_LAUNCH(NT_, WAVES_, MASS_, 2);            \
+    else PT_STEP_LAUNCH(NT_, WAVES_, MASS_, 1);                              \
+  } while (0)
 #define PT_STEP_PICK_MASS(NT_, WAVES_) \
   do { if (mass) PT_STEP_PICK_ENC(NT_, WAVES_, true); else PT_STEP_PICK_ENC(NT_, WAVES_, false); } while (0)
   if (waves == 8) {

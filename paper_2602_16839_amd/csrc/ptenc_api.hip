@@ -41,7 +41,8 @@ hipError_t builtin_scratch(void** out) {
 
 struct StateLayout {
   size_t S, Qa, S0, len, base, len2, base2, n_prompt, err, tick_rollout, tick_slab, tick_enc, WKp, WVp;
-  size_t mass, pos, victims, qprev, mlprev, mtag, selected, total;   // importance-based eviction
+  size_t mass, pos, victims, qprev, mlprev, mtag, selected;   // importance-based eviction
+  size_t pend, enc_done, total;
 };
 
 StateLayout state_layout(const ptenc_config& c) {
@@ -71,6 +72,8 @@ StateLayout state_layout(const ptenc_config& c) {
   L.mlprev = off;  off = align256(off + 2 * rows * 2 * sizeof(float));
   L.mtag = off;    off = align256(off + slabs * sizeof(long long));
   L.selected = off; off = align256(off + (size_t)c.batch * sizeof(int));
+  L.pend = off;     off = align256(off + gr * c.batch);
+  L.enc_done = off; off = align256(off + (size_t)c.batch * sizeof(int));
   L.total = off;
   return L;
 }
@@ -158,6 +161,7 @@ void replan(ptenc_ctx* x) {
   x->encode_kernel = x->attn_kernel;
   x->dev.enc_parts = x->opt_enc_parts > 0 ? x->opt_enc_parts : enc_parts_for(x->cfg, false);
   x->dev.enc_parts_inline = x->opt_enc_parts > 0 ? x->opt_enc_parts : enc_parts_for(x->cfg, true);
+  x->dev.enc_inline_opt = x->opt_enc_inline;
   x->dev.n_splits = x->opt_splits > 0 ? x->opt_splits : heuristic_splits(x, x->cfg.batch);
   x->waves = pick_waves(x, x->cfg.batch, x->dev.n_splits);
   // a cache that fits the 256 MiB memory-side cache is better served by ordinary loads
@@ -182,7 +186,9 @@ inline ptenc_status hip_status(hipError_t e) { return e == hipSuccess ? PTENC_OK
 // steps are launched without them and without the eviction logic; should the bound ever be wrong, the
 // append on the full ring sets PTENC_DEVERR_APPEND_FULL instead of going unnoticed.  Steps that may be
 // replayed from a graph (counters in place) always carry them.
-bool may_evict(const ptenc_ctx* x) { return x->opt_in_place != 0 || x->dev.live_ub >= x->dev.Wr; }
+// (A ring that is within a chunk of full already has groups of its next chunk folded ahead of time by the
+// steps that fill it, which is part of the same machinery.)
+bool may_evict(const ptenc_ctx* x) { return x->opt_in_place != 0 || x->dev.live_ub >= x->dev.Wr - x->dev.C; }
 void appended_one(ptenc_ctx* x) { if (x->dev.live_ub < x->dev.Wr) ++x->dev.live_ub; }
 
 // Scored policy: a decode step chooses the next victims itself when its append fills a ring.  A ring
@@ -236,6 +242,7 @@ ptenc_status ptenc_create(const ptenc_config* cfg, void* d_cache, void* d_state,
   if (x->cfg.norm_eps == 0.f) x->cfg.norm_eps = 1e-12f;
   ptenc_query_sizes(cfg, &x->cache_bytes, &x->state_bytes, &x->scratch_bytes);
   x->opt_nontemporal = -1;
+  x->opt_enc_inline = -1;
   const StateLayout L = state_layout(*cfg);
   char* sp = (char*)d_state;
   PtDev& d = x->dev;
@@ -266,6 +273,7 @@ ptenc_status ptenc_create(const ptenc_config* cfg, void* d_cache, void* d_state,
   d.qprev = (uint16_t*)(sp + L.qprev); d.mlprev = (float*)(sp + L.mlprev);
   d.mtag = (long long*)(sp + L.mtag);
   d.selected = (int*)(sp + L.selected);
+  d.pend = (float*)(sp + L.pend); d.enc_done = (int*)(sp + L.enc_done);
   x->select_stale = 1;
   x->opt_recent = -1;
   x->dev.live_ub = d.Wr;       // nothing is known about the counters the state block holds
@@ -294,6 +302,10 @@ ptenc_status ptenc_set_option(ptenc_ctx* ctx, int32_t option, int32_t value) {
     case PTENC_OPT_ENCODE_PARTS:
       if (value < 0 || value > PT_MAX_ENC_PARTS) return PTENC_ERR_INVALID_ARG;
       ctx->opt_enc_parts = value;
+      break;
+    case PTENC_OPT_ENCODE_INLINE:
+      if (value < -1 || value > 1) return PTENC_ERR_INVALID_ARG;
+      ctx->opt_enc_inline = value;
       break;
     case PTENC_OPT_WAVES:
       if (value != 0 && value != 4 && value != 8) return PTENC_ERR_INVALID_ARG;
@@ -602,6 +614,10 @@ ptenc_status ptenc_set_counters(ptenc_ctx* ctx, const int64_t* h_len, const int6
     if (hipMemsetAsync(ctx->dev.selected, 0, sizeof(int) * ctx->cfg.batch, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
     ctx->select_stale = 1;
   }
+  // whatever was folded ahead of time belongs to the old counters' next chunk
+  if (hipMemsetAsync(ctx->dev.enc_done, 0, sizeof(int) * ctx->cfg.batch, S(stream)) != hipSuccess) return PTENC_ERR_HIP;
+  if (hipMemsetAsync(ctx->dev.pend, 0, sizeof(float) * ctx->cfg.batch * ctx->cfg.n_global * ctx->cfg.rank, S(stream)) != hipSuccess)
+    return PTENC_ERR_HIP;
   ctx->dev.live_ub = 0;
   for (int b = 0; b < ctx->cfg.batch; ++b)
     if (h_len[b] - h_base[b] > ctx->dev.live_ub) ctx->dev.live_ub = h_len[b] - h_base[b];

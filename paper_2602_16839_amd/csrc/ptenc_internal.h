@@ -41,7 +41,11 @@ struct PtDev {
   int enc_parts;      // workgroups that share one rollout's chunk (1 unless the chunk is long): encoding workgroups
                       //   of their own
   int enc_parts_inline; // the same where the row's own workgroups encode before they walk (capped by their number)
+  int enc_inline_opt;   // -1: the launch decides by its size who encodes; 0 / 1: forced (PTENC_OPT_ENCODE_INLINE)
   float* enc_part;    // [B][enc_parts][G*r] their partial S', in the scratch buffer after `partial`
+  float* pend;        // [B][G*r] what has been folded ahead of time of the chunk the rollout evicts next (the
+                      //   sliding window's next chunk is known C steps before it leaves); added to S' by the eviction
+  int* enc_done;      // [B] how many of that chunk's 32-token groups `pend` holds (0 after every eviction)
   void* WKp;          // W^a_K, W^a_V repacked as MFMA B operands: [H_kv][4][4][64 lanes][8] bf16
   void* WVp;
   // importance-based eviction (MFMA path only)
@@ -71,6 +75,7 @@ struct ptenc_ctx {
   int nontemporal;       // resolved
   int opt_waves;         // 0 = heuristic, 4, 8
   int opt_enc_parts;     // 0 = heuristic, 1..PT_MAX_ENC_PARTS
+  int opt_enc_inline;    // -1 = heuristic, 0, 1
   int opt_in_place;      // 1 = counters are updated in place (no buffer rotation on the host)
   int opt_policy;        // 0 sliding window, 1 scored
   int opt_recent;        // -1 = default

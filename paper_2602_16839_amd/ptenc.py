@@ -22,7 +22,7 @@ F32, BF16 = 0, 1
 NORM_FROBENIUS, NORM_ROW_L2, NORM_NONE = 0, 1, 2
 DEVERR_APPEND_FULL, DEVERR_ATTEND_EMPTY, DEVERR_BAD_ID = 1, 2, 4
 OPT_SPLITS, OPT_FORCE_GENERIC, OPT_NONTEMPORAL, OPT_WAVES, OPT_COUNTERS_IN_PLACE = 0, 1, 2, 3, 4
-OPT_EVICT_POLICY, OPT_RECENT, OPT_ENCODE_PARTS = 5, 6, 7
+OPT_EVICT_POLICY, OPT_RECENT, OPT_ENCODE_PARTS, OPT_ENCODE_INLINE = 5, 6, 7, 8
 POLICY_SLIDING, POLICY_SCORED = 0, 1
 MAX_SPLITS = 32
 

@@ -91,7 +91,7 @@ def make_oracle(wl, enc, norm_mode=po.NORM_FROBENIUS, keep_chunks=False, softmax
 
 
 def make_layer(wl, enc, norm_mode=0, splits=0, force_generic=False, poison=True, softmax_scale=0.0, waves=0,
-               enc_parts=0):
+               enc_parts=0, enc_inline=-1):
     from paper_2602_16839_amd import ptenc
     layer = ptenc.Layer(wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.window, wl.chunk,
                         dtype=wl.torch_dtype, n_global=wl.n_global, rank=wl.rank, norm_mode=norm_mode,
@@ -104,6 +104,8 @@ def make_layer(wl, enc, norm_mode=0, splits=0, force_generic=False, poison=True,
         layer.set_option(ptenc.OPT_WAVES, waves)
     if enc_parts:
         layer.set_option(ptenc.OPT_ENCODE_PARTS, enc_parts)
+    if enc_inline >= 0:
+        layer.set_option(ptenc.OPT_ENCODE_INLINE, enc_inline)
     dev = {k: v.to("cuda:0") for k, v in enc.items()}
     layer.set_encoder(dev["q_g"], dev["WaQ"], dev["WaK"], dev["WaV"], dev.get("k_g"), dev.get("v_g"))
     layer.reset()
@@ -122,13 +124,13 @@ def prefill_both(wl, orc, layer, prompt_len=None):
 
 
 def run_both(wl, T, norm_mode=0, splits=0, force_generic=False, lengths=None, with_global_kv=True,
-             q_gain=1.0, check_every=1, prompt_len=None, waves=0, enc_parts=0):
+             q_gain=1.0, check_every=1, prompt_len=None, waves=0, enc_parts=0, enc_inline=-1):
     """Decode T steps on the oracle and on the HIP layer; compare outputs every `check_every` steps,
     counters every step, and the state at the end.  Returns (layer, oracle)."""
     enc = I.encoder_params(wl, with_global_kv=with_global_kv)
     orc = make_oracle(wl, enc, norm_mode=norm_mode)
     layer = make_layer(wl, enc, norm_mode=norm_mode, splits=splits, force_generic=force_generic, waves=waves,
-                       enc_parts=enc_parts)
+                       enc_parts=enc_parts, enc_inline=enc_inline)
     if wl.n_sink:
         prefill_both(wl, orc, layer, prompt_len)
     q, k, v = I.qkv_steps(wl, 0, T)

@@ -72,6 +72,61 @@ def test_chunks_are_encoded_by_several_workgroups(W, C, n_sink, waves, splits, p
     assert [int(x) for x in base] == [-(-(int(T) - Wr) // C) * C for T in lengths]      # an eviction at steps Wr, Wr + C, ...
 
 
+@pytest.mark.parametrize("W,C,n_sink,waves,splits", [(1056, 520, 0, 4, 1), (1120, 800, 32, 8, 2), (2112, 2070, 0, 4, 3),
+                                                     (1024, 1024, 0, 8, 1), (160, 48, 0, 4, 1), (96, 33, 0, 4, 1),
+                                                     (64, 1, 0, 4, 1), (128, 32, 0, 8, 2)])
+def test_chunks_folded_ahead_of_time_by_the_rollouts_own_workgroups(W, C, n_sink, waves, splits):
+    # the way launches that fill the chip encode (forced here at small sizes): the workgroup of KV head 0 folds the
+    # next chunk's groups into the pending block one at a time while the ring refills, and the evicting step
+    # adds what is pending.  Chunks that are not whole groups, that wrap, that are the whole ring, single tokens;
+    # a rollout that stops between evictions with groups pending.
+    wl = small("qwen3b", batch=2, n_q_heads=4, n_kv_heads=2, window=W, n_sink=n_sink, chunk=C,
+               steps=(W - n_sink) + 2 * C + 40)
+    lengths = np.array([wl.steps, (W - n_sink) + C + max(1, C // 2)])
+    layer, _ = H.run_both(wl, wl.steps, splits=splits, waves=waves, check_every=61, lengths=lengths,
+                          prompt_len=[n_sink, 5] if n_sink else None, enc_inline=1)
+    assert layer.plan()[:2] == (1, splits)
+    ln, base = layer.counters()
+    Wr = W - n_sink
+    assert [int(x) for x in base] == [-(-(int(T) - Wr) // C) * C for T in lengths]
+
+
+@pytest.mark.parametrize("inline_a,inline_b", [(1, 0), (0, 1), (1, 1)])
+def test_pending_groups_survive_changes_of_who_encodes_and_of_entry_point(inline_a, inline_b):
+    # Groups folded ahead of time wait in the pending block until the eviction, whoever performs it: the mode
+    # changes in mid-refill (a ragged batch shrinks from a launch that fills the chip to one that does not), steps
+    # are taken through the separate entry points (which fold nothing ahead), counters are rewritten with the
+    # same values by the host (which drops what is pending: the eviction then folds the whole chunk itself).
+    from paper_2602_16839_amd import ptenc
+    wl = small("qwen7b", batch=3, n_q_heads=4, n_kv_heads=2, window=192, chunk=96, steps=192 + 3 * 96 + 11)
+    enc = I.encoder_params(wl)
+    orc = H.make_oracle(wl, enc)
+    layer = H.make_layer(wl, enc, enc_inline=inline_a)
+    q, k, v = I.qkv_steps(wl, 0, wl.steps)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    qn, kn, vn = H.f64(q), H.f64(k), H.f64(v)
+    for t in range(wl.steps):
+        ref = orc.step(qn[t], kn[t], vn[t])
+        if t == 192 + 40:                     # first refill under way: somebody else takes over
+            layer.set_option(ptenc.OPT_ENCODE_INLINE, inline_b)
+        if t == 192 + 96 + 30:                # second refill: the host rewrites the counters as they are
+            ln, base = layer.counters()
+            layer.set_counters(ln, base)
+        if 192 + 2 * 96 + 20 <= t < 192 + 2 * 96 + 50:   # third refill: thirty steps through the separate calls
+            layer.evict_encode()
+            layer.append(kd[t], vd[t])
+            out = layer.attend(qd[t])
+        else:
+            out = layer.step(qd[t], kd[t], vd[t])
+        if t % 7 == 0 or t == wl.steps - 1:
+            H.assert_close(H.f64(out), ref, H.BF16_ABS, H.BF16_REL, "out at step %d" % t)
+        if t in (192, 192 + 96, 192 + 2 * 96, 192 + 3 * 96, wl.steps - 1):
+            H.assert_close(layer.get_state(), orc.state(), H.S_ABS, H.S_REL, "state after step %d" % t)
+    ln, base = layer.counters()
+    oln, obase = orc.counters()
+    assert np.array_equal(ln, oln) and np.array_equal(base, obase) and layer.poll_error() == 0
+
+
 def test_bf16_generic_path_small_window():
     wl = small("qwen3b", batch=2, n_q_heads=8, n_kv_heads=2, window=96, chunk=40, steps=250)
     layer, _ = H.run_both(wl, wl.steps, force_generic=True, splits=2)

@@ -50,7 +50,10 @@ def test_random_configuration(kind, seed):
     orc = H.make_oracle(wl, enc)
     # (a generator of its own, so that the cases drawn before this option existed stay what they were)
     parts = int(np.random.default_rng(5000 + seed).choice([0, 1, 2, 3, 5, 8])) if kind == "mfma" else 0
-    layer = H.make_layer(wl, enc, splits=splits, waves=waves, enc_parts=parts)
+    # who encodes evicted chunks (again a generator of its own): the launch's own choice, encoding workgroups,
+    # or the rollouts' own workgroups ahead of time
+    inline = int(np.random.default_rng(7000 + seed).choice([-1, 0, 1, 1])) if kind == "mfma" else -1
+    layer = H.make_layer(wl, enc, splits=splits, waves=waves, enc_parts=parts, enc_inline=inline)
     assert layer.plan()[0] == (1 if kind == "mfma" else 0), (kind, wl)
     prompt_len = None
     if wl.n_sink:
