@@ -166,25 +166,38 @@ class Bench:
     def _make_segment(self, t0, t1):
         torch, np, I, wl, dev = self.torch, self.np, self.I, self.wl, self.dev
         n = t1 - t0
-        q = torch.empty((n, wl.batch, wl.n_q_heads, wl.head_dim), dtype=wl.torch_dtype, device=dev)
-        k = torch.empty((n, wl.batch, wl.n_kv_heads, wl.head_dim), dtype=wl.torch_dtype, device=dev)
-        v = torch.empty_like(k)
-        blk = max(1, (1 << 26) // (wl.batch * wl.d_q))
-        for a in range(0, n, blk):
-            b = min(n, a + blk)
-            q[a:b], k[a:b], v[a:b] = I.qkv_steps(wl, t0 + a, t0 + b, device=dev)
         active = ids = row_offsets = None
-        if wl.ragged:
-            tt = torch.arange(t0, t1, device=dev).view(-1, 1)
-            alive = tt < torch.from_numpy(self.lengths).to(dev).view(1, -1)          # [n, B]
-            if self.compact:
-                # what a rollout engine feeds: only the rollouts still running, with their ids
-                ids = torch.nonzero(alive)[:, 1].to(torch.int32).contiguous()
-                q, k, v = q[alive].contiguous(), k[alive].contiguous(), v[alive].contiguous()
-                counts = np.array([(self.lengths > t).sum() for t in range(t0, t1)], dtype=np.int64)
-                row_offsets = np.concatenate([[0], np.cumsum(counts)])
-            else:
-                active = alive.to(torch.uint8).contiguous()
+        blk = max(1, (1 << 26) // (wl.batch * wl.d_q))
+        if self.compact:
+            # what a rollout engine feeds: only the rollouts still running, with their ids (rows of step t, then
+            # of step t + 1, ...); built block by block so that no full [steps, B] tensor ever exists
+            counts = np.array([(self.lengths > t).sum() for t in range(t0, t1)], dtype=np.int64)
+            row_offsets = np.concatenate([[0], np.cumsum(counts)])
+            rows = int(row_offsets[-1])
+            q = torch.empty((rows, wl.n_q_heads, wl.head_dim), dtype=wl.torch_dtype, device=dev)
+            k = torch.empty((rows, wl.n_kv_heads, wl.head_dim), dtype=wl.torch_dtype, device=dev)
+            v = torch.empty_like(k)
+            ids = torch.empty(rows, dtype=torch.int32, device=dev)
+            len_dev = torch.from_numpy(self.lengths).to(dev).view(1, -1)
+            for a in range(0, n, blk):
+                b = min(n, a + blk)
+                r0, r1 = int(row_offsets[a]), int(row_offsets[b])
+                if r1 == r0:
+                    continue
+                alive = torch.arange(t0 + a, t0 + b, device=dev).view(-1, 1) < len_dev          # [b - a, B]
+                qb, kb, vb = I.qkv_steps(wl, t0 + a, t0 + b, device=dev)
+                q[r0:r1], k[r0:r1], v[r0:r1] = qb[alive], kb[alive], vb[alive]
+                ids[r0:r1] = torch.nonzero(alive)[:, 1].to(torch.int32)
+        else:
+            q = torch.empty((n, wl.batch, wl.n_q_heads, wl.head_dim), dtype=wl.torch_dtype, device=dev)
+            k = torch.empty((n, wl.batch, wl.n_kv_heads, wl.head_dim), dtype=wl.torch_dtype, device=dev)
+            v = torch.empty_like(k)
+            for a in range(0, n, blk):
+                b = min(n, a + blk)
+                q[a:b], k[a:b], v[a:b] = I.qkv_steps(wl, t0 + a, t0 + b, device=dev)
+            if wl.ragged:
+                tt = torch.arange(t0, t1, device=dev).view(-1, 1)
+                active = (tt < torch.from_numpy(self.lengths).to(dev).view(1, -1)).to(torch.uint8).contiguous()
         out = torch.empty_like(q)
         torch.cuda.synchronize()
         return (t0, t1, q, k, v, out, active, ids, row_offsets)
@@ -331,6 +344,9 @@ def main() -> int:
                     help="only the untimed steps 1..T-K and the K timed steps (profiler runs): no full run, no "
                          "staggered evictions, no other workloads, no CPU baseline")
     ap.add_argument("--no-workloads", action="store_true", help="skip the other configurations")
+    ap.add_argument("--progress", action="store_true",
+                    help="decode the untimed steps in pieces of 1024 and report each on stderr (runs under a profiler's "
+                         "counters take minutes)")
     ap.add_argument("--no-stagger", action="store_true", help="skip the staggered-evictions figures")
     ap.add_argument("--extras", action="store_true",
                     help="also time the state-as-weight-delta application (and the question-token prefill)")
@@ -375,9 +391,12 @@ def main() -> int:
     if T - K > 0:
         a = 0
         while a < T - K:
-            b_ = (T - K) if hb.resident else min(T - K, a + seg_steps)
+            b_ = (T - K) if (hb.resident and not args.progress) else min(T - K, a + (1024 if hb.resident else seg_steps))
             hb._segment_for(a, b_)
             hb.launch(a, b_)
+            if args.progress:
+                torch.cuda.synchronize()
+                print("bench.py: steps 1..%d of %d decoded (untimed)" % (b_, T), file=sys.stderr, flush=True)
             a = b_
     else:
         hb._segment_for(0, min(T, max(Wu, 1)))
