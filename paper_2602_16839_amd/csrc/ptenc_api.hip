@@ -181,11 +181,12 @@ ptenc_status advanced(ptenc_ctx* x, hipError_t e) {
 }
 inline ptenc_status hip_status(hipError_t e) { return e == hipSuccess ? PTENC_OK : PTENC_ERR_HIP; }
 
-// Launches that may evict carry encoding workgroups for every row.  While no ring can be full yet (the host
+// Launches that may evict carry the eviction machinery (encoding workgroups for every row, or the code with which
+// the rows' own workgroups encode).  While no ring can be full yet (the host
 // keeps an upper bound on the fullest one: appends since the last full reset or ptenc_set_counters),
-// steps are launched without them and without the eviction logic; should the bound ever be wrong, the
+// steps are launched without it; should the bound ever be wrong, the
 // append on the full ring sets PTENC_DEVERR_APPEND_FULL instead of going unnoticed.  Steps that may be
-// replayed from a graph (counters in place) always carry them.
+// replayed from a graph (counters in place) always carry it.
 // (A ring that is within a chunk of full already has groups of its next chunk folded ahead of time by the
 // steps that fill it, which is part of the same machinery.)
 bool may_evict(const ptenc_ctx* x) { return x->opt_in_place != 0 || x->dev.live_ub >= x->dev.Wr - x->dev.C; }

@@ -26,9 +26,12 @@ def _make_stack(wl, L, encs):
     return st
 
 
-@pytest.mark.parametrize("kind", ["mfma", "f32"])
+@pytest.mark.parametrize("kind", ["mfma", "mfma_inline", "f32"])
 def test_stack_steps_and_graph_replays_match_per_layer_oracles(kind):
     L = 3
+    inline = kind == "mfma_inline"
+    if inline:
+        kind = "mfma"
     if kind == "mfma":
         wl = I.WORKLOADS["qwen7b"].replace(batch=3, n_q_heads=14, n_kv_heads=2, window=96, chunk=32, steps=150)
     else:
@@ -41,7 +44,12 @@ def test_stack_steps_and_graph_replays_match_per_layer_oracles(kind):
     if kind == "mfma":
         # two encoding workgroups per rollout: their shares of S' meet in the scratch buffer the layers share
         for layer in st.layers:
-            layer.set_option(ptenc.OPT_ENCODE_PARTS, 2)
+            if inline:
+                # ... or the rollouts' own workgroups fold their next chunk ahead of time: the pending block and its
+                # group count are updated in place by replays and eager steps alike
+                layer.set_option(ptenc.OPT_ENCODE_INLINE, 1)
+            else:
+                layer.set_option(ptenc.OPT_ENCODE_PARTS, 2)
     T = wl.steps
     qkv = [I.qkv_steps(w, 0, T) for w in wls]
     dev = [tuple(x.cuda() for x in t) for t in qkv]
