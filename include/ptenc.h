@@ -279,7 +279,11 @@ ptenc_status ptenc_apply_delta(ptenc_ctx* ctx, const void* d_x, const void* d_At
                                void* stream);
 
 /* Counters to / from host arrays of B int64 each.  set_counters requires
- * 0 <= base <= len <= base + W - n_sink for every rollout (used for resume and rotation tests). */
+ * 0 <= base <= len <= base + W - n_sink for every rollout (used for resume and rotation tests).
+ * It also drops whatever a rollout had folded ahead of time of its next chunk (PTENC_OPT_ENCODE_INLINE): the
+ * next eviction then folds the whole chunk itself, and S may differ in the last bits from a run whose
+ * counters were never rewritten (a resume from cache + S + counters is bit-identical where chunks are
+ * folded by encoding workgroups of their own, equal to rounding otherwise). */
 ptenc_status ptenc_get_counters(ptenc_ctx* ctx, int64_t* h_len, int64_t* h_base, void* stream);
 ptenc_status ptenc_set_counters(ptenc_ctx* ctx, const int64_t* h_len, const int64_t* h_base, void* stream);
 
