@@ -122,18 +122,40 @@ bool mfma_attn_applies(const ptenc_config& c) {
 
 // Window splits.  Splitting a (rollout, KV head) row over several workgroups costs a round trip
 // through memory for the partial results; it pays while the launch has fewer workgroups than the
-// chip has CUs.  Measured on MI355X (2 KV heads, windows of 1024 and 2048, both interfaces): from
+// chip has CUs.  Measured on MI355X (2 KV heads, windows of 1024, 2048 and 4096, both interfaces): from
 // 60 rows up the best count is the largest one that keeps rows x splits within about 240 workgroups
 // (one split from 121 rows), below that about 128 workgroups; never fewer than 256 tokens per split.
+// Two refinements for the MFMA kernel, whose wavefronts take whole 32-token groups: a count that deals
+// the groups unevenly (32 groups to 3 x 8 wavefronts: some get two, the step lasts as long as if all did)
+// gives way to the next count that deals them evenly: a larger one if the launch stays within 224
+// workgroups, else a smaller one if the busiest wavefront has no more groups under it than under the
+// uneven count (otherwise the uneven count stays: 64 groups to 3 x 8 wavefronts is 3 at most, against 4
+// under two splits, and measures best); and 96 to 128 rows, which fill up to half the chip, are split
+// in two only when each wavefront still keeps 8 groups or more (112 rows at a window of 4096: 38 us
+// against 48; at 2048 and below one split is 0-6 % faster).
 int heuristic_splits(const ptenc_ctx* x, long n_rollouts) {
   const ptenc_config& c = x->cfg;
   const long rows = n_rollouts * (x->attn_kernel ? c.n_kv_heads : c.n_q_heads);
   long want = rows >= 60 ? 240 / rows : (128 + rows - 1) / rows;
   long cap = (c.window - c.n_sink) / 256;
   if (cap < 1) cap = 1;
+  if (cap > PTENC_MAX_SPLITS) cap = PTENC_MAX_SPLITS;
   if (want > cap) want = cap;
-  if (want > PTENC_MAX_SPLITS) want = PTENC_MAX_SPLITS;
   if (want < 1) want = 1;
+  if (x->attn_kernel) {
+    const long ng = (c.window - c.n_sink) / PT_GROUP_TOKENS;
+    const long waves = (rows * want <= 256 && x->dev.group <= 8 && x->opt_waves != 4) ? 8 : 4;
+    auto even = [&](long s) { return ng % (s * waves) == 0; };
+    if (want > 1 && !even(want)) {
+      long up = want + 1, down = want - 1;
+      while (up <= cap && !even(up)) ++up;
+      while (down > 1 && !even(down)) --down;
+      const auto longest = [&](long s) { return (ng + s * waves - 1) / (s * waves); };
+      if (up <= cap && rows * up <= 224) want = up;
+      else if (longest(down) == longest(want)) want = down;
+    }
+    if (rows >= 96 && rows <= 128 && cap >= 2) want = ng / (2 * waves) >= 8 ? 2 : 1;
+  }
   return (int)want;
 }
 

@@ -204,13 +204,18 @@ def test_oracle_and_product_do_not_import_each_other():
     (128, 28, 4, 4096, 1),      # qwen7b: 512 (rollout, KV head) rows
     (64, 16, 2, 2048, 1),       # qwen3b: 128 rows, one split from 121 rows up
     (256, 32, 8, 8192, 1),      # llama8b
-    (60, 16, 2, 2048, 2),       # 120 rows: the largest count within about 240 workgroups
+    (60, 16, 2, 2048, 1),       # 120 rows: two splits would leave a wavefront 4 groups: not worth the hand-over
+    (56, 16, 2, 4096, 2),       # 112 rows at twice the window: 8 groups per wavefront under two splits
     (40, 16, 2, 2048, 3),       # 80 rows
     (30, 16, 2, 2048, 4),       # 60 rows
     (16, 16, 2, 2048, 4),       # 32 rows: about 128 workgroups
     (4, 16, 2, 2048, 8),        # 8 rows: capped by 256 tokens per split
     (4, 16, 2, 512, 2),         # a short window allows two splits only
     (1, 8, 1, 8192, 32),        # one row: the maximum
+    (24, 16, 2, 1024, 4),       # 48 rows: 3 splits deal 32 groups unevenly to 24 wavefronts; 4 fit the chip
+    (32, 16, 2, 1024, 2),       # 64 rows: 4 splits no longer fit, and 3 are no shorter than 2
+    (32, 16, 2, 2048, 3),       # 64 groups: 3 at most under 3 splits against 4 under 2: stays
+    (64, 16, 2, 4096, 2),       # 128 rows fill half the chip and every wavefront keeps 8 groups
 ])
 def test_window_split_plan_for_known_shapes(batch, hq, hkv, window, splits):
     # the measured rule of the host's plan (documented with the heuristic): a change shows up here
