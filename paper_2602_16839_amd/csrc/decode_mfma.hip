@@ -98,25 +98,28 @@ struct Acc {
 // per KV head, columns 8..15 of the score MFMA are free, and carry the previous step's queries (saved
 // by that step, with its softmax maximum and 1 / sum).  Lane (kgrp, n >= 8) then holds, in p[], head
 // n - 8's unnormalised probabilities of its 8 tokens; il = 1 / sum (0 in lanes that carry nothing).
-// The sum over heads is a sum over the 16 lanes of a row (four rotate-and-add steps); afterwards lane
-// (kgrp, n < 8) keeps the total of token tl = (n / 4) * 16 + 4 kgrp + n % 4.
+// The sum over heads is taken among the eight lanes 8..15 of a row as a reduce-scatter: three
+// exchanges (with the lane mirrored within the eight, then two apart, then one apart), each lane keeping
+// the half of its values that its side of the exchange is responsible for, so that lane 8 + e ends with
+// the total of the e-th of the lane's tokens, tl = (e / 4) * 16 + 4 kgrp + e % 4 (29 vector
+// instructions per group instead of 56 for eight full sums; the walk pays for every one of them).
 template <int CTRL>
-__device__ inline float row_ror_add(float v) {
-  return v + __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xf, 0xf, true));
+__device__ inline float dpp_add(float keep, float send) {
+  return keep + __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(send), CTRL, 0xf, 0xf, true));
 }
 
 __device__ inline void lagged_mass_park(const float p[8], float il, float* park_grp, int n, int kgrp) {
-  float mine = 0.f;
+  float v[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    float v = p[e] * il;                 // 0 in the lanes of this step's own heads
-    v = row_ror_add<0x128>(v);           // row_ror:8
-    v = row_ror_add<0x124>(v);           // row_ror:4
-    v = row_ror_add<0x122>(v);           // row_ror:2
-    v = row_ror_add<0x121>(v);           // row_ror:1
-    mine = n == e ? v : mine;
-  }
-  if (n < 8) park_grp[(n >> 2) * 16 + 4 * kgrp + (n & 3)] = mine;
+  for (int e = 0; e < 8; ++e) v[e] = p[e] * il;       // 0 in the lanes of this step's own heads
+  const bool lo4 = (n & 4) == 0, lo2 = (n & 2) == 0, lo1 = (n & 1) == 0;
+  float r4[4], r2[2];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) r4[k] = dpp_add<0x141>(lo4 ? v[k] : v[4 + k], lo4 ? v[4 + k] : v[k]);      // row_half_mirror
+#pragma unroll
+  for (int k = 0; k < 2; ++k) r2[k] = dpp_add<0x4E>(lo2 ? r4[k] : r4[2 + k], lo2 ? r4[2 + k] : r4[k]);   // quad_perm [2,3,0,1]
+  const float mine = dpp_add<0xB1>(lo1 ? r2[0] : r2[1], lo1 ? r2[1] : r2[0]);                             // quad_perm [1,0,3,2]
+  if (n >= 8) park_grp[((n - 8) >> 2) * 16 + 4 * kgrp + (n & 3)] = mine;
 }
 
 // jg = logical index of the group's first slot within its region (question tokens or ring walk),
@@ -1060,6 +1063,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
     acc.m = -INFINITY;
     acc.l = 0.f;
 
+    bool fold = false;                     // MASS: the previous step's probabilities join the scores in this walk
+    float* mass_slab = nullptr;
     {
       const bool patch = appending && owner;       // this workgroup walks the group the new token goes to
       const int p_tl = s_new & 31;
@@ -1077,9 +1082,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
       }
       // the previous step's queries and statistics, if they wait to be folded into the scores
       // (saved by the step that left len == len0, in the buffer of that parity)
-      bool fold = false, lag = false;      // lag: this lane's column carries a head of the previous step
+      bool lag = false;                    // this lane's column carries a head of the previous step
       float il = 0.f;                      // that step's 1 / sum for the lane's head
-      float* mass_slab = nullptr;
       float* park = dyn_lds;               // MASS: 32 floats per group this workgroup walks
       auto grp_ptr = [&](int pg) { return (const u32x4*)slab_p + (size_t)pg * (PT_GROUP_ELEMS / 8); };
       // where a group's 32 masses are parked: by its index in the slab
@@ -1141,34 +1145,6 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
         }
         i = nx;
       }
-      if constexpr (MASS) {
-        // every wavefront folds the groups it walked: lanes 0..31 own a group's 32 accumulators
-        // (slot = 32 pg + lane).  The token this step appended starts at zero and took no part in the
-        // previous step; question tokens are not scored.
-        // one lane adds to one accumulator once per step, so a returnless hardware float add gives the same
-        // bits as load-add-store and needs no round trip
-        int pgc = next_live(pg_first);
-        while (pgc < NGt) {
-          float add[8];
-          int pgs[8];
-#pragma unroll
-          for (int u = 0; u < 8; ++u) {          // the LDS reads of a batch together, then its adds
-            pgs[u] = pgc;
-            add[u] = (pgc < NGt && pgc >= gs && lane < 32) ? park_of(pgc)[lane] : 0.f;
-            if (pgc < NGt) pgc = next_live(pgc + stride);
-          }
-#pragma unroll
-          for (int u = 0; u < 8; ++u) {
-            const int pgu = pgs[u];
-            if (pgu >= NGt || pgu < gs || lane >= 32) continue;
-            int j = (pgu - gs) * PT_GROUP_TOKENS + lane - s0;          // logical index of the slot
-            j += j < 0 ? c.Wr : 0;
-            float* mp = mass_slab + (size_t)pgu * PT_GROUP_TOKENS + lane;
-            if (appending && j == n_live - 1) *mp = 0.f;
-            else if (fold && (unsigned)j < (unsigned)(n_live - 1)) unsafeAtomicAdd(mp, add[u]);
-          }
-        }
-      }
       // the store of the new token rides behind the walk: its inputs arrived long ago, and the
       // chunk of an evicting step was read before anything could overwrite its oldest slot
       if (patch && wave == 0 && !evicting)
@@ -1195,6 +1171,40 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
       for (int i = 0; i < 8; ++i) *(f32x4*)&sm.merge.o[wave][n][16 * i + 4 * kgrp] = acc.o[i];
     }
     __syncthreads();
+
+    if constexpr (MASS) {
+      // The masses parked during the walk join the accumulators: the workgroup's threads share out the
+      // slots (slot = 32 pg + token) of the ring groups this workgroup walked.
+      // The token this step appended starts at zero and took no part in the previous step; question
+      // tokens are not scored.  One thread adds to one accumulator once per step, so a returnless
+      // hardware float add gives the same bits as load-add-store and needs no round trip; the adds
+      // are on their way while the merge below runs.
+      if (appending && owner && tid == 0) mass_slab[c.n_sink + s_new] = 0.f;
+      if (fold) {
+        // half a wavefront per group: the m-th group this workgroup walks is
+        // (m / WAVES) * stride + split * WAVES + m % WAVES (wavefront w of split s takes s * WAVES + w, + stride, ...)
+        const float* park = dyn_lds;
+        const int l5 = tid & 31;
+        constexpr int kPer = 2 * kWaves, kBatch = 4;       // groups per pass of the workgroup; passes per batch
+        for (int m0 = tid >> 5; (m0 / kWaves) * stride < NGt; m0 += kBatch * kPer) {
+          float add[kBatch];
+          int slots[kBatch];
+#pragma unroll
+          for (int u = 0; u < kBatch; ++u) {     // the LDS reads of a batch together, then its adds
+            const int m = m0 + u * kPer, pg = (m / kWaves) * stride + split * kWaves + (m % kWaves);
+            const bool mine = pg >= gs && pg < NGt;
+            slots[u] = mine ? pg * PT_GROUP_TOKENS + l5 : -1;
+            add[u] = mine ? park[pg * PT_GROUP_TOKENS + l5] : 0.f;
+          }
+#pragma unroll
+          for (int u = 0; u < kBatch; ++u) {
+            int j = slots[u] - gs * PT_GROUP_TOKENS - s0;             // logical index of the slot
+            j += j < 0 ? c.Wr : 0;
+            if (slots[u] >= 0 && (unsigned)j < (unsigned)(n_live - 1)) unsafeAtomicAdd(mass_slab + slots[u], add[u]);
+          }
+        }
+      }
+    }
 
     const int qn = tid >> 4, part = tid & 15;   // 16 threads per query, 8 columns each
     const bool has_row = qn < g;
