@@ -117,7 +117,13 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(PtDev c, const T
         }
         for (; i < c.d; ++i) d0 = fmaf(qs[i], pt_ld<T>(kr + i), d0);
       } else {
-        for (int i = 0; i < c.d; ++i) d0 = fmaf(qs[i], pt_ld<T>(slab + pt_k_off(1, c.W, c.d, slot, i)), d0);
+        // (the same four chains; d is a multiple of 8 in the tiled layout)
+        for (int i = 0; i < c.d; i += 4) {
+          d0 = fmaf(qs[i], pt_ld<T>(slab + pt_k_off(1, c.W, c.d, slot, i)), d0);
+          d1 = fmaf(qs[i + 1], pt_ld<T>(slab + pt_k_off(1, c.W, c.d, slot, i + 1)), d1);
+          d2 = fmaf(qs[i + 2], pt_ld<T>(slab + pt_k_off(1, c.W, c.d, slot, i + 2)), d2);
+          d3 = fmaf(qs[i + 3], pt_ld<T>(slab + pt_k_off(1, c.W, c.d, slot, i + 3)), d3);
+        }
       }
       s = ((d0 + d1) + (d2 + d3)) * c.scale_log2;
     }
@@ -132,7 +138,9 @@ __global__ __launch_bounds__(kThreads) void attn_generic_kernel(PtDev c, const T
     if (vwork) {
       acc *= alpha;
       const int n = min(kThreads, j1 - jb);
-      for (int x = vpart; x < n; x += parts) {
+#pragma unroll 8
+      for (int x = vpart; x < n; x += parts) {     // independent loads: eight in flight at a time (measured: -21 % per step at
+                                                   // 4 rollouts x 4 heads x 256 tokens; sixteen are no better)
         const int sl = slots[x];
         const float vv = (FUSED && sl < 0) ? pt_ld<T>(vnew + new_off + vcol)
                                            : pt_ld<T>(slab + pt_v_off(c.tiled, c.W, c.d, sl, vcol));
