@@ -64,8 +64,8 @@ def test_encoder_params_shapes():
 
 def test_bench_byte_model_gives_the_workloads_published_totals():
     # the algorithmic bytes bench.py prices a run at (K and V stream over the live window, q in / out out,
-    # append, chunk re-read and S update per eviction) summed over the three model-shaped runs: the
-    # totals the workload table of the survey quotes (GB, 4 significant digits there)
+    # append, chunk re-read and S update per eviction) summed over the three model-shaped runs, against the
+    # totals worked out by hand from the shapes (GB, 4 significant digits)
     import bench
     for name, total_gb in (("qwen3b", 410.7), ("qwen7b", 6547.7), ("llama8b", 104557.0)):
         wl = I.WORKLOADS[name]
