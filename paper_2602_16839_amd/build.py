@@ -102,6 +102,27 @@ def build_host_sanitized(verbose: bool = False) -> str:
     return SAN_LIB_PATH
 
 
+TIMELINE_LIB_PATH = os.path.join(PKG_DIR, "libptenc_timeline.so")
+
+
+def build_timeline(verbose: bool = False) -> str:
+    """The same library with -DPTENC_TIMELINE: the step kernel notes the wall clock at the boundaries of its phases
+    (entry, walk begins, walk ends, wavefronts merged, result out, ...) per workgroup, at the end of the state block.
+    A profiling build for `python -m paper_2602_16839_amd.step_timeline`, which selects it through PTENC_LIB; nothing
+    else loads it."""
+    from concurrent.futures import ThreadPoolExecutor
+    tl_dir = os.path.join(OBJ_DIR, "timeline")
+    os.makedirs(tl_dir, exist_ok=True)
+    objs = [os.path.join(tl_dir, s.replace(".hip", ".o")) for s in SOURCES]
+    cmds = [[hipcc_path()] + HIPCC_FLAGS + ["-DPTENC_TIMELINE"] + EXTRA_FLAGS.get(s, []) + ["-c", os.path.join(CSRC, s), "-o", o]
+            for s, o in zip(SOURCES, objs)]
+    with ThreadPoolExecutor(max_workers=min(8, len(cmds))) as pool:
+        list(pool.map(lambda c: _run(c, verbose), cmds))
+    _run([hipcc_path(), "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", TIMELINE_LIB_PATH + ".tmp"], verbose)
+    os.replace(TIMELINE_LIB_PATH + ".tmp", TIMELINE_LIB_PATH)
+    return TIMELINE_LIB_PATH
+
+
 C_SMOKE_SRC = os.path.join(ROOT, "tests", "c_abi", "abi_smoke.c")
 C_SMOKE_BIN = os.path.join(ROOT, "tests", "c_abi", "abi_smoke")
 
@@ -124,4 +145,6 @@ def build_c_smoke(verbose: bool = True) -> str:
 
 if __name__ == "__main__":
     build()
+    if "--timeline" in sys.argv[1:]:
+        print(build_timeline(verbose=True))
     sys.exit(0)

@@ -851,6 +851,19 @@ __device__ inline void encoder_role(const PtDev& c, const StepArgs& a, StepSmem<
 // 1 = may evict, encoding workgroups of their own behind the attention workgroups; 2 = may evict, the rows'
 // own workgroups encode before they walk.  (One instantiation per way of encoding, so that neither carries
 // the other's code and registers.)
+// Profiling build (-DPTENC_TIMELINE, see build.py): thread 0 of every workgroup notes the 100 MHz wall clock at
+// the boundaries of the step's phases; nothing of it exists in the library proper.
+#ifdef PTENC_TIMELINE
+#define PT_STAMP_AT(k, who)                                                                              \
+  do {                                                                                                   \
+    const size_t wg_ = (size_t)blockIdx.x + (size_t)gridDim.x * blockIdx.y;                              \
+    if ((who) && wg_ < (size_t)PT_TIMELINE_WGS) c.timeline[wg_ * PT_TIMELINE_SLOTS + (k)] = wall_clock64(); \
+  } while (0)
+#else
+#define PT_STAMP_AT(k, who) ((void)0)
+#endif
+#define PT_STAMP(k) PT_STAMP_AT(k, threadIdx.x == 0)
+
 template <bool NT, int WAVES, bool MASS, int ENC>
 __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
     // what the walk cannot start without comes first, as plain scalars: the build asks for these
@@ -870,6 +883,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
   __shared__ StepSmem<WAVES> sm;
   __shared__ int sm_ticket;
   extern __shared__ __align__(16) float dyn_lds[];   // MASS only: parked masses
+  PT_STAMP(0);
 
   // row j of the launch (and of q / k / v / out) is rollout b: j itself, or ids[j] for a compact list
   const int j_row = blockIdx.x / n_kv_heads, hkv = blockIdx.x - j_row * n_kv_heads, split = blockIdx.y;
@@ -1056,6 +1070,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
   }
   if (append_full && owner && hkv == 0 && tid == 0) atomicOr(c.err, PTENC_DEVERR_APPEND_FULL);
 
+  PT_STAMP(1);
   if (a.do_attend) {
     Acc acc;
 #pragma unroll
@@ -1162,6 +1177,8 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
       }
     }
 
+    PT_STAMP(2);
+    PT_STAMP_AT(8 + (threadIdx.x >> 6), (threadIdx.x & 63) == 0);
     // ---- merge the 4 wavefronts through LDS ----
     acc.l += __shfl_xor(acc.l, 16, 64);
     acc.l += __shfl_xor(acc.l, 32, 64);
@@ -1171,6 +1188,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
       for (int i = 0; i < 8; ++i) *(f32x4*)&sm.merge.o[wave][n][16 * i + 4 * kgrp] = acc.o[i];
     }
     __syncthreads();
+    PT_STAMP(3);
 
     if constexpr (MASS) {
       // The masses parked during the walk join the accumulators: the workgroup's threads share out the
@@ -1206,6 +1224,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
       }
     }
 
+    PT_STAMP(4);
     const int qn = tid >> 4, part = tid & 15;   // 16 threads per query, 8 columns each
     const bool has_row = qn < g;
     const size_t row = (size_t)b * c.Hq + hkv * g + (has_row ? qn : 0);          // scratch row
@@ -1240,6 +1259,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
       __syncthreads();
       if (tid == 0) sm_ticket = atomicAdd(c.tick_slab + slab, 1);
       __syncthreads();
+      PT_STAMP(6);
       const bool last = sm_ticket == ns - 1;
       write_out = has_row && last;
       if (last) {
@@ -1308,6 +1328,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void decode_mfma_kernel(
     }
   }
 
+  PT_STAMP(5);
   // ---- counters ----
   // They go to the other buffer (nobody reads that one in this kernel), so no workgroup waits for the
   // rest of its rollout; under a compact list as "the larger of what is there and mine", which commutes

@@ -43,6 +43,9 @@ struct StateLayout {
   size_t S, Qa, S0, len, base, len2, base2, n_prompt, err, tick_rollout, tick_slab, tick_enc, WKp, WVp;
   size_t mass, pos, victims, qprev, mlprev, mtag, selected;   // importance-based eviction
   size_t pend, enc_done, total;
+#ifdef PTENC_TIMELINE
+  size_t timeline;
+#endif
 };
 
 StateLayout state_layout(const ptenc_config& c) {
@@ -74,6 +77,9 @@ StateLayout state_layout(const ptenc_config& c) {
   L.selected = off; off = align256(off + (size_t)c.batch * sizeof(int));
   L.pend = off;     off = align256(off + gr * c.batch);
   L.enc_done = off; off = align256(off + (size_t)c.batch * sizeof(int));
+#ifdef PTENC_TIMELINE
+  L.timeline = off; off = align256(off + (size_t)PT_TIMELINE_WGS * PT_TIMELINE_SLOTS * sizeof(long long));
+#endif
   L.total = off;
   return L;
 }
@@ -297,6 +303,9 @@ ptenc_status ptenc_create(const ptenc_config* cfg, void* d_cache, void* d_state,
   d.mtag = (long long*)(sp + L.mtag);
   d.selected = (int*)(sp + L.selected);
   d.pend = (float*)(sp + L.pend); d.enc_done = (int*)(sp + L.enc_done);
+#ifdef PTENC_TIMELINE
+  d.timeline = (long long*)(sp + L.timeline);
+#endif
   x->select_stale = 1;
   x->opt_recent = -1;
   x->dev.live_ub = d.Wr;       // nothing is known about the counters the state block holds
@@ -304,6 +313,17 @@ ptenc_status ptenc_create(const ptenc_config* cfg, void* d_cache, void* d_state,
   *out = x;
   return PTENC_OK;
 }
+
+#ifdef PTENC_TIMELINE
+// profiling build only: where in the state block the step kernel's phase stamps are
+extern "C" ptenc_status ptenc_timeline_region(const ptenc_config* cfg, size_t* offset, size_t* bytes, int* slots_per_workgroup) {
+  if (check_config(cfg) != PTENC_OK || !offset || !bytes || !slots_per_workgroup) return PTENC_ERR_INVALID_ARG;
+  *offset = state_layout(*cfg).timeline;
+  *bytes = (size_t)PT_TIMELINE_WGS * PT_TIMELINE_SLOTS * sizeof(long long);
+  *slots_per_workgroup = PT_TIMELINE_SLOTS;
+  return PTENC_OK;
+}
+#endif
 
 ptenc_status ptenc_destroy(ptenc_ctx* ctx) {
   if (!ctx) return PTENC_ERR_INVALID_ARG;

@@ -62,7 +62,18 @@ struct PtDev {
   // host side only (travels with the launch parameters): upper bound on the live thinking tokens of the
   // fullest ring, this launch's append included (appends since the last full reset or ptenc_set_counters)
   long long live_ub;
+#ifdef PTENC_TIMELINE
+  // profiling build only (see build.py): wall-clock stamps of the step kernel's phases, PT_TIMELINE_SLOTS per
+  // workgroup, at the end of the state block
+  long long* timeline;
+#endif
 };
+
+#ifdef PTENC_TIMELINE
+constexpr int PT_TIMELINE_SLOTS = 16;      // per workgroup: 0 entry, 1 walk begins, 2 walk ends, 3 wavefronts merged,
+                                           //   4 scores folded, 5 result out, 6 split ticket taken, 8.. walk end of wavefront w
+constexpr int PT_TIMELINE_WGS = 8192;      // workgroups (x + grid.x * y) that have room
+#endif
 
 struct ptenc_ctx {
   ptenc_config cfg;
